@@ -1,0 +1,178 @@
+"""ctypes front end of the CPU oracle (oracle/civic_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the benchmark's
+cpu_baseline leg.  It shares nothing with the HIP library and the product path never
+imports it.  All arrays are host numpy arrays; bf16 inputs are passed as their exact fp32
+widening (floating-point steps) or as raw bytes (copy steps).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "civic_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP on the outermost loops)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11",
+                               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+class Grid(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("frames", "height", "width", "cell_h", "cell_w",
+                                         "cell_floor", "frame_floor", "budget")]
+
+
+_lib: Optional[C.CDLL] = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        L = C.CDLL(build())
+        P = C.c_void_p
+        L.oracle_threads.restype = C.c_int
+        L.oracle_anchor_normalize.restype = C.c_int
+        L.oracle_anchor_normalize.argtypes = [P, C.c_int32, C.c_double, P]
+        L.oracle_score.restype = None
+        L.oracle_score.argtypes = [P, C.c_int64, C.c_int64, C.c_int32, P, C.c_double, P]
+        L.oracle_select_batch.restype = C.c_int64
+        L.oracle_select_batch.argtypes = [P, C.c_int32, C.POINTER(Grid), C.c_int, P, C.c_int64, P]
+        L.oracle_kept_count.restype = C.c_int64
+        L.oracle_kept_count.argtypes = [C.POINTER(Grid), C.c_int]
+        L.oracle_compact.restype = C.c_int64
+        L.oracle_compact.argtypes = [P, C.c_int64, P, C.c_int32, C.c_int64, C.POINTER(Grid), P, P,
+                                     C.c_int64, C.c_int64, P, P, P]
+        L.oracle_attention.restype = None
+        L.oracle_attention.argtypes = [P, P, P, P, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                       C.c_int32, P, P, C.c_int, C.c_double, C.c_int32]
+        L.oracle_kv_write.restype = C.c_int64
+        L.oracle_kv_write.argtypes = [P, P, P, P, P, C.c_int32, C.c_int32, C.c_int32, C.c_int64,
+                                      C.c_int64, C.c_int64]
+        _lib = L
+    return _lib
+
+
+def _ptr(a: np.ndarray) -> C.c_void_p:
+    return C.c_void_p(a.ctypes.data)
+
+
+def _grid(g: Sequence[int]) -> Grid:
+    return Grid(*[int(x) for x in g])
+
+
+def threads() -> int:
+    return int(lib().oracle_threads())
+
+
+def anchor_normalize(a: np.ndarray, eps: float = 1e-6) -> np.ndarray:
+    """Q_A = Norm(LN(a)) (Eq. 8) as float64 [dim]."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    q = np.empty(a.shape[0], dtype=np.float64)
+    rc = lib().oracle_anchor_normalize(_ptr(a), a.shape[0], float(eps), _ptr(q))
+    if rc != 0:
+        raise ValueError("anchor has zero variance")
+    return q
+
+
+def score(x: np.ndarray, q: np.ndarray, inv_tau: float = 1.0) -> np.ndarray:
+    """Anchor logit of Eq. 8 for every row of x [n_rows, dim] (fp32 widening of the input);
+    q is the fp32 pre-normalised anchor the library is given.  Returns fp32 [n_rows]."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    q = np.ascontiguousarray(q, dtype=np.float32)
+    assert x.ndim == 2 and q.shape == (x.shape[1],)
+    out = np.empty(x.shape[0], dtype=np.float32)
+    lib().oracle_score(_ptr(x), x.shape[0], x.shape[1], x.shape[1], _ptr(q), float(inv_tau), _ptr(out))
+    return out
+
+
+def kept_count(grid: Sequence[int], nested: bool = False) -> int:
+    k = int(lib().oracle_kept_count(C.byref(_grid(grid)), int(nested)))
+    if k < 0:
+        raise ValueError(f"bad grid {tuple(grid)}")
+    return k
+
+
+def select(scores: np.ndarray, grid: Sequence[int], nested: bool = False) -> Tuple[np.ndarray, np.ndarray]:
+    """scores fp32 [batch, N_v] -> (kept_idx int32 [batch, K] ascending, keep_flags u8 [batch, N_v])."""
+    s = np.ascontiguousarray(scores, dtype=np.float32)
+    assert s.ndim == 2
+    g = _grid(grid)
+    k = kept_count(grid, nested)
+    idx = np.full((s.shape[0], k), -1, dtype=np.int32)
+    flags = np.zeros(s.shape, dtype=np.uint8)
+    rc = int(lib().oracle_select_batch(_ptr(s), s.shape[0], C.byref(g), int(nested), _ptr(idx), k, _ptr(flags)))
+    if rc == -2:
+        raise ValueError("NaN score")
+    if rc != k and s.shape[0] > 0:
+        raise RuntimeError(f"oracle_select_batch returned {rc}, expected {k}")
+    return idx, flags
+
+
+def compact(hidden: np.ndarray, pos_ids: np.ndarray, grid: Sequence[int], frame_start: np.ndarray,
+            kept_idx: np.ndarray) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """hidden [batch, S, dim] (any dtype; rows copied as bytes), pos_ids int32 [3, batch, S],
+    kept_idx int32 [batch, K] -> (hidden_c [batch, S_c, dim], pos_c [3, batch, S_c], src_idx [batch, S_c])."""
+    h = np.ascontiguousarray(hidden)
+    p = np.ascontiguousarray(pos_ids, dtype=np.int32)
+    fs = np.ascontiguousarray(frame_start, dtype=np.int64)
+    ki = np.ascontiguousarray(kept_idx, dtype=np.int32)
+    batch, seq, dim = h.shape
+    g = _grid(grid)
+    nv = g.frames * g.height * g.width
+    cap = seq - nv + ki.shape[1]
+    hc = np.zeros((batch, cap, dim), dtype=h.dtype)
+    pc = np.zeros((3, batch, cap), dtype=np.int32)
+    si = np.zeros((batch, cap), dtype=np.int32)
+    row_bytes = dim * h.dtype.itemsize
+    rc = int(lib().oracle_compact(_ptr(h), row_bytes, _ptr(p), batch, seq, C.byref(g), _ptr(fs), _ptr(ki),
+                                  ki.shape[1], cap, _ptr(hc), _ptr(pc), _ptr(si)))
+    if rc != cap:
+        raise RuntimeError(f"oracle_compact produced length {rc}, expected {cap}")
+    return hc, pc, si
+
+
+def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, causal: bool, scale: Optional[float] = None,
+              row_step: int = 1) -> np.ndarray:
+    """q [batch, seq, H_q, d], k/v [batch, seq, H_kv, d] as fp32 views (strides honoured on the
+    first three axes) -> float64 [batch, seq, H_q, d].  With row_step > 1 only rows
+    i % row_step == 0 are filled (the rest stay NaN)."""
+    for a in (q, k, v):
+        assert a.dtype == np.float32 and a.ndim == 4 and a.strides[3] == 4
+    batch, seq, hq, d = q.shape
+    hkv = k.shape[2]
+    assert v.shape == k.shape and k.shape[0] == batch and k.shape[1] == seq and hq % hkv == 0
+    assert k.strides == v.strides
+    qs = np.asarray([s // 4 for s in q.strides[:3]], dtype=np.int64)
+    ks = np.asarray([s // 4 for s in k.strides[:3]], dtype=np.int64)
+    out = np.full((batch, seq, hq, d), np.nan, dtype=np.float64)
+    sc = (1.0 / np.sqrt(d)) if scale is None else float(scale)
+    lib().oracle_attention(_ptr(q), _ptr(k), _ptr(v), _ptr(out), batch, seq, hq, hkv, d, _ptr(qs), _ptr(ks),
+                           int(bool(causal)), sc, int(row_step))
+    return out
+
+
+def kv_write(k: np.ndarray, v: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray, pos0: int = 0) -> int:
+    """k/v [batch, seq, H_kv, d] (any dtype, strided on the first three axes) are copied into
+    k_cache/v_cache [batch, H_kv, s_max, d] (C-contiguous, modified in place) at rows
+    [pos0, pos0 + seq).  Returns the bytes written."""
+    batch, seq, hkv, d = k.shape
+    assert v.shape == k.shape and k.strides == v.strides and k.strides[3] == k.dtype.itemsize
+    assert k_cache.flags.c_contiguous and v_cache.flags.c_contiguous
+    assert k_cache.shape == v_cache.shape and k_cache.shape[0] == batch and k_cache.shape[1] == hkv
+    assert k_cache.shape[3] == d and k_cache.dtype == k.dtype
+    s_max = k_cache.shape[2]
+    assert 0 <= pos0 and pos0 + seq <= s_max
+    st = np.asarray(k.strides[:3], dtype=np.int64)
+    return int(lib().oracle_kv_write(_ptr(k), _ptr(v), _ptr(st), _ptr(k_cache), _ptr(v_cache), batch, seq, hkv,
+                                     d * k.dtype.itemsize, s_max, int(pos0)))
