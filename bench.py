@@ -1,0 +1,246 @@
+#!/usr/bin/env python3
+"""Benchmark of the compact-prefill path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 8b] [--sets R] [--no-cpu]
+
+A step is one pass of the whole path over one batch of synthetic input already resident in HBM:
+civic_score -> civic_select -> civic_compact -> civic_prefill_attn -> civic_kv_write, back to back
+on one stream, for one transformer layer.  The timed region runs exactly K steps between device
+synchronisations; `value` is compact-prefill tokens/s = batch * S_c * K / time.  Buffers rotate over
+R independent sets so that consecutive steps do not find their inputs in the last-level cache.
+
+A second pass of the same K steps brackets every stage with HIP events (recorded on the stream the
+kernels run on) and yields the per-stage averages; `roofline` describes the dominant kernel (the
+attention) against the MI355X bf16 MFMA peak.  `cpu_baseline` times the CPU oracle, as it stands, on
+a bounded sample of the same workload on this machine's host cores.
+Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+import torch
+
+from paper_2605_28115_amd import workloads as wl
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+STAGES = ("score", "select", "compact", "attn", "kv_write")
+
+
+def dev(storage: np.ndarray) -> torch.Tensor:
+    if storage.dtype == np.uint16:
+        return torch.from_numpy(storage.view(np.int16)).view(torch.bfloat16).cuda()
+    return torch.from_numpy(storage).cuda()
+
+
+class BufferSet:
+    """Device inputs and outputs of one step (one independent copy per rotation slot)."""
+
+    def __init__(self, bd, w: wl.Workload, trial: int):
+        hw = w.height * w.width
+        fs = wl.frame_starts(w)
+        hid, _ = wl.hidden(w, trial)
+        self.hidden = dev(hid)
+        # the scored rows are the visual rows of the dense sequence, gathered once (input preparation)
+        self.visual = torch.cat([self.hidden[:, s:s + hw] for s in fs], dim=1).contiguous()
+        self.pos = torch.from_numpy(wl.position_ids(w)).cuda()
+        (q, _), (k, _), (v, _) = wl.qkv(w, trial)
+        self.q, self.k, self.v = dev(q), dev(k), dev(v)
+        self.anchor_q = torch.from_numpy(bd.civic_anchor_normalize(wl.anchor(w, trial))).cuda()
+        b, sc = w.batch, w.seq_compact
+        dt = self.hidden.dtype
+        # civic_select is measured on the workload's own score distribution; civic_score writes its
+        # logits into a separate buffer of the same shape
+        self.scores_in = torch.from_numpy(wl.scores(w, trial)).cuda()
+        self.scores = torch.empty((b, w.n_visual), dtype=torch.float32, device="cuda")
+        self.kept = torch.empty((b, w.kept), dtype=torch.int32, device="cuda")
+        self.hidden_c = torch.empty((b, sc, w.dim), dtype=dt, device="cuda")
+        self.pos_c = torch.empty((3, b, sc), dtype=torch.int32, device="cuda")
+        self.src_idx = torch.empty((b, sc), dtype=torch.int32, device="cuda")
+        self.out = torch.empty((b, sc, w.n_q_heads, w.head_dim), dtype=dt, device="cuda")
+        self.k_cache = torch.empty((b, w.n_kv_heads, sc, w.head_dim), dtype=dt, device="cuda")
+        self.v_cache = torch.empty_like(self.k_cache)
+
+
+def make_stage_calls(bd, w: wl.Workload, fs):
+    grid = bd.make_grid(w.grid_tuple())
+
+    def score(s):
+        bd.civic_score(s.visual, s.anchor_q, 1.0, scores=s.scores)
+
+    def select(s):
+        bd.civic_select(s.scores_in, grid, kept_idx=s.kept)
+
+    def compact(s):
+        bd.civic_compact(s.hidden, s.pos, grid, fs, s.kept, hidden_c=s.hidden_c, pos_c=s.pos_c, src_idx=s.src_idx)
+
+    def attn(s):
+        bd.civic_prefill_attn(s.q, s.k, s.v, w.causal, 0.0, out=s.out)
+
+    def kv_write(s):
+        bd.civic_kv_write(s.k, s.v, s.k_cache, s.v_cache, 0)
+
+    return dict(score=score, select=select, compact=compact, attn=attn, kv_write=kv_write)
+
+
+def algorithmic_work(w: wl.Workload) -> dict:
+    """Bytes (or flops) the method itself must move per step, per stage."""
+    e = 2 if w.dtype == "bf16" else 4
+    b, sc, k = w.batch, w.seq_compact, w.kept
+    attn_flops = 4 * w.n_q_heads * w.head_dim * (sc * (sc + 1) // 2 if w.causal else sc * sc) * b
+    return dict(
+        score=b * w.n_visual * (w.dim * e + 4),
+        select=b * (4 * w.n_visual + 4 * k),
+        compact=b * sc * (2 * w.dim * e + 24 + 4),
+        kv_write=b * sc * 4 * w.n_kv_heads * w.head_dim * e,
+        attn_flops=attn_flops,
+        attn_bytes=b * sc * (2 * w.n_q_heads + 2 * w.n_kv_heads) * w.head_dim * e,
+    )
+
+
+def cpu_baseline(w: wl.Workload, target_seconds: float = 20.0) -> dict:
+    """Times the oracle on a bounded sample of the workload: every stage in full except the
+    attention, which computes every `row_step`-th query row and is scaled by row_step."""
+    import oracle
+    oracle.build()
+    fs, grid = wl.frame_starts(w), w.grid_tuple()
+    hw = w.height * w.width
+    hid, hid32 = wl.hidden(w, 0)
+    vis32 = np.ascontiguousarray(np.concatenate([hid32[:, s:s + hw] for s in fs], axis=1).reshape(-1, w.dim))
+    q_anchor = oracle.anchor_normalize(wl.anchor(w, 0)).astype(np.float32)
+    sc_in = wl.scores(w, 0)
+    pos = wl.position_ids(w)
+    (q, q32), (k, k32), (v, v32) = wl.qkv(w, 0)
+    t = {}
+    t0 = time.perf_counter(); oracle.score(vis32, q_anchor, 1.0); t["score"] = time.perf_counter() - t0
+    t0 = time.perf_counter(); kept, _ = oracle.select(sc_in, grid); t["select"] = time.perf_counter() - t0
+    t0 = time.perf_counter(); oracle.compact(hid, pos, grid, fs, kept); t["compact"] = time.perf_counter() - t0
+    # choose the attention sample from a short probe so the whole leg stays near target_seconds
+    t0 = time.perf_counter(); oracle.attention(q32, k32, v32, w.causal, row_step=256); probe = time.perf_counter() - t0
+    full_est = probe * 256
+    row_step = max(1, int(np.ceil(full_est / target_seconds)))
+    t0 = time.perf_counter(); oracle.attention(q32, k32, v32, w.causal, row_step=row_step)
+    t["attn"] = (time.perf_counter() - t0) * row_step
+    kc = np.zeros((w.batch, w.n_kv_heads, w.seq_compact, w.head_dim), dtype=k.dtype)
+    vc = np.zeros_like(kc)
+    t0 = time.perf_counter(); oracle.kv_write(k, v, kc, vc, 0); t["kv_write"] = time.perf_counter() - t0
+    total = sum(t.values())
+    return {"value": w.batch * w.seq_compact / total, "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": (f"workload {w.name}: score, select, compact and kv_write in full; attention on every "
+                       f"{row_step}-th query row, its time scaled by {row_step}"),
+            "stage_ms": {s: round(1e3 * x, 3) for s, x in t.items()}}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="8b", choices=list(wl.WORKLOADS))
+    ap.add_argument("--sets", type=int, default=4, help="independent buffer sets rotated through (1 = warm cache)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py measures the one-GPU path only: run it with --gpus 1 (no multi-GPU figure exists for "
+              "this build; the design note on sharding is in DESIGN.md)", file=sys.stderr)
+        return 2
+    if not torch.cuda.is_available():
+        print("bench.py needs the MI355X: no GPU visible", file=sys.stderr)
+        return 2
+
+    from paper_2605_28115_amd import binding as bd     # raises if libcivic.so is not built
+    torch.cuda.set_device(0)
+    w = wl.WORKLOADS[args.workload]
+    assert bd.civic_kept_count(w.grid_tuple()) == w.kept
+    fs = wl.frame_starts(w)
+    sets = [BufferSet(bd, w, trial) for trial in range(max(1, args.sets))]
+    calls = make_stage_calls(bd, w, fs)
+    order = [calls[s] for s in STAGES]
+
+    def step(i):
+        s = sets[i % len(sets)]
+        for c in order:
+            c(s)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    tokens = w.batch * w.seq_compact
+
+    # second pass: the same steps with an event between stages (torch's current stream is the launch stream)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(STAGES) + 1)] for _ in range(args.steps)]
+    for i in range(args.steps):
+        s = sets[i % len(sets)]
+        ev[i][0].record()
+        for j, c in enumerate(order):
+            c(s)
+            ev[i][j + 1].record()
+    torch.cuda.synchronize()
+    stage_us = {}
+    for j, name in enumerate(STAGES):
+        d = np.asarray([ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(args.steps)]) * 1e3
+        stage_us[name] = {"mean": float(d.mean()), "median": float(np.median(d)), "min": float(d.min())}
+
+    work = algorithmic_work(w)
+    stages = {}
+    for name in STAGES:
+        us = stage_us[name]["mean"]
+        entry = {"us": round(us, 2), "us_median": round(stage_us[name]["median"], 2)}
+        if name == "attn":
+            tf = work["attn_flops"] / (us * 1e-6) / 1e12
+            entry.update(tflops=round(tf, 1), frac_mfma_peak=round(tf / MFMA_BF16_PEAK_TFLOPS, 4))
+        else:
+            gbs = work[name] / (us * 1e-6) / 1e9
+            entry.update(gbs=round(gbs, 1), frac_hbm_peak=round(gbs / HBM_PEAK_GBS, 4))
+        stages[name] = entry
+    sg = (work["select"] + work["compact"]) / ((stage_us["select"]["mean"] + stage_us["compact"]["mean"]) * 1e-6) / 1e9
+    stages["select+compact"] = {"gbs": round(sg, 1), "frac_hbm_peak": round(sg / HBM_PEAK_GBS, 4)}
+
+    attn_us = stage_us["attn"]["mean"]
+    attn_tf = work["attn_flops"] / (attn_us * 1e-6) / 1e12
+    if w.dtype == "bf16":
+        roofline = {"bound": "mfma", "kernel": "attn_mfma_kernel (civic_prefill_attn)", "achieved": round(attn_tf, 2),
+                    "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(attn_tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                    "traffic": None, "launch_us": round(attn_us, 2), "flops_per_launch": work["attn_flops"]}
+    else:
+        roofline = {"bound": "alu", "kernel": "attn_plain_kernel (civic_prefill_attn)", "achieved": round(attn_tf, 3),
+                    "peak": 157.3, "unit": "TFLOP/s", "frac": round(attn_tf / 157.3, 5), "traffic": None,
+                    "launch_us": round(attn_us, 2), "flops_per_launch": work["attn_flops"]}
+
+    result = {
+        "metric": "compact-prefill tokens/s", "value": round(tokens / (ms_per_step * 1e-3), 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"Qwen3-VL-{w.name}-shaped" if w.name in ("2b", "8b") else w.name,
+                   "batch": w.batch, "seq_dense": w.seq_len, "seq_compact": w.seq_compact, "visual_tokens": w.n_visual,
+                   "kept_visual": w.kept, "hidden": w.dim, "heads": f"{w.n_q_heads}q/{w.n_kv_heads}kv x {w.head_dim}",
+                   "causal": w.causal, "layers_timed": 1, "buffer_sets": len(sets)},
+        "dense_equivalent_tokens_per_s": round(w.batch * w.seq_len / (ms_per_step * 1e-3), 1),
+        "stages": stages,
+        "roofline": roofline,
+    }
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,178 @@
+/*
+ * civic.h — C ABI of the compact-prefill hot path of CIVIC (path-consistent compact
+ * inference for vision-language models) for AMD MI355X (gfx950).
+ *
+ * The path, in call order:
+ *   civic_score        per visual token, the anchor logit of Eq. 8
+ *   civic_select       kept set under a global token budget and spatial retention floors
+ *   civic_compact      Merge of Eq. 13: one contiguous, order-preserving sequence with the
+ *                      position ids carried along (sentence after Eq. 14)
+ *   civic_prefill_attn dense grouped-query prefill attention over the compact sequence
+ *                      (the beta * N_l * (L+M_p)^2 * D_l term of Eq. 7)
+ *   civic_kv_write     contiguous, un-paged KV-cache rows (the gamma * N_l * (L+M_p) * D_l
+ *                      term of Eq. 7, ratio of Eq. 14)
+ *
+ * Conventions shared by every call
+ *   - Plain C.  Every function that launches work returns int: CIVIC_OK or a negative
+ *     CIVIC_ERR_* code.  Nothing throws, aborts or prints.
+ *   - Unless a parameter says "host", tensor pointers are DEVICE pointers owned by the
+ *     caller.  The library allocates nothing, frees nothing and keeps no pointer after the
+ *     call returns.  civic_grid and frame_start are HOST memory, read during the call only.
+ *   - Calls are asynchronous on the hipStream_t passed as `void* stream` (NULL = the
+ *     default stream).  They never synchronise and never read device memory back: every
+ *     output shape is a function of the arguments alone (civic_kept_count).
+ *   - All argument checks happen before the first HIP call, so a rejected call has no
+ *     side effect.  On CIVIC_ERR_HIP the outputs are unspecified; no out-of-bounds access
+ *     is made in any case.
+ *   - dtype: CIVIC_F32 (4-byte IEEE) or CIVIC_BF16 (2-byte bfloat16).
+ *   - Re-entrant; no global mutable state except the last HIP error code.
+ */
+#ifndef CIVIC_H
+#define CIVIC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    CIVIC_OK = 0,
+    CIVIC_ERR_INVALID_ARG = -1, /* null pointer, bad shape, misalignment, inconsistent sizes  */
+    CIVIC_ERR_WORKSPACE   = -2, /* workspace missing or smaller than the *_workspace_bytes()  */
+    CIVIC_ERR_UNSUPPORTED = -3, /* valid but outside what the kernels cover (limits below)    */
+    CIVIC_ERR_HIP         = -4  /* a HIP call failed; see civic_last_hip_error()              */
+};
+
+enum { CIVIC_F32 = 0, CIVIC_BF16 = 1 };
+
+/* Limits of this implementation (exceeding them gives CIVIC_ERR_UNSUPPORTED). */
+#define CIVIC_MAX_VISUAL_TOKENS 32768 /* N_v per sample: civic_select keeps the keys in LDS  */
+#define CIVIC_MAX_FRAMES        128   /* frames per sample in civic_compact                  */
+#define CIVIC_MAX_SCORE_DIM     8192  /* hidden size in civic_score (bf16; 4096 for fp32)    */
+#define CIVIC_MAX_HEAD_DIM      256   /* head_dim in civic_prefill_attn                      */
+
+/* One sample's visual layout; every batch item shares it.  Visual-local token index
+ * v = f*height*width + r*width + c (frame-major raster).  The cell of v is
+ * (f, r / cell_h, c / cell_w); cells at the right/bottom edge may be smaller.  The paper
+ * names the budget ("token budget", the maximum number of visual tokens propagated
+ * downstream) and the floor ("minimum keep ratio", "adaptive spatial retention floor") in
+ * its Ablation Study without a formula; the reading implemented is documented at
+ * civic_select. */
+typedef struct {
+    int32_t frames;      /* images or video frames, each one contiguous raster span, > 0     */
+    int32_t height;      /* merged-grid rows per frame, > 0                                   */
+    int32_t width;       /* merged-grid columns per frame, > 0                                */
+    int32_t cell_h;      /* spatial cell height, > 0                                          */
+    int32_t cell_w;      /* spatial cell width, > 0                                           */
+    int32_t cell_floor;  /* tokens kept per cell at least (clipped to the cell's size), >= 0  */
+    int32_t frame_floor; /* further tokens kept per frame on top of its cells' floors, >= 0   */
+    int32_t budget;      /* global keep budget over the sample's N_v tokens, 0..N_v           */
+} civic_grid;
+
+/* Last hipError_t (as int) recorded by a call that returned CIVIC_ERR_HIP on this thread's
+ * process; 0 if none. */
+int civic_last_hip_error(void);
+
+/* Number of visual tokens civic_select keeps per sample: K = max(budget, sum of floors),
+ * where a cell contributes min(cell_floor, its size) and a frame min(frame_floor, what its
+ * cell floors leave).  A pure host function of the grid; negative CIVIC_ERR_* on a bad grid.
+ * The compact sequence length of Eq. 13 is L + M_p = seq_len - N_v + K. */
+int64_t civic_kept_count(const civic_grid* grid /* host */);
+
+/* Scratch sizes (host functions; 0 is a valid answer and then workspace may be NULL). */
+size_t civic_select_workspace_bytes(const civic_grid* grid /* host */, int32_t batch);
+size_t civic_compact_workspace_bytes(int32_t batch, int64_t seq_len);
+
+/* Q_A = Norm(LN(a)) of Eq. 8 for one anchor row: layer norm without affine (its epsilon
+ * cancels under the l2 normalisation that follows), then unit l2 norm.  HOST pointers;
+ * computed in double, rounded to fp32.  The result has zero mean and unit norm, which is
+ * what civic_score expects.  CIVIC_ERR_INVALID_ARG if a has no variance. */
+int civic_anchor_normalize(const float* anchor /* host [dim] */, int32_t dim,
+                           float* anchor_q /* host [dim] */);
+
+/* Token scoring.  scores[i] = inv_tau * < anchor_q, Norm(LN(x_i)) > for each of n_rows
+ * hidden rows x_i: the pre-softmax logit of Eq. 8 with a single anchor (with one anchor the
+ * softmax over tokens is monotone in it).  Norm(LN(x)) = (x - mean) / ||x - mean||; a row
+ * without variance scores 0.  fp32 accumulation, two passes over the row held in registers.
+ *   hidden     [n_rows, row_stride] elements of `dtype`, row_stride >= dim, in elements
+ *   anchor_q   device [dim] fp32, zero mean, unit norm (civic_anchor_normalize)
+ *   scores     device [n_rows] fp32
+ * dim must be a multiple of 8 (bf16) or 4 (fp32) and at most CIVIC_MAX_SCORE_DIM (half of
+ * it for fp32); hidden and row_stride*sizeof(element) must be 16-byte aligned. */
+int civic_score(const void* hidden, int dtype, int64_t n_rows, int64_t row_stride, int32_t dim,
+                const float* anchor_q, float inv_tau, float* scores, void* stream);
+
+/* Token selection.  With the strict order "higher score first, equal scores (IEEE ==, so
+ * -0 equals +0) to the lower index", per sample:
+ *   (1) every cell keeps its first min(cell_floor, size) tokens;
+ *   (2) every frame keeps the first min(frame_floor, remaining) of its tokens not kept yet;
+ *   (3) the first max(0, budget - kept so far) tokens of the sample not kept yet are kept.
+ * Exactly K = civic_kept_count(grid) tokens result for any scores.  NaN scores are a caller
+ * error (the result is then unspecified, but in bounds).
+ *   scores     device [batch, N_v] fp32
+ *   kept_idx   device [batch, K] int32, visual-local indices in ascending order
+ *   keep_flags device [batch, N_v] uint8 (1 = kept) or NULL
+ * N_v <= CIVIC_MAX_VISUAL_TOKENS. */
+int civic_select(const float* scores, int32_t batch, const civic_grid* grid /* host */,
+                 int32_t* kept_idx, uint8_t* keep_flags,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* Compact merge (Eq. 13).  Frame f of the grid occupies sequence positions
+ * [frame_start[f], frame_start[f] + height*width); every other position is text.  The
+ * output keeps all text tokens and the visual tokens listed in kept_idx, in their original
+ * order, as one dense sequence of length S_c = seq_len - N_v + K.  Rows are copied bit for
+ * bit; position ids are copied, never renumbered (text positions preserved, visual
+ * positions inherited from the dense span).
+ *   hidden      device [batch, seq_len, dim] of `dtype`, dense
+ *   pos_ids     device [3, batch, seq_len] int32 (temporal, height, width ids)
+ *   frame_start host [grid->frames] int64, ascending, spans inside [0, seq_len), disjoint
+ *   kept_idx    device [batch, n_kept] int32 ascending (civic_select's output);
+ *               n_kept in [0, N_v]
+ *   hidden_c    device [batch, S_c, dim]
+ *   pos_c       device [3, batch, S_c] int32
+ *   src_idx     device [batch, S_c] int32: dense sequence index of every compact token
+ * frames <= CIVIC_MAX_FRAMES and seq_len < 2^31.  hidden and hidden_c must be aligned to
+ * min(16, largest power of two dividing the row size in bytes). */
+int civic_compact(const void* hidden, int dtype, int32_t dim, const int32_t* pos_ids,
+                  int32_t batch, int64_t seq_len, const civic_grid* grid /* host */,
+                  const int64_t* frame_start /* host */, const int32_t* kept_idx, int64_t n_kept,
+                  void* hidden_c, int32_t* pos_c, int32_t* src_idx,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* Prefill attention over the compact sequence: out[b,i,h,:] = sum_j softmax_j(scale *
+ * <q[b,i,h,:], k[b,j,g,:]>) v[b,j,g,:] with g = h / (n_q_heads / n_kv_heads); j <= i when
+ * causal (order of the compact sequence, not the position ids), every j otherwise.
+ * bf16: MFMA with fp32 accumulation, fp32 online softmax, bf16 round-to-nearest-even
+ * output.  fp32: plain fp32 arithmetic.
+ *   q, out     device [batch, seq, n_q_heads, head_dim]; strides in ELEMENTS for
+ *              (batch, token, head) in q_strides / o_strides (host int64[3]); head_dim is
+ *              contiguous
+ *   k, v       device [batch, seq, n_kv_heads, head_dim]; both use kv_strides
+ *   softmax_scale  0 means 1/sqrt(head_dim)
+ * Pointers and strides*sizeof(element) must be 16-byte aligned; head_dim a multiple of 8
+ * and at most CIVIC_MAX_HEAD_DIM; n_q_heads a multiple of n_kv_heads. */
+int civic_prefill_attn(const void* q, const void* k, const void* v, void* out, int dtype,
+                       int32_t batch, int32_t seq, int32_t n_q_heads, int32_t n_kv_heads,
+                       int32_t head_dim, const int64_t* q_strides /* host [3] */,
+                       const int64_t* kv_strides /* host [3] */,
+                       const int64_t* o_strides /* host [3] */,
+                       int32_t causal, float softmax_scale, void* stream);
+
+/* KV-cache write: k_cache[b, g, pos0 + i, :] = k[b, i, g, :] and the same for v, bit for
+ * bit; no other byte of the caches is touched.
+ *   k, v       device [batch, seq, n_kv_heads, head_dim], strides in elements in kv_strides
+ *   k_cache, v_cache  device [batch, n_kv_heads, s_max, head_dim] dense
+ *   pos0       first cache row written; pos0 >= 0 and pos0 + seq <= s_max
+ * Pointers and strides*sizeof(element) must be 16-byte aligned and head_dim*sizeof(element)
+ * a multiple of 16. */
+int civic_kv_write(const void* k, const void* v, const int64_t* kv_strides /* host [3] */,
+                   int dtype, void* k_cache, void* v_cache, int32_t batch, int32_t seq,
+                   int32_t n_kv_heads, int32_t head_dim, int64_t s_max, int64_t pos0,
+                   void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CIVIC_H */

@@ -1,0 +1,222 @@
+"""Thin ctypes binding of libcivic.so (include/civic.h): argument marshalling only.
+
+Every step of the path runs in the HIP kernels behind the C ABI; PyTorch is used for device
+memory and the current stream, nothing else.  There is no CPU fallback: if the library is not
+built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcivic.so")
+
+CIVIC_OK, ERR_INVALID_ARG, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_HIP = 0, -1, -2, -3, -4
+CIVIC_F32, CIVIC_BF16 = 0, 1
+MAX_VISUAL_TOKENS, MAX_FRAMES, MAX_SCORE_DIM, MAX_HEAD_DIM = 32768, 128, 8192, 256
+
+EXPORTS = ("civic_last_hip_error", "civic_kept_count", "civic_select_workspace_bytes",
+           "civic_compact_workspace_bytes", "civic_anchor_normalize", "civic_score", "civic_select",
+           "civic_compact", "civic_prefill_attn", "civic_kv_write")
+
+
+class CivicError(RuntimeError):
+    def __init__(self, call: str, code: int, hip: int = 0):
+        names = {ERR_INVALID_ARG: "CIVIC_ERR_INVALID_ARG", ERR_WORKSPACE: "CIVIC_ERR_WORKSPACE",
+                 ERR_UNSUPPORTED: "CIVIC_ERR_UNSUPPORTED", ERR_HIP: "CIVIC_ERR_HIP"}
+        super().__init__(f"{call} failed: {names.get(code, code)}" + (f" (hipError {hip})" if code == ERR_HIP else ""))
+        self.code = code
+
+
+class Grid(C.Structure):
+    """Mirror of civic_grid."""
+    _fields_ = [(n, C.c_int32) for n in ("frames", "height", "width", "cell_h", "cell_w",
+                                         "cell_floor", "frame_floor", "budget")]
+
+    @property
+    def n_visual(self) -> int:
+        return self.frames * self.height * self.width
+
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2605_28115_amd.build` (no CPU fallback exists)")
+
+lib = C.CDLL(LIB_PATH)
+_P = C.c_void_p
+lib.civic_last_hip_error.restype = C.c_int
+lib.civic_kept_count.restype = C.c_int64
+lib.civic_kept_count.argtypes = [C.POINTER(Grid)]
+lib.civic_select_workspace_bytes.restype = C.c_size_t
+lib.civic_select_workspace_bytes.argtypes = [C.POINTER(Grid), C.c_int32]
+lib.civic_compact_workspace_bytes.restype = C.c_size_t
+lib.civic_compact_workspace_bytes.argtypes = [C.c_int32, C.c_int64]
+lib.civic_anchor_normalize.restype = C.c_int
+lib.civic_anchor_normalize.argtypes = [_P, C.c_int32, _P]
+lib.civic_score.restype = C.c_int
+lib.civic_score.argtypes = [_P, C.c_int, C.c_int64, C.c_int64, C.c_int32, _P, C.c_float, _P, _P]
+lib.civic_select.restype = C.c_int
+lib.civic_select.argtypes = [_P, C.c_int32, C.POINTER(Grid), _P, _P, _P, C.c_size_t, _P]
+lib.civic_compact.restype = C.c_int
+lib.civic_compact.argtypes = [_P, C.c_int, C.c_int32, _P, C.c_int32, C.c_int64, C.POINTER(Grid), _P, _P, C.c_int64,
+                              _P, _P, _P, _P, C.c_size_t, _P]
+lib.civic_prefill_attn.restype = C.c_int
+lib.civic_prefill_attn.argtypes = [_P, _P, _P, _P, C.c_int, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                   _P, _P, _P, C.c_int32, C.c_float, _P]
+lib.civic_kv_write.restype = C.c_int
+lib.civic_kv_write.argtypes = [_P, _P, _P, C.c_int, _P, _P, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int64,
+                               C.c_int64, _P]
+
+
+def _check(call: str, rc: int) -> None:
+    if rc != CIVIC_OK:
+        raise CivicError(call, rc, lib.civic_last_hip_error() if rc == ERR_HIP else 0)
+
+
+def make_grid(grid) -> Grid:
+    return grid if isinstance(grid, Grid) else Grid(*[int(x) for x in grid])
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return CIVIC_F32
+    if t.dtype == torch.bfloat16:
+        return CIVIC_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _stream(stream) -> C.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _dev(t: Optional[torch.Tensor]) -> C.c_void_p:
+    if t is None:
+        return C.c_void_p(0)
+    if not t.is_cuda:
+        raise ValueError("device tensor expected")
+    return C.c_void_p(t.data_ptr())
+
+
+def _strides3(t: torch.Tensor):
+    if t.dim() != 4 or t.stride(3) != 1:
+        raise ValueError("expected [batch, seq, heads, head_dim] with contiguous head_dim")
+    return (C.c_int64 * 3)(t.stride(0), t.stride(1), t.stride(2))
+
+
+# ------------------------------------------------------------------------------ host functions
+def civic_kept_count(grid) -> int:
+    k = int(lib.civic_kept_count(C.byref(make_grid(grid))))
+    if k < 0:
+        raise CivicError("civic_kept_count", k)
+    return k
+
+
+def civic_select_workspace_bytes(grid, batch: int) -> int:
+    return int(lib.civic_select_workspace_bytes(C.byref(make_grid(grid)), batch))
+
+
+def civic_compact_workspace_bytes(batch: int, seq_len: int) -> int:
+    return int(lib.civic_compact_workspace_bytes(batch, seq_len))
+
+
+def civic_anchor_normalize(anchor: np.ndarray) -> np.ndarray:
+    a = np.ascontiguousarray(anchor, dtype=np.float32)
+    q = np.empty_like(a)
+    _check("civic_anchor_normalize", lib.civic_anchor_normalize(C.c_void_p(a.ctypes.data), a.shape[0], C.c_void_p(q.ctypes.data)))
+    return q
+
+
+# ---------------------------------------------------------------------------- device functions
+def civic_score(hidden: torch.Tensor, anchor_q: torch.Tensor, inv_tau: float = 1.0,
+                scores: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """hidden [..., dim] with contiguous last axis and one uniform row stride -> fp32 scores [...]."""
+    dim = hidden.shape[-1]
+    rows = hidden.reshape(-1, dim) if hidden.is_contiguous() else hidden
+    if rows.dim() != 2 or rows.stride(1) != 1:
+        raise ValueError("hidden must be viewable as [n_rows, dim] rows")
+    if scores is None:
+        scores = torch.empty(hidden.shape[:-1], dtype=torch.float32, device=hidden.device)
+    _check("civic_score", lib.civic_score(_dev(rows), _dtype_code(rows), rows.shape[0], rows.stride(0), dim,
+                                          _dev(anchor_q), float(inv_tau), _dev(scores), _stream(stream)))
+    return scores
+
+
+def civic_select(scores: torch.Tensor, grid, kept_idx: Optional[torch.Tensor] = None,
+                 keep_flags: Optional[torch.Tensor] = None, want_flags: bool = False,
+                 workspace: Optional[torch.Tensor] = None, stream=None) -> Tuple[torch.Tensor, Optional[torch.Tensor]]:
+    g = make_grid(grid)
+    if scores.dim() != 2 or scores.shape[1] != g.n_visual or not scores.is_contiguous() or scores.dtype != torch.float32:
+        raise ValueError("scores must be contiguous fp32 [batch, N_v]")
+    batch = scores.shape[0]
+    k = civic_kept_count(g)
+    if kept_idx is None:
+        kept_idx = torch.empty((batch, k), dtype=torch.int32, device=scores.device)
+    if keep_flags is None and want_flags:
+        keep_flags = torch.empty((batch, g.n_visual), dtype=torch.uint8, device=scores.device)
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check("civic_select", lib.civic_select(_dev(scores), batch, C.byref(g), _dev(kept_idx), _dev(keep_flags),
+                                            _dev(workspace), ws_bytes, _stream(stream)))
+    return kept_idx, keep_flags
+
+
+def civic_compact(hidden: torch.Tensor, pos_ids: torch.Tensor, grid, frame_start: Sequence[int],
+                  kept_idx: torch.Tensor, hidden_c: Optional[torch.Tensor] = None,
+                  pos_c: Optional[torch.Tensor] = None, src_idx: Optional[torch.Tensor] = None,
+                  workspace: Optional[torch.Tensor] = None, stream=None):
+    g = make_grid(grid)
+    if hidden.dim() != 3 or not hidden.is_contiguous() or not pos_ids.is_contiguous() or not kept_idx.is_contiguous():
+        raise ValueError("hidden [batch, S, dim], pos_ids [3, batch, S] and kept_idx [batch, K] must be contiguous")
+    batch, seq_len, dim = hidden.shape
+    if tuple(pos_ids.shape) != (3, batch, seq_len) or pos_ids.dtype != torch.int32 or kept_idx.dtype != torch.int32:
+        raise ValueError("pos_ids must be int32 [3, batch, S] and kept_idx int32")
+    n_kept = kept_idx.shape[1]
+    seq_c = seq_len - g.n_visual + n_kept
+    fs = np.ascontiguousarray(np.asarray(frame_start, dtype=np.int64))
+    if fs.shape != (g.frames,):
+        raise ValueError("frame_start must have one entry per frame")
+    if hidden_c is None:
+        hidden_c = torch.empty((batch, seq_c, dim), dtype=hidden.dtype, device=hidden.device)
+    if pos_c is None:
+        pos_c = torch.empty((3, batch, seq_c), dtype=torch.int32, device=hidden.device)
+    if src_idx is None:
+        src_idx = torch.empty((batch, seq_c), dtype=torch.int32, device=hidden.device)
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check("civic_compact", lib.civic_compact(_dev(hidden), _dtype_code(hidden), dim, _dev(pos_ids), batch, seq_len,
+                                              C.byref(g), C.c_void_p(fs.ctypes.data), _dev(kept_idx), n_kept,
+                                              _dev(hidden_c), _dev(pos_c), _dev(src_idx), _dev(workspace), ws_bytes,
+                                              _stream(stream)))
+    return hidden_c, pos_c, src_idx
+
+
+def civic_prefill_attn(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, causal: bool = True,
+                       softmax_scale: float = 0.0, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """q [batch, seq, H_q, d]; k, v [batch, seq, H_kv, d] with identical strides; strided views are fine."""
+    if k.shape != v.shape or k.stride() != v.stride() or q.dtype != k.dtype or q.dtype != v.dtype:
+        raise ValueError("k and v must share shape, strides and dtype with q's dtype")
+    batch, seq, hq, d = q.shape
+    if out is None:
+        out = torch.empty((batch, seq, hq, d), dtype=q.dtype, device=q.device)
+    _check("civic_prefill_attn", lib.civic_prefill_attn(_dev(q), _dev(k), _dev(v), _dev(out), _dtype_code(q), batch, seq,
+                                                        hq, k.shape[2], d, _strides3(q), _strides3(k), _strides3(out),
+                                                        int(bool(causal)), float(softmax_scale), _stream(stream)))
+    return out
+
+
+def civic_kv_write(k: torch.Tensor, v: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, pos0: int = 0,
+                   stream=None) -> None:
+    """k, v [batch, seq, H_kv, d] -> caches [batch, H_kv, s_max, d] (contiguous) at rows [pos0, pos0 + seq)."""
+    if k.shape != v.shape or k.stride() != v.stride() or k.dtype != v.dtype:
+        raise ValueError("k and v must share shape, strides and dtype")
+    batch, seq, hkv, d = k.shape
+    if (not k_cache.is_contiguous() or not v_cache.is_contiguous() or k_cache.shape != v_cache.shape
+            or k_cache.dtype != k.dtype or v_cache.dtype != k.dtype
+            or k_cache.shape[0] != batch or k_cache.shape[1] != hkv or k_cache.shape[3] != d):
+        raise ValueError("caches must be contiguous [batch, H_kv, s_max, d] of the inputs' dtype")
+    _check("civic_kv_write", lib.civic_kv_write(_dev(k), _dev(v), _strides3(k), _dtype_code(k), _dev(k_cache), _dev(v_cache),
+                                                batch, seq, hkv, d, k_cache.shape[2], int(pos0), _stream(stream)))

@@ -1,0 +1,38 @@
+"""Builds libcivic.so (HIP, gfx950) in-tree.  `python -m paper_2605_28115_amd.build`."""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libcivic.so")
+SOURCES = ["api.hip", "score.hip", "select.hip", "compact.hip", "attn.hip", "kv_write.hip"]
+
+# Packed-fp32 VALU forms are switched off for all device code (compiler flag, not a host flag).
+HIPCC_FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               "-Wall", "-Wno-unused-command-line-argument", "-Wno-unknown-attributes"]
+
+
+def build(verbose: bool = False) -> str:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+           "-o", LIB, *[os.path.join(CSRC, s) for s in SOURCES]]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    # the host pass does not know the packed-fp32 feature and says so; everything else is shown
+    noise = ("is not a recognized feature for this target", "warning generated", "warnings generated")
+    out = "\n".join(l for l in proc.stdout.splitlines() if not any(n in l for n in noise))
+    if out.strip():
+        print(out, file=sys.stderr)
+    if proc.returncode != 0:
+        raise RuntimeError("hipcc failed building libcivic.so")
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

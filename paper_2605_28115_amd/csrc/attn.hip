@@ -1,0 +1,349 @@
+// civic_prefill_attn: dense grouped-query prefill attention over the compact sequence (the
+// beta * N_l * (L+M_p)^2 * D_l term of Eq. 7; softmax(Q K^T / sqrt(d)) V as in Eq. 9).
+//
+// bf16 path (MFMA-bound): flash-style, one 256-thread workgroup = 4 wavefronts x 32 query rows.  The
+// four wavefronts are the query heads of one KV group over the same 32 rows when the group has four
+// or more heads (so one K/V tile staged in LDS serves the whole group and all four wavefronts have
+// the same causal extent); smaller groups put several row tiles of the same head in the workgroup.
+// Scores are computed TRANSPOSED, S^T = K Q^T with v_mfma_f32_32x32x16_bf16: a lane then owns one
+// query column, so the softmax row maximum and row sum are in-lane reductions plus one exchange
+// between the two half-waves, and the rescale factor is a per-lane scalar.  The exponentiated
+// tile, rounded to bf16, is already laid out as the B operand of O^T += V^T P^T; V is staged
+// transposed in LDS so its A operand is two 8-byte reads.  fp32 accumulation throughout, online
+// softmax in the exp2 domain, output rounded to bf16 (nearest even).
+//
+// fp32 path and head sizes the MFMA path does not cover: a plain fp32 kernel, one wavefront per
+// query row (lanes over keys for Q K^T, lanes over channels for P V).
+#include <cmath>
+
+#include "civic_internal.h"
+
+namespace civic {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+struct AttnArgs {
+    const void* q; const void* k; const void* v; void* out;
+    int64_t qs[3], ks[3], os[3];          // element strides: batch, token, head
+    int32_t batch, seq, n_q_heads, n_kv_heads, head_dim, causal;
+    float scale;                          // softmax scale (natural-exponent domain)
+    int32_t heads_per_block, row_tiles;   // MFMA path: block shape and number of 32*rows_per_block tiles
+};
+
+// ------------------------------------------------------------------------------------ fp32 ALU path
+template <bool BF16>
+__device__ __forceinline__ float load_elem(const void* p, int64_t i)
+{
+    if constexpr (BF16) return bf16_bits_to_float(static_cast<const uint16_t*>(p)[i]);
+    else return static_cast<const float*>(p)[i];
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+    return v;
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void attn_plain_kernel(AttnArgs a)
+{
+    __shared__ float q_s[4][CIVIC_MAX_HEAD_DIM];
+    __shared__ float p_s[4][kWave];
+    const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x >> 6;
+    const int i = blockIdx.x * 4 + w, h = blockIdx.y, b = blockIdx.z;
+    if (i >= a.seq) return;                                   // no workgroup barrier below
+    const int g = h / (a.n_q_heads / a.n_kv_heads), d = a.head_dim;
+    const int64_t q_off = b * a.qs[0] + i * a.qs[1] + h * a.qs[2];
+    const int64_t kv_off = b * a.ks[0] + g * a.ks[2];
+    for (int c = lane; c < d; c += kWave) q_s[w][c] = load_elem<BF16>(a.q, q_off + c) * a.scale;
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+
+    float acc[CIVIC_MAX_HEAD_DIM / kWave];
+#pragma unroll
+    for (int t = 0; t < CIVIC_MAX_HEAD_DIM / kWave; ++t) acc[t] = 0.f;
+    float m = -INFINITY, l = 0.f;
+    const int last = a.causal ? i : a.seq - 1;
+    for (int j0 = 0; j0 <= last; j0 += kWave) {
+        const int j = j0 + lane;
+        float z = -INFINITY;
+        if (j <= last) {
+            const int64_t base = kv_off + j * a.ks[1];
+            float dot = 0.f;
+            for (int c = 0; c < d; c += 8) {
+                if constexpr (BF16) {
+                    const uint4 raw = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(a.k) + base + c);
+                    const uint32_t wds[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        dot = fmaf(q_s[w][c + 2 * e], __uint_as_float(wds[e] << 16), dot);
+                        dot = fmaf(q_s[w][c + 2 * e + 1], __uint_as_float(wds[e] & 0xFFFF0000u), dot);
+                    }
+                } else {
+                    const float4 lo = *reinterpret_cast<const float4*>(static_cast<const float*>(a.k) + base + c);
+                    const float4 hi = *reinterpret_cast<const float4*>(static_cast<const float*>(a.k) + base + c + 4);
+                    dot = fmaf(q_s[w][c], lo.x, dot); dot = fmaf(q_s[w][c + 1], lo.y, dot);
+                    dot = fmaf(q_s[w][c + 2], lo.z, dot); dot = fmaf(q_s[w][c + 3], lo.w, dot);
+                    dot = fmaf(q_s[w][c + 4], hi.x, dot); dot = fmaf(q_s[w][c + 5], hi.y, dot);
+                    dot = fmaf(q_s[w][c + 6], hi.z, dot); dot = fmaf(q_s[w][c + 7], hi.w, dot);
+                }
+            }
+            z = dot;
+        }
+        const float m_new = fmaxf(m, wave_max(z));           // finite: key j0 is always visible
+        const float p = expf(z - m_new);
+        const float alpha = expf(m - m_new);
+        l = l * alpha + wave_sum(p);
+        m = m_new;
+        p_s[w][lane] = p;
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        const int nk = min(kWave, last - j0 + 1);
+#pragma unroll
+        for (int t = 0; t < CIVIC_MAX_HEAD_DIM / kWave; ++t) {
+            const int c = lane + t * kWave;
+            if (c < d) {
+                float s = acc[t] * alpha;
+                for (int jj = 0; jj < nk; ++jj)
+                    s = fmaf(p_s[w][jj], load_elem<BF16>(a.v, kv_off + (j0 + jj) * a.ks[1] + c), s);
+                acc[t] = s;
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+    const float inv = 1.f / l;
+    const int64_t o_off = b * a.os[0] + i * a.os[1] + h * a.os[2];
+#pragma unroll
+    for (int t = 0; t < CIVIC_MAX_HEAD_DIM / kWave; ++t) {
+        const int c = lane + t * kWave;
+        if (c < d) {
+            const float o = acc[t] * inv;
+            if constexpr (BF16) static_cast<__bf16*>(a.out)[o_off + c] = static_cast<__bf16>(o);
+            else static_cast<float*>(a.out)[o_off + c] = o;
+        }
+    }
+}
+
+// --------------------------------------------------------------------------------------- MFMA path
+constexpr int kBN = 64;                 // keys per LDS tile
+constexpr int kKPad = 8;                // bf16 elements of row padding in the K tile
+constexpr int kVPad = 8;                // bf16 elements of row padding in the transposed V tile
+
+// DP: head_dim rounded up to a multiple of 32 (zero filled).
+template <int DP>
+__global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a)
+{
+    constexpr int KSTEPS = DP / 16;      // MFMA k-steps of Q K^T
+    constexpr int DT = DP / 32;          // 32-row tiles of O^T
+    constexpr int CPR = DP / 8;          // 16-byte chunks per K/V row
+    constexpr int KROW = DP + kKPad;
+    constexpr int VROW = kBN + kVPad;
+    __shared__ __attribute__((aligned(16))) __bf16 k_s[kBN * KROW];
+    __shared__ __attribute__((aligned(16))) __bf16 vt_s[DP * VROW];
+
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid >> 6;
+    const int col = lane & 31, half = lane >> 5;
+    const int HB = a.heads_per_block, RB = 4 / HB;           // heads and 32-row sub-tiles per block
+    const int group = a.n_q_heads / a.n_kv_heads;
+    const int head_blocks = group / HB;
+
+    // blockIdx.x -> (row tile, head block, kv head, batch); the heaviest causal row tiles come first
+    int bid = blockIdx.x;
+    const int rt = a.row_tiles - 1 - bid / (head_blocks * a.n_kv_heads * a.batch);
+    bid %= head_blocks * a.n_kv_heads * a.batch;
+    const int hb = bid % head_blocks; bid /= head_blocks;
+    const int g = bid % a.n_kv_heads;
+    const int b = bid / a.n_kv_heads;
+
+    const int h = g * group + hb * HB + (w % HB);
+    const int row0 = (rt * RB + w / HB) * 32;                 // this wavefront's first query row
+    const int block_row0 = rt * RB * 32;
+    const int block_rows_end = min(block_row0 + RB * 32, a.seq);
+    const int qi = row0 + col;                                // this lane's query row
+    const float sl2 = a.scale * 1.4426950408889634f;          // scale * log2(e)
+
+    // Q^T as B operand: lane (col, half) holds Q[qi][16 s + 8 half .. +7] for every k-step s
+    bf16x8 qreg[KSTEPS];
+    {
+        const __bf16* qp = static_cast<const __bf16*>(a.q) + b * a.qs[0] + static_cast<int64_t>(min(qi, a.seq - 1)) * a.qs[1] + h * a.qs[2];
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s) {
+            const int c = 16 * s + 8 * half;
+            bf16x8 t = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (c < a.head_dim) t = *reinterpret_cast<const bf16x8*>(qp + c);
+            qreg[s] = t;
+        }
+    }
+
+    f32x16 acc_o[DT];
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_o[t][r] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    const int kv_end = a.causal ? block_rows_end : a.seq;     // keys [0, kv_end) are visible to the block
+    const int n_tiles = (kv_end + kBN - 1) / kBN;
+    const __bf16* kp = static_cast<const __bf16*>(a.k) + b * a.ks[0] + g * a.ks[2];
+    const __bf16* vp = static_cast<const __bf16*>(a.v) + b * a.ks[0] + g * a.ks[2];
+
+    for (int kt = 0; kt < n_tiles; ++kt) {
+        const int key0 = kt * kBN;
+        __syncthreads();                                      // previous tile fully consumed
+        for (int id = tid; id < kBN * CPR; id += 256) {
+            const int key = id / CPR, dc = id - key * CPR;
+            bf16x8 kv8 = {0, 0, 0, 0, 0, 0, 0, 0}, vv8 = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (key0 + key < a.seq && dc * 8 < a.head_dim) {
+                const int64_t off = static_cast<int64_t>(key0 + key) * a.ks[1] + dc * 8;
+                kv8 = *reinterpret_cast<const bf16x8*>(kp + off);
+                vv8 = *reinterpret_cast<const bf16x8*>(vp + off);
+            }
+            *reinterpret_cast<bf16x8*>(&k_s[key * KROW + dc * 8]) = kv8;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) vt_s[(dc * 8 + e) * VROW + key] = vv8[e];
+        }
+        __syncthreads();
+
+        const bool wave_live = !a.causal || key0 <= row0 + 31;   // some key of the tile is visible to the wavefront
+        if (wave_live) {
+            // S^T tile: rows = keys (two 32-key sub-tiles), columns = this wavefront's 32 queries
+            f32x16 acc_s[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc_s[t][r] = 0.f;
+#pragma unroll
+                for (int s = 0; s < KSTEPS; ++s) {
+                    const bf16x8 ka = *reinterpret_cast<const bf16x8*>(&k_s[(32 * t + col) * KROW + 16 * s + 8 * half]);
+                    acc_s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[s], acc_s[t], 0, 0, 0);
+                }
+            }
+            // mask + running maximum (exp2 domain)
+            float mx = -INFINITY;
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int kj = key0 + 32 * t + 8 * (r >> 2) + 4 * half + (r & 3);
+                    const bool ok = kj < a.seq && (!a.causal || kj <= qi);
+                    const float z = ok ? acc_s[t][r] * sl2 : -INFINITY;
+                    acc_s[t][r] = z;
+                    mx = fmaxf(mx, z);
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+            const float m_new = fmaxf(m_run, mx);
+            const float m_use = m_new == -INFINITY ? 0.f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);   // m_run = -inf -> 0
+            m_run = m_new;
+            float rs = 0.f;
+            bf16x8 pb[2][2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float p = __builtin_amdgcn_exp2f(acc_s[t][8 * u + e] - m_use);
+                        rs += p;
+                        pb[t][u][e] = static_cast<__bf16>(p);
+                    }
+            l_run = l_run * alpha + rs;
+#pragma unroll
+            for (int t = 0; t < DT; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc_o[t][r] *= alpha;
+            // O^T += V^T P^T.  The k-slot (half, e) of step (t, u) is key 32t + 16u + 8(e/4) + 4 half + e%4.
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) {
+                        const __bf16* vr = &vt_s[(32 * dt + col) * VROW + 32 * t + 16 * u + 4 * half];
+                        const bf16x4 lo = *reinterpret_cast<const bf16x4*>(vr);
+                        const bf16x4 hi = *reinterpret_cast<const bf16x4*>(vr + 8);
+                        const bf16x8 va = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                        acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[t][u], acc_o[dt], 0, 0, 0);
+                    }
+        }
+    }
+
+    const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
+    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+    if (qi < a.seq) {
+        __bf16* op = static_cast<__bf16*>(a.out) + b * a.os[0] + static_cast<int64_t>(qi) * a.os[1] + h * a.os[2];
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                const int c = 32 * dt + 8 * rq + 4 * half;
+                if (c < a.head_dim) {
+                    bf16x4 o4;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o4[e] = static_cast<__bf16>(acc_o[dt][4 * rq + e] * inv);
+                    *reinterpret_cast<bf16x4*>(op + c) = o4;
+                }
+            }
+    }
+}
+
+template <int DP>
+static int launch_mfma(AttnArgs& a, hipStream_t s)
+{
+    const int group = a.n_q_heads / a.n_kv_heads;
+    a.heads_per_block = (group % 4 == 0) ? 4 : (group % 2 == 0) ? 2 : 1;
+    const int rows_per_block = 32 * (4 / a.heads_per_block);
+    a.row_tiles = (a.seq + rows_per_block - 1) / rows_per_block;
+    const int64_t blocks = static_cast<int64_t>(a.row_tiles) * (group / a.heads_per_block) * a.n_kv_heads * a.batch;
+    if (blocks > INT32_MAX) return CIVIC_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((attn_mfma_kernel<DP>), dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, a);
+    return check_launch();
+}
+
+}  // namespace civic
+
+extern "C" int civic_prefill_attn(const void* q, const void* k, const void* v, void* out, int dtype, int32_t batch,
+                                  int32_t seq, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                  const int64_t* q_strides, const int64_t* kv_strides, const int64_t* o_strides,
+                                  int32_t causal, float softmax_scale, void* stream)
+{
+    using namespace civic;
+    const int esz = dtype_size(dtype);
+    if (!esz || !q || !k || !v || !out || !q_strides || !kv_strides || !o_strides) return CIVIC_ERR_INVALID_ARG;
+    if (batch < 0 || seq < 0 || n_q_heads <= 0 || n_kv_heads <= 0 || head_dim <= 0) return CIVIC_ERR_INVALID_ARG;
+    if (n_q_heads % n_kv_heads) return CIVIC_ERR_INVALID_ARG;
+    if (head_dim % 8) return CIVIC_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return CIVIC_ERR_INVALID_ARG;
+    for (int i = 0; i < 3; ++i) {
+        if (q_strides[i] < 0 || kv_strides[i] < 0 || o_strides[i] < 0) return CIVIC_ERR_INVALID_ARG;
+        if ((q_strides[i] * esz) % 16 || (kv_strides[i] * esz) % 16 || (o_strides[i] * esz) % 16) return CIVIC_ERR_INVALID_ARG;
+    }
+    if (!(softmax_scale >= 0.f) || std::isinf(softmax_scale)) return CIVIC_ERR_INVALID_ARG;
+    if (head_dim > CIVIC_MAX_HEAD_DIM || batch > 65535 || n_q_heads > 65535) return CIVIC_ERR_UNSUPPORTED;
+    if (batch == 0 || seq == 0) return CIVIC_OK;
+
+    AttnArgs a;
+    a.q = q; a.k = k; a.v = v; a.out = out;
+    for (int i = 0; i < 3; ++i) { a.qs[i] = q_strides[i]; a.ks[i] = kv_strides[i]; a.os[i] = o_strides[i]; }
+    a.batch = batch; a.seq = seq; a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads; a.head_dim = head_dim;
+    a.causal = causal ? 1 : 0;
+    a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt(static_cast<float>(head_dim));
+    a.heads_per_block = 1; a.row_tiles = 0;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    if (dtype == CIVIC_BF16 && head_dim <= 128) {
+        if (head_dim <= 64) return launch_mfma<64>(a, s);
+        if (head_dim <= 96) return launch_mfma<96>(a, s);
+        return launch_mfma<128>(a, s);
+    }
+    const dim3 grid(static_cast<unsigned>((seq + 3) / 4), static_cast<unsigned>(n_q_heads), static_cast<unsigned>(batch));
+    if (dtype == CIVIC_BF16) hipLaunchKernelGGL((attn_plain_kernel<true>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((attn_plain_kernel<false>), grid, dim3(256), 0, s, a);
+    return check_launch();
+}

@@ -1,0 +1,188 @@
+// civic_compact: Merge of Eq. 13.  Builds the contiguous, order-preserving compact sequence (all
+// text tokens + kept visual tokens) and carries the position ids along unchanged.  HBM-bound row
+// gather: only kept rows are ever read.
+//
+// One launch, no scratch.  A block owns a run of consecutive compact rows of one batch item and
+// derives their dense source indices itself:
+//   - kept_idx is ascending, so the number of kept tokens before frame f (kb[f]) is the position
+//     where the frame id of consecutive entries steps past f; every thread looks at one entry and
+//     its predecessor and fills the table in LDS.  The same pass drops the source index of every
+//     kept visual token whose compact slot falls into the block's run.
+//   - in compact space frame f starts at cs[f] = frame_start[f] - f*HW + kb[f] (text before it plus
+//     kept tokens before it); a slot not claimed by a visual token is text and maps back by adding
+//     the visual tokens dropped before it.
+// The rows are then moved with the widest vector the row size allows (16 bytes for every Qwen3-VL
+// shape), several rows in flight per thread so that loads are issued back to back before any store.
+#include "civic_internal.h"
+
+namespace civic {
+
+constexpr int kCompactThreads = 256;
+constexpr int kCompactMaxRows = 64;   // compact rows per block (LDS table size)
+constexpr int kCompactUnroll = 4;
+
+struct FrameTable {
+    int32_t n;                          // frames
+    int32_t hw;                         // tokens per frame
+    int32_t start[CIVIC_MAX_FRAMES];    // sequence index of each frame's first token
+};
+
+template <typename V>
+__global__ __launch_bounds__(kCompactThreads) void compact_kernel(
+    const uint8_t* __restrict__ hidden, int64_t row_bytes, const int32_t* __restrict__ pos_ids, int32_t batch,
+    int32_t seq_len, FrameTable ft, const int32_t* __restrict__ kept_idx, int32_t n_kept, int32_t seq_c,
+    int32_t rows_per_block, int32_t threads_per_row, uint8_t* __restrict__ hidden_c, int32_t* __restrict__ pos_c,
+    int32_t* __restrict__ src_idx)
+{
+    __shared__ int32_t kb[CIVIC_MAX_FRAMES + 1];
+    __shared__ int32_t row_src[kCompactMaxRows];
+
+    const int tid = threadIdx.x;
+    const int b = blockIdx.y;
+    const int32_t j0 = blockIdx.x * rows_per_block;
+    const int32_t nrows = min(rows_per_block, seq_c - j0);
+    const int32_t* kept = kept_idx + static_cast<int64_t>(b) * n_kept;
+    const int32_t F = ft.n, hw = ft.hw;
+
+    for (int32_t i = tid; i <= n_kept; i += kCompactThreads) {
+        int32_t f_prev = -1, f_cur = F;
+        if (i > 0) f_prev = min(max(kept[i - 1] / hw, 0), F - 1);
+        if (i < n_kept) {
+            const int32_t v = kept[i];
+            f_cur = min(max(v / hw, 0), F - 1);
+            const int32_t j = ft.start[f_cur] - f_cur * hw + i - j0;      // compact slot of this kept token
+            if (j >= 0 && j < nrows) row_src[j] = ft.start[f_cur] + v - f_cur * hw;
+        }
+        for (int32_t f = f_prev + 1; f <= f_cur; ++f) kb[f] = i;
+    }
+    __syncthreads();
+
+    for (int32_t r = tid; r < nrows; r += kCompactThreads) {
+        const int32_t j = j0 + r;
+        // number of frames whose compact start is <= j (cs is non-decreasing in f)
+        int32_t lo = 0, hi = F;
+        while (lo < hi) {
+            const int32_t mid = (lo + hi) >> 1;
+            if (ft.start[mid] - mid * hw + kb[mid] <= j) lo = mid + 1; else hi = mid;
+        }
+        if (lo == 0) {
+            row_src[r] = j;                                           // text before the first frame
+        } else {
+            const int32_t f = lo - 1;
+            const int32_t vis_end = ft.start[f] - f * hw + kb[f + 1];  // end of frame f's kept tokens
+            if (j >= vis_end) row_src[r] = j + lo * hw - kb[lo];      // text: add the dropped tokens back
+        }
+    }
+    __syncthreads();
+
+    for (int32_t r = tid; r < nrows; r += kCompactThreads) {
+        const int32_t src = min(max(row_src[r], 0), seq_len - 1);
+        const int64_t o = static_cast<int64_t>(b) * seq_c + j0 + r;
+        src_idx[o] = src;
+#pragma unroll
+        for (int a = 0; a < 3; ++a)
+            pos_c[(static_cast<int64_t>(a) * batch + b) * seq_c + j0 + r] =
+                pos_ids[(static_cast<int64_t>(a) * batch + b) * seq_len + src];
+    }
+
+    const int32_t vpr = static_cast<int32_t>(row_bytes / sizeof(V));    // vectors per row
+    const int32_t rows_per_pass = kCompactThreads / threads_per_row;
+    const int32_t rr = tid / threads_per_row, c0 = tid - rr * threads_per_row;
+    const uint8_t* in_b = hidden + static_cast<int64_t>(b) * seq_len * row_bytes;
+    uint8_t* out_b = hidden_c + (static_cast<int64_t>(b) * seq_c + j0) * row_bytes;
+    for (int32_t rbase = 0; rbase < nrows; rbase += rows_per_pass * kCompactUnroll) {
+        const V* in[kCompactUnroll];
+        V* out[kCompactUnroll];
+#pragma unroll
+        for (int u = 0; u < kCompactUnroll; ++u) {
+            const int32_t r = rbase + u * rows_per_pass + rr;
+            in[u] = nullptr; out[u] = nullptr;
+            if (r < nrows) {
+                const int32_t src = min(max(row_src[r], 0), seq_len - 1);
+                in[u] = reinterpret_cast<const V*>(in_b + static_cast<int64_t>(src) * row_bytes);
+                out[u] = reinterpret_cast<V*>(out_b + static_cast<int64_t>(r) * row_bytes);
+            }
+        }
+        for (int32_t c = c0; c < vpr; c += threads_per_row) {
+            V val[kCompactUnroll];
+#pragma unroll
+            for (int u = 0; u < kCompactUnroll; ++u)
+                if (in[u]) val[u] = load_streaming(in[u] + c);
+#pragma unroll
+            for (int u = 0; u < kCompactUnroll; ++u)
+                if (out[u]) out[u][c] = val[u];
+        }
+    }
+}
+
+}  // namespace civic
+
+extern "C" int civic_compact(const void* hidden, int dtype, int32_t dim, const int32_t* pos_ids, int32_t batch,
+                             int64_t seq_len, const civic_grid* grid, const int64_t* frame_start,
+                             const int32_t* kept_idx, int64_t n_kept, void* hidden_c, int32_t* pos_c,
+                             int32_t* src_idx, void* workspace, size_t workspace_bytes, void* stream)
+{
+    using namespace civic;
+    (void)workspace; (void)workspace_bytes;
+    const int esz = dtype_size(dtype);
+    GridInfo gi;
+    if (grid_info(grid, &gi) != CIVIC_OK) return CIVIC_ERR_INVALID_ARG;
+    if (!esz || !hidden || !pos_ids || !frame_start || !hidden_c || !pos_c || !src_idx) return CIVIC_ERR_INVALID_ARG;
+    if (dim <= 0 || batch < 0 || seq_len < gi.nv || n_kept < 0 || n_kept > gi.nv) return CIVIC_ERR_INVALID_ARG;
+    if (n_kept > 0 && !kept_idx) return CIVIC_ERR_INVALID_ARG;
+    int64_t prev_end = 0;
+    for (int32_t f = 0; f < gi.frames; ++f) {
+        if (frame_start[f] < prev_end || frame_start[f] + gi.hw > seq_len) return CIVIC_ERR_INVALID_ARG;
+        prev_end = frame_start[f] + gi.hw;
+    }
+    const int64_t row_bytes = static_cast<int64_t>(dim) * esz;
+    int vec = 16;
+    while (row_bytes % vec) vec >>= 1;
+    const uintptr_t both = reinterpret_cast<uintptr_t>(hidden) | reinterpret_cast<uintptr_t>(hidden_c);
+    if (both & static_cast<uintptr_t>(vec - 1)) return CIVIC_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(pos_ids) | reinterpret_cast<uintptr_t>(pos_c) |
+         reinterpret_cast<uintptr_t>(src_idx) | reinterpret_cast<uintptr_t>(kept_idx)) & 3u)
+        return CIVIC_ERR_INVALID_ARG;
+    if (gi.frames > CIVIC_MAX_FRAMES || seq_len > INT32_MAX || batch > 65535) return CIVIC_ERR_UNSUPPORTED;
+    const int64_t seq_c = seq_len - gi.nv + n_kept;
+    if (batch == 0 || seq_c == 0) return CIVIC_OK;
+
+    FrameTable ft;
+    ft.n = gi.frames; ft.hw = gi.hw;
+    for (int32_t f = 0; f < CIVIC_MAX_FRAMES; ++f) ft.start[f] = f < gi.frames ? static_cast<int32_t>(frame_start[f]) : 0;
+
+    // Threads per row: the power of two in [16, 256] that wastes the fewest lanes on this row length.
+    const int64_t vpr = row_bytes / vec;
+    int tpr = 256;
+    int64_t best = -1;
+    for (int t = 256; t >= 16; t >>= 1) {
+        const int64_t slots = (vpr + t - 1) / t * t;
+        if (best < 0 || slots < best) { best = slots; tpr = t; }
+    }
+    // Rows per block: enough blocks to give every CU several, few enough that the per-block pass over
+    // kept_idx stays small next to the rows it moves.
+    const int64_t total_rows = seq_c * batch;
+    int64_t rpb = total_rows / (256 * 4);
+    const int64_t min_rows = (256 / tpr) * 2;
+    if (rpb < min_rows) rpb = min_rows;
+    if (rpb < 4) rpb = 4;
+    if (rpb > kCompactMaxRows) rpb = kCompactMaxRows;
+    const int64_t blocks = (seq_c + rpb - 1) / rpb;
+
+    const uint8_t* h = static_cast<const uint8_t*>(hidden);
+    uint8_t* hc = static_cast<uint8_t*>(hidden_c);
+    const dim3 g(static_cast<unsigned>(blocks), static_cast<unsigned>(batch)), blk(kCompactThreads);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+#define CIVIC_COMPACT_LAUNCH(V)                                                                               \
+    hipLaunchKernelGGL((compact_kernel<V>), g, blk, 0, s, h, row_bytes, pos_ids, batch,                         \
+                       static_cast<int32_t>(seq_len), ft, kept_idx, static_cast<int32_t>(n_kept),               \
+                       static_cast<int32_t>(seq_c), static_cast<int32_t>(rpb), tpr, hc, pos_c, src_idx)
+    switch (vec) {
+        case 16: CIVIC_COMPACT_LAUNCH(u32x4); break;
+        case 8: CIVIC_COMPACT_LAUNCH(u32x2); break;
+        case 4: CIVIC_COMPACT_LAUNCH(uint32_t); break;
+        default: CIVIC_COMPACT_LAUNCH(uint16_t); break;
+    }
+#undef CIVIC_COMPACT_LAUNCH
+    return check_launch();
+}

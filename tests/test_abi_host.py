@@ -1,0 +1,133 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares, the
+host-side functions agree with the tabulated grids, and every documented argument error is
+rejected before any HIP call (no compute call is made here)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2605_28115_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def bd():
+    from paper_2605_28115_amd import binding
+    return binding
+
+
+def test_exports_every_declared_symbol(bd):
+    header = open(os.path.join(ROOT, "include", "civic.h")).read()
+    declared = set(re.findall(r"\b(civic_[a-z_]+)\s*\(", header))
+    assert declared == set(bd.EXPORTS)
+    for name in declared:
+        assert hasattr(bd.lib, name), name
+    assert bd.lib.civic_last_hip_error() == 0
+
+
+def test_header_limits_match_binding(bd):
+    header = open(os.path.join(ROOT, "include", "civic.h")).read()
+    lim = dict(re.findall(r"#define (CIVIC_MAX_[A-Z_]+)\s+(\d+)", header))
+    assert int(lim["CIVIC_MAX_VISUAL_TOKENS"]) == bd.MAX_VISUAL_TOKENS
+    assert int(lim["CIVIC_MAX_FRAMES"]) == bd.MAX_FRAMES
+    assert int(lim["CIVIC_MAX_SCORE_DIM"]) == bd.MAX_SCORE_DIM
+    assert int(lim["CIVIC_MAX_HEAD_DIM"]) == bd.MAX_HEAD_DIM
+
+
+@pytest.mark.parametrize("name", list(wl.WORKLOADS))
+def test_kept_count_of_tabulated_workloads(bd, name):
+    w = wl.WORKLOADS[name]
+    assert bd.civic_kept_count(w.grid_tuple()) == w.kept
+    assert bd.civic_select_workspace_bytes(w.grid_tuple(), w.batch) == 0
+    assert bd.civic_compact_workspace_bytes(w.batch, w.seq_len) == 0
+
+
+def test_kept_count_closed_form_on_ragged_grids(bd):
+    for grid in wl.small_grid_cases():
+        frames, H, W, ch, cw, cf, ff, budget = grid
+        per_frame = 0
+        for r0 in range(0, H, ch):
+            for c0 in range(0, W, cw):
+                per_frame += min(cf, (min(r0 + ch, H) - r0) * (min(c0 + cw, W) - c0))
+        per_frame += min(ff, H * W - per_frame)
+        assert bd.civic_kept_count(grid) == max(budget, frames * per_frame), grid
+
+
+@pytest.mark.parametrize("grid", [
+    (0, 4, 4, 2, 2, 1, 0, 1), (1, 0, 4, 2, 2, 1, 0, 1), (1, 4, -1, 2, 2, 1, 0, 1), (1, 4, 4, 0, 2, 1, 0, 1),
+    (1, 4, 4, 2, 0, 1, 0, 1), (1, 4, 4, 2, 2, -1, 0, 1), (1, 4, 4, 2, 2, 1, -1, 1), (1, 4, 4, 2, 2, 1, 0, -1),
+    (1, 4, 4, 2, 2, 1, 0, 17), (70000, 70000, 2, 2, 2, 1, 0, 1),
+])
+def test_bad_grids_are_rejected(bd, grid):
+    assert bd.lib.civic_kept_count(C.byref(bd.make_grid(grid))) == bd.ERR_INVALID_ARG
+    assert bd.lib.civic_kept_count(None) == bd.ERR_INVALID_ARG
+    fake = C.c_void_p(0x1000)
+    assert bd.lib.civic_select(fake, 1, C.byref(bd.make_grid(grid)), fake, None, None, 0, None) == bd.ERR_INVALID_ARG
+
+
+def test_anchor_normalize_host(bd):
+    rng = np.random.default_rng(0)
+    a = (rng.standard_normal(300) * 2 + 5).astype(np.float32)
+    q = bd.civic_anchor_normalize(a)
+    assert abs(float(q.astype(np.float64).sum())) < 1e-5 and abs(float((q.astype(np.float64) ** 2).sum()) - 1) < 1e-6
+    c = a.astype(np.float64) - a.astype(np.float64).mean()
+    assert np.abs(q - c / np.linalg.norm(c)).max() < 1e-7
+    with pytest.raises(bd.CivicError):
+        bd.civic_anchor_normalize(np.full(8, 3.0, dtype=np.float32))
+    assert bd.lib.civic_anchor_normalize(None, 8, None) == bd.ERR_INVALID_ARG
+
+
+def test_argument_errors_precede_any_hip_call(bd):
+    L, F, I = bd.lib, C.c_void_p(0x1000), bd.ERR_INVALID_ARG
+    odd = C.c_void_p(0x1004)
+    st = (C.c_int64 * 3)(1024, 128, 128)
+    g = bd.make_grid((1, 4, 4, 2, 2, 1, 0, 5))
+    # civic_score: null, bad dtype, dim not a vector multiple, stride < dim, misaligned, too wide
+    assert L.civic_score(None, 1, 4, 64, 64, F, 1.0, F, None) == I
+    assert L.civic_score(F, 7, 4, 64, 64, F, 1.0, F, None) == I
+    assert L.civic_score(F, 1, 4, 64, 60, F, 1.0, F, None) == I
+    assert L.civic_score(F, 1, 4, 32, 64, F, 1.0, F, None) == I
+    assert L.civic_score(odd, 1, 4, 64, 64, F, 1.0, F, None) == I
+    assert L.civic_score(F, 1, -1, 64, 64, F, 1.0, F, None) == I
+    assert L.civic_score(F, 1, 4, 16384, 16384, F, 1.0, F, None) == bd.ERR_UNSUPPORTED
+    assert L.civic_score(F, 1, 0, 64, 64, F, 1.0, F, None) == bd.CIVIC_OK          # nothing to do
+    # civic_select: null scores / output, too many tokens
+    assert L.civic_select(None, 1, C.byref(g), F, None, None, 0, None) == I
+    assert L.civic_select(F, 1, C.byref(g), None, None, None, 0, None) == I
+    assert L.civic_select(F, -1, C.byref(g), F, None, None, 0, None) == I
+    big = bd.make_grid((1, 256, 256, 4, 4, 1, 0, 100))
+    assert L.civic_select(F, 1, C.byref(big), F, None, None, 0, None) == bd.ERR_UNSUPPORTED
+    assert L.civic_select(F, 0, C.byref(g), F, None, None, 0, None) == bd.CIVIC_OK
+    # civic_compact: frame spans out of range / overlapping / not ascending, seq shorter than N_v
+    def compact(fs, seq_len=40, n_kept=5, grid=g, hidden=F, dim=64):
+        arr = np.asarray(fs, dtype=np.int64)
+        return L.civic_compact(hidden, 1, dim, F, 1, seq_len, C.byref(grid), C.c_void_p(arr.ctypes.data), F, n_kept,
+                               F, F, F, None, 0, None)
+    assert compact([30]) == I and compact([-1]) == I and compact([0], seq_len=15) == I
+    assert compact([0], n_kept=17) == I and compact([0], hidden=None) == I and compact([0], hidden=odd) == I
+    g2 = bd.make_grid((2, 4, 4, 2, 2, 1, 0, 5))
+    assert compact([0, 8], grid=g2) == I and compact([20, 0], grid=g2) == I
+    many = bd.make_grid((200, 1, 1, 1, 1, 0, 0, 5))
+    assert compact(list(range(200)), seq_len=400, grid=many) == bd.ERR_UNSUPPORTED
+    # civic_prefill_attn: head mismatch, head_dim, alignment, scale
+    def attn(**kw):
+        a = dict(q=F, k=F, v=F, o=F, dt=1, b=1, s=8, hq=4, hkv=2, d=64, qs=st, ks=st, os=st, causal=1, scale=0.0)
+        a.update(kw)
+        return L.civic_prefill_attn(a["q"], a["k"], a["v"], a["o"], a["dt"], a["b"], a["s"], a["hq"], a["hkv"], a["d"],
+                                    a["qs"], a["ks"], a["os"], a["causal"], C.c_float(a["scale"]), None)
+    assert attn(hq=3) == I and attn(d=60) == I and attn(q=odd) == I and attn(k=None) == I and attn(dt=2) == I
+    assert attn(scale=-1.0) == I and attn(scale=float("nan")) == I and attn(qs=None) == I
+    assert attn(qs=(C.c_int64 * 3)(1024, 100, 68)) == I
+    assert attn(d=512) == bd.ERR_UNSUPPORTED and attn(s=0) == bd.CIVIC_OK
+    # civic_kv_write: rows past the cache end, negative pos0, head bytes not a vector multiple
+    def kvw(**kw):
+        a = dict(k=F, v=F, st=st, dt=1, kc=F, vc=F, b=1, s=8, h=2, d=64, smax=16, pos0=0)
+        a.update(kw)
+        return L.civic_kv_write(a["k"], a["v"], a["st"], a["dt"], a["kc"], a["vc"], a["b"], a["s"], a["h"], a["d"],
+                                a["smax"], a["pos0"], None)
+    assert kvw(pos0=9) == I and kvw(pos0=-1) == I and kvw(d=4) == I and kvw(kc=None) == I and kvw(v=odd) == I
+    assert kvw(st=None) == I and kvw(h=0) == I and kvw(s=0) == bd.CIVIC_OK
+    assert bd.lib.civic_last_hip_error() == 0

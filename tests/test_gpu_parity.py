@@ -1,0 +1,294 @@
+"""GPU parity: every stage of the HIP path, called through the C ABI, against the CPU oracle on the
+same seeded inputs.  Integer, byte and index results are bit-exact; attention is within
+2e-2 * max(1, max|ref|) for bf16 and 1e-4 * max(1, max|ref|) for fp32; scores within 2e-5 / tau."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_28115_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def bd():
+    from paper_2605_28115_amd import binding
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return binding
+
+
+def to_dev(storage: np.ndarray) -> torch.Tensor:
+    if storage.dtype == np.uint16:
+        return torch.from_numpy(storage.view(np.int16)).view(torch.bfloat16).cuda()
+    return torch.from_numpy(storage).cuda()
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    t = t.detach().cpu().contiguous()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).numpy().view(np.uint16)
+    return t.numpy()
+
+
+def widen(storage: np.ndarray) -> np.ndarray:
+    return wl.bf16_bits_to_f32(storage) if storage.dtype == np.uint16 else storage.astype(np.float32)
+
+
+def log(*a):
+    print(*a, flush=True)
+
+
+# ----------------------------------------------------------------------------------------- score
+@pytest.mark.parametrize("name", list(wl.WORKLOADS))
+def test_score_matches_oracle(bd, name):
+    w = wl.WORKLOADS[name]
+    log("score", name)
+    rows = min(w.batch * w.seq_len, 3000)
+    hid, hid32 = wl.hidden(w, 0)
+    hid = hid.reshape(-1, w.dim)[:rows]
+    hid32 = hid32.reshape(-1, w.dim)[:rows]
+    q = bd.civic_anchor_normalize(wl.anchor(w, 0))
+    assert np.abs(q - oracle.anchor_normalize(wl.anchor(w, 0))).max() < 1e-7
+    for inv_tau in (1.0, 14.0):
+        s = to_host(bd.civic_score(to_dev(hid), torch.from_numpy(q).cuda(), inv_tau))
+        ref = oracle.score(hid32, q, inv_tau)
+        assert s.shape == ref.shape and np.abs(s - ref).max() <= 2e-5 * inv_tau
+
+
+def test_score_edge_rows_and_strides(bd):
+    rng = np.random.default_rng(0)
+    for dim, dtype in ((8, "bf16"), (520, "bf16"), (1152, "bf16"), (8192, "bf16"), (4, "fp32"), (260, "fp32"), (4096, "fp32")):
+        log("score edge", dim, dtype)
+        x = rng.standard_normal((37, dim)).astype(np.float32) * 3 + 40          # large mean: needs the centred pass
+        x[0] = 1.25                                                              # constant row -> 0
+        st, x32 = wl.quantize(x, dtype)
+        q = bd.civic_anchor_normalize(rng.standard_normal(dim).astype(np.float32))
+        s = to_host(bd.civic_score(to_dev(st), torch.from_numpy(q).cuda(), 2.0))
+        ref = oracle.score(x32, q, 2.0)
+        assert s[0] == 0.0 and np.abs(s - ref).max() <= 4e-5
+    # rows embedded in a wider buffer (row stride > dim)
+    x = rng.standard_normal((50, 256)).astype(np.float32)
+    st, x32 = wl.quantize(x, "bf16")
+    q = bd.civic_anchor_normalize(rng.standard_normal(64).astype(np.float32))
+    s = to_host(bd.civic_score(to_dev(st)[:, 64:128], torch.from_numpy(q).cuda(), 1.0))
+    assert np.abs(s - oracle.score(np.ascontiguousarray(x32[:, 64:128]), q, 1.0)).max() <= 2e-5
+
+
+# ---------------------------------------------------------------------------------------- select
+def check_select(bd, scores: np.ndarray, grid):
+    idx, flags = bd.civic_select(torch.from_numpy(scores).cuda(), grid, want_flags=True)
+    ref_idx, ref_flags = oracle.select(scores, grid)
+    assert np.array_equal(to_host(idx), ref_idx), grid
+    assert np.array_equal(to_host(flags), ref_flags), grid
+
+
+@pytest.mark.parametrize("name", list(wl.WORKLOADS))
+def test_select_matches_oracle_on_workloads(bd, name):
+    w = wl.WORKLOADS[name]
+    for trial in range(5):
+        log("select", name, trial)
+        check_select(bd, wl.scores(w, trial), w.grid_tuple())
+
+
+@pytest.mark.parametrize("grid", wl.small_grid_cases())
+def test_select_matches_oracle_on_degenerate_grids(bd, grid):
+    log("select grid", grid)
+    nv = grid[0] * grid[1] * grid[2]
+    rng = np.random.default_rng(nv)
+    s = np.stack([
+        rng.standard_normal(nv),
+        np.round(rng.standard_normal(nv) * 2) / 2,               # heavy ties
+        np.zeros(nv),
+        rng.integers(0, 2, nv) * 1.0,
+        np.where(rng.random(nv) < 0.5, 0.0, -0.0),               # signed zeros tie
+        np.where(rng.random(nv) < 0.1, np.inf, np.where(rng.random(nv) < 0.1, -np.inf, rng.integers(-1, 2, nv))),
+        -np.arange(nv, dtype=np.float64), np.arange(nv, dtype=np.float64),
+    ]).astype(np.float32)
+    check_select(bd, s, grid)
+
+
+def test_select_budget_sweep_and_ties_at_the_threshold(bd):
+    w = wl.WORKLOADS["8b"]
+    s = np.round(wl.scores(w, 3) * 8) / 8                        # many equal keys at any threshold
+    g = list(w.grid_tuple())
+    for budget in (0, 1, 127, 128, 129, 682, 1500, 2047, 2048):
+        log("select budget", budget)
+        g[7] = budget
+        check_select(bd, s.astype(np.float32), g)
+    g = list(wl.WORKLOADS["video"].grid_tuple())
+    sv = np.round(wl.scores(wl.WORKLOADS["video"], 1) * 4) / 4
+    for ff in (0, 1, 16, 540, 576):
+        log("select frame floor", ff)
+        g[6] = ff
+        check_select(bd, sv.astype(np.float32), g)
+
+
+def test_select_at_the_size_limit(bd):
+    grid = (8, 64, 64, 4, 4, 1, 50, 32768 // 3)                   # N_v = 32768, the documented maximum
+    rng = np.random.default_rng(1)
+    log("select limit")
+    check_select(bd, rng.standard_normal((2, 32768)).astype(np.float32), grid)
+    check_select(bd, np.zeros((1, 32768), dtype=np.float32), grid)
+
+
+# --------------------------------------------------------------------------------------- compact
+def check_compact(bd, hid, pos, grid, fs, kept):
+    hc, pc, si = bd.civic_compact(to_dev(hid), torch.from_numpy(pos).cuda(), grid, fs, torch.from_numpy(kept).cuda())
+    rhc, rpc, rsi = oracle.compact(hid, pos, grid, fs, kept)
+    assert np.array_equal(to_host(si), rsi)
+    assert np.array_equal(to_host(pc), rpc)
+    assert np.array_equal(to_host(hc), rhc)
+
+
+@pytest.mark.parametrize("name", list(wl.WORKLOADS))
+def test_compact_matches_oracle_on_workloads(bd, name):
+    w = wl.WORKLOADS[name]
+    for trial in range(2):
+        log("compact", name, trial)
+        hid, _ = wl.hidden(w, trial)
+        kept, _ = oracle.select(wl.scores(w, trial), w.grid_tuple())
+        check_compact(bd, hid, wl.position_ids(w), w.grid_tuple(), wl.frame_starts(w), kept)
+
+
+def test_compact_edge_cases(bd):
+    rng = np.random.default_rng(2)
+    w = wl.WORKLOADS["tiny"]
+    hid, _ = wl.hidden(w, 3)
+    pos, fs = wl.position_ids(w), wl.frame_starts(w)
+    log("compact keep-all / keep-none")
+    check_compact(bd, hid, pos, (1, 16, 16, 4, 4, 0, 0, 256), fs, np.arange(256, dtype=np.int32)[None])
+    check_compact(bd, hid, pos, (1, 16, 16, 4, 4, 0, 0, 0), fs, np.zeros((1, 0), dtype=np.int32))
+    # frames scattered through the text, some frames with no kept token, odd row sizes (2, 4, 8 byte vectors)
+    for dim, dtype in ((7, np.uint16), (6, np.uint16), (3, np.float32), (36, np.uint16), (1152, np.uint16)):
+        log("compact odd rows", dim, dtype)
+        grid = (5, 3, 4, 2, 2, 0, 0, 0)
+        fs = np.asarray([2, 14, 30, 42, 60], dtype=np.int64)
+        seq = 75
+        hid = rng.integers(0, 60000, (3, seq, dim)).astype(dtype)
+        pos = rng.integers(0, 1000, (3, 3, seq)).astype(np.int32)
+        kept = np.stack([np.sort(rng.choice(np.r_[0:12, 36:60], 9, replace=False)) for _ in range(3)]).astype(np.int32)
+        check_compact(bd, hid, pos, grid, fs, kept)
+    # 128 frames (the documented maximum) of 2x2 tokens, no text at all
+    log("compact 128 frames")
+    grid = (128, 2, 2, 2, 2, 1, 0, 200)
+    hid = rng.integers(0, 60000, (2, 512, 64)).astype(np.uint16)
+    pos = rng.integers(0, 1000, (3, 2, 512)).astype(np.int32)
+    kept, _ = oracle.select(rng.standard_normal((2, 512)).astype(np.float32), grid)
+    check_compact(bd, hid, pos, grid, np.arange(128, dtype=np.int64) * 4, kept)
+
+
+# ------------------------------------------------------------------------------------- attention
+def attn_tol(ref: np.ndarray, dtype: str) -> float:
+    return (2e-2 if dtype == "bf16" else 1e-4) * max(1.0, float(np.nanmax(np.abs(ref))))
+
+
+def check_attn(bd, q, k, v, causal, dtype, row_step=1, scale=0.0):
+    out = to_host(bd.civic_prefill_attn(to_dev(q), to_dev(k), to_dev(v), causal, scale))
+    ref = oracle.attention(widen(q), widen(k), widen(v), causal, scale=None if scale == 0.0 else scale, row_step=row_step)
+    got = widen(out).astype(np.float64)[:, ::row_step]
+    ref = ref[:, ::row_step]
+    err = float(np.abs(got - ref).max())
+    log("   max abs err", err, "tol", attn_tol(ref, dtype))
+    assert np.isfinite(got).all() and err <= attn_tol(ref, dtype)
+
+
+@pytest.mark.parametrize("name,row_step", [("tiny", 1), ("2b", 1), ("8b", 7), ("vit", 11), ("video", 61)])
+def test_attention_matches_oracle_on_workloads(bd, name, row_step):
+    w = wl.WORKLOADS[name]
+    log("attention", name)
+    (q, _), (k, _), (v, _) = wl.qkv(w, 0)
+    check_attn(bd, q, k, v, w.causal, w.dtype, row_step)
+
+
+@pytest.mark.parametrize("shape", [
+    (1, 1, 4, 4, 128), (2, 31, 8, 2, 128), (1, 33, 4, 1, 128), (1, 64, 2, 2, 128), (1, 65, 6, 3, 128),
+    (2, 200, 8, 8, 64), (1, 257, 12, 4, 64), (1, 130, 16, 16, 72), (1, 77, 3, 3, 96), (1, 90, 4, 2, 32),
+    (1, 100, 2, 1, 256), (1, 50, 4, 2, 160),
+])
+@pytest.mark.parametrize("causal", [True, False])
+def test_attention_shapes_tails_and_head_dims(bd, shape, causal):
+    b, s, hq, hkv, d = shape
+    log("attention shape", shape, causal)
+    rng = np.random.default_rng(s * 7 + d)
+    mk = lambda h: wl.quantize(rng.standard_normal((b, s, h, d)).astype(np.float32) * 1.5, "bf16")[0]
+    check_attn(bd, mk(hq), mk(hkv), mk(hkv), causal, "bf16")
+    if d <= 64:
+        mk32 = lambda h: rng.standard_normal((b, s, h, d)).astype(np.float32)
+        check_attn(bd, mk32(hq), mk32(hkv), mk32(hkv), causal, "fp32", scale=0.2)
+
+
+def test_attention_large_logits_stay_finite(bd):
+    rng = np.random.default_rng(5)
+    log("attention large logits")
+    q = wl.quantize(rng.standard_normal((1, 150, 4, 128)).astype(np.float32) * 30, "bf16")[0]
+    k = wl.quantize(rng.standard_normal((1, 150, 2, 128)).astype(np.float32) * 30, "bf16")[0]
+    v = wl.quantize(rng.standard_normal((1, 150, 2, 128)).astype(np.float32), "bf16")[0]
+    check_attn(bd, q, k, v, True, "bf16")
+    check_attn(bd, q, k, v, False, "bf16")
+
+
+# -------------------------------------------------------------------------------------- KV write
+@pytest.mark.parametrize("name", ["tiny", "2b", "8b", "video"])
+def test_kv_write_matches_oracle(bd, name):
+    w = wl.WORKLOADS[name]
+    log("kv_write", name)
+    _, (k, _), (v, _) = wl.qkv(w, 1)
+    seq = k.shape[1]
+    for s_max, pos0 in ((seq, 0), (seq + 37, 21)):
+        fill = 0x7B7B if k.dtype == np.uint16 else 123.0
+        kc = np.full((w.batch, w.n_kv_heads, s_max, w.head_dim), fill, dtype=k.dtype)
+        vc = kc.copy()
+        dk, dv = to_dev(kc), to_dev(vc)
+        bd.civic_kv_write(to_dev(k), to_dev(v), dk, dv, pos0)
+        oracle.kv_write(k, v, kc, vc, pos0)
+        assert np.array_equal(to_host(dk), kc) and np.array_equal(to_host(dv), vc)   # includes the untouched rows
+
+
+# -------------------------------------------------------------------------------------- the path
+@pytest.mark.parametrize("name", ["tiny", "2b", "8b", "video"])
+def test_whole_path_chained(bd, name):
+    """score -> select -> compact -> attention -> KV write on device, each stage fed by the previous
+    one's device output.  Selection parity is defined on a given score array, so the oracle selects on
+    the scores the GPU produced; since H_q * d = D the compact rows serve as Q and their first
+    H_kv * d columns as K = V (strided views)."""
+    w = wl.WORKLOADS[name]
+    log("chain", name)
+    hid, hid32 = wl.hidden(w, 4)
+    pos, fs, grid = wl.position_ids(w), wl.frame_starts(w), w.grid_tuple()
+    hw = w.height * w.width
+    d_hid = to_dev(hid)
+    q_anchor = bd.civic_anchor_normalize(wl.anchor(w, 4))
+    vis = torch.cat([d_hid[:, s:s + hw] for s in fs], dim=1).contiguous()          # [batch, N_v, dim]
+    scores = bd.civic_score(vis, torch.from_numpy(q_anchor).cuda(), 1.0)
+    kept, _ = bd.civic_select(scores, grid)
+    hc, pc, si = bd.civic_compact(d_hid, torch.from_numpy(pos).cuda(), grid, fs, kept)
+    s_c = hc.shape[1]
+    assert s_c == w.seq_compact
+    qv = hc.view(w.batch, s_c, w.n_q_heads, w.head_dim)
+    kv = hc[:, :, :w.n_kv_heads * w.head_dim].unflatten(2, (w.n_kv_heads, w.head_dim))
+    out = bd.civic_prefill_attn(qv, kv, kv, w.causal)
+    kc = torch.zeros((w.batch, w.n_kv_heads, s_c, w.head_dim), dtype=hc.dtype, device="cuda")
+    vc = torch.zeros_like(kc)
+    bd.civic_kv_write(kv, kv, kc, vc, 0)
+    torch.cuda.synchronize()
+
+    h_scores = to_host(scores)
+    vis32 = np.concatenate([hid32[:, s:s + hw] for s in fs], axis=1).reshape(-1, w.dim)
+    assert np.abs(h_scores.reshape(-1) - oracle.score(vis32, q_anchor, 1.0)).max() <= 2e-5
+    ref_kept, _ = oracle.select(h_scores, grid)
+    assert np.array_equal(to_host(kept), ref_kept)
+    rhc, rpc, rsi = oracle.compact(hid, pos, grid, fs, ref_kept)
+    assert np.array_equal(to_host(si), rsi) and np.array_equal(to_host(pc), rpc) and np.array_equal(to_host(hc), rhc)
+    r32 = widen(rhc)
+    rq = r32.reshape(w.batch, s_c, w.n_q_heads, w.head_dim)
+    rkv = r32[:, :, :w.n_kv_heads * w.head_dim].reshape(w.batch, s_c, w.n_kv_heads, w.head_dim)
+    step = 1 if s_c < 600 else 13 if s_c < 2000 else 97
+    ref = oracle.attention(rq, rkv, rkv, w.causal, row_step=step)[:, ::step]
+    got = widen(to_host(out)).astype(np.float64)[:, ::step]
+    assert np.abs(got - ref).max() <= attn_tol(ref, w.dtype)
+    rkc = np.zeros((w.batch, w.n_kv_heads, s_c, w.head_dim), dtype=rhc.dtype)
+    rvc = rkc.copy()
+    rkv_bits = rhc[:, :, :w.n_kv_heads * w.head_dim].reshape(w.batch, s_c, w.n_kv_heads, w.head_dim)
+    oracle.kv_write(rkv_bits, rkv_bits, rkc, rvc, 0)
+    assert np.array_equal(to_host(kc), rkc) and np.array_equal(to_host(vc), rvc)
