@@ -132,20 +132,33 @@ __global__ __launch_bounds__(256) void attn_plain_kernel(AttnArgs a)
 
 // --------------------------------------------------------------------------------------- MFMA path
 constexpr int kBN = 64;                 // keys per LDS tile
-constexpr int kKPad = 8;                // bf16 elements of row padding in the K tile
-constexpr int kVPad = 8;                // bf16 elements of row padding in the transposed V tile
 
-// DP: head_dim rounded up to a multiple of 32 (zero filled).
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+// LDS transpose read (gfx950): the 16 lanes of a group each name 4 consecutive bf16 of a 4 x 16 block
+// (lane i -> row i/4, columns 4(i%4)..+3); lane i receives column i of the block, rows 0..3.
+__device__ __forceinline__ s16x4 lds_read_tr16(const __bf16* p)
+{
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (s16x4 __attribute__((address_space(3)))*)(const_cast<__bf16*>(p)));
+}
+
+// DP: head_dim rounded up to a multiple of 32 (zero filled in LDS and registers only).
 template <int DP>
-__global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a)
+__global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a)
 {
     constexpr int KSTEPS = DP / 16;      // MFMA k-steps of Q K^T
     constexpr int DT = DP / 32;          // 32-row tiles of O^T
     constexpr int CPR = DP / 8;          // 16-byte chunks per K/V row
-    constexpr int KROW = DP + kKPad;
-    constexpr int VROW = kBN + kVPad;
-    __shared__ __attribute__((aligned(16))) __bf16 k_s[kBN * KROW];
-    __shared__ __attribute__((aligned(16))) __bf16 vt_s[DP * VROW];
+    constexpr int NLD = kBN * CPR / 256; // chunks of each tile a thread stages
+    // Row pitches (elements) chosen so that the 16 lanes of a 128-bit K read and the 32 lanes of a
+    // transposing 64-bit V read fall on distinct LDS banks.
+    constexpr int KROW = DP + 8;
+    constexpr int VROW = (DP % 64 == 0) ? DP + 32 : DP + 64;
+    constexpr int KTILE = kBN * KROW, VTILE = kBN * VROW;
+    extern __shared__ __attribute__((aligned(16))) __bf16 smem[];
+    __bf16* k_s = smem;                  // [2][kBN][KROW]
+    __bf16* v_s = smem + 2 * KTILE;      // [2][kBN][VROW]
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
@@ -155,8 +168,9 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a)
 
     // blockIdx.x -> (row tile, head block, kv head, batch); the heaviest causal row tiles come first
     int bid = blockIdx.x;
-    const int rt = a.row_tiles - 1 - bid / (head_blocks * a.n_kv_heads * a.batch);
-    bid %= head_blocks * a.n_kv_heads * a.batch;
+    const int per_rt = head_blocks * a.n_kv_heads * a.batch;
+    const int rt = a.row_tiles - 1 - bid / per_rt;
+    bid %= per_rt;
     const int hb = bid % head_blocks; bid /= head_blocks;
     const int g = bid % a.n_kv_heads;
     const int b = bid / a.n_kv_heads;
@@ -171,7 +185,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a)
     // Q^T as B operand: lane (col, half) holds Q[qi][16 s + 8 half .. +7] for every k-step s
     bf16x8 qreg[KSTEPS];
     {
-        const __bf16* qp = static_cast<const __bf16*>(a.q) + b * a.qs[0] + static_cast<int64_t>(min(qi, a.seq - 1)) * a.qs[1] + h * a.qs[2];
+        const __bf16* qp = static_cast<const __bf16*>(a.q) + b * a.qs[0] +
+                           static_cast<int64_t>(min(qi, a.seq - 1)) * a.qs[1] + h * a.qs[2];
 #pragma unroll
         for (int s = 0; s < KSTEPS; ++s) {
             const int c = 16 * s + 8 * half;
@@ -186,32 +201,53 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a)
     for (int t = 0; t < DT; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc_o[t][r] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;                    // running maximum (raw logits) and row sum
 
     const int kv_end = a.causal ? block_rows_end : a.seq;     // keys [0, kv_end) are visible to the block
     const int n_tiles = (kv_end + kBN - 1) / kBN;
     const __bf16* kp = static_cast<const __bf16*>(a.k) + b * a.ks[0] + g * a.ks[2];
     const __bf16* vp = static_cast<const __bf16*>(a.v) + b * a.ks[0] + g * a.ks[2];
 
-    for (int kt = 0; kt < n_tiles; ++kt) {
-        const int key0 = kt * kBN;
-        __syncthreads();                                      // previous tile fully consumed
-        for (int id = tid; id < kBN * CPR; id += 256) {
+    // staging: thread -> NLD (key, chunk) pairs of each tile
+    bf16x8 kst[NLD], vst[NLD];
+    auto fetch = [&](int key0) {
+#pragma unroll
+        for (int u = 0; u < NLD; ++u) {
+            const int id = tid + 256 * u;
             const int key = id / CPR, dc = id - key * CPR;
-            bf16x8 kv8 = {0, 0, 0, 0, 0, 0, 0, 0}, vv8 = {0, 0, 0, 0, 0, 0, 0, 0};
+            bf16x8 kk = {0, 0, 0, 0, 0, 0, 0, 0}, vv = {0, 0, 0, 0, 0, 0, 0, 0};
             if (key0 + key < a.seq && dc * 8 < a.head_dim) {
                 const int64_t off = static_cast<int64_t>(key0 + key) * a.ks[1] + dc * 8;
-                kv8 = *reinterpret_cast<const bf16x8*>(kp + off);
-                vv8 = *reinterpret_cast<const bf16x8*>(vp + off);
+                kk = *reinterpret_cast<const bf16x8*>(kp + off);
+                vv = *reinterpret_cast<const bf16x8*>(vp + off);
             }
-            *reinterpret_cast<bf16x8*>(&k_s[key * KROW + dc * 8]) = kv8;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) vt_s[(dc * 8 + e) * VROW + key] = vv8[e];
+            kst[u] = kk; vst[u] = vv;
         }
-        __syncthreads();
+    };
+    auto stage = [&](int buf) {
+#pragma unroll
+        for (int u = 0; u < NLD; ++u) {
+            const int id = tid + 256 * u;
+            const int key = id / CPR, dc = id - key * CPR;
+            *reinterpret_cast<bf16x8*>(&k_s[buf * KTILE + key * KROW + dc * 8]) = kst[u];
+            *reinterpret_cast<bf16x8*>(&v_s[buf * VTILE + key * VROW + dc * 8]) = vst[u];
+        }
+    };
+
+    fetch(0);
+    stage(0);
+    __syncthreads();
+
+    const int l16 = lane & 15, g16 = (lane >> 4) & 1;
+    for (int kt = 0; kt < n_tiles; ++kt) {
+        const int key0 = kt * kBN;
+        const int buf = kt & 1;
+        if (kt + 1 < n_tiles) fetch(key0 + kBN);              // global loads in flight during the MFMAs
 
         const bool wave_live = !a.causal || key0 <= row0 + 31;   // some key of the tile is visible to the wavefront
         if (wave_live) {
+            const __bf16* kb = k_s + buf * KTILE;
+            const __bf16* vb = v_s + buf * VTILE;
             // S^T tile: rows = keys (two 32-key sub-tiles), columns = this wavefront's 32 queries
             f32x16 acc_s[2];
 #pragma unroll
@@ -220,27 +256,40 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a)
                 for (int r = 0; r < 16; ++r) acc_s[t][r] = 0.f;
 #pragma unroll
                 for (int s = 0; s < KSTEPS; ++s) {
-                    const bf16x8 ka = *reinterpret_cast<const bf16x8*>(&k_s[(32 * t + col) * KROW + 16 * s + 8 * half]);
+                    const bf16x8 ka = *reinterpret_cast<const bf16x8*>(&kb[(32 * t + col) * KROW + 16 * s + 8 * half]);
                     acc_s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[s], acc_s[t], 0, 0, 0);
                 }
             }
-            // mask + running maximum (exp2 domain)
-            float mx = -INFINITY;
+            // mask only where the tile crosses the diagonal or the end of the sequence (wave-uniform)
+            if ((a.causal && key0 + kBN - 1 > row0) || key0 + kBN > a.seq) {
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int kj = key0 + 32 * t + 8 * (r >> 2) + 4 * half + (r & 3);
+                        const bool ok = kj < a.seq && (!a.causal || kj <= qi);
+                        acc_s[t][r] = ok ? acc_s[t][r] : -INFINITY;
+                    }
+            }
+            float mx = acc_s[0][0];
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int kj = key0 + 32 * t + 8 * (r >> 2) + 4 * half + (r & 3);
-                    const bool ok = kj < a.seq && (!a.causal || kj <= qi);
-                    const float z = ok ? acc_s[t][r] * sl2 : -INFINITY;
-                    acc_s[t][r] = z;
-                    mx = fmaxf(mx, z);
-                }
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc_s[t][r]);
             mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-            const float m_new = fmaxf(m_run, mx);
-            const float m_use = m_new == -INFINITY ? 0.f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);   // m_run = -inf -> 0
-            m_run = m_new;
+            // Rescale only when some row's maximum moved up by more than 8 in the exp2 domain; until
+            // then the stale maximum is kept (terms stay below 2^8, far inside fp32 and bf16 range).
+            if (__any((mx - m_run) * sl2 > 8.0f)) {
+                const float m_new = fmaxf(m_run, mx);
+                const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sl2);   // m_run = -inf -> 0
+                m_run = m_new;
+                l_run *= alpha;
+#pragma unroll
+                for (int t = 0; t < DT; ++t)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc_o[t][r] *= alpha;
+            }
+            const float moff = m_run == -INFINITY ? 0.f : -m_run * sl2;
             float rs = 0.f;
             bf16x8 pb[2][2];
 #pragma unroll
@@ -249,48 +298,65 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a)
                 for (int u = 0; u < 2; ++u)
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
-                        const float p = __builtin_amdgcn_exp2f(acc_s[t][8 * u + e] - m_use);
+                        const float p = __builtin_amdgcn_exp2f(fmaf(acc_s[t][8 * u + e], sl2, moff));
                         rs += p;
                         pb[t][u][e] = static_cast<__bf16>(p);
                     }
-            l_run = l_run * alpha + rs;
-#pragma unroll
-            for (int t = 0; t < DT; ++t)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc_o[t][r] *= alpha;
+            l_run += rs;
             // O^T += V^T P^T.  The k-slot (half, e) of step (t, u) is key 32t + 16u + 8(e/4) + 4 half + e%4.
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
+            for (int t = 0; t < 2; ++t)
 #pragma unroll
-                for (int t = 0; t < 2; ++t)
+                for (int u = 0; u < 2; ++u) {
+                    const __bf16* vrow = vb + (32 * t + 16 * u + 4 * half + (l16 >> 2)) * VROW + 16 * g16 + 4 * (l16 & 3);
 #pragma unroll
-                    for (int u = 0; u < 2; ++u) {
-                        const __bf16* vr = &vt_s[(32 * dt + col) * VROW + 32 * t + 16 * u + 4 * half];
-                        const bf16x4 lo = *reinterpret_cast<const bf16x4*>(vr);
-                        const bf16x4 hi = *reinterpret_cast<const bf16x4*>(vr + 8);
-                        const bf16x8 va = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    for (int dt = 0; dt < DT; ++dt) {
+                        const s16x4 lo = lds_read_tr16(vrow + 32 * dt);
+                        const s16x4 hi = lds_read_tr16(vrow + 8 * VROW + 32 * dt);
+                        const short va16[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                        bf16x8 va;
+                        __builtin_memcpy(&va, va16, 16);
                         acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[t][u], acc_o[dt], 0, 0, 0);
                     }
+                }
         }
+        if (kt + 1 < n_tiles) stage(buf ^ 1);                 // the other buffer was released by the last barrier
+        __syncthreads();
     }
 
     const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    if (qi < a.seq) {
-        __bf16* op = static_cast<__bf16*>(a.out) + b * a.os[0] + static_cast<int64_t>(qi) * a.os[1] + h * a.os[2];
+    // Stage the wavefront's 32 x DP output tile in LDS (all tiles are consumed: the loop ended with a
+    // barrier) and write it out as whole 16-byte row segments.
+    constexpr int OROW = DP + 8;
+    __bf16* o_s = smem + w * 32 * OROW;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
+    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-            for (int rq = 0; rq < 4; ++rq) {
-                const int c = 32 * dt + 8 * rq + 4 * half;
-                if (c < a.head_dim) {
-                    bf16x4 o4;
+        for (int rq = 0; rq < 4; ++rq) {
+            bf16x4 o4;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) o4[e] = static_cast<__bf16>(acc_o[dt][4 * rq + e] * inv);
-                    *reinterpret_cast<bf16x4*>(op + c) = o4;
-                }
-            }
+            for (int e = 0; e < 4; ++e) o4[e] = static_cast<__bf16>(acc_o[dt][4 * rq + e] * inv);
+            *reinterpret_cast<bf16x4*>(&o_s[col * OROW + 32 * dt + 8 * rq + 4 * half]) = o4;
+        }
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __bf16* ob = static_cast<__bf16*>(a.out) + b * a.os[0] + h * a.os[2];
+#pragma unroll
+    for (int it = 0; it < 32 * CPR / kWave; ++it) {
+        const int id = it * kWave + lane;
+        const int r = id / CPR, dc = id - r * CPR;
+        if (row0 + r < a.seq && dc * 8 < a.head_dim)
+            *reinterpret_cast<bf16x8*>(ob + static_cast<int64_t>(row0 + r) * a.os[1] + dc * 8) =
+                *reinterpret_cast<const bf16x8*>(&o_s[r * OROW + dc * 8]);
     }
+}
+
+template <int DP>
+static constexpr size_t attn_mfma_lds_bytes()
+{
+    constexpr int KROW = DP + 8, VROW = (DP % 64 == 0) ? DP + 32 : DP + 64;
+    return sizeof(__bf16) * 2 * kBN * (KROW + VROW);
 }
 
 template <int DP>
@@ -302,7 +368,13 @@ static int launch_mfma(AttnArgs& a, hipStream_t s)
     a.row_tiles = (a.seq + rows_per_block - 1) / rows_per_block;
     const int64_t blocks = static_cast<int64_t>(a.row_tiles) * (group / a.heads_per_block) * a.n_kv_heads * a.batch;
     if (blocks > INT32_MAX) return CIVIC_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((attn_mfma_kernel<DP>), dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s, a);
+    constexpr size_t lds = attn_mfma_lds_bytes<DP>();
+    if (lds > 64 * 1024) {
+        static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<DP>),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        if (attr != hipSuccess) return record_hip_error(attr);
+    }
+    hipLaunchKernelGGL((attn_mfma_kernel<DP>), dim3(static_cast<unsigned>(blocks)), dim3(256), lds, s, a);
     return check_launch();
 }
 
