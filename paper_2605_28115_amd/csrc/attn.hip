@@ -1,20 +1,29 @@
 // civic_prefill_attn: dense grouped-query prefill attention over the compact sequence (the
 // beta * N_l * (L+M_p)^2 * D_l term of Eq. 7; softmax(Q K^T / sqrt(d)) V as in Eq. 9).
 //
-// bf16 path (MFMA-bound): flash-style, one 256-thread workgroup = 4 wavefronts x 32 query rows.  The
-// four wavefronts are the query heads of one KV group over the same 32 rows when the group has four
-// or more heads (so one K/V tile staged in LDS serves the whole group and all four wavefronts have
-// the same causal extent); smaller groups put several row tiles of the same head in the workgroup.
-// Scores are computed TRANSPOSED, S^T = K Q^T with v_mfma_f32_32x32x16_bf16: a lane then owns one
-// query column, so the softmax row maximum and row sum are in-lane reductions plus one exchange
-// between the two half-waves, and the rescale factor is a per-lane scalar.  The exponentiated
-// tile, rounded to bf16, is already laid out as the B operand of O^T += V^T P^T; V is staged
-// transposed in LDS so its A operand is two 8-byte reads.  fp32 accumulation throughout, online
-// softmax in the exp2 domain, output rounded to bf16 (nearest even).
+// bf16 path (MFMA-bound): flash-style, one 512-thread workgroup = 8 wavefronts x 32 query rows over
+// one KV head.  With four or more query heads per KV head the wavefronts are 4 heads x 2 row tiles
+// (64 rows), so one K/V tile staged in LDS serves the whole group and all wavefronts share the
+// causal extent; smaller groups put more row tiles of the same head in the workgroup.
+//   - K/V tiles of 64 keys go from global memory straight into a 4-stage LDS ring
+//     (global_load_lds_dwordx4, 16 bytes per lane), three tiles ahead of the one being consumed;
+//     the ring is tracked with explicit vmcnt waits and fence-free workgroup barriers.  Rows keep a
+//     256-byte pitch and the 16-byte chunks are XOR-swizzled, so neither the 128-bit K reads nor the
+//     transposing V reads hit a bank conflict.
+//   - Scores are computed TRANSPOSED, S^T = K Q^T with v_mfma_f32_32x32x16_bf16: a lane owns one
+//     query column, so the softmax row maximum and row sum are in-lane reductions plus one exchange
+//     between the two half-waves, and the rescale factor is a per-lane scalar.  The exponentiated
+//     tile, rounded to bf16, is already laid out as the B operand of O^T += V^T P^T; the matching A
+//     operand comes from the row-major V tile through the LDS transpose read ds_read_b64_tr_b16.
+//   - fp32 accumulation, online softmax in the exp2 domain with a thresholded (lazy) rescale, row
+//     sums taken from the rounded probabilities with v_dot2c_f32_bf16, bf16 output (nearest even)
+//     staged through LDS into whole 16-byte row segments.
+//   - Workgroups are ordered heaviest causal row tile first.
 //
 // fp32 path and head sizes the MFMA path does not cover: a plain fp32 kernel, one wavefront per
 // query row (lanes over keys for Q K^T, lanes over channels for P V).
 #include <cmath>
+#include <type_traits>
 
 #include "civic_internal.h"
 
@@ -143,26 +152,77 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const __bf16* p)
         (s16x4 __attribute__((address_space(3)))*)(const_cast<__bf16*>(p)));
 }
 
-// DP: head_dim rounded up to a multiple of 32 (zero filled in LDS and registers only).
-template <int DP>
-__global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a)
+// K/V tiles live in LDS with a fixed row pitch of PITCH 16-byte chunks and an XOR swizzle of the chunk
+// index by a function of the row, so that no padding is needed (global -> LDS loads write 64
+// consecutive 16-byte slots per wavefront instruction) and both the 128-bit K reads (16 lanes = 16
+// consecutive rows, same logical chunk) and the transposing 64-bit V reads (32 lanes = 4 consecutive
+// rows x 4 chunks) fall on distinct banks.
+template <int PITCH>
+__device__ __forceinline__ int swz(int row)
 {
-    constexpr int KSTEPS = DP / 16;      // MFMA k-steps of Q K^T
-    constexpr int DT = DP / 32;          // 32-row tiles of O^T
-    constexpr int CPR = DP / 8;          // 16-byte chunks per K/V row
-    constexpr int NLD = kBN * CPR / 256; // chunks of each tile a thread stages
-    // Row pitches (elements) chosen so that the 16 lanes of a 128-bit K read and the 32 lanes of a
-    // transposing 64-bit V read fall on distinct LDS banks.
-    constexpr int KROW = DP + 8;
-    constexpr int VROW = (DP % 64 == 0) ? DP + 32 : DP + 64;
-    constexpr int KTILE = kBN * KROW, VTILE = kBN * VROW;
+    if constexpr (PITCH == 16) return ((row & 3) << 2) | ((row >> 2) & 3);
+    else return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+}
+
+constexpr int kAttnWaves = 8;            // wavefronts per workgroup
+constexpr int kAttnThreads = kAttnWaves * kWave;
+constexpr int kStages = 4;               // K/V tiles in flight in LDS
+
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) char lds_char;
+
+// 16 bytes per lane from global memory (scalar base + per-lane byte offset) straight into LDS at
+// lds_addr + lane * 16 (lds_addr wave-uniform).  Issued as inline assembly on purpose: the pipeline
+// tracks these loads with explicit s_waitcnt vmcnt(N), and an LDS read the compiler could see racing
+// with an asynchronous LDS write would make it drain the whole load queue first.
+__device__ __forceinline__ void dma16(const void* base, uint32_t byte_off, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(byte_off), "s"(base) : "memory");
+}
+
+// Workgroup barrier without the memory fence __syncthreads() implies (which would wait for every
+// outstanding load, including the prefetches that are meant to stay in flight).
+__device__ __forceinline__ void block_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+template <int N> __device__ __forceinline__ void wait_vmcnt()
+{
+    // s_waitcnt immediate (gfx9): vmcnt = bits [3:0] and [15:14]; expcnt and lgkmcnt left at their maxima
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+__device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+
+template <int DP>
+struct AttnTile {
+    static constexpr int KSTEPS = DP / 16;      // MFMA k-steps of Q K^T
+    static constexpr int DT = DP / 32;          // 32-row tiles of O^T
+    static constexpr int PITCH = DP == 64 ? 8 : 16;        // 16-byte chunks per LDS row
+    static constexpr int PITCHB = PITCH * 16;              // ... in bytes
+    static constexpr int TILEB = kBN * PITCHB;             // bytes per K (or V) tile
+    static constexpr int NI = kBN * PITCH / kAttnThreads;  // global->LDS instructions per wavefront, tile and tensor
+    static constexpr int TLOADS = 2 * NI;                  // ... per tile (K and V)
+    static constexpr int VBASE = kStages * TILEB;          // byte offset of the V stages
+};
+
+// DP: head_dim rounded up to a multiple of 32.
+template <int DP>
+__global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(AttnArgs a)
+{
+    using T = AttnTile<DP>;
+    constexpr int KSTEPS = T::KSTEPS, DT = T::DT, PITCH = T::PITCH, PITCHB = T::PITCHB, TILEB = T::TILEB;
+    constexpr int NI = T::NI, TLOADS = T::TLOADS, VBASE = T::VBASE;
     extern __shared__ __attribute__((aligned(16))) __bf16 smem[];
-    __bf16* k_s = smem;                  // [2][kBN][KROW]
-    __bf16* v_s = smem + 2 * KTILE;      // [2][kBN][VROW]
+    lds_char* const lds = (lds_char*)smem;    // K stages at [0, VBASE), V stages at [VBASE, 2 VBASE)
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
-    const int HB = a.heads_per_block, RB = 4 / HB;           // heads and 32-row sub-tiles per block
+    const int HB = a.heads_per_block, RB = kAttnWaves / HB;   // heads and 32-row sub-tiles per block
     const int group = a.n_q_heads / a.n_kv_heads;
     const int head_blocks = group / HB;
 
@@ -182,6 +242,50 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a)
     const int qi = row0 + col;                                // this lane's query row
     const float sl2 = a.scale * 1.4426950408889634f;          // scale * log2(e)
 
+    const int kv_end = a.causal ? block_rows_end : a.seq;     // keys [0, kv_end) are visible to the block
+    const int n_tiles = (kv_end + kBN - 1) / kBN;
+    const __bf16* kp = static_cast<const __bf16*>(a.k) + b * a.ks[0] + g * a.ks[2];
+    const __bf16* vp = static_cast<const __bf16*>(a.v) + b * a.ks[0] + g * a.ks[2];
+    const uint32_t row_bytes = static_cast<uint32_t>(a.ks[1]) * 2u;   // K/V token stride
+
+    // Global -> LDS: instruction j of wavefront w fills slots [(w*NI + j)*64, +64) of a tile; slot ->
+    // (row, physical chunk); the lane fetches the logical chunk that belongs there.  Every lane always
+    // loads (the count of outstanding loads is what the pipeline waits on): rows past the end of the
+    // sequence re-read the last row (their scores are masked), chunks past head_dim re-read chunk 0
+    // (they meet zero-filled Q columns, or produce output columns that are never stored).  The tile's
+    // first key enters through the scalar base, so the per-lane offsets are loop invariant; only the
+    // tile that holds the end of the sequence needs the clamped set.
+    uint32_t ld_voff[NI], ld_voff_tail[NI];
+    const int tail_tile = (a.seq - 1) / kBN;                  // the tile that may run past the sequence
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+        const int slot = (w * NI + j) * kWave + lane;
+        const int row = slot / PITCH;
+        const int c = (slot % PITCH) ^ swz<PITCH>(row);
+        const uint32_t cb = (c * 8 < a.head_dim) ? c * 16 : 0;
+        ld_voff[j] = row * row_bytes + cb;
+        ld_voff_tail[j] = (min(tail_tile * kBN + row, a.seq - 1) - tail_tile * kBN) * row_bytes + cb;
+    }
+    const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(
+        static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds)) + w * NI * kWave * 16);
+    auto issue_tile = [&](int kt, int st) {
+        const char* kb = reinterpret_cast<const char*>(kp) + static_cast<int64_t>(kt) * kBN * row_bytes;
+        const char* vb = reinterpret_cast<const char*>(vp) + static_cast<int64_t>(kt) * kBN * row_bytes;
+        const bool tail = kt == tail_tile;
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const uint32_t off = tail ? ld_voff_tail[j] : ld_voff[j];
+            const uint32_t la = lds_wave + st * TILEB + j * kWave * 16;
+            dma16(kb, off, la);
+            dma16(vb, off, la + VBASE);
+        }
+    };
+
+    // Start the pipeline before anything else: tiles 0 .. kStages-2
+#pragma unroll
+    for (int p = 0; p < kStages - 1; ++p)
+        if (p < n_tiles) issue_tile(p, p);
+
     // Q^T as B operand: lane (col, half) holds Q[qi][16 s + 8 half .. +7] for every k-step s
     bf16x8 qreg[KSTEPS];
     {
@@ -196,139 +300,147 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a)
         }
     }
 
+    // Per-lane LDS read addresses (bytes) inside stage 0; stage, t, u add compile-time immediates.
+    lds_char* kaddr[KSTEPS];              // K: row col, logical chunk 2s + half
+#pragma unroll
+    for (int s = 0; s < KSTEPS; ++s) kaddr[s] = lds + col * PITCHB + (((2 * s + half) ^ swz<PITCH>(col & 15)) << 4);
+    const int l16 = lane & 15, g16 = (lane >> 4) & 1;
+    lds_char* vaddr[2][DT];               // V: row 4 half + 8 hi + l16/4 (+ 32t + 16u), columns 32dt + 16 g16 + 4 (l16 % 4)
+#pragma unroll
+    for (int hi = 0; hi < 2; ++hi)
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            const int low4 = 4 * half + 8 * hi + (l16 >> 2);
+            const int el = 32 * dt + 16 * g16 + 4 * (l16 & 3);
+            vaddr[hi][dt] = lds + VBASE + low4 * PITCHB + (((el >> 3) ^ swz<PITCH>(low4)) << 4) + (el & 7) * 2;
+        }
+
     f32x16 acc_o[DT];
 #pragma unroll
     for (int t = 0; t < DT; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc_o[t][r] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;                    // running maximum (raw logits) and row sum
+    float m_run = -INFINITY;               // running maximum (raw logits)
+    float l_run[2] = {0.f, 0.f};           // running row sum, two partial accumulators
+    const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
 
-    const int kv_end = a.causal ? block_rows_end : a.seq;     // keys [0, kv_end) are visible to the block
-    const int n_tiles = (kv_end + kBN - 1) / kBN;
-    const __bf16* kp = static_cast<const __bf16*>(a.k) + b * a.ks[0] + g * a.ks[2];
-    const __bf16* vp = static_cast<const __bf16*>(a.v) + b * a.ks[0] + g * a.ks[2];
+    // One tile: wait until it has landed, release the previous one, refill the freed stage, compute.
+    auto tile = [&](int kt, auto stage_c) {
+        constexpr int ST = decltype(stage_c)::value;
+        // Loads retire in order.  Younger than tile kt are the tiles issued after it (at most
+        // kStages-2 of them); the Q loads are older than every tile except the first kStages-1.
+        const int younger = min(n_tiles - 1 - kt, kStages - 2);
+        if (younger >= 2) wait_vmcnt<2 * TLOADS>();
+        else if (younger == 1) wait_vmcnt<TLOADS>();
+        else wait_vmcnt<0>();
+        block_barrier();                                      // landed for every wavefront; tile kt-1 is released
+        if (kt + kStages - 1 < n_tiles) issue_tile(kt + kStages - 1, (ST + kStages - 1) % kStages);
 
-    // staging: thread -> NLD (key, chunk) pairs of each tile
-    bf16x8 kst[NLD], vst[NLD];
-    auto fetch = [&](int key0) {
-#pragma unroll
-        for (int u = 0; u < NLD; ++u) {
-            const int id = tid + 256 * u;
-            const int key = id / CPR, dc = id - key * CPR;
-            bf16x8 kk = {0, 0, 0, 0, 0, 0, 0, 0}, vv = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (key0 + key < a.seq && dc * 8 < a.head_dim) {
-                const int64_t off = static_cast<int64_t>(key0 + key) * a.ks[1] + dc * 8;
-                kk = *reinterpret_cast<const bf16x8*>(kp + off);
-                vv = *reinterpret_cast<const bf16x8*>(vp + off);
-            }
-            kst[u] = kk; vst[u] = vv;
-        }
-    };
-    auto stage = [&](int buf) {
-#pragma unroll
-        for (int u = 0; u < NLD; ++u) {
-            const int id = tid + 256 * u;
-            const int key = id / CPR, dc = id - key * CPR;
-            *reinterpret_cast<bf16x8*>(&k_s[buf * KTILE + key * KROW + dc * 8]) = kst[u];
-            *reinterpret_cast<bf16x8*>(&v_s[buf * VTILE + key * VROW + dc * 8]) = vst[u];
-        }
-    };
-
-    fetch(0);
-    stage(0);
-    __syncthreads();
-
-    const int l16 = lane & 15, g16 = (lane >> 4) & 1;
-    for (int kt = 0; kt < n_tiles; ++kt) {
         const int key0 = kt * kBN;
-        const int buf = kt & 1;
-        if (kt + 1 < n_tiles) fetch(key0 + kBN);              // global loads in flight during the MFMAs
-
-        const bool wave_live = !a.causal || key0 <= row0 + 31;   // some key of the tile is visible to the wavefront
-        if (wave_live) {
-            const __bf16* kb = k_s + buf * KTILE;
-            const __bf16* vb = v_s + buf * VTILE;
-            // S^T tile: rows = keys (two 32-key sub-tiles), columns = this wavefront's 32 queries
-            f32x16 acc_s[2];
+        if (a.causal && key0 > row0 + 31) return;             // no key of the tile is visible to this wavefront
+        // S^T tile: rows = keys (two 32-key sub-tiles), columns = this wavefront's 32 queries
+        f32x16 acc_s[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc_s[t][r] = 0.f;
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s)
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc_s[t][r] = 0.f;
-#pragma unroll
-                for (int s = 0; s < KSTEPS; ++s) {
-                    const bf16x8 ka = *reinterpret_cast<const bf16x8*>(&kb[(32 * t + col) * KROW + 16 * s + 8 * half]);
-                    acc_s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[s], acc_s[t], 0, 0, 0);
-                }
+                const bf16x8 ka = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
+                    kaddr[s] + ST * TILEB + 32 * t * PITCHB);
+                acc_s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[s], acc_s[t], 0, 0, 0);
             }
-            // mask only where the tile crosses the diagonal or the end of the sequence (wave-uniform)
-            if ((a.causal && key0 + kBN - 1 > row0) || key0 + kBN > a.seq) {
+        // keep 4 K fragments in flight ahead of the MFMA that consumes them
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
 #pragma unroll
-                for (int t = 0; t < 2; ++t)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int kj = key0 + 32 * t + 8 * (r >> 2) + 4 * half + (r & 3);
-                        const bool ok = kj < a.seq && (!a.causal || kj <= qi);
-                        acc_s[t][r] = ok ? acc_s[t][r] : -INFINITY;
-                    }
-            }
-            float mx = acc_s[0][0];
+        for (int i = 0; i < 2 * KSTEPS - 4; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+
+        // mask only where the tile crosses the diagonal or the end of the sequence (wave-uniform)
+        if ((a.causal && key0 + kBN - 1 > row0) || key0 + kBN > a.seq) {
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc_s[t][r]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-            // Rescale only when some row's maximum moved up by more than 8 in the exp2 domain; until
-            // then the stale maximum is kept (terms stay below 2^8, far inside fp32 and bf16 range).
-            if (__any((mx - m_run) * sl2 > 8.0f)) {
-                const float m_new = fmaxf(m_run, mx);
-                const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sl2);   // m_run = -inf -> 0
-                m_run = m_new;
-                l_run *= alpha;
-#pragma unroll
-                for (int t = 0; t < DT; ++t)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc_o[t][r] *= alpha;
-            }
-            const float moff = m_run == -INFINITY ? 0.f : -m_run * sl2;
-            float rs = 0.f;
-            bf16x8 pb[2][2];
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int u = 0; u < 2; ++u)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const float p = __builtin_amdgcn_exp2f(fmaf(acc_s[t][8 * u + e], sl2, moff));
-                        rs += p;
-                        pb[t][u][e] = static_cast<__bf16>(p);
-                    }
-            l_run += rs;
-            // O^T += V^T P^T.  The k-slot (half, e) of step (t, u) is key 32t + 16u + 8(e/4) + 4 half + e%4.
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    const __bf16* vrow = vb + (32 * t + 16 * u + 4 * half + (l16 >> 2)) * VROW + 16 * g16 + 4 * (l16 & 3);
-#pragma unroll
-                    for (int dt = 0; dt < DT; ++dt) {
-                        const s16x4 lo = lds_read_tr16(vrow + 32 * dt);
-                        const s16x4 hi = lds_read_tr16(vrow + 8 * VROW + 32 * dt);
-                        const short va16[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                        bf16x8 va;
-                        __builtin_memcpy(&va, va16, 16);
-                        acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[t][u], acc_o[dt], 0, 0, 0);
-                    }
+                for (int r = 0; r < 16; ++r) {
+                    const int kj = key0 + 32 * t + 8 * (r >> 2) + 4 * half + (r & 3);
+                    const bool ok = kj < a.seq && (!a.causal || kj <= qi);
+                    acc_s[t][r] = ok ? acc_s[t][r] : -INFINITY;
                 }
         }
-        if (kt + 1 < n_tiles) stage(buf ^ 1);                 // the other buffer was released by the last barrier
-        __syncthreads();
-    }
+        float mq[4];
+#pragma unroll
+        for (int c4 = 0; c4 < 4; ++c4) {
+            const f32x16& x = acc_s[c4 >> 1];
+            const int o = 8 * (c4 & 1);
+            mq[c4] = fmaxf(max3(max3(x[o], x[o + 1], x[o + 2]), x[o + 3], x[o + 4]), max3(x[o + 5], x[o + 6], x[o + 7]));
+        }
+        float mx = fmaxf(fmaxf(mq[0], mq[1]), fmaxf(mq[2], mq[3]));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+        // Rescale only when some row's maximum moved up by more than 8 in the exp2 domain; until
+        // then the stale maximum is kept (terms stay below 2^8, far inside fp32 and bf16 range).
+        if (__any((mx - m_run) * sl2 > 8.0f)) {
+            const float m_new = fmaxf(m_run, mx);
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sl2);   // m_run = -inf -> 0
+            m_run = m_new;
+            l_run[0] *= alpha; l_run[1] *= alpha;
+#pragma unroll
+            for (int t = 0; t < DT; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc_o[t][r] *= alpha;
+        }
+        const float moff = m_run == -INFINITY ? 0.f : -m_run * sl2;
+        bf16x8 pb[2][2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                u32x4 packed;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float p0 = __builtin_amdgcn_exp2f(fmaf(acc_s[t][8 * u + 2 * e], sl2, moff));
+                    const float p1 = __builtin_amdgcn_exp2f(fmaf(acc_s[t][8 * u + 2 * e + 1], sl2, moff));
+                    const bf16x2 pp = {static_cast<__bf16>(p0), static_cast<__bf16>(p1)};
+                    packed[e] = __builtin_bit_cast(uint32_t, pp);
+                    // row sum of the rounded probabilities (what the PV product actually uses)
+                    l_run[e & 1] = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, l_run[e & 1], false);
+                }
+                pb[t][u] = __builtin_bit_cast(bf16x8, packed);
+            }
+        // O^T += V^T P^T.  The k-slot (half, e) of step (t, u) is key 32t + 16u + 8(e/4) + 4 half + e%4.
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (__attribute__((address_space(3))) s16x4*)(vaddr[0][dt] + ST * TILEB + (32 * t + 16 * u) * PITCHB));
+                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (__attribute__((address_space(3))) s16x4*)(vaddr[1][dt] + ST * TILEB + (32 * t + 16 * u) * PITCHB));
+                    const s16x8 v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, v8), pb[t][u], acc_o[dt], 0, 0, 0);
+                }
+    };
 
-    const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
+    for (int kt = 0; kt < n_tiles; kt += kStages) {
+        tile(kt, std::integral_constant<int, 0>{});
+        if (kt + 1 < n_tiles) tile(kt + 1, std::integral_constant<int, 1>{});
+        if (kt + 2 < n_tiles) tile(kt + 2, std::integral_constant<int, 2>{});
+        if (kt + 3 < n_tiles) tile(kt + 3, std::integral_constant<int, 3>{});
+    }
+    __syncthreads();                                          // every tile consumed: LDS is free
+
+    float l_sum = l_run[0] + l_run[1];
+    const float l_tot = l_sum + __shfl_xor(l_sum, 32, kWave);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    // Stage the wavefront's 32 x DP output tile in LDS (all tiles are consumed: the loop ended with a
-    // barrier) and write it out as whole 16-byte row segments.
+    // Stage the wavefront's 32 x DP output tile in LDS and write it out as whole 16-byte row segments.
     constexpr int OROW = DP + 8;
+    constexpr int CPR = DP / 8;
     __bf16* o_s = smem + w * 32 * OROW;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
@@ -355,8 +467,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(AttnArgs a)
 template <int DP>
 static constexpr size_t attn_mfma_lds_bytes()
 {
-    constexpr int KROW = DP + 8, VROW = (DP % 64 == 0) ? DP + 32 : DP + 64;
-    return sizeof(__bf16) * 2 * kBN * (KROW + VROW);
+    constexpr int PITCHE = (DP == 64 ? 8 : 16) * 8;
+    return sizeof(__bf16) * 2 * kStages * kBN * PITCHE;
 }
 
 template <int DP>
@@ -364,7 +476,7 @@ static int launch_mfma(AttnArgs& a, hipStream_t s)
 {
     const int group = a.n_q_heads / a.n_kv_heads;
     a.heads_per_block = (group % 4 == 0) ? 4 : (group % 2 == 0) ? 2 : 1;
-    const int rows_per_block = 32 * (4 / a.heads_per_block);
+    const int rows_per_block = 32 * (kAttnWaves / a.heads_per_block);
     a.row_tiles = (a.seq + rows_per_block - 1) / rows_per_block;
     const int64_t blocks = static_cast<int64_t>(a.row_tiles) * (group / a.heads_per_block) * a.n_kv_heads * a.batch;
     if (blocks > INT32_MAX) return CIVIC_ERR_UNSUPPORTED;
@@ -374,7 +486,7 @@ static int launch_mfma(AttnArgs& a, hipStream_t s)
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
         if (attr != hipSuccess) return record_hip_error(attr);
     }
-    hipLaunchKernelGGL((attn_mfma_kernel<DP>), dim3(static_cast<unsigned>(blocks)), dim3(256), lds, s, a);
+    hipLaunchKernelGGL((attn_mfma_kernel<DP>), dim3(static_cast<unsigned>(blocks)), dim3(kAttnThreads), lds, s, a);
     return check_launch();
 }
 
@@ -409,7 +521,8 @@ extern "C" int civic_prefill_attn(const void* q, const void* k, const void* v, v
     a.heads_per_block = 1; a.row_tiles = 0;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
-    if (dtype == CIVIC_BF16 && head_dim <= 128) {
+    // the MFMA path addresses a K/V tile with 32-bit per-lane byte offsets
+    if (dtype == CIVIC_BF16 && head_dim <= 128 && kv_strides[1] * 2 < (1 << 25)) {
         if (head_dim <= 64) return launch_mfma<64>(a, s);
         if (head_dim <= 96) return launch_mfma<96>(a, s);
         return launch_mfma<128>(a, s);
@@ -419,3 +532,4 @@ extern "C" int civic_prefill_attn(const void* q, const void* k, const void* v, v
     else hipLaunchKernelGGL((attn_plain_kernel<false>), grid, dim3(256), 0, s, a);
     return check_launch();
 }
+
