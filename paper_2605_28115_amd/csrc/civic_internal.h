@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "civic.h"
 
 namespace civic {
@@ -43,11 +45,25 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 template <typename T>
 __device__ __forceinline__ T load_streaming(const T* p) { return __builtin_nontemporal_load(p); }
 
+// Sum over the 64 lanes of a wavefront, returned in every lane.  Data-parallel-primitive (DPP) adds:
+// an inclusive scan inside each row of 16 lanes (row_shr 1, 2, 4, 8), then the row totals are carried
+// across rows (row_bcast 15 into rows 1 and 3, row_bcast 31 into rows 2 and 3) so that lane 63 holds
+// the total; no LDS traffic, unlike a shuffle.
 __device__ __forceinline__ float wave_sum(float v)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
-    return v;
+    auto dpp_add = [](float x, auto ctrl, auto row_mask) {
+        const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(x), decltype(ctrl)::value,
+                                                      decltype(row_mask)::value, 0xF, false);
+        return x + __int_as_float(moved);
+    };
+    using std::integral_constant;
+    v = dpp_add(v, integral_constant<int, 0x111>{}, integral_constant<int, 0xF>{});   // row_shr:1
+    v = dpp_add(v, integral_constant<int, 0x112>{}, integral_constant<int, 0xF>{});   // row_shr:2
+    v = dpp_add(v, integral_constant<int, 0x114>{}, integral_constant<int, 0xF>{});   // row_shr:4
+    v = dpp_add(v, integral_constant<int, 0x118>{}, integral_constant<int, 0xF>{});   // row_shr:8
+    v = dpp_add(v, integral_constant<int, 0x142>{}, integral_constant<int, 0xA>{});   // row_bcast:15 -> rows 1, 3
+    v = dpp_add(v, integral_constant<int, 0x143>{}, integral_constant<int, 0xC>{});   // row_bcast:31 -> rows 2, 3
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) { return __uint_as_float(bits16 << 16); }

@@ -36,6 +36,7 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
 {
     __shared__ int32_t kb[CIVIC_MAX_FRAMES + 1];
     __shared__ int32_t row_src[kCompactMaxRows];
+    __shared__ int32_t fstart[CIVIC_MAX_FRAMES];   // frame_start - f*HW: text tokens before frame f
 
     const int tid = threadIdx.x;
     const int b = blockIdx.y;
@@ -43,17 +44,33 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
     const int32_t nrows = min(rows_per_block, seq_c - j0);
     const int32_t* kept = kept_idx + static_cast<int64_t>(b) * n_kept;
     const int32_t F = ft.n, hw = ft.hw;
+    if (tid < F) fstart[tid] = ft.start[tid] - tid * hw;
 
-    for (int32_t i = tid; i <= n_kept; i += kCompactThreads) {
-        int32_t f_prev = -1, f_cur = F;
-        if (i > 0) f_prev = min(max(kept[i - 1] / hw, 0), F - 1);
-        if (i < n_kept) {
-            const int32_t v = kept[i];
-            f_cur = min(max(v / hw, 0), F - 1);
-            const int32_t j = ft.start[f_cur] - f_cur * hw + i - j0;      // compact slot of this kept token
-            if (j >= 0 && j < nrows) row_src[j] = ft.start[f_cur] + v - f_cur * hw;
+    __syncthreads();
+    // Entries are visited four strided positions per thread at a time, all loads of a batch issued
+    // before any is used (one memory latency per batch instead of one per entry).
+    for (int32_t base = 0; base <= n_kept; base += kCompactThreads * 4) {
+        int32_t cur[4], prev[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int32_t i = base + u * kCompactThreads + tid;
+            cur[u] = i < n_kept ? kept[i] : 0;
+            prev[u] = (i > 0 && i <= n_kept) ? kept[i - 1] : 0;
         }
-        for (int32_t f = f_prev + 1; f <= f_cur; ++f) kb[f] = i;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int32_t i = base + u * kCompactThreads + tid;
+            if (i > n_kept) continue;
+            int32_t f_prev = -1, f_cur = F;
+            if (i > 0) f_prev = min(max(prev[u] / hw, 0), F - 1);
+            if (i < n_kept) {
+                const int32_t v = cur[u];
+                f_cur = min(max(v / hw, 0), F - 1);
+                const int32_t j = fstart[f_cur] + i - j0;                  // compact slot of this kept token
+                if (j >= 0 && j < nrows) row_src[j] = fstart[f_cur] + v;
+            }
+            for (int32_t f = f_prev + 1; f <= f_cur; ++f) kb[f] = i;
+        }
     }
     __syncthreads();
 
@@ -63,13 +80,13 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
         int32_t lo = 0, hi = F;
         while (lo < hi) {
             const int32_t mid = (lo + hi) >> 1;
-            if (ft.start[mid] - mid * hw + kb[mid] <= j) lo = mid + 1; else hi = mid;
+            if (fstart[mid] + kb[mid] <= j) lo = mid + 1; else hi = mid;
         }
         if (lo == 0) {
             row_src[r] = j;                                           // text before the first frame
         } else {
             const int32_t f = lo - 1;
-            const int32_t vis_end = ft.start[f] - f * hw + kb[f + 1];  // end of frame f's kept tokens
+            const int32_t vis_end = fstart[f] + kb[f + 1];              // end of frame f's kept tokens
             if (j >= vis_end) row_src[r] = j + lo * hw - kb[lo];      // text: add the dropped tokens back
         }
     }
@@ -103,14 +120,22 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
                 out[u] = reinterpret_cast<V*>(out_b + static_cast<int64_t>(r) * row_bytes);
             }
         }
-        for (int32_t c = c0; c < vpr; c += threads_per_row) {
-            V val[kCompactUnroll];
+        // two column steps x kCompactUnroll rows: up to 8 independent 16-byte loads before the first store
+        for (int32_t c = c0; c < vpr; c += 2 * threads_per_row) {
+            V val[2][kCompactUnroll];
+            const bool second = c + threads_per_row < vpr;
 #pragma unroll
             for (int u = 0; u < kCompactUnroll; ++u)
-                if (in[u]) val[u] = load_streaming(in[u] + c);
+                if (in[u]) {
+                    val[0][u] = load_streaming(in[u] + c);
+                    if (second) val[1][u] = load_streaming(in[u] + c + threads_per_row);
+                }
 #pragma unroll
             for (int u = 0; u < kCompactUnroll; ++u)
-                if (out[u]) out[u][c] = val[u];
+                if (out[u]) {
+                    out[u][c] = val[0][u];
+                    if (second) out[u][c + threads_per_row] = val[1][u];
+                }
         }
     }
 }

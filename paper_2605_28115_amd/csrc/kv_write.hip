@@ -18,29 +18,28 @@ struct KvArgs {
     int64_t s_max, pos0;
     int32_t seq, n_kv_heads, chunks_per_head;
     int32_t chunks_per_token;                // n_kv_heads * chunks_per_head
+    int32_t total;                           // seq * chunks_per_token (< 2^31)
 };
 
 __global__ __launch_bounds__(kKvThreads) void kv_write_kernel(KvArgs a)
 {
     const int b = blockIdx.y;
-    const u32x4* __restrict__ src = a.src[blockIdx.z];
-    u32x4* __restrict__ dst = a.dst[blockIdx.z];
-    const int64_t total = static_cast<int64_t>(a.seq) * a.chunks_per_token;
-    const int64_t base = static_cast<int64_t>(blockIdx.x) * (kKvThreads * kKvUnroll) + threadIdx.x;
+    const u32x4* __restrict__ src = a.src[blockIdx.z] + b * a.stride_b;
+    u32x4* __restrict__ dst = a.dst[blockIdx.z] + static_cast<int64_t>(b) * a.n_kv_heads * a.s_max * a.chunks_per_head;
+    const uint32_t base = blockIdx.x * (kKvThreads * kKvUnroll) + threadIdx.x;
+    const uint32_t cpt = a.chunks_per_token, cph = a.chunks_per_head;
 
     u32x4 val[kKvUnroll];
     int64_t out[kKvUnroll];
 #pragma unroll
     for (int u = 0; u < kKvUnroll; ++u) {
-        const int64_t idx = base + static_cast<int64_t>(u) * kKvThreads;
+        const uint32_t idx = base + u * kKvThreads;
         out[u] = -1;
-        if (idx < total) {
-            const int32_t tok = static_cast<int32_t>(idx / a.chunks_per_token);
-            const int32_t rem = static_cast<int32_t>(idx - static_cast<int64_t>(tok) * a.chunks_per_token);
-            const int32_t head = rem / a.chunks_per_head;
-            const int32_t c = rem - head * a.chunks_per_head;
-            val[u] = load_streaming(src + b * a.stride_b + tok * a.stride_t + head * a.stride_h + c);
-            out[u] = ((static_cast<int64_t>(b) * a.n_kv_heads + head) * a.s_max + a.pos0 + tok) * a.chunks_per_head + c;
+        if (idx < static_cast<uint32_t>(a.total)) {
+            const uint32_t tok = idx / cpt, rem = idx - tok * cpt;
+            const uint32_t head = rem / cph, c = rem - head * cph;
+            val[u] = load_streaming(src + tok * a.stride_t + head * a.stride_h + c);
+            out[u] = (head * a.s_max + a.pos0 + tok) * cph + c;
         }
     }
 #pragma unroll
@@ -76,6 +75,8 @@ extern "C" int civic_kv_write(const void* k, const void* v, const int64_t* kv_st
     a.chunks_per_head = head_dim * esz / 16;
     a.chunks_per_token = n_kv_heads * a.chunks_per_head;
     const int64_t total = static_cast<int64_t>(seq) * a.chunks_per_token;
+    if (total > INT32_MAX) return CIVIC_ERR_UNSUPPORTED;
+    a.total = static_cast<int32_t>(total);
     const int64_t per_block = kKvThreads * kKvUnroll;
     const int64_t blocks = (total + per_block - 1) / per_block;
     if (blocks > INT32_MAX) return CIVIC_ERR_UNSUPPORTED;

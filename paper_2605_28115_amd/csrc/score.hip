@@ -3,8 +3,9 @@
 // One wavefront owns a row at a time.  The row is fetched once with 16-byte loads (lane l takes
 // chunks l, l+64, ...) and held in registers, so the centred second pass (norm and dot product of
 // x - mean) costs no second trip to memory and has none of the cancellation a one-pass
-// sum-of-squares formula would have.  The anchor chunks a lane needs are the same for every row
-// and stay in registers for the lifetime of the wave.
+// sum-of-squares formula would have.  The anchor is staged once per 16-wave block in LDS; the three
+// wave-wide sums are DPP reductions.  The next row's loads are issued before the reductions of the
+// current one.
 #include "civic_internal.h"
 
 namespace civic {
@@ -31,67 +32,77 @@ template <> struct Chunk<false> {
     }
 };
 
+constexpr int kScoreThreads = 512;    // 8 wavefronts share one copy of the anchor in LDS
+
 template <int CHUNKS, bool BF16>
-__global__ __launch_bounds__(256) void score_kernel(const uint8_t* __restrict__ hidden, int64_t n_rows,
-                                                    int64_t row_stride_bytes, int32_t dim,
-                                                    const float* __restrict__ anchor_q, float inv_tau,
-                                                    float* __restrict__ scores)
+__global__ __launch_bounds__(kScoreThreads, 2) void score_kernel(const uint8_t* __restrict__ hidden, int64_t n_rows,
+                                                              int64_t row_stride_bytes, int32_t dim,
+                                                              const float* __restrict__ anchor_q, float inv_tau,
+                                                              float* __restrict__ scores)
 {
     constexpr int E = Chunk<BF16>::kElems;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int64_t wave = (static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x) >> 6;
-    const int64_t n_waves = (static_cast<int64_t>(gridDim.x) * blockDim.x) >> 6;
+    extern __shared__ __attribute__((aligned(16))) float q_s[];      // [dim]
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
     const int n_chunks = dim / E;
     const float inv_dim = 1.0f / static_cast<float>(dim);
+    const int64_t first = static_cast<int64_t>(blockIdx.x) * (kScoreThreads / kWave) + wave;
+    const int64_t step = static_cast<int64_t>(gridDim.x) * (kScoreThreads / kWave);
 
-    float q[CHUNKS][E];
-#pragma unroll
-    for (int c = 0; c < CHUNKS; ++c) {
-        const int ch = c * kWave + lane;
-#pragma unroll
-        for (int e = 0; e < E; e += 4) {
-            float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (ch < n_chunks) t = *reinterpret_cast<const float4*>(anchor_q + ch * E + e);
-            q[c][e] = t.x; q[c][e + 1] = t.y; q[c][e + 2] = t.z; q[c][e + 3] = t.w;
-        }
-    }
-
-    for (int64_t row = wave; row < n_rows; row += n_waves) {
+    // The first row's loads go out before anything else; the anchor is staged while they are in flight.
+    u32x4 raw[CHUNKS];
+    auto fetch = [&](int64_t row) {
         const u32x4* src = reinterpret_cast<const u32x4*>(hidden + row * row_stride_bytes);
-        u32x4 raw[CHUNKS];
 #pragma unroll
         for (int c = 0; c < CHUNKS; ++c) {
             const int ch = c * kWave + lane;
             raw[c] = u32x4{0u, 0u, 0u, 0u};
             if (ch < n_chunks) raw[c] = load_streaming(src + ch);
         }
-        // first element of the row, for the exact "no variance" test (equal elements <=> max == min)
-        const float first = __uint_as_float(__builtin_amdgcn_readfirstlane(BF16 ? (raw[0].x << 16) : raw[0].x));
+    };
+    if (first < n_rows) fetch(first);
+    for (int i = threadIdx.x * 4; i < dim; i += kScoreThreads * 4)
+        *reinterpret_cast<float4*>(q_s + i) = *reinterpret_cast<const float4*>(anchor_q + i);
+    __syncthreads();
+
+    for (int64_t row = first; row < n_rows; row += step) {
+        // Pass 1: row sum, and the exact "no variance" test (every 32-bit word equals the first one
+        // with its halves equal, i.e. every element carries the same bits).
+        const uint32_t w0 = __builtin_amdgcn_readfirstlane(raw[0].x);
+        const bool w0_uniform = !BF16 || (w0 >> 16) == (w0 & 0xFFFFu);
         float sum = 0.f;
-        bool same = true;
+        bool same = w0_uniform;
 #pragma unroll
         for (int c = 0; c < CHUNKS; ++c) {
             const bool live = (c * kWave + lane) < n_chunks;
+            same = same && (!live || (raw[c].x == w0 && raw[c].y == w0 && raw[c].z == w0 && raw[c].w == w0));
             float x[E];
-            Chunk<BF16>::unpack(raw[c], x);
+            Chunk<BF16>::unpack(raw[c], x);                   // dead chunks are zero filled and add nothing
 #pragma unroll
-            for (int e = 0; e < E; ++e) { sum += x[e]; same = same && (!live || x[e] == first); }
+            for (int e = 0; e < E; ++e) sum += x[e];
         }
         const bool constant_row = __ballot(!same) == 0ull;
         const float mean = wave_sum(sum) * inv_dim;
         float n2 = 0.f, dot = 0.f;
 #pragma unroll
         for (int c = 0; c < CHUNKS; ++c) {
-            const bool live = (c * kWave + lane) < n_chunks;
-            float x[E];
-            Chunk<BF16>::unpack(raw[c], x);
+            const int ch = c * kWave + lane;
+            if (ch < n_chunks) {
+                float x[E], q[E];
+                Chunk<BF16>::unpack(raw[c], x);
 #pragma unroll
-            for (int e = 0; e < E; ++e) {
-                const float d = live ? x[e] - mean : 0.f;
-                n2 = fmaf(d, d, n2);
-                dot = fmaf(q[c][e], d, dot);
+                for (int e = 0; e < E; e += 4) {
+                    const float4 t = *reinterpret_cast<const float4*>(q_s + ch * E + e);
+                    q[e] = t.x; q[e + 1] = t.y; q[e + 2] = t.z; q[e + 3] = t.w;
+                }
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    const float d = x[e] - mean;
+                    n2 = fmaf(d, d, n2);
+                    dot = fmaf(q[e], d, dot);
+                }
             }
         }
+        if (row + step < n_rows) fetch(row + step);          // next row in flight during the reductions
         n2 = wave_sum(n2);
         dot = wave_sum(dot);
         if (lane == 0) scores[row] = (n2 > 0.f && !constant_row) ? inv_tau * dot / sqrtf(n2) : 0.f;
@@ -102,17 +113,19 @@ template <int CHUNKS>
 static int launch_score(bool bf16, const void* hidden, int64_t n_rows, int64_t row_stride_bytes, int32_t dim,
                         const float* anchor_q, float inv_tau, float* scores, hipStream_t stream)
 {
-    // 16 resident waves per CU on 256 CUs keep enough 16-byte loads in flight to cover HBM latency.
-    const int64_t max_waves = 256 * 16;
-    int64_t waves = n_rows < max_waves ? n_rows : max_waves;
-    const unsigned blocks = static_cast<unsigned>((waves + 3) / 4);
+    // Two 8-wave blocks per CU on 256 CUs; a wavefront loops over its rows with the next row's loads in
+    // flight while the current one is reduced, so the vector work overlaps the stream from HBM.
+    constexpr int rows_per_block = kScoreThreads / kWave;
+    int64_t blocks = (n_rows + rows_per_block - 1) / rows_per_block;
+    if (blocks > 256 * 2) blocks = 256 * 2;
     const uint8_t* h = static_cast<const uint8_t*>(hidden);
+    const size_t lds = sizeof(float) * static_cast<size_t>(dim);
     if (bf16)
-        hipLaunchKernelGGL((score_kernel<CHUNKS, true>), dim3(blocks), dim3(256), 0, stream, h, n_rows,
-                           row_stride_bytes, dim, anchor_q, inv_tau, scores);
+        hipLaunchKernelGGL((score_kernel<CHUNKS, true>), dim3(static_cast<unsigned>(blocks)), dim3(kScoreThreads), lds,
+                           stream, h, n_rows, row_stride_bytes, dim, anchor_q, inv_tau, scores);
     else
-        hipLaunchKernelGGL((score_kernel<CHUNKS, false>), dim3(blocks), dim3(256), 0, stream, h, n_rows,
-                           row_stride_bytes, dim, anchor_q, inv_tau, scores);
+        hipLaunchKernelGGL((score_kernel<CHUNKS, false>), dim3(static_cast<unsigned>(blocks)), dim3(kScoreThreads), lds,
+                           stream, h, n_rows, row_stride_bytes, dim, anchor_q, inv_tau, scores);
     return check_launch();
 }
 
