@@ -5,8 +5,8 @@
 // mark bit per token.  The strict order "higher score first, equal scores to the lower index" becomes
 // (key ascending, index ascending) after mapping the float bits to an unsigned key (with -0 folded
 // onto +0).
-//   cells   small cells: every token counts the members of its cell that precede it (all pairs in
-//           LDS); the wavefront ballot of "rank < floor" IS the 64-bit mark word of those 64 tokens.
+//   cells   small cells: one thread per cell picks the cell's best remaining member cell_floor times
+//           (members scanned in index order, strict key comparison = the tie rule).
 //           large cells: one wavefront per cell runs the radix select below.
 //   frames  one wavefront per frame: radix select (4 passes of 8 bits over a per-wave LDS histogram)
 //           finds the key of the frame_floor-th unmarked token; equal keys are admitted in index
@@ -29,6 +29,7 @@ struct SelArgs {
     int32_t frames, height, width, hw, nv, nv_pad;
     int32_t cell_h, cell_w, cell_floor, frame_floor;
     int32_t cells_y, cells_x;
+    int32_t floor_sum;     // tokens the floors protect
     int32_t fill;          // tokens the global budget adds after the floors
     int32_t kept;          // K
     int32_t big_cells;     // 1: cells go through the per-wave radix select
@@ -42,22 +43,37 @@ __device__ __forceinline__ uint32_t order_key(float s)
     return ~asc;                                                 // higher score -> smaller key
 }
 
-// A rectangle of one frame in raster order: token i -> base + (i / w) * pitch + i % w.
+// A rectangle of one frame in raster order: token i -> base + (i / w) * pitch + i % w.  CONTIG: the
+// rectangle spans whole grid rows (w == pitch), so token i is simply base + i.
 struct Region {
     int32_t base, w, pitch, count;
-    __device__ __forceinline__ int32_t token(int32_t i) const { return base + (i / w) * pitch + (i % w); }
+    template <bool CONTIG>
+    __device__ __forceinline__ int32_t token(int32_t i) const
+    {
+        if constexpr (CONTIG) return base + i;
+        else return base + (i / w) * pitch + (i % w);
+    }
 };
 
 __device__ __forceinline__ bool is_marked(const uint32_t* marks, int32_t v) { return (marks[v >> 5] >> (v & 31)) & 1u; }
 __device__ __forceinline__ void set_mark(uint32_t* marks, int32_t v) { atomicOr(&marks[v >> 5], 1u << (v & 31)); }
 
-__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, int lane)
+// Inclusive prefix sum over the 64 lanes with DPP adds: scan inside each row of 16 lanes (row_shr 1, 2,
+// 4, 8; lanes without a source keep their value), then carry row totals forward (row_bcast 15 into rows
+// 1 and 3, row_bcast 31 into rows 2 and 3).
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, int)
 {
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        const uint32_t t = __shfl_up(v, off, kWave);
-        if (lane >= off) v += t;
-    }
+    auto step = [](uint32_t x, auto ctrl, auto row_mask) {
+        return x + static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), decltype(ctrl)::value,
+                                                                      decltype(row_mask)::value, 0xF, false));
+    };
+    using std::integral_constant;
+    v = step(v, integral_constant<int, 0x111>{}, integral_constant<int, 0xF>{});
+    v = step(v, integral_constant<int, 0x112>{}, integral_constant<int, 0xF>{});
+    v = step(v, integral_constant<int, 0x114>{}, integral_constant<int, 0xF>{});
+    v = step(v, integral_constant<int, 0x118>{}, integral_constant<int, 0xF>{});
+    v = step(v, integral_constant<int, 0x142>{}, integral_constant<int, 0xA>{});
+    v = step(v, integral_constant<int, 0x143>{}, integral_constant<int, 0xC>{});
     return v;
 }
 
@@ -76,11 +92,13 @@ __device__ __forceinline__ void team_sync()
 
 // Marks the first m tokens, in (key, index) order, among the eligible tokens of `reg`; eligible means
 // not marked yet when only_unmarked is set.  Run by one wavefront (BLOCK = false) or by the whole
-// workgroup (BLOCK = true; every thread must call it with the same arguments).
-//   hist  256 counters owned by the team;  bc  4 words owned by the team.
-template <bool BLOCK>
+// workgroup (BLOCK = true; every thread must call it with the same arguments, and `eligible` must be
+// given).  eligible < 0 (wavefront only): counted here.
+//   hist  counters owned by the team: 2 x 256 for the workgroup (double buffered, so the next pass's
+//         clear hides behind the scan), 256 for a wavefront;  bc  8 words owned by the team.
+template <bool BLOCK, bool CONTIG>
 __device__ void select_first(const uint32_t* keys, uint32_t* marks, uint32_t* hist, uint32_t* bc, const Region reg,
-                             int32_t m, bool only_unmarked)
+                             int32_t m, bool only_unmarked, int32_t eligible)
 {
     constexpr int TEAM = BLOCK ? kSelThreads : kWave;
     const int rank = BLOCK ? threadIdx.x : (threadIdx.x & (kWave - 1));
@@ -88,64 +106,69 @@ __device__ void select_first(const uint32_t* keys, uint32_t* marks, uint32_t* hi
     const int32_t n_iter = (reg.count + TEAM - 1) / TEAM;
     if (m <= 0) return;
 
-    // eligible count
-    if (rank == 0) bc[0] = 0;
-    team_sync<BLOCK>();
-    for (int32_t it = 0; it < n_iter; ++it) {
-        const int32_t i = it * TEAM + rank;
-        bool e = false;
-        if (i < reg.count) { const int32_t v = reg.token(i); e = !(only_unmarked && is_marked(marks, v)); }
-        const uint64_t bal = __ballot(e);
-        if (lane == 0 && bal) atomicAdd(&bc[0], static_cast<uint32_t>(__popcll(bal)));
+    if (!BLOCK && eligible < 0) {                                // wave-uniform count from ballots
+        eligible = 0;
+        for (int32_t it = 0; it < n_iter; ++it) {
+            const int32_t i = it * TEAM + rank;
+            bool e = false;
+            if (i < reg.count) { const int32_t v = reg.token<CONTIG>(i); e = !(only_unmarked && is_marked(marks, v)); }
+            eligible += __popcll(__ballot(e));
+        }
     }
-    team_sync<BLOCK>();
-    const int32_t eligible = static_cast<int32_t>(bc[0]);
-    team_sync<BLOCK>();
     if (m >= eligible) {                                         // floor covers everything that is left
         for (int32_t it = 0; it < n_iter; ++it) {
             const int32_t i = it * TEAM + rank;
-            if (i < reg.count) { const int32_t v = reg.token(i); if (!(only_unmarked && is_marked(marks, v))) set_mark(marks, v); }
+            if (i < reg.count) { const int32_t v = reg.token<CONTIG>(i); if (!(only_unmarked && is_marked(marks, v))) set_mark(marks, v); }
         }
         team_sync<BLOCK>();
         return;
     }
 
     // Radix select of the m-th smallest key among the eligible tokens: 4 digits of 8 bits, high first.
+    for (int i = rank; i < (BLOCK ? 512 : 256); i += TEAM) hist[i] = 0;
+    team_sync<BLOCK>();
     uint32_t prefix = 0, remaining = static_cast<uint32_t>(m), ties = 0;
 #pragma unroll 1
-    for (int shift = 24; shift >= 0; shift -= 8) {
-        for (int i = rank; i < 256; i += TEAM) hist[i] = 0;
-        team_sync<BLOCK>();
-        const uint32_t hi_mask = shift == 24 ? 0u : (0xFFFFFFFFu << (shift + 8));
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+        uint32_t* h = hist + (BLOCK ? (pass & 1) * 256 : 0);
+        const uint32_t hi_mask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
         for (int32_t it = 0; it < n_iter; ++it) {
             const int32_t i = it * TEAM + rank;
             if (i < reg.count) {
-                const int32_t v = reg.token(i);
+                const int32_t v = reg.token<CONTIG>(i);
                 const uint32_t k = keys[v];
-                if (!(only_unmarked && is_marked(marks, v)) && (k & hi_mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
+                if ((k & hi_mask) == prefix && !(only_unmarked && is_marked(marks, v))) atomicAdd(&h[(k >> shift) & 255u], 1u);
             }
         }
         team_sync<BLOCK>();
         if (!BLOCK || threadIdx.x < kWave) {                     // one wavefront scans the 256 bins
             uint32_t c[4];
 #pragma unroll
-            for (int t = 0; t < 4; ++t) c[t] = hist[lane * 4 + t];
+            for (int t = 0; t < 4; ++t) c[t] = h[lane * 4 + t];
             const uint32_t mine = c[0] + c[1] + c[2] + c[3];
             const uint32_t incl = wave_incl_scan(mine, lane);
             uint32_t before = incl - mine;
             if (before < remaining && remaining <= incl) {       // exactly one lane
                 int t = 0;
                 while (before + c[t] < remaining) { before += c[t]; ++t; }
-                bc[0] = static_cast<uint32_t>(lane * 4 + t);       // digit
-                bc[1] = before;                                   // eligible tokens below that digit
-                bc[2] = c[t];                                     // tokens with that digit
+                bc[(pass & 1) * 4 + 0] = static_cast<uint32_t>(lane * 4 + t);   // digit
+                bc[(pass & 1) * 4 + 1] = before;                                // eligible tokens below that digit
+                bc[(pass & 1) * 4 + 2] = c[t];                                  // tokens with that digit
             }
         }
-        team_sync<BLOCK>();
-        prefix |= bc[0] << shift;
-        remaining -= bc[1];
-        ties = bc[2];
-        team_sync<BLOCK>();
+        if constexpr (BLOCK) {
+            // the other histogram is cleared for the next pass while this one is scanned
+            if (threadIdx.x >= kWave && threadIdx.x < kWave + 256) hist[((pass + 1) & 1) * 256 + threadIdx.x - kWave] = 0;
+            __syncthreads();
+        } else {
+            team_sync<false>();
+            for (int i = lane; i < 256; i += kWave) hist[i] = 0;      // a wavefront orders its own LDS traffic for free
+            team_sync<false>();
+        }
+        prefix |= bc[(pass & 1) * 4 + 0] << shift;
+        remaining -= bc[(pass & 1) * 4 + 1];
+        ties = bc[(pass & 1) * 4 + 2];
     }
     // prefix is now the threshold key; `remaining` of the `ties` tokens that carry it are admitted.
 
@@ -153,7 +176,7 @@ __device__ void select_first(const uint32_t* keys, uint32_t* marks, uint32_t* hi
         for (int32_t it = 0; it < n_iter; ++it) {
             const int32_t i = it * TEAM + rank;
             if (i < reg.count) {
-                const int32_t v = reg.token(i);
+                const int32_t v = reg.token<CONTIG>(i);
                 if (!(only_unmarked && is_marked(marks, v)) && keys[v] <= prefix) set_mark(marks, v);
             }
         }
@@ -165,12 +188,13 @@ __device__ void select_first(const uint32_t* keys, uint32_t* marks, uint32_t* hi
     // ballot prefix inside a wavefront plus a running count across wavefronts gives each its rank.
     uint32_t running = 0;
     uint32_t* wave_cnt = hist;                                   // reuse: kSelWaves counters
+    team_sync<BLOCK>();
     for (int32_t it = 0; it < n_iter; ++it) {
         const int32_t i = it * TEAM + rank;
         bool eq = false;
         int32_t v = 0;
         if (i < reg.count) {
-            v = reg.token(i);
+            v = reg.token<CONTIG>(i);
             if (!(only_unmarked && is_marked(marks, v))) {
                 const uint32_t k = keys[v];
                 if (k < prefix) set_mark(marks, v);
@@ -201,9 +225,9 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelArgs a)
     extern __shared__ uint32_t smem[];
     uint32_t* keys = smem;                                   // [nv_pad]
     uint32_t* marks = keys + a.nv_pad;                       // [nv_pad / 32]
-    uint32_t* hist = marks + a.nv_pad / 32;                  // [kSelWaves][256]
-    uint32_t* bcast = hist + kSelWaves * 256;                // [kSelWaves][4]
-    uint32_t* word_prefix = bcast + kSelWaves * 4;           // [nv_pad / 64]
+    uint32_t* hist = marks + a.nv_pad / 32;                  // [kSelWaves][256]; the workgroup-wide select uses the first 512
+    uint32_t* bcast = hist + kSelWaves * 256;                // [kSelWaves][8]
+    uint32_t* word_prefix = bcast + kSelWaves * 8;           // [nv_pad / 64]
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
     const int b = blockIdx.x;
@@ -216,33 +240,39 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelArgs a)
     // ---- (1) cell floors
     if (a.cell_floor > 0) {
         if (!a.big_cells) {
-            for (int32_t v0 = 0; v0 < a.nv_pad; v0 += kSelThreads) {
-                const int32_t v = v0 + tid;
-                bool mark = false;
-                if (v < a.nv) {
-                    const int32_t f = v / a.hw, rem = v - f * a.hw;
-                    const int32_t r = rem / a.width, c = rem - r * a.width;
-                    const int32_t r0 = (r / a.cell_h) * a.cell_h, c0 = (c / a.cell_w) * a.cell_w;
-                    const int32_t r1 = min(r0 + a.cell_h, a.height), c1 = min(c0 + a.cell_w, a.width);
-                    if ((r1 - r0) * (c1 - c0) <= a.cell_floor) {
-                        mark = true;
-                    } else {
-                        const uint32_t kv = keys[v];
-                        int32_t ahead = 0;
-                        for (int32_t rr = r0; rr < r1; ++rr) {
-                            const int32_t u0 = f * a.hw + rr * a.width;
-                            for (int32_t cc = c0; cc < c1; ++cc) {
-                                const uint32_t ku = keys[u0 + cc];
-                                ahead += (ku < kv || (ku == kv && u0 + cc < v)) ? 1 : 0;
+            // One thread per cell: cell_floor rounds of "best member after the previous winner".  Members
+            // are scanned in ascending index with a strict key comparison, which is the tie rule.  The
+            // work is cells * floor * size instead of tokens * size for an all-pairs rank.
+            const int32_t cells_f = a.cells_y * a.cells_x, cells = a.frames * cells_f;
+            for (int32_t cell = tid; cell < cells; cell += kSelThreads) {
+                const int32_t f = cell / cells_f, rem = cell - f * cells_f;
+                const int32_t cy = rem / a.cells_x, cx = rem - cy * a.cells_x;
+                const int32_t r0 = cy * a.cell_h, c0 = cx * a.cell_w;
+                const int32_t r1 = min(r0 + a.cell_h, a.height), c1 = min(c0 + a.cell_w, a.width);
+                const int32_t base = f * a.hw;
+                const int32_t rounds = min(a.cell_floor, (r1 - r0) * (c1 - c0));
+                uint32_t last_key = 0;
+                int32_t last_idx = -1;                             // nothing chosen yet
+                for (int32_t k = 0; k < rounds; ++k) {
+                    uint32_t best_key = 0xFFFFFFFFu;
+                    int32_t best_idx = -1;
+                    for (int32_t rr = r0; rr < r1; ++rr) {
+                        const int32_t u0 = base + rr * a.width;
+                        for (int32_t cc = c0; cc < c1; cc += 4) {           // 4 independent LDS reads at a time
+                            uint32_t ku[4];
+#pragma unroll
+                            for (int x = 0; x < 4; ++x) ku[x] = cc + x < c1 ? keys[u0 + cc + x] : 0xFFFFFFFFu;
+#pragma unroll
+                            for (int x = 0; x < 4; ++x) {
+                                const int32_t u = u0 + cc + x;
+                                const bool after_last = last_idx < 0 || ku[x] > last_key || (ku[x] == last_key && u > last_idx);
+                                const bool better = best_idx < 0 || ku[x] < best_key;
+                                if (cc + x < c1 && after_last && better) { best_key = ku[x]; best_idx = u; }
                             }
                         }
-                        mark = ahead < a.cell_floor;
                     }
-                }
-                const uint64_t bal = __ballot(mark);
-                if (lane == 0 && v < a.nv_pad) {
-                    marks[v >> 5] = static_cast<uint32_t>(bal);
-                    marks[(v >> 5) + 1] = static_cast<uint32_t>(bal >> 32);
+                    if (best_idx >= 0) set_mark(marks, best_idx);
+                    last_key = best_key; last_idx = best_idx;
                 }
             }
         } else {
@@ -253,7 +283,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelArgs a)
                 const int32_t r0 = cy * a.cell_h, c0 = cx * a.cell_w;
                 const int32_t hgt = min(a.cell_h, a.height - r0), wid = min(a.cell_w, a.width - c0);
                 const Region reg{f * a.hw + r0 * a.width + c0, wid, a.width, hgt * wid};
-                select_first<false>(keys, marks, hist + wave * 256, bcast + wave * 4, reg, a.cell_floor, false);
+                select_first<false, false>(keys, marks, hist + wave * 256, bcast + wave * 8, reg, a.cell_floor, false, hgt * wid);
             }
         }
         __syncthreads();
@@ -263,7 +293,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelArgs a)
     if (a.frame_floor > 0) {
         for (int32_t f = wave; f < a.frames; f += kSelWaves) {
             const Region reg{f * a.hw, a.hw, a.hw, a.hw};
-            select_first<false>(keys, marks, hist + wave * 256, bcast + wave * 4, reg, a.frame_floor, true);
+            select_first<false, true>(keys, marks, hist + wave * 256, bcast + wave * 8, reg, a.frame_floor, true, -1);
         }
         __syncthreads();
     }
@@ -271,7 +301,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelArgs a)
     // ---- (3) global budget
     if (a.fill > 0) {
         const Region reg{0, a.nv, a.nv, a.nv};
-        select_first<true>(keys, marks, hist, bcast, reg, a.fill, true);
+        select_first<true, true>(keys, marks, hist, bcast, reg, a.fill, true, a.nv - a.floor_sum);
     }
     __syncthreads();
 
@@ -324,11 +354,11 @@ extern "C" int civic_select(const float* scores, int32_t batch, const civic_grid
     a.cell_floor = gi.cell_floor; a.frame_floor = gi.frame_floor;
     a.cells_y = (gi.height + a.cell_h - 1) / a.cell_h;
     a.cells_x = (gi.width + a.cell_w - 1) / a.cell_w;
-    a.fill = gi.fill; a.kept = gi.kept;
+    a.floor_sum = gi.floor_sum; a.fill = gi.fill; a.kept = gi.kept;
     a.big_cells = static_cast<int64_t>(a.cell_h) * a.cell_w > kSmallCell ? 1 : 0;
 
     const size_t lds = sizeof(uint32_t) * (static_cast<size_t>(a.nv_pad) + a.nv_pad / 32 + kSelWaves * 256 +
-                                           kSelWaves * 4 + a.nv_pad / 64 + 2);
+                                           kSelWaves * 8 + a.nv_pad / 64 + 2);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel),
