@@ -35,6 +35,10 @@ from paper_2605_28115_amd import workloads as wl
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 STAGES = ("score", "select", "compact", "attn", "kv_write")
+# HBM bytes per attention launch from the profiler's FETCH_SIZE / WRITE_SIZE counters, each scaled by what the
+# same counter reads for a plain copy of known size (profiles/bench_8b_hbm_traffic.txt); measured offline,
+# per workload, and only quoted here.
+MEASURED_ATTN_TRAFFIC_BYTES = {"8b": 78.10e6}
 
 
 def dev(storage: np.ndarray) -> torch.Tensor:
@@ -149,6 +153,9 @@ def main() -> int:
     ap.add_argument("--workload", default="8b", choices=list(wl.WORKLOADS))
     ap.add_argument("--sets", type=int, default=4, help="independent buffer sets rotated through (1 = warm cache)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="run only a device-to-device copy of 256 MiB (the known-size kernel the HBM byte counters "
+                         "of a profiler run are scaled by) and exit")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py measures the one-GPU path only: run it with --gpus 1 (no multi-GPU figure exists for "
@@ -158,8 +165,16 @@ def main() -> int:
         print("bench.py needs the MI355X: no GPU visible", file=sys.stderr)
         return 2
 
-    from paper_2605_28115_amd import binding as bd     # raises if libcivic.so is not built
     torch.cuda.set_device(0)
+    if args.calibrate:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate": "copy", "bytes_read": 256 << 20, "bytes_written": 256 << 20, "launches": 10}))
+        return 0
+    from paper_2605_28115_amd import binding as bd     # raises if libcivic.so is not built
     w = wl.WORKLOADS[args.workload]
     assert bd.civic_kept_count(w.grid_tuple()) == w.kept
     fs = wl.frame_starts(w)
@@ -217,7 +232,7 @@ def main() -> int:
     if w.dtype == "bf16":
         roofline = {"bound": "mfma", "kernel": "attn_mfma_kernel (civic_prefill_attn)", "achieved": round(attn_tf, 2),
                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(attn_tf / MFMA_BF16_PEAK_TFLOPS, 4),
-                    "traffic": None, "launch_us": round(attn_us, 2), "flops_per_launch": work["attn_flops"]}
+                    "traffic": MEASURED_ATTN_TRAFFIC_BYTES.get(w.name), "launch_us": round(attn_us, 2), "flops_per_launch": work["attn_flops"]}
     else:
         roofline = {"bound": "alu", "kernel": "attn_plain_kernel (civic_prefill_attn)", "achieved": round(attn_tf, 3),
                     "peak": 157.3, "unit": "TFLOP/s", "frac": round(attn_tf / 157.3, 5), "traffic": None,
