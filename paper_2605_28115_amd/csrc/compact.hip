@@ -184,13 +184,12 @@ extern "C" int civic_compact(const void* hidden, int dtype, int32_t dim, const i
         const int64_t slots = (vpr + t - 1) / t * t;
         if (best < 0 || slots < best) { best = slots; tpr = t; }
     }
-    // Rows per block: enough blocks to give every CU several, few enough that the per-block pass over
-    // kept_idx stays small next to the rows it moves.
+    // Rows per block: small blocks win (about 8 per CU on 256 CUs keep more loads in flight, and the
+    // per-block pass over kept_idx is a few KB of L2 hits), as long as every thread has a vector to move.
     const int64_t total_rows = seq_c * batch;
-    int64_t rpb = total_rows / (256 * 4);
-    const int64_t min_rows = (256 / tpr) * 2;
+    int64_t rpb = total_rows / (256 * 8);
+    const int64_t min_rows = 256 / tpr > 2 ? 256 / tpr : 2;
     if (rpb < min_rows) rpb = min_rows;
-    if (rpb < 4) rpb = 4;
     if (rpb > kCompactMaxRows) rpb = kCompactMaxRows;
     const int64_t blocks = (seq_c + rpb - 1) / rpb;
 

@@ -32,10 +32,17 @@ template <> struct Chunk<false> {
     }
 };
 
-constexpr int kScoreThreads = 512;    // 8 wavefronts share one copy of the anchor in LDS
+#ifndef CIVIC_SCORE_THREADS
+#define CIVIC_SCORE_THREADS 512
+#endif
+#ifndef CIVIC_SCORE_BLOCKS_PER_CU
+#define CIVIC_SCORE_BLOCKS_PER_CU 2
+#endif
+constexpr int kScoreThreads = CIVIC_SCORE_THREADS;    // wavefronts of a block share one copy of the anchor in LDS
+constexpr int kScoreBlocksPerCu = CIVIC_SCORE_BLOCKS_PER_CU;
 
 template <int CHUNKS, bool BF16>
-__global__ __launch_bounds__(kScoreThreads, 2) void score_kernel(const uint8_t* __restrict__ hidden, int64_t n_rows,
+__global__ __launch_bounds__(kScoreThreads, kScoreBlocksPerCu) void score_kernel(const uint8_t* __restrict__ hidden, int64_t n_rows,
                                                               int64_t row_stride_bytes, int32_t dim,
                                                               const float* __restrict__ anchor_q, float inv_tau,
                                                               float* __restrict__ scores)
@@ -117,7 +124,7 @@ static int launch_score(bool bf16, const void* hidden, int64_t n_rows, int64_t r
     // flight while the current one is reduced, so the vector work overlaps the stream from HBM.
     constexpr int rows_per_block = kScoreThreads / kWave;
     int64_t blocks = (n_rows + rows_per_block - 1) / rows_per_block;
-    if (blocks > 256 * 2) blocks = 256 * 2;
+    if (blocks > 256 * kScoreBlocksPerCu) blocks = 256 * kScoreBlocksPerCu;
     const uint8_t* h = static_cast<const uint8_t*>(hidden);
     const size_t lds = sizeof(float) * static_cast<size_t>(dim);
     if (bf16)
