@@ -158,8 +158,8 @@ def main() -> int:
                          "of a profiler run are scaled by) and exit")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py measures the one-GPU path only: run it with --gpus 1 (no multi-GPU figure exists for "
-              "this build; the design note on sharding is in DESIGN.md)", file=sys.stderr)
+        print("bench.py measures the one-GPU path only: run it with --gpus 1 (this build has no collective or "
+              "sharded path, so no multi-GPU figure exists)", file=sys.stderr)
         return 2
     if not torch.cuda.is_available():
         print("bench.py needs the MI355X: no GPU visible", file=sys.stderr)
