@@ -281,24 +281,53 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(AttnArgs a)
         }
     };
 
-    // Start the pipeline before anything else: tiles 0 .. kStages-2
+    // Q goes through LDS as well (same swizzled layout as a K tile, 32 rows per wavefront), so that the
+    // kernel holds no register-destination global load: the compiler then never emits a vmcnt wait of
+    // its own, which would drain the K/V prefetches along with it.  The staging area is the last ring
+    // stage, which the pipeline first fills after its first barrier, plus a tail behind the ring.
+    constexpr int QW = 32 * PITCHB;                           // bytes of one wavefront's Q tile
+    const uint32_t q_lds = w < 2 ? (kStages - 1) * TILEB + w * QW
+                         : w < 4 ? VBASE + (kStages - 1) * TILEB + (w - 2) * QW
+                                 : 2 * VBASE + (w - 4) * QW;
+    {
+        const char* qb = reinterpret_cast<const char*>(static_cast<const __bf16*>(a.q) + b * a.qs[0] + h * a.qs[2]);
+        const uint64_t qb_bits = reinterpret_cast<uint64_t>(qb);
+        // (the builtin returns a signed int: widen each half as unsigned)
+        const uint32_t qb_hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(qb_bits >> 32)));
+        const uint32_t qb_lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(qb_bits)));
+        const uint64_t qb_uni = (static_cast<uint64_t>(qb_hi) << 32) | qb_lo;
+        const uint32_t q_row_bytes = static_cast<uint32_t>(a.qs[1]) * 2u;
+        const uint32_t q_lds_uni = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds)) + q_lds);
+#pragma unroll
+        for (int j = 0; j < PITCH / 2; ++j) {
+            const int slot = j * kWave + lane;
+            const int row = slot / PITCH;
+            const int c = (slot % PITCH) ^ swz<PITCH>(row);
+            const uint32_t cb = (c * 8 < a.head_dim) ? c * 16 : 0;
+            dma16(reinterpret_cast<const void*>(qb_uni), static_cast<uint32_t>(min(row0 + row, a.seq - 1)) * q_row_bytes + cb,
+                  q_lds_uni + j * kWave * 16);
+        }
+    }
+    // Start the pipeline: tiles 0 .. kStages-2
 #pragma unroll
     for (int p = 0; p < kStages - 1; ++p)
         if (p < n_tiles) issue_tile(p, p);
 
-    // Q^T as B operand: lane (col, half) holds Q[qi][16 s + 8 half .. +7] for every k-step s
+    // Q^T as B operand: lane (col, half) holds Q[qi][16 s + 8 half .. +7] for every k-step s.  Loads
+    // retire in order and Q was issued first: wait until only the tile loads are outstanding.
+    if (n_tiles >= 3) wait_vmcnt<3 * TLOADS>();
+    else if (n_tiles == 2) wait_vmcnt<2 * TLOADS>();
+    else wait_vmcnt<TLOADS>();
     bf16x8 qreg[KSTEPS];
-    {
-        const __bf16* qp = static_cast<const __bf16*>(a.q) + b * a.qs[0] +
-                           static_cast<int64_t>(min(qi, a.seq - 1)) * a.qs[1] + h * a.qs[2];
 #pragma unroll
-        for (int s = 0; s < KSTEPS; ++s) {
-            const int c = 16 * s + 8 * half;
-            bf16x8 t = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (c < a.head_dim) t = *reinterpret_cast<const bf16x8*>(qp + c);
-            qreg[s] = t;
-        }
+    for (int s = 0; s < KSTEPS; ++s) {
+        const bf16x8 t = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
+            lds + q_lds + col * PITCHB + (((2 * s + half) ^ swz<PITCH>(col & 15)) << 4));
+        const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+        qreg[s] = (16 * s + 8 * half < a.head_dim) ? t : zero;
     }
+    // in registers before the first barrier, after which the staging area is refilled
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 
     // Per-lane LDS read addresses (bytes) inside stage 0; stage, t, u add compile-time immediates.
     lds_char* kaddr[KSTEPS];              // K: row col, logical chunk 2s + half
@@ -328,7 +357,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(AttnArgs a)
     auto tile = [&](int kt, auto stage_c) {
         constexpr int ST = decltype(stage_c)::value;
         // Loads retire in order.  Younger than tile kt are the tiles issued after it (at most
-        // kStages-2 of them); the Q loads are older than every tile except the first kStages-1.
+        // kStages-2 of them).
         const int younger = min(n_tiles - 1 - kt, kStages - 2);
         if (younger >= 2) wait_vmcnt<2 * TLOADS>();
         else if (younger == 1) wait_vmcnt<TLOADS>();
@@ -468,7 +497,7 @@ template <int DP>
 static constexpr size_t attn_mfma_lds_bytes()
 {
     constexpr int PITCHE = (DP == 64 ? 8 : 16) * 8;
-    return sizeof(__bf16) * 2 * kStages * kBN * PITCHE;
+    return sizeof(__bf16) * (2 * kStages + 2) * kBN * PITCHE;   // K and V rings, Q staging tail
 }
 
 template <int DP>
@@ -521,8 +550,9 @@ extern "C" int civic_prefill_attn(const void* q, const void* k, const void* v, v
     a.heads_per_block = 1; a.row_tiles = 0;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
-    // the MFMA path addresses a K/V tile with 32-bit per-lane byte offsets
-    if (dtype == CIVIC_BF16 && head_dim <= 128 && kv_strides[1] * 2 < (1 << 25)) {
+    // the MFMA path addresses a K/V tile, and a head's Q rows, with 32-bit per-lane byte offsets
+    if (dtype == CIVIC_BF16 && head_dim <= 128 && kv_strides[1] * 2 < (1 << 25) &&
+        static_cast<int64_t>(seq) * q_strides[1] * 2 < (int64_t{1} << 32)) {
         if (head_dim <= 64) return launch_mfma<64>(a, s);
         if (head_dim <= 96) return launch_mfma<96>(a, s);
         return launch_mfma<128>(a, s);
