@@ -5,19 +5,23 @@
 // one KV head.  With four or more query heads per KV head the wavefronts are 4 heads x 2 row tiles
 // (64 rows), so one K/V tile staged in LDS serves the whole group and all wavefronts share the
 // causal extent; smaller groups put more row tiles of the same head in the workgroup.
-//   - K/V tiles of 64 keys go from global memory straight into a 4-stage LDS ring
-//     (global_load_lds_dwordx4, 16 bytes per lane), three tiles ahead of the one being consumed;
-//     the ring is tracked with explicit vmcnt waits and fence-free workgroup barriers.  Rows keep a
-//     256-byte pitch and the 16-byte chunks are XOR-swizzled, so neither the 128-bit K reads nor the
+//   - K/V tiles of 64 keys go from global memory straight into a small LDS ring
+//     (global_load_lds_dwordx4, 16 bytes per lane), one tile ahead of the one being consumed; Q is
+//     staged the same way, so the kernel has no register-destination global load, and the ring is
+//     tracked with explicit vmcnt waits and fence-free workgroup barriers.  Rows keep a 256-byte
+//     pitch and the 16-byte chunks are XOR-swizzled, so neither the 128-bit K reads nor the
 //     transposing V reads hit a bank conflict.
 //   - Scores are computed TRANSPOSED, S^T = K Q^T with v_mfma_f32_32x32x16_bf16: a lane owns one
-//     query column, so the softmax row maximum and row sum are in-lane reductions plus one exchange
-//     between the two half-waves, and the rescale factor is a per-lane scalar.  The exponentiated
-//     tile, rounded to bf16, is already laid out as the B operand of O^T += V^T P^T; the matching A
-//     operand comes from the row-major V tile through the LDS transpose read ds_read_b64_tr_b16.
-//   - fp32 accumulation, online softmax in the exp2 domain with a thresholded (lazy) rescale, row
-//     sums taken from the rounded probabilities with v_dot2c_f32_bf16, bf16 output (nearest even)
-//     staged through LDS into whole 16-byte row segments.
+//     query column, so softmax row statistics are in-lane reductions plus one exchange between the
+//     two half-waves, and the rescale factor is a per-lane scalar.  The exponentiated tile, rounded
+//     to bf16, is already laid out as the B operand of O^T += V^T P^T; the matching A operand comes
+//     from the row-major V tile through the LDS transpose read ds_read_b64_tr_b16.
+//   - Little vector work per score: the score accumulators start from minus the running offset (the
+//     C operand of the first MFMA), so a probability is exp2(accumulator * scale * log2 e), one
+//     multiply and one v_exp_f32; the offset is the first tile's row maximum and moves later only
+//     when the row sums show that a tile outgrew it (no per-tile maximum pass).
+//   - fp32 accumulation, row sums taken from the rounded probabilities with v_dot2c_f32_bf16, bf16
+//     output (nearest even) staged through LDS into whole 16-byte row segments.
 //   - Workgroups are ordered heaviest causal row tile first.
 //
 // fp32 path and head sizes the MFMA path does not cover: a plain fp32 kernel, one wavefront per
@@ -164,9 +168,6 @@ __device__ __forceinline__ int swz(int row)
     else return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
 }
 
-constexpr int kAttnWaves = 8;            // wavefronts per workgroup
-constexpr int kAttnThreads = kAttnWaves * kWave;
-constexpr int kStages = 4;               // K/V tiles in flight in LDS
 
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) char lds_char;
@@ -190,6 +191,16 @@ __device__ __forceinline__ void block_barrier()
     asm volatile("" ::: "memory");
 }
 
+// The same pointer with both halves forced into scalar registers (the value must be wave-uniform).
+__device__ __forceinline__ const char* uniform_ptr(const void* p)
+{
+    const uint64_t bits = reinterpret_cast<uint64_t>(p);
+    // the builtin returns a signed int: widen each half as unsigned
+    const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(bits >> 32)));
+    const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(bits)));
+    return reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | lo);
+}
+
 template <int N> __device__ __forceinline__ void wait_vmcnt()
 {
     // s_waitcnt immediate (gfx9): vmcnt = bits [3:0] and [15:14]; expcnt and lgkmcnt left at their maxima
@@ -198,23 +209,41 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
 
 __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 
-template <int DP>
+// DP: head_dim rounded up to a multiple of 32; WAVES: wavefronts per workgroup (4 or 8); STAGES: K/V
+// tiles in flight in LDS.
+template <int DP, int WAVES, int STAGES>
 struct AttnTile {
+    static constexpr int THREADS = WAVES * kWave;
     static constexpr int KSTEPS = DP / 16;      // MFMA k-steps of Q K^T
     static constexpr int DT = DP / 32;          // 32-row tiles of O^T
     static constexpr int PITCH = DP == 64 ? 8 : 16;        // 16-byte chunks per LDS row
     static constexpr int PITCHB = PITCH * 16;              // ... in bytes
     static constexpr int TILEB = kBN * PITCHB;             // bytes per K (or V) tile
-    static constexpr int NI = kBN * PITCH / kAttnThreads;  // global->LDS instructions per wavefront, tile and tensor
+    static constexpr int NI = kBN * PITCH / THREADS;       // global->LDS instructions per wavefront, tile and tensor
     static constexpr int TLOADS = 2 * NI;                  // ... per tile (K and V)
-    static constexpr int VBASE = kStages * TILEB;          // byte offset of the V stages
+    static constexpr int VBASE = STAGES * TILEB;           // byte offset of the V stages
+    // K ring, V ring, and a tail that stages Q for the wavefronts the last ring stage has no room for
+    static constexpr int LDS_BYTES = (2 * STAGES + (WAVES > 4 ? 2 : 0)) * TILEB;
+    static_assert(WAVES == 4 || WAVES == 8, "Q staging places wavefronts 0-3 in the last ring stage");
+    static_assert(STAGES >= 2 && STAGES <= 4 && (STAGES - 1) * TLOADS <= 63, "vmcnt is a 6-bit counter");
 };
 
-// DP: head_dim rounded up to a multiple of 32.
-template <int DP>
-__global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(AttnArgs a)
+// Waits until at most `younger` tiles' worth of loads (TL per tile) are outstanding, younger <= MAXY.
+template <int MAXY, int TL>
+__device__ __forceinline__ void wait_tiles(int younger)
 {
-    using T = AttnTile<DP>;
+    if constexpr (MAXY == 0) wait_vmcnt<0>();
+    else {
+        if (younger >= MAXY) wait_vmcnt<MAXY * TL>();
+        else wait_tiles<MAXY - 1, TL>(younger);
+    }
+}
+
+template <int DP, int WAVES, int STAGES>
+__global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
+{
+    using T = AttnTile<DP, WAVES, STAGES>;
+    constexpr int kAttnWaves = WAVES, kStages = STAGES;
     constexpr int KSTEPS = T::KSTEPS, DT = T::DT, PITCH = T::PITCH, PITCHB = T::PITCHB, TILEB = T::TILEB;
     constexpr int NI = T::NI, TLOADS = T::TLOADS, VBASE = T::VBASE;
     extern __shared__ __attribute__((aligned(16))) __bf16 smem[];
@@ -315,9 +344,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(AttnArgs a)
 
     // Q^T as B operand: lane (col, half) holds Q[qi][16 s + 8 half .. +7] for every k-step s.  Loads
     // retire in order and Q was issued first: wait until only the tile loads are outstanding.
-    if (n_tiles >= 3) wait_vmcnt<3 * TLOADS>();
-    else if (n_tiles == 2) wait_vmcnt<2 * TLOADS>();
-    else wait_vmcnt<TLOADS>();
+    wait_tiles<kStages - 1, TLOADS>(min(n_tiles, kStages - 1));
     bf16x8 qreg[KSTEPS];
 #pragma unroll
     for (int s = 0; s < KSTEPS; ++s) {
@@ -326,13 +353,18 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(AttnArgs a)
         const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
         qreg[s] = (16 * s + 8 * half < a.head_dim) ? t : zero;
     }
+
     // in registers before the first barrier, after which the staging area is refilled
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 
     // Per-lane LDS read addresses (bytes) inside stage 0; stage, t, u add compile-time immediates.
     lds_char* kaddr[KSTEPS];              // K: row col, logical chunk 2s + half
 #pragma unroll
-    for (int s = 0; s < KSTEPS; ++s) kaddr[s] = lds + col * PITCHB + (((2 * s + half) ^ swz<PITCH>(col & 15)) << 4);
+    for (int s = 0; s < KSTEPS; ++s) {
+        kaddr[s] = lds + col * PITCHB + (((2 * s + half) ^ swz<PITCH>(col & 15)) << 4);
+        // opaque to the optimiser: one register per address, every use is register + immediate
+        asm volatile("" : "+v"(kaddr[s]));
+    }
     const int l16 = lane & 15, g16 = (lane >> 4) & 1;
     lds_char* vaddr[2][DT];               // V: row 4 half + 8 hi + l16/4 (+ 32t + 16u), columns 32dt + 16 g16 + 4 (l16 % 4)
 #pragma unroll
@@ -342,6 +374,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(AttnArgs a)
             const int low4 = 4 * half + 8 * hi + (l16 >> 2);
             const int el = 32 * dt + 16 * g16 + 4 * (l16 & 3);
             vaddr[hi][dt] = lds + VBASE + low4 * PITCHB + (((el >> 3) ^ swz<PITCH>(low4)) << 4) + (el & 7) * 2;
+            asm volatile("" : "+v"(vaddr[hi][dt]));
         }
 
     f32x16 acc_o[DT];
@@ -349,7 +382,10 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(AttnArgs a)
     for (int t = 0; t < DT; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc_o[t][r] = 0.f;
-    float m_run = -INFINITY;               // running maximum (raw logits)
+    float m_run = 0.f;                     // offset subtracted from the raw logits (a recent row maximum)
+    f32x16 neg_m;                          // -m_run in every element: the C operand that starts a score tile
+#pragma unroll
+    for (int r = 0; r < 16; ++r) neg_m[r] = 0.f;
     float l_run[2] = {0.f, 0.f};           // running row sum, two partial accumulators
     const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
 
@@ -358,21 +394,14 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(AttnArgs a)
         constexpr int ST = decltype(stage_c)::value;
         // Loads retire in order.  Younger than tile kt are the tiles issued after it (at most
         // kStages-2 of them).
-        const int younger = min(n_tiles - 1 - kt, kStages - 2);
-        if (younger >= 2) wait_vmcnt<2 * TLOADS>();
-        else if (younger == 1) wait_vmcnt<TLOADS>();
-        else wait_vmcnt<0>();
+        wait_tiles<kStages - 2, TLOADS>(min(n_tiles - 1 - kt, kStages - 2));
         block_barrier();                                      // landed for every wavefront; tile kt-1 is released
         if (kt + kStages - 1 < n_tiles) issue_tile(kt + kStages - 1, (ST + kStages - 1) % kStages);
 
         const int key0 = kt * kBN;
         if (a.causal && key0 > row0 + 31) return;             // no key of the tile is visible to this wavefront
         // S^T tile: rows = keys (two 32-key sub-tiles), columns = this wavefront's 32 queries
-        f32x16 acc_s[2];
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc_s[t][r] = 0.f;
+        f32x16 acc_s[2] = {neg_m, neg_m};                     // raw logits minus the current offset
 #pragma unroll
         for (int s = 0; s < KSTEPS; ++s)
 #pragma unroll
@@ -401,45 +430,62 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(AttnArgs a)
                     acc_s[t][r] = ok ? acc_s[t][r] : -INFINITY;
                 }
         }
-        float mq[4];
-#pragma unroll
-        for (int c4 = 0; c4 < 4; ++c4) {
-            const f32x16& x = acc_s[c4 >> 1];
-            const int o = 8 * (c4 & 1);
-            mq[c4] = fmaxf(max3(max3(x[o], x[o + 1], x[o + 2]), x[o + 3], x[o + 4]), max3(x[o + 5], x[o + 6], x[o + 7]));
-        }
-        float mx = fmaxf(fmaxf(mq[0], mq[1]), fmaxf(mq[2], mq[3]));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-        // Rescale only when some row's maximum moved up by more than 8 in the exp2 domain; until
-        // then the stale maximum is kept (terms stay below 2^8, far inside fp32 and bf16 range).
-        if (__any((mx - m_run) * sl2 > 8.0f)) {
-            const float m_new = fmaxf(m_run, mx);
-            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sl2);   // m_run = -inf -> 0
-            m_run = m_new;
-            l_run[0] *= alpha; l_run[1] *= alpha;
-#pragma unroll
-            for (int t = 0; t < DT; ++t)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc_o[t][r] *= alpha;
-        }
-        const float moff = m_run == -INFINITY ? 0.f : -m_run * sl2;
+        // P = exp2((acc_s - shift) * scale * log2 e), rounded to bf16, laid out as the B operands; lt = the
+        // lane's two partial row sums of the rounded probabilities (what the PV product actually uses).
         bf16x8 pb[2][2];
+        float lt[2];
+        auto probs = [&](float shift) __attribute__((always_inline)) {
+            const float off = -shift * sl2;
+            lt[0] = 0.f; lt[1] = 0.f;
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+            for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                u32x4 packed;
+                for (int u = 0; u < 2; ++u) {
+                    u32x4 packed;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float p0 = __builtin_amdgcn_exp2f(fmaf(acc_s[t][8 * u + 2 * e], sl2, moff));
-                    const float p1 = __builtin_amdgcn_exp2f(fmaf(acc_s[t][8 * u + 2 * e + 1], sl2, moff));
-                    const bf16x2 pp = {static_cast<__bf16>(p0), static_cast<__bf16>(p1)};
-                    packed[e] = __builtin_bit_cast(uint32_t, pp);
-                    // row sum of the rounded probabilities (what the PV product actually uses)
-                    l_run[e & 1] = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, l_run[e & 1], false);
+                    for (int e = 0; e < 4; ++e) {
+                        const float p0 = __builtin_amdgcn_exp2f(fmaf(acc_s[t][8 * u + 2 * e], sl2, off));
+                        const float p1 = __builtin_amdgcn_exp2f(fmaf(acc_s[t][8 * u + 2 * e + 1], sl2, off));
+                        const bf16x2 pp = {static_cast<__bf16>(p0), static_cast<__bf16>(p1)};
+                        packed[e] = __builtin_bit_cast(uint32_t, pp);
+                        lt[e & 1] = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, lt[e & 1], false);
+                    }
+                    pb[t][u] = __builtin_bit_cast(bf16x8, packed);
                 }
-                pb[t][u] = __builtin_bit_cast(bf16x8, packed);
+        };
+        // The offset m_run is not the exact running maximum.  The first tile sets it to that tile's
+        // row maximum; afterwards it moves (never down) only when a tile's probabilities come out
+        // large, a row maximum 2^20 or so above it, which the row sums reveal without a separate
+        // maximum pass.  Until then every term stays far inside the fp32 and bf16 ranges, and since P,
+        // the row sum and the output accumulator all carry the same factor 2^-m_run the result does
+        // not depend on it.
+        const bool first = kt == 0;
+        if (!first) probs(0.f);
+        if (first || __any(lt[0] + lt[1] > 1048576.f)) {
+            float mq[4];
+#pragma unroll
+            for (int c4 = 0; c4 < 4; ++c4) {
+                const f32x16& x = acc_s[c4 >> 1];
+                const int o = 8 * (c4 & 1);
+                mq[c4] = fmaxf(max3(max3(x[o], x[o + 1], x[o + 2]), x[o + 3], x[o + 4]), max3(x[o + 5], x[o + 6], x[o + 7]));
             }
+            float mx = fmaxf(fmaxf(mq[0], mq[1]), fmaxf(mq[2], mq[3]));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));        // finite on the first tile: key 0 is visible to every row
+            const float inc = first ? mx : fmaxf(mx, 0.f);    // acc_s is relative to the current offset
+            if (!first) {
+                const float alpha = __builtin_amdgcn_exp2f(-inc * sl2);
+                l_run[0] *= alpha; l_run[1] *= alpha;
+#pragma unroll
+                for (int t = 0; t < DT; ++t)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc_o[t][r] *= alpha;
+            }
+            m_run += inc;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) neg_m[r] = -m_run;
+            probs(inc);
+        }
+        l_run[0] += lt[0]; l_run[1] += lt[1];
         // O^T += V^T P^T.  The k-slot (half, e) of step (t, u) is key 32t + 16u + 8(e/4) + 4 half + e%4.
 #pragma unroll
         for (int t = 0; t < 2; ++t)
@@ -459,8 +505,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(AttnArgs a)
     for (int kt = 0; kt < n_tiles; kt += kStages) {
         tile(kt, std::integral_constant<int, 0>{});
         if (kt + 1 < n_tiles) tile(kt + 1, std::integral_constant<int, 1>{});
-        if (kt + 2 < n_tiles) tile(kt + 2, std::integral_constant<int, 2>{});
-        if (kt + 3 < n_tiles) tile(kt + 3, std::integral_constant<int, 3>{});
+        if constexpr (kStages > 2) if (kt + 2 < n_tiles) tile(kt + 2, std::integral_constant<int, 2>{});
+        if constexpr (kStages > 3) if (kt + 3 < n_tiles) tile(kt + 3, std::integral_constant<int, 3>{});
     }
     __syncthreads();                                          // every tile consumed: LDS is free
 
@@ -493,31 +539,32 @@ __global__ __launch_bounds__(kAttnThreads) void attn_mfma_kernel(AttnArgs a)
     }
 }
 
-template <int DP>
-static constexpr size_t attn_mfma_lds_bytes()
-{
-    constexpr int PITCHE = (DP == 64 ? 8 : 16) * 8;
-    return sizeof(__bf16) * (2 * kStages + 2) * kBN * PITCHE;   // K and V rings, Q staging tail
-}
-
-template <int DP>
+template <int DP, int WAVES, int STAGES>
 static int launch_mfma(AttnArgs& a, hipStream_t s)
 {
+    using T = AttnTile<DP, WAVES, STAGES>;
     const int group = a.n_q_heads / a.n_kv_heads;
     a.heads_per_block = (group % 4 == 0) ? 4 : (group % 2 == 0) ? 2 : 1;
-    const int rows_per_block = 32 * (kAttnWaves / a.heads_per_block);
+    const int rows_per_block = 32 * (WAVES / a.heads_per_block);
     a.row_tiles = (a.seq + rows_per_block - 1) / rows_per_block;
     const int64_t blocks = static_cast<int64_t>(a.row_tiles) * (group / a.heads_per_block) * a.n_kv_heads * a.batch;
     if (blocks > INT32_MAX) return CIVIC_ERR_UNSUPPORTED;
-    constexpr size_t lds = attn_mfma_lds_bytes<DP>();
+    constexpr size_t lds = T::LDS_BYTES;
     if (lds > 64 * 1024) {
-        static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<DP>),
+        static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<DP, WAVES, STAGES>),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
         if (attr != hipSuccess) return record_hip_error(attr);
     }
-    hipLaunchKernelGGL((attn_mfma_kernel<DP>), dim3(static_cast<unsigned>(blocks)), dim3(kAttnThreads), lds, s, a);
+    hipLaunchKernelGGL((attn_mfma_kernel<DP, WAVES, STAGES>), dim3(static_cast<unsigned>(blocks)), dim3(T::THREADS), lds, s, a);
     return check_launch();
 }
+
+#ifndef CIVIC_ATTN_WAVES
+#define CIVIC_ATTN_WAVES 8
+#endif
+#ifndef CIVIC_ATTN_STAGES
+#define CIVIC_ATTN_STAGES 2
+#endif
 
 }  // namespace civic
 
@@ -553,9 +600,9 @@ extern "C" int civic_prefill_attn(const void* q, const void* k, const void* v, v
     // the MFMA path addresses a K/V tile, and a head's Q rows, with 32-bit per-lane byte offsets
     if (dtype == CIVIC_BF16 && head_dim <= 128 && kv_strides[1] * 2 < (1 << 25) &&
         static_cast<int64_t>(seq) * q_strides[1] * 2 < (int64_t{1} << 32)) {
-        if (head_dim <= 64) return launch_mfma<64>(a, s);
-        if (head_dim <= 96) return launch_mfma<96>(a, s);
-        return launch_mfma<128>(a, s);
+        if (head_dim <= 64) return launch_mfma<64, CIVIC_ATTN_WAVES, CIVIC_ATTN_STAGES>(a, s);
+        if (head_dim <= 96) return launch_mfma<96, CIVIC_ATTN_WAVES, CIVIC_ATTN_STAGES>(a, s);
+        return launch_mfma<128, CIVIC_ATTN_WAVES, CIVIC_ATTN_STAGES>(a, s);
     }
     const dim3 grid(static_cast<unsigned>((seq + 3) / 4), static_cast<unsigned>(n_q_heads), static_cast<unsigned>(batch));
     if (dtype == CIVIC_BF16) hipLaunchKernelGGL((attn_plain_kernel<true>), grid, dim3(256), 0, s, a);
