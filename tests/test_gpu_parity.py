@@ -228,6 +228,27 @@ def test_attention_large_logits_stay_finite(bd):
     check_attn(bd, q, k, v, False, "bf16")
 
 
+@pytest.mark.parametrize("causal", [True, False])
+def test_attention_logits_growing_along_the_sequence(bd, causal):
+    """Keys whose logits grow steadily with the key index: every later tile outgrows the softmax
+    offset taken from the first tile by far more than fp32 can absorb, so the running offset has to
+    move, again and again, with rescaling of everything accumulated so far."""
+    log("attention growing logits", causal)
+    rng = np.random.default_rng(11)
+    b, s, hq, hkv, d = 1, 700, 8, 2, 128
+    q = rng.standard_normal((b, s, hq, d)).astype(np.float32)
+    q[..., 0] = 8.0                                          # logit = 8 * k[..., 0] / sqrt(d) + noise
+    k = rng.standard_normal((b, s, hkv, d)).astype(np.float32)
+    k[..., 0] = np.arange(s, dtype=np.float32)[None, :, None] * 2.0      # about +1.4 per key, +90 per 64-key tile
+    v = rng.standard_normal((b, s, hkv, d)).astype(np.float32)
+    q, k, v = (wl.quantize(x, "bf16")[0] for x in (q, k, v))
+    check_attn(bd, q, k, v, causal, "bf16")
+    # and decreasing: the first tile holds the maximum, later terms underflow towards zero
+    k2 = widen(k).copy()
+    k2[..., 0] = -k2[..., 0]
+    check_attn(bd, q, wl.quantize(k2, "bf16")[0], v, causal, "bf16")
+
+
 # -------------------------------------------------------------------------------------- KV write
 @pytest.mark.parametrize("name", ["tiny", "2b", "8b", "video"])
 def test_kv_write_matches_oracle(bd, name):
