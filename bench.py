@@ -4,8 +4,9 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 8b] [--sets R] [--no-cpu]
 
 A step is one pass of the whole path over one batch of synthetic input already resident in HBM:
-civic_score -> civic_select -> civic_compact -> civic_prefill_attn -> civic_kv_write, back to back
-on one stream, for one transformer layer.  The timed region runs exactly K steps between device
+civic_score -> civic_select -> civic_compact -> civic_prefill_attn_kv (attention and the KV-cache
+write of the same K/V as one call; --unfused runs civic_prefill_attn -> civic_kv_write instead),
+back to back on one stream, for one transformer layer.  The timed region runs exactly K steps between device
 synchronisations; `value` is compact-prefill tokens/s = batch * S_c * K / time.  Buffers rotate over
 R independent sets so that consecutive steps do not find their inputs in the last-level cache.
 
@@ -34,7 +35,8 @@ from paper_2605_28115_amd import workloads as wl
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
-STAGES = ("score", "select", "compact", "attn", "kv_write")
+STAGES_FUSED = ("score", "select", "compact", "attn_kv")
+STAGES_UNFUSED = ("score", "select", "compact", "attn", "kv_write")
 # HBM bytes per attention launch from the profiler's FETCH_SIZE / WRITE_SIZE counters, each scaled by what the
 # same counter reads for a plain copy of known size (profiles/bench_8b_hbm_traffic.txt); measured offline,
 # per workload, and only quoted here.
@@ -94,7 +96,10 @@ def make_stage_calls(bd, w: wl.Workload, fs):
     def kv_write(s):
         bd.civic_kv_write(s.k, s.v, s.k_cache, s.v_cache, 0)
 
-    return dict(score=score, select=select, compact=compact, attn=attn, kv_write=kv_write)
+    def attn_kv(s):
+        bd.civic_prefill_attn_kv(s.q, s.k, s.v, s.k_cache, s.v_cache, 0, w.causal, 0.0, out=s.out)
+
+    return dict(score=score, select=select, compact=compact, attn=attn, kv_write=kv_write, attn_kv=attn_kv)
 
 
 def algorithmic_work(w: wl.Workload) -> dict:
@@ -153,6 +158,7 @@ def main() -> int:
     ap.add_argument("--workload", default="8b", choices=list(wl.WORKLOADS))
     ap.add_argument("--sets", type=int, default=4, help="independent buffer sets rotated through (1 = warm cache)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--unfused", action="store_true", help="attention and KV write as two calls")
     ap.add_argument("--calibrate", action="store_true",
                     help="run only a device-to-device copy of 256 MiB (the known-size kernel the HBM byte counters "
                          "of a profiler run are scaled by) and exit")
@@ -180,6 +186,7 @@ def main() -> int:
     fs = wl.frame_starts(w)
     sets = [BufferSet(bd, w, trial) for trial in range(max(1, args.sets))]
     calls = make_stage_calls(bd, w, fs)
+    STAGES = STAGES_UNFUSED if args.unfused else STAGES_FUSED
     order = [calls[s] for s in STAGES]
 
     def step(i):
@@ -217,9 +224,11 @@ def main() -> int:
     for name in STAGES:
         us = stage_us[name]["mean"]
         entry = {"us": round(us, 2), "us_median": round(stage_us[name]["median"], 2)}
-        if name == "attn":
+        if name in ("attn", "attn_kv"):
             tf = work["attn_flops"] / (us * 1e-6) / 1e12
             entry.update(tflops=round(tf, 1), frac_mfma_peak=round(tf / MFMA_BF16_PEAK_TFLOPS, 4))
+            if name == "attn_kv":
+                entry["kv_write_bytes"] = work["kv_write"]     # copied inside the attention launch
         else:
             gbs = work[name] / (us * 1e-6) / 1e9
             entry.update(gbs=round(gbs, 1), frac_hbm_peak=round(gbs / HBM_PEAK_GBS, 4))
@@ -227,14 +236,15 @@ def main() -> int:
     sg = (work["select"] + work["compact"]) / ((stage_us["select"]["mean"] + stage_us["compact"]["mean"]) * 1e-6) / 1e9
     stages["select+compact"] = {"gbs": round(sg, 1), "frac_hbm_peak": round(sg / HBM_PEAK_GBS, 4)}
 
-    attn_us = stage_us["attn"]["mean"]
+    attn_name = "attn" if args.unfused else "attn_kv"
+    attn_us = stage_us[attn_name]["mean"]
     attn_tf = work["attn_flops"] / (attn_us * 1e-6) / 1e12
     if w.dtype == "bf16":
-        roofline = {"bound": "mfma", "kernel": "attn_mfma_kernel (civic_prefill_attn)", "achieved": round(attn_tf, 2),
+        roofline = {"bound": "mfma", "kernel": f"attn_mfma_kernel (civic_prefill_{attn_name})", "achieved": round(attn_tf, 2),
                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(attn_tf / MFMA_BF16_PEAK_TFLOPS, 4),
                     "traffic": MEASURED_ATTN_TRAFFIC_BYTES.get(w.name), "launch_us": round(attn_us, 2), "flops_per_launch": work["attn_flops"]}
     else:
-        roofline = {"bound": "alu", "kernel": "attn_plain_kernel (civic_prefill_attn)", "achieved": round(attn_tf, 3),
+        roofline = {"bound": "alu", "kernel": f"attn_plain_kernel (civic_prefill_{attn_name})", "achieved": round(attn_tf, 3),
                     "peak": 157.3, "unit": "TFLOP/s", "frac": round(attn_tf / 157.3, 5), "traffic": None,
                     "launch_us": round(attn_us, 2), "flops_per_launch": work["attn_flops"]}
 
@@ -246,7 +256,8 @@ def main() -> int:
         "config": {"workload": f"Qwen3-VL-{w.name}-shaped" if w.name in ("2b", "8b") else w.name,
                    "batch": w.batch, "seq_dense": w.seq_len, "seq_compact": w.seq_compact, "visual_tokens": w.n_visual,
                    "kept_visual": w.kept, "hidden": w.dim, "heads": f"{w.n_q_heads}q/{w.n_kv_heads}kv x {w.head_dim}",
-                   "causal": w.causal, "layers_timed": 1, "buffer_sets": len(sets)},
+                   "causal": w.causal, "layers_timed": 1, "buffer_sets": len(sets),
+                   "calls": "+".join(STAGES)},
         "dense_equivalent_tokens_per_s": round(w.batch * w.seq_len / (ms_per_step * 1e-3), 1),
         "stages": stages,
         "roofline": roofline,

@@ -11,6 +11,7 @@
  *                      (the beta * N_l * (L+M_p)^2 * D_l term of Eq. 7)
  *   civic_kv_write     contiguous, un-paged KV-cache rows (the gamma * N_l * (L+M_p) * D_l
  *                      term of Eq. 7, ratio of Eq. 14)
+ *   civic_prefill_attn_kv  the last two as one call (the K/V rows are read once)
  *
  * Conventions shared by every call
  *   - Plain C.  Every function that launches work returns int: CIVIC_OK or a negative
@@ -171,6 +172,21 @@ int civic_kv_write(const void* k, const void* v, const int64_t* kv_strides /* ho
                    int dtype, void* k_cache, void* v_cache, int32_t batch, int32_t seq,
                    int32_t n_kv_heads, int32_t head_dim, int64_t s_max, int64_t pos0,
                    void* stream);
+
+/* civic_prefill_attn followed by civic_kv_write on the same K and V, as one call: the attention
+ * term and the KV-write term of Eq. 7 belong to the same layer and read the same rows, so where the
+ * MFMA attention kernel runs (bf16, head_dim <= 128) the workgroup that has just streamed a block
+ * of K/V rows also copies them into the caches and no second pass over K and V is made; otherwise
+ * the two steps run back to back.  Results are those of the two separate calls, bit for bit.
+ * Arguments, layouts and error behaviour are theirs; k_cache and v_cache must not be null. */
+int civic_prefill_attn_kv(const void* q, const void* k, const void* v, void* out,
+                          void* k_cache, void* v_cache, int dtype,
+                          int32_t batch, int32_t seq, int32_t n_q_heads, int32_t n_kv_heads,
+                          int32_t head_dim, const int64_t* q_strides /* host [3] */,
+                          const int64_t* kv_strides /* host [3] */,
+                          const int64_t* o_strides /* host [3] */,
+                          int64_t s_max, int64_t pos0, int32_t causal, float softmax_scale,
+                          void* stream);
 
 #ifdef __cplusplus
 }

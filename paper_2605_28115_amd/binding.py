@@ -22,7 +22,7 @@ MAX_VISUAL_TOKENS, MAX_FRAMES, MAX_SCORE_DIM, MAX_HEAD_DIM = 32768, 128, 8192, 2
 
 EXPORTS = ("civic_last_hip_error", "civic_kept_count", "civic_select_workspace_bytes",
            "civic_compact_workspace_bytes", "civic_anchor_normalize", "civic_score", "civic_select",
-           "civic_compact", "civic_prefill_attn", "civic_kv_write")
+           "civic_compact", "civic_prefill_attn", "civic_kv_write", "civic_prefill_attn_kv")
 
 
 class CivicError(RuntimeError):
@@ -70,6 +70,9 @@ lib.civic_prefill_attn.argtypes = [_P, _P, _P, _P, C.c_int, C.c_int32, C.c_int32
 lib.civic_kv_write.restype = C.c_int
 lib.civic_kv_write.argtypes = [_P, _P, _P, C.c_int, _P, _P, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int64,
                                C.c_int64, _P]
+lib.civic_prefill_attn_kv.restype = C.c_int
+lib.civic_prefill_attn_kv.argtypes = [_P, _P, _P, _P, _P, _P, C.c_int, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                      _P, _P, _P, C.c_int64, C.c_int64, C.c_int32, C.c_float, _P]
 
 
 def _check(call: str, rc: int) -> None:
@@ -220,3 +223,24 @@ def civic_kv_write(k: torch.Tensor, v: torch.Tensor, k_cache: torch.Tensor, v_ca
         raise ValueError("caches must be contiguous [batch, H_kv, s_max, d] of the inputs' dtype")
     _check("civic_kv_write", lib.civic_kv_write(_dev(k), _dev(v), _strides3(k), _dtype_code(k), _dev(k_cache), _dev(v_cache),
                                                 batch, seq, hkv, d, k_cache.shape[2], int(pos0), _stream(stream)))
+
+
+def civic_prefill_attn_kv(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                          pos0: int = 0, causal: bool = True, softmax_scale: float = 0.0,
+                          out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """civic_prefill_attn and civic_kv_write on the same k, v as one call (same arguments, same results)."""
+    if k.shape != v.shape or k.stride() != v.stride() or q.dtype != k.dtype or q.dtype != v.dtype:
+        raise ValueError("k and v must share shape, strides and dtype with q's dtype")
+    batch, seq, hq, d = q.shape
+    hkv = k.shape[2]
+    if (not k_cache.is_contiguous() or not v_cache.is_contiguous() or k_cache.shape != v_cache.shape
+            or k_cache.dtype != k.dtype or v_cache.dtype != k.dtype
+            or k_cache.shape[0] != batch or k_cache.shape[1] != hkv or k_cache.shape[3] != d):
+        raise ValueError("caches must be contiguous [batch, H_kv, s_max, d] of the inputs' dtype")
+    if out is None:
+        out = torch.empty((batch, seq, hq, d), dtype=q.dtype, device=q.device)
+    _check("civic_prefill_attn_kv", lib.civic_prefill_attn_kv(
+        _dev(q), _dev(k), _dev(v), _dev(out), _dev(k_cache), _dev(v_cache), _dtype_code(q), batch, seq, hq, hkv, d,
+        _strides3(q), _strides3(k), _strides3(out), k_cache.shape[2], int(pos0), int(bool(causal)), float(softmax_scale),
+        _stream(stream)))
+    return out

@@ -45,6 +45,9 @@ struct AttnArgs {
     int32_t batch, seq, n_q_heads, n_kv_heads, head_dim, causal;
     float scale;                          // softmax scale (natural-exponent domain)
     int32_t heads_per_block, row_tiles;   // MFMA path: block shape and number of 32*rows_per_block tiles
+    // fused KV-cache write (MFMA path; null = none): caches are dense [batch, n_kv_heads, s_max, head_dim]
+    void* k_cache; void* v_cache;
+    int64_t s_max, pos0;
 };
 
 // ------------------------------------------------------------------------------------ fp32 ALU path
@@ -510,6 +513,38 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
     }
     __syncthreads();                                          // every tile consumed: LDS is free
 
+    // Fused KV-cache write: the workgroup of the first head block copies the K and V rows of its own
+    // query rows (keys block_row0 .. block_rows_end-1, which it has just streamed through LDS, so
+    // the reads hit L2) into the cache.  Loads go out here, stores at the very end.  Four 16-byte
+    // pieces per thread cover the usual block (64 rows of 128 channels, K and V); taller blocks take
+    // the rest in a plain loop at the end.
+    constexpr int kKvPieces = 4;
+    u32x4 kv_piece[kKvPieces];
+    const bool kv_fused = a.k_cache != nullptr && hb == 0;
+    const int kv_cpr = a.head_dim / 8;                         // 16-byte pieces per row
+    const int kv_half = (block_rows_end - block_row0) * kv_cpr;   // pieces of one tensor
+    auto kv_src = [&](int id) {
+        const int which = id >= kv_half;                       // 0: K, 1: V
+        const int rem = id - which * kv_half;
+        const int r = rem / kv_cpr, c = rem - r * kv_cpr;
+        return reinterpret_cast<const u32x4*>((which ? vp : kp) + static_cast<int64_t>(block_row0 + r) * a.ks[1] + c * 8);
+    };
+    auto kv_dst = [&](int id) {
+        const int which = id >= kv_half;
+        const int rem = id - which * kv_half;
+        const int r = rem / kv_cpr, c = rem - r * kv_cpr;
+        const int64_t cache_row = (static_cast<int64_t>(b) * a.n_kv_heads + g) * a.s_max + a.pos0 + block_row0 + r;
+        return reinterpret_cast<u32x4*>(static_cast<__bf16*>(which ? a.v_cache : a.k_cache) + cache_row * a.head_dim + c * 8);
+    };
+    if (kv_fused) {
+#pragma unroll
+        for (int i = 0; i < kKvPieces; ++i) {
+            const int id = i * (WAVES * kWave) + tid;
+            kv_piece[i] = u32x4{0u, 0u, 0u, 0u};
+            if (id < 2 * kv_half) kv_piece[i] = *kv_src(id);
+        }
+    }
+
     float l_sum = l_run[0] + l_run[1];
     const float l_tot = l_sum + __shfl_xor(l_sum, 32, kWave);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
@@ -536,6 +571,14 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
         if (row0 + r < a.seq && dc * 8 < a.head_dim)
             *reinterpret_cast<bf16x8*>(ob + static_cast<int64_t>(row0 + r) * a.os[1] + dc * 8) =
                 *reinterpret_cast<const bf16x8*>(&o_s[r * OROW + dc * 8]);
+    }
+    if (kv_fused) {
+#pragma unroll
+        for (int i = 0; i < kKvPieces; ++i) {
+            const int id = i * (WAVES * kWave) + tid;
+            if (id < 2 * kv_half) *kv_dst(id) = kv_piece[i];
+        }
+        for (int id = kKvPieces * (WAVES * kWave) + tid; id < 2 * kv_half; id += WAVES * kWave) *kv_dst(id) = *kv_src(id);
     }
 }
 
@@ -568,12 +611,15 @@ static int launch_mfma(AttnArgs& a, hipStream_t s)
 
 }  // namespace civic
 
-extern "C" int civic_prefill_attn(const void* q, const void* k, const void* v, void* out, int dtype, int32_t batch,
-                                  int32_t seq, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
-                                  const int64_t* q_strides, const int64_t* kv_strides, const int64_t* o_strides,
-                                  int32_t causal, float softmax_scale, void* stream)
+namespace civic {
+
+// Attention, and the KV-cache write when k_cache is not null (inside the attention kernel where the
+// MFMA path runs, as a second launch otherwise).
+static int prefill_attn(const void* q, const void* k, const void* v, void* out, int dtype, int32_t batch, int32_t seq,
+                        int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, const int64_t* q_strides,
+                        const int64_t* kv_strides, const int64_t* o_strides, int32_t causal, float softmax_scale,
+                        void* k_cache, void* v_cache, int64_t s_max, int64_t pos0, void* stream)
 {
-    using namespace civic;
     const int esz = dtype_size(dtype);
     if (!esz || !q || !k || !v || !out || !q_strides || !kv_strides || !o_strides) return CIVIC_ERR_INVALID_ARG;
     if (batch < 0 || seq < 0 || n_q_heads <= 0 || n_kv_heads <= 0 || head_dim <= 0) return CIVIC_ERR_INVALID_ARG;
@@ -585,6 +631,11 @@ extern "C" int civic_prefill_attn(const void* q, const void* k, const void* v, v
         if ((q_strides[i] * esz) % 16 || (kv_strides[i] * esz) % 16 || (o_strides[i] * esz) % 16) return CIVIC_ERR_INVALID_ARG;
     }
     if (!(softmax_scale >= 0.f) || std::isinf(softmax_scale)) return CIVIC_ERR_INVALID_ARG;
+    if (k_cache) {
+        if (!v_cache || !aligned16(k_cache) || !aligned16(v_cache)) return CIVIC_ERR_INVALID_ARG;
+        if (pos0 < 0 || s_max < 0 || pos0 + seq > s_max) return CIVIC_ERR_INVALID_ARG;
+        if (kv_strides[2] < head_dim && n_kv_heads > 1) return CIVIC_ERR_INVALID_ARG;
+    }
     if (head_dim > CIVIC_MAX_HEAD_DIM || batch > 65535 || n_q_heads > 65535) return CIVIC_ERR_UNSUPPORTED;
     if (batch == 0 || seq == 0) return CIVIC_OK;
 
@@ -595,6 +646,7 @@ extern "C" int civic_prefill_attn(const void* q, const void* k, const void* v, v
     a.causal = causal ? 1 : 0;
     a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt(static_cast<float>(head_dim));
     a.heads_per_block = 1; a.row_tiles = 0;
+    a.k_cache = k_cache; a.v_cache = v_cache; a.s_max = s_max; a.pos0 = pos0;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
     // the MFMA path addresses a K/V tile, and a head's Q rows, with 32-bit per-lane byte offsets
@@ -607,6 +659,29 @@ extern "C" int civic_prefill_attn(const void* q, const void* k, const void* v, v
     const dim3 grid(static_cast<unsigned>((seq + 3) / 4), static_cast<unsigned>(n_q_heads), static_cast<unsigned>(batch));
     if (dtype == CIVIC_BF16) hipLaunchKernelGGL((attn_plain_kernel<true>), grid, dim3(256), 0, s, a);
     else hipLaunchKernelGGL((attn_plain_kernel<false>), grid, dim3(256), 0, s, a);
-    return check_launch();
+    const int rc = check_launch();
+    if (rc != CIVIC_OK || !k_cache) return rc;
+    return civic_kv_write(k, v, kv_strides, dtype, k_cache, v_cache, batch, seq, n_kv_heads, head_dim, s_max, pos0, stream);
 }
 
+}  // namespace civic
+
+extern "C" int civic_prefill_attn(const void* q, const void* k, const void* v, void* out, int dtype, int32_t batch,
+                                  int32_t seq, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                  const int64_t* q_strides, const int64_t* kv_strides, const int64_t* o_strides,
+                                  int32_t causal, float softmax_scale, void* stream)
+{
+    return civic::prefill_attn(q, k, v, out, dtype, batch, seq, n_q_heads, n_kv_heads, head_dim, q_strides, kv_strides,
+                               o_strides, causal, softmax_scale, nullptr, nullptr, 0, 0, stream);
+}
+
+extern "C" int civic_prefill_attn_kv(const void* q, const void* k, const void* v, void* out, void* k_cache, void* v_cache,
+                                     int dtype, int32_t batch, int32_t seq, int32_t n_q_heads, int32_t n_kv_heads,
+                                     int32_t head_dim, const int64_t* q_strides, const int64_t* kv_strides,
+                                     const int64_t* o_strides, int64_t s_max, int64_t pos0, int32_t causal,
+                                     float softmax_scale, void* stream)
+{
+    if (!k_cache || !v_cache) return CIVIC_ERR_INVALID_ARG;
+    return civic::prefill_attn(q, k, v, out, dtype, batch, seq, n_q_heads, n_kv_heads, head_dim, q_strides, kv_strides,
+                               o_strides, causal, softmax_scale, k_cache, v_cache, s_max, pos0, stream);
+}

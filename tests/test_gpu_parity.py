@@ -266,6 +266,34 @@ def test_kv_write_matches_oracle(bd, name):
         assert np.array_equal(to_host(dk), kc) and np.array_equal(to_host(dv), vc)   # includes the untouched rows
 
 
+@pytest.mark.parametrize("shape,causal,dtype", [
+    ((4, 938, 32, 8, 128), True, "bf16"), ((1, 469, 16, 8, 128), True, "bf16"), ((2, 333, 16, 16, 72), False, "bf16"),
+    ((1, 257, 12, 4, 64), True, "bf16"), ((1, 130, 8, 8, 128), False, "bf16"), ((1, 200, 3, 1, 96), True, "bf16"),
+    ((1, 100, 2, 1, 256), True, "bf16"), ((1, 77, 4, 2, 32), True, "fp32"),
+])
+def test_fused_attention_kv_write_equals_the_two_calls(bd, shape, causal, dtype):
+    """civic_prefill_attn_kv against civic_prefill_attn + civic_kv_write (both already checked against the
+    oracle above): same attention output and same caches, bit for bit, including the untouched rows."""
+    b, s, hq, hkv, d = shape
+    log("fused attention + kv write", shape, causal, dtype)
+    rng = np.random.default_rng(s + d)
+    mk = lambda h: wl.quantize(rng.standard_normal((b, s, h, d)).astype(np.float32), dtype)[0]
+    q, k, v = mk(hq), mk(hkv), mk(hkv)
+    s_max, pos0 = s + 19, 7
+    fill = 0x7B7B if k.dtype == np.uint16 else 123.0
+    cache = np.full((b, hkv, s_max, d), fill, dtype=k.dtype)
+    dq, dk, dv = to_dev(q), to_dev(k), to_dev(v)
+    kc1, vc1, kc2, vc2 = (to_dev(cache.copy()) for _ in range(4))
+    out1 = bd.civic_prefill_attn(dq, dk, dv, causal)
+    bd.civic_kv_write(dk, dv, kc1, vc1, pos0)
+    out2 = bd.civic_prefill_attn_kv(dq, dk, dv, kc2, vc2, pos0, causal)
+    assert np.array_equal(to_host(out1), to_host(out2))
+    assert np.array_equal(to_host(kc1), to_host(kc2)) and np.array_equal(to_host(vc1), to_host(vc2))
+    ref_k, ref_v = cache.copy(), cache.copy()
+    oracle.kv_write(k, v, ref_k, ref_v, pos0)
+    assert np.array_equal(to_host(kc2), ref_k) and np.array_equal(to_host(vc2), ref_v)
+
+
 # -------------------------------------------------------------------------------------- the path
 @pytest.mark.parametrize("name", ["tiny", "2b", "8b", "video"])
 def test_whole_path_chained(bd, name):
