@@ -16,10 +16,9 @@
 //     two half-waves, and the rescale factor is a per-lane scalar.  The exponentiated tile, rounded
 //     to bf16, is already laid out as the B operand of O^T += V^T P^T; the matching A operand comes
 //     from the row-major V tile through the LDS transpose read ds_read_b64_tr_b16.
-//   - Little vector work per score: the score accumulators start from minus the running offset (the
-//     C operand of the first MFMA), so a probability is exp2(accumulator * scale * log2 e), one
-//     multiply and one v_exp_f32; the offset is the first tile's row maximum and moves later only
-//     when the row sums show that a tile outgrew it (no per-tile maximum pass).
+//   - Little vector work per score: a probability is exp2(fma(score, scale * log2 e, -offset)), one
+//     fused multiply-add and one v_exp_f32; the offset is the first tile's row maximum and moves
+//     later only when the row sums show that a tile outgrew it (no per-tile maximum pass).
 //   - fp32 accumulation, row sums taken from the rounded probabilities with v_dot2c_f32_bf16, bf16
 //     output (nearest even) staged through LDS into whole 16-byte row segments.
 //   - Workgroups are ordered heaviest causal row tile first.
@@ -386,9 +385,6 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc_o[t][r] = 0.f;
     float m_run = 0.f;                     // offset subtracted from the raw logits (a recent row maximum)
-    f32x16 neg_m;                          // -m_run in every element: the C operand that starts a score tile
-#pragma unroll
-    for (int r = 0; r < 16; ++r) neg_m[r] = 0.f;
     float l_run[2] = {0.f, 0.f};           // running row sum, two partial accumulators
     const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
 
@@ -404,7 +400,11 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
         const int key0 = kt * kBN;
         if (a.causal && key0 > row0 + 31) return;             // no key of the tile is visible to this wavefront
         // S^T tile: rows = keys (two 32-key sub-tiles), columns = this wavefront's 32 queries
-        f32x16 acc_s[2] = {neg_m, neg_m};                     // raw logits minus the current offset
+        f32x16 acc_s[2];                                      // raw logits
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc_s[t][r] = 0.f;
 #pragma unroll
         for (int s = 0; s < KSTEPS; ++s)
 #pragma unroll
@@ -433,12 +433,12 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
                     acc_s[t][r] = ok ? acc_s[t][r] : -INFINITY;
                 }
         }
-        // P = exp2((acc_s - shift) * scale * log2 e), rounded to bf16, laid out as the B operands; lt = the
+        // P = exp2((acc_s - m_run) * scale * log2 e), rounded to bf16, laid out as the B operands; lt = the
         // lane's two partial row sums of the rounded probabilities (what the PV product actually uses).
         bf16x8 pb[2][2];
         float lt[2];
-        auto probs = [&](float shift) __attribute__((always_inline)) {
-            const float off = -shift * sl2;
+        auto probs = [&]() __attribute__((always_inline)) {
+            const float off = -m_run * sl2;
             lt[0] = 0.f; lt[1] = 0.f;
 #pragma unroll
             for (int t = 0; t < 2; ++t)
@@ -463,7 +463,7 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
         // the row sum and the output accumulator all carry the same factor 2^-m_run the result does
         // not depend on it.
         const bool first = kt == 0;
-        if (!first) probs(0.f);
+        if (!first) probs();
         if (first || __any(lt[0] + lt[1] > 1048576.f)) {
             float mq[4];
 #pragma unroll
@@ -474,19 +474,17 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
             }
             float mx = fmaxf(fmaxf(mq[0], mq[1]), fmaxf(mq[2], mq[3]));
             mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));        // finite on the first tile: key 0 is visible to every row
-            const float inc = first ? mx : fmaxf(mx, 0.f);    // acc_s is relative to the current offset
+            const float m_new = first ? mx : fmaxf(mx, m_run);
             if (!first) {
-                const float alpha = __builtin_amdgcn_exp2f(-inc * sl2);
+                const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sl2);
                 l_run[0] *= alpha; l_run[1] *= alpha;
 #pragma unroll
                 for (int t = 0; t < DT; ++t)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) acc_o[t][r] *= alpha;
             }
-            m_run += inc;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) neg_m[r] = -m_run;
-            probs(inc);
+            m_run = m_new;
+            probs();
         }
         l_run[0] += lt[0]; l_run[1] += lt[1];
         // O^T += V^T P^T.  The k-slot (half, e) of step (t, u) is key 32t + 16u + 8(e/4) + 4 half + e%4.
@@ -515,11 +513,16 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
 
     // Fused KV-cache write: the workgroup of the first head block copies the K and V rows of its own
     // query rows (keys block_row0 .. block_rows_end-1, which it has just streamed through LDS, so
-    // the reads hit L2) into the cache.  Loads go out here, stores at the very end.  Four 16-byte
+    // the reads hit L2) into the cache; loads go out before the output rows are stored, stores after.  Four 16-byte
     // pieces per thread cover the usual block (64 rows of 128 channels, K and V); taller blocks take
     // the rest in a plain loop at the end.
     constexpr int kKvPieces = 4;
     u32x4 kv_piece[kKvPieces];
+    // opaque copies: they keep the address arithmetic of the epilogue down here, instead of in registers
+    // (or spilled) across the main loop
+    int tid_late = tid, lane_late = lane;
+    asm volatile("" : "+v"(tid_late), "+v"(lane_late));
+    const int col_late = lane_late & 31, half_late = lane_late >> 5;
     const bool kv_fused = a.k_cache != nullptr && hb == 0;
     const int kv_cpr = a.head_dim / 8;                         // 16-byte pieces per row
     const int kv_half = (block_rows_end - block_row0) * kv_cpr;   // pieces of one tensor
@@ -536,15 +539,6 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
         const int64_t cache_row = (static_cast<int64_t>(b) * a.n_kv_heads + g) * a.s_max + a.pos0 + block_row0 + r;
         return reinterpret_cast<u32x4*>(static_cast<__bf16*>(which ? a.v_cache : a.k_cache) + cache_row * a.head_dim + c * 8);
     };
-    if (kv_fused) {
-#pragma unroll
-        for (int i = 0; i < kKvPieces; ++i) {
-            const int id = i * (WAVES * kWave) + tid;
-            kv_piece[i] = u32x4{0u, 0u, 0u, 0u};
-            if (id < 2 * kv_half) kv_piece[i] = *kv_src(id);
-        }
-    }
-
     float l_sum = l_run[0] + l_run[1];
     const float l_tot = l_sum + __shfl_xor(l_sum, 32, kWave);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
@@ -559,14 +553,22 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
             bf16x4 o4;
 #pragma unroll
             for (int e = 0; e < 4; ++e) o4[e] = static_cast<__bf16>(acc_o[dt][4 * rq + e] * inv);
-            *reinterpret_cast<bf16x4*>(&o_s[col * OROW + 32 * dt + 8 * rq + 4 * half]) = o4;
+            *reinterpret_cast<bf16x4*>(&o_s[col_late * OROW + 32 * dt + 8 * rq + 4 * half_late]) = o4;
         }
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
     __builtin_amdgcn_wave_barrier();
+    if (kv_fused) {                                           // (the accumulators are dead by now: registers are free)
+#pragma unroll
+        for (int i = 0; i < kKvPieces; ++i) {
+            const int id = i * (WAVES * kWave) + tid_late;
+            kv_piece[i] = u32x4{0u, 0u, 0u, 0u};
+            if (id < 2 * kv_half) kv_piece[i] = *kv_src(id);
+        }
+    }
     __bf16* ob = static_cast<__bf16*>(a.out) + b * a.os[0] + h * a.os[2];
 #pragma unroll
     for (int it = 0; it < 32 * CPR / kWave; ++it) {
-        const int id = it * kWave + lane;
+        const int id = it * kWave + lane_late;
         const int r = id / CPR, dc = id - r * CPR;
         if (row0 + r < a.seq && dc * 8 < a.head_dim)
             *reinterpret_cast<bf16x8*>(ob + static_cast<int64_t>(row0 + r) * a.os[1] + dc * 8) =
@@ -575,10 +577,10 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
     if (kv_fused) {
 #pragma unroll
         for (int i = 0; i < kKvPieces; ++i) {
-            const int id = i * (WAVES * kWave) + tid;
+            const int id = i * (WAVES * kWave) + tid_late;
             if (id < 2 * kv_half) *kv_dst(id) = kv_piece[i];
         }
-        for (int id = kKvPieces * (WAVES * kWave) + tid; id < 2 * kv_half; id += WAVES * kWave) *kv_dst(id) = *kv_src(id);
+        for (int id = kKvPieces * (WAVES * kWave) + tid_late; id < 2 * kv_half; id += WAVES * kWave) *kv_dst(id) = *kv_src(id);
     }
 }
 
