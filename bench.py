@@ -40,7 +40,7 @@ STAGES_UNFUSED = ("score", "select", "compact", "attn", "kv_write")
 # HBM bytes per attention launch from the profiler's FETCH_SIZE / WRITE_SIZE counters, each scaled by what the
 # same counter reads for a plain copy of known size (profiles/bench_8b_hbm_traffic.txt); measured offline,
 # per workload, and only quoted here.
-MEASURED_ATTN_TRAFFIC_BYTES = {"8b": 78.10e6}
+MEASURED_ATTN_TRAFFIC_BYTES = {("8b", "attn_kv"): 97.61e6, ("8b", "attn"): 78.10e6}
 
 
 def dev(storage: np.ndarray) -> torch.Tensor:
@@ -242,7 +242,7 @@ def main() -> int:
     if w.dtype == "bf16":
         roofline = {"bound": "mfma", "kernel": f"attn_mfma_kernel (civic_prefill_{attn_name})", "achieved": round(attn_tf, 2),
                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(attn_tf / MFMA_BF16_PEAK_TFLOPS, 4),
-                    "traffic": MEASURED_ATTN_TRAFFIC_BYTES.get(w.name), "launch_us": round(attn_us, 2), "flops_per_launch": work["attn_flops"]}
+                    "traffic": MEASURED_ATTN_TRAFFIC_BYTES.get((w.name, attn_name)), "launch_us": round(attn_us, 2), "flops_per_launch": work["attn_flops"]}
     else:
         roofline = {"bound": "alu", "kernel": f"attn_plain_kernel (civic_prefill_{attn_name})", "achieved": round(attn_tf, 3),
                     "peak": 157.3, "unit": "TFLOP/s", "frac": round(attn_tf / 157.3, 5), "traffic": None,
