@@ -130,4 +130,17 @@ def test_argument_errors_precede_any_hip_call(bd):
                                 a["smax"], a["pos0"], None)
     assert kvw(pos0=9) == I and kvw(pos0=-1) == I and kvw(d=4) == I and kvw(kc=None) == I and kvw(v=odd) == I
     assert kvw(st=None) == I and kvw(h=0) == I and kvw(s=0) == bd.CIVIC_OK
+    # civic_prefill_attn_kv: the checks of both calls, and the caches are mandatory
+    def attn_kv(**kw):
+        a = dict(q=F, k=F, v=F, o=F, kc=F, vc=F, dt=1, b=1, s=8, hq=4, hkv=2, d=64, qs=st, ks=st, os=st, smax=16, pos0=0,
+                 causal=1, scale=0.0)
+        a.update(kw)
+        return L.civic_prefill_attn_kv(a["q"], a["k"], a["v"], a["o"], a["kc"], a["vc"], a["dt"], a["b"], a["s"], a["hq"],
+                                       a["hkv"], a["d"], a["qs"], a["ks"], a["os"], a["smax"], a["pos0"], a["causal"],
+                                       C.c_float(a["scale"]), None)
+    assert attn_kv(kc=None) == I and attn_kv(vc=None) == I and attn_kv(vc=odd) == I
+    assert attn_kv(pos0=9) == I and attn_kv(pos0=-1) == I and attn_kv(smax=7) == I
+    assert attn_kv(hq=3) == I and attn_kv(d=60) == I and attn_kv(scale=-1.0) == I and attn_kv(ks=None) == I
+    wide = (C.c_int64 * 3)(8192, 1024, 512)
+    assert attn_kv(d=512, qs=wide, ks=wide, os=wide) == bd.ERR_UNSUPPORTED and attn_kv(s=0) == bd.CIVIC_OK
     assert bd.lib.civic_last_hip_error() == 0
