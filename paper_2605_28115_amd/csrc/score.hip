@@ -1,14 +1,39 @@
 // civic_score: anchor logit of Eq. 8 for every hidden row.  HBM-bound row reduction.
 //
-// One wavefront owns a row at a time.  The row is fetched once with 16-byte loads (lane l takes
-// chunks l, l+64, ...) and held in registers, so the centred second pass (norm and dot product of
+// One wavefront owns a row at a time and fetches it with 16-byte loads (lane l takes chunks l, l+64,
+// ...); the anchor is staged once per block in LDS and the wave-wide sums are DPP reductions.
+//
+// fp32 rows: the row is held in registers, so the centred second pass (norm and dot product of
 // x - mean) costs no second trip to memory and has none of the cancellation a one-pass
-// sum-of-squares formula would have.  The anchor is staged once per 16-wave block in LDS; the three
-// wave-wide sums are DPP reductions.  The next row's loads are issued before the reductions of the
-// current one.
+// sum-of-squares formula would have.  The next row's loads are issued before the reductions.
+//
+// bf16 rows: at 8 rows per SIMD that two-pass arithmetic (7 vector instructions per element) takes as
+// long as the row's trip from HBM, so the common case runs in one pass on the packed words with
+// v_dot2c_f32_bf16, two elements per instruction: sum x (against a word of ones), sum x^2 (a word
+// against itself) and sum q*x with the anchor split into a bf16 head and a bf16 tail (16 mantissa
+// bits).  Then n2 = sum x^2 - N*mean^2 and dot = sum q*x - mean * sum q.  A chunk's register is
+// refilled with the next row's chunk as soon as it is consumed.  The one-pass result is only used
+// when the subtraction cancels at most one bit (N*mean^2 <= half of sum x^2, i.e. |mean| <= the
+// standard deviation); any other row - large offset, constant, Inf/NaN - is re-read (from L2) and
+// takes the centred two-pass arithmetic.
 #include "civic_internal.h"
 
 namespace civic {
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), acc, false);
+}
+
+// Round-to-nearest-even bf16 bits of a finite float (NaN stays NaN).
+__device__ __forceinline__ uint32_t bf16_rne_bits(float f)
+{
+    const uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0u;
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
 
 template <bool BF16> struct Chunk;
 template <> struct Chunk<true> {
@@ -40,6 +65,10 @@ template <> struct Chunk<false> {
 #endif
 constexpr int kScoreThreads = CIVIC_SCORE_THREADS;    // wavefronts of a block share one copy of the anchor in LDS
 constexpr int kScoreBlocksPerCu = CIVIC_SCORE_BLOCKS_PER_CU;
+#ifndef CIVIC_SCORE_WAVES_PER_SIMD
+#define CIVIC_SCORE_WAVES_PER_SIMD 4
+#endif
+constexpr int kScoreWavesPerSimd = CIVIC_SCORE_WAVES_PER_SIMD;   // register budget of the bf16 kernel: 512 / this
 
 template <int CHUNKS, bool BF16>
 __global__ __launch_bounds__(kScoreThreads, kScoreBlocksPerCu) void score_kernel(const uint8_t* __restrict__ hidden, int64_t n_rows,
@@ -116,6 +145,128 @@ __global__ __launch_bounds__(kScoreThreads, kScoreBlocksPerCu) void score_kernel
     }
 }
 
+// bf16 rows, one pass on packed words (see the file header).  LDS: q_hi[dim/2] and q_lo[dim/2] words
+// (element pairs packed like the row's own words), then the per-wave partial sums of q.
+template <int CHUNKS>
+__global__ __launch_bounds__(kScoreThreads, kScoreWavesPerSimd) void score_bf16_kernel(
+    const uint8_t* __restrict__ hidden, int64_t n_rows, int64_t row_stride_bytes, int32_t dim,
+    const float* __restrict__ anchor_q, float inv_tau, float* __restrict__ scores)
+{
+    constexpr int kWaves = kScoreThreads / kWave;
+    extern __shared__ __attribute__((aligned(16))) uint32_t q_w[];
+    uint32_t* q_hi = q_w;
+    uint32_t* q_lo = q_w + dim / 2;
+    float* q_part = reinterpret_cast<float*>(q_w + dim);          // [kWaves]
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int n_chunks = dim / 8;
+    const float inv_dim = 1.0f / static_cast<float>(dim);
+    const int64_t first = static_cast<int64_t>(blockIdx.x) * kWaves + wave;
+    const int64_t step = static_cast<int64_t>(gridDim.x) * kWaves;
+
+    u32x4 raw[CHUNKS];
+    auto fetch_chunk = [&](int64_t row, int c) {
+        const int ch = c * kWave + lane;
+        raw[c] = u32x4{0u, 0u, 0u, 0u};                            // a dead chunk adds nothing to any sum
+        if (ch < n_chunks) raw[c] = load_streaming(reinterpret_cast<const u32x4*>(hidden + row * row_stride_bytes) + ch);
+    };
+    if (first < n_rows) {
+#pragma unroll
+        for (int c = 0; c < CHUNKS; ++c) fetch_chunk(first, c);
+    }
+
+    // Anchor: head = bf16(q), tail = bf16(q - head); sum_q is the sum of what the two words represent.
+    float q_sum = 0.f;
+    for (int i = threadIdx.x * 4; i < dim; i += kScoreThreads * 4) {
+        const float4 t = *reinterpret_cast<const float4*>(anchor_q + i);
+        const float v[4] = {t.x, t.y, t.z, t.w};
+        uint32_t h[4], l[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            h[e] = bf16_rne_bits(v[e]);
+            const float head = bf16_bits_to_float(h[e]);
+            l[e] = bf16_rne_bits(v[e] - head);
+            q_sum += head + bf16_bits_to_float(l[e]);
+        }
+        *reinterpret_cast<u32x2*>(q_hi + i / 2) = u32x2{h[0] | (h[1] << 16), h[2] | (h[3] << 16)};
+        *reinterpret_cast<u32x2*>(q_lo + i / 2) = u32x2{l[0] | (l[1] << 16), l[2] | (l[3] << 16)};
+    }
+    q_sum = wave_sum(q_sum);
+    if (lane == 0) q_part[wave] = q_sum;
+    __syncthreads();
+    q_sum = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) q_sum += q_part[w];
+
+    constexpr uint32_t kOnes = 0x3F803F80u;                        // two bf16 ones
+    for (int64_t row = first; row < n_rows; row += step) {
+        const bool more = row + step < n_rows;
+        float sum = 0.f, sq = 0.f, dh = 0.f, dl = 0.f;
+#pragma unroll
+        for (int c = 0; c < CHUNKS; ++c) {
+            int qw = min(c * kWave + lane, n_chunks - 1) * 4;      // dead chunks read a valid anchor word and multiply it by 0
+            asm volatile("" : "+v"(qw));                           // re-read per row: 64 registers of anchor would halve the occupancy
+            const u32x4 qh = *reinterpret_cast<const u32x4*>(q_hi + qw);
+            const u32x4 ql = *reinterpret_cast<const u32x4*>(q_lo + qw);
+            const uint32_t w[4] = {raw[c].x, raw[c].y, raw[c].z, raw[c].w};
+            const uint32_t a[4] = {qh.x, qh.y, qh.z, qh.w}, b[4] = {ql.x, ql.y, ql.z, ql.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                sum = dot2_bf16(w[e], kOnes, sum);
+                sq = dot2_bf16(w[e], w[e], sq);
+                dh = dot2_bf16(w[e], a[e], dh);
+                dl = dot2_bf16(w[e], b[e], dl);
+            }
+            if (more) {
+                // The register is free again.  The refill is tied to the sums above so that the chunks are
+                // consumed and refilled one after the other, never all 8 fetched into fresh registers.
+                int64_t next = row + step;
+                asm volatile("" : "+v"(next) : "v"(sum), "v"(sq), "v"(dh), "v"(dl));
+                fetch_chunk(next, c);
+            }
+        }
+        sum = wave_sum(sum);
+        sq = wave_sum(sq);
+        const float qx = wave_sum(dh + dl);
+        const float mean = sum * inv_dim;
+        float n2 = sq - sum * mean;
+        float dot = qx - mean * q_sum;
+        if (!(n2 >= 0.5f * sq && sq >= 1e-30f)) {                 // also rows whose squares leave the normal range
+            // Centred two passes over the row, re-read chunk by chunk (wave-uniform branch: every
+            // operand of the test is a wave-wide sum).
+            const u32x4* src = reinterpret_cast<const u32x4*>(hidden + row * row_stride_bytes);
+            const uint32_t w0 = __builtin_amdgcn_readfirstlane(src[0].x);
+            bool same = (w0 >> 16) == (w0 & 0xFFFFu);
+            float s1 = 0.f;
+            for (int ch = lane; ch < n_chunks; ch += kWave) {
+                const u32x4 r = src[ch];
+                same = same && r.x == w0 && r.y == w0 && r.z == w0 && r.w == w0;
+                float x[8];
+                Chunk<true>::unpack(r, x);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) s1 += x[e];
+            }
+            const bool constant_row = __ballot(!same) == 0ull;
+            const float mean2 = wave_sum(s1) * inv_dim;
+            float n2c = 0.f, dotc = 0.f;
+            for (int ch = lane; ch < n_chunks; ch += kWave) {
+                float x[8], qa[8], qb[8];
+                Chunk<true>::unpack(src[ch], x);
+                Chunk<true>::unpack(*reinterpret_cast<const u32x4*>(q_hi + ch * 4), qa);
+                Chunk<true>::unpack(*reinterpret_cast<const u32x4*>(q_lo + ch * 4), qb);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float d = x[e] - mean2;
+                    n2c = fmaf(d, d, n2c);
+                    dotc = fmaf(qa[e] + qb[e], d, dotc);
+                }
+            }
+            n2 = constant_row ? 0.f : wave_sum(n2c);
+            dot = wave_sum(dotc);
+        }
+        if (lane == 0) scores[row] = n2 > 0.f ? inv_tau * dot / sqrtf(n2) : 0.f;
+    }
+}
+
 template <int CHUNKS>
 static int launch_score(bool bf16, const void* hidden, int64_t n_rows, int64_t row_stride_bytes, int32_t dim,
                         const float* anchor_q, float inv_tau, float* scores, hipStream_t stream)
@@ -128,8 +279,9 @@ static int launch_score(bool bf16, const void* hidden, int64_t n_rows, int64_t r
     const uint8_t* h = static_cast<const uint8_t*>(hidden);
     const size_t lds = sizeof(float) * static_cast<size_t>(dim);
     if (bf16)
-        hipLaunchKernelGGL((score_kernel<CHUNKS, true>), dim3(static_cast<unsigned>(blocks)), dim3(kScoreThreads), lds,
-                           stream, h, n_rows, row_stride_bytes, dim, anchor_q, inv_tau, scores);
+        hipLaunchKernelGGL((score_bf16_kernel<CHUNKS>), dim3(static_cast<unsigned>(blocks)), dim3(kScoreThreads),
+                           lds + sizeof(float) * rows_per_block, stream, h, n_rows, row_stride_bytes, dim, anchor_q,
+                           inv_tau, scores);
     else
         hipLaunchKernelGGL((score_kernel<CHUNKS, false>), dim3(static_cast<unsigned>(blocks)), dim3(kScoreThreads), lds,
                            stream, h, n_rows, row_stride_bytes, dim, anchor_q, inv_tau, scores);

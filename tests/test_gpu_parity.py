@@ -67,6 +67,22 @@ def test_score_edge_rows_and_strides(bd):
         s = to_host(bd.civic_score(to_dev(st), torch.from_numpy(q).cuda(), 2.0))
         ref = oracle.score(x32, q, 2.0)
         assert s[0] == 0.0 and np.abs(s - ref).max() <= 4e-5
+    # offsets on both sides of |mean| = standard deviation, where the bf16 kernel changes from its one-pass
+    # sums to the centred two passes; magnitudes far from 1; all-zero and constant rows in between
+    for dim in (256, 4096):
+        ratios = np.array([0.0, 0.3, 0.7, 0.9, 0.97, 1.0, 1.03, 1.1, 1.5, 3.0, -0.95, -1.05, 30.0])
+        mags = np.array([1.0, 1e-12, 1e-17, 1e12, 1e15, 37.0])      # squares stay inside fp32
+        x = rng.standard_normal((len(mags), len(ratios), dim)).astype(np.float32)
+        x = (x + ratios[None, :, None]) * mags[:, None, None]
+        x = x.reshape(-1, dim).astype(np.float32)
+        x[5] = 0.0
+        x[17] = -3.5
+        log("score offsets", dim)
+        st, x32 = wl.quantize(x, "bf16")
+        q = bd.civic_anchor_normalize(rng.standard_normal(dim).astype(np.float32) + 0.25)
+        s = to_host(bd.civic_score(to_dev(st), torch.from_numpy(q).cuda(), 1.0))
+        ref = oracle.score(x32, q, 1.0)
+        assert s[5] == 0.0 and s[17] == 0.0 and np.abs(s - ref).max() <= 2e-5
     # rows embedded in a wider buffer (row stride > dim)
     x = rng.standard_normal((50, 256)).astype(np.float32)
     st, x32 = wl.quantize(x, "bf16")
