@@ -8,10 +8,12 @@
 //   cells   small cells: one thread per cell picks the cell's best remaining member cell_floor times
 //           (members scanned in index order, strict key comparison = the tie rule).
 //           large cells: one wavefront per cell runs the radix select below.
-//   frames  one wavefront per frame: radix select (4 passes of 8 bits over a per-wave LDS histogram)
-//           finds the key of the frame_floor-th unmarked token; equal keys are admitted in index
-//           order with ballot prefix counts.
-//   budget  the same radix select run by the whole workgroup over the unmarked tokens of the sample.
+//   frames  one wavefront per frame: radix select (digits of 8 bits, high first, over a per-wave LDS
+//           histogram) finds the key of the frame_floor-th unmarked token; equal keys are admitted
+//           in index order with ballot prefix counts.
+//   budget  the same radix select run by the whole workgroup over the unmarked tokens of the sample,
+//           with digits of 11 bits.  A select stops after the first digit whose bin is admitted
+//           whole (typically the second of three), because the threshold's low bits no longer matter.
 //   output  popcounts of the 64-bit mark words -> LDS prefix scan -> every set bit writes its index
 //           at (prefix of its word + set bits below it): ascending kept_idx without any sort.
 #include "civic_internal.h"
@@ -33,7 +35,14 @@ struct SelArgs {
     int32_t fill;          // tokens the global budget adds after the floors
     int32_t kept;          // K
     int32_t big_cells;     // 1: cells go through the per-wave radix select
+    uint32_t magic_cells_f, magic_cells_x;   // ceil(2^32 / d) for d = cells per frame, cells per grid row (0 for d = 1)
 };
+
+// n / d for 0 <= n, n * d < 2^32, with magic = ceil(2^32 / d) for d >= 2 and magic = 0 for d = 1.
+__device__ __forceinline__ int32_t div_magic(int32_t n, uint32_t magic)
+{
+    return magic ? static_cast<int32_t>(__umulhi(static_cast<uint32_t>(n), magic)) : n;
+}
 
 __device__ __forceinline__ uint32_t order_key(float s)
 {
@@ -94,8 +103,9 @@ __device__ __forceinline__ void team_sync()
 // not marked yet when only_unmarked is set.  Run by one wavefront (BLOCK = false) or by the whole
 // workgroup (BLOCK = true; every thread must call it with the same arguments, and `eligible` must be
 // given).  eligible < 0 (wavefront only): counted here.
-//   hist  counters owned by the team: 2 x 256 for the workgroup (double buffered, so the next pass's
-//         clear hides behind the scan), 256 for a wavefront;  bc  8 words owned by the team.
+//   hist  counters owned by the team: 2 x 2048 for the workgroup (double buffered, so the next pass's
+//         clear hides behind the scan; both must be zero on entry and are left dirty), 256 for a
+//         wavefront (cleared here, left zero);  bc  8 words owned by the team, 16 for the workgroup.
 template <bool BLOCK, bool CONTIG>
 __device__ void select_first(const uint32_t* keys, uint32_t* marks, uint32_t* hist, uint32_t* bc, const Region reg,
                              int32_t m, bool only_unmarked, int32_t eligible)
@@ -124,60 +134,106 @@ __device__ void select_first(const uint32_t* keys, uint32_t* marks, uint32_t* hi
         return;
     }
 
-    // Radix select of the m-th smallest key among the eligible tokens: 4 digits of 8 bits, high first.
-    for (int i = rank; i < (BLOCK ? 512 : 256); i += TEAM) hist[i] = 0;
-    team_sync<BLOCK>();
+    // Radix select of the m-th smallest key among the eligible tokens, high digit first.
+    constexpr int BITS = BLOCK ? 11 : 8;
+    constexpr int BINS = 1 << BITS;
+    constexpr int PASSES = (32 + BITS - 1) / BITS;
+    constexpr int CH = BINS / 256;                               // the scanning wavefront takes 4 bins per lane and chunk
+    static_assert(CH <= 8, "chunk totals are read as two quads");
+    if constexpr (!BLOCK) {                                      // the workgroup's histograms are clear on entry (see the kernel)
+        for (int i = rank; i < BINS; i += TEAM) hist[i] = 0;
+        team_sync<false>();
+    }
     uint32_t prefix = 0, remaining = static_cast<uint32_t>(m), ties = 0;
+    int done_shift = 0;                                          // key bits below this were never looked at
 #pragma unroll 1
-    for (int pass = 0; pass < 4; ++pass) {
-        const int shift = 24 - 8 * pass;
-        uint32_t* h = hist + (BLOCK ? (pass & 1) * 256 : 0);
-        const uint32_t hi_mask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
+    for (int pass = 0; pass < PASSES; ++pass) {
+        const int shift = 32 - BITS * (pass + 1) > 0 ? 32 - BITS * (pass + 1) : 0;
+        const int width = 32 - BITS * pass < BITS ? 32 - BITS * pass : BITS;
+        const uint32_t digit_mask = (1u << width) - 1u;
+        uint32_t* h = hist + (BLOCK ? (pass & 1) * BINS : 0);
+        const uint32_t hi_mask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + width));
         for (int32_t it = 0; it < n_iter; ++it) {
             const int32_t i = it * TEAM + rank;
             if (i < reg.count) {
                 const int32_t v = reg.token<CONTIG>(i);
                 const uint32_t k = keys[v];
-                if ((k & hi_mask) == prefix && !(only_unmarked && is_marked(marks, v))) atomicAdd(&h[(k >> shift) & 255u], 1u);
+                if ((k & hi_mask) == prefix && !(only_unmarked && is_marked(marks, v))) atomicAdd(&h[(k >> shift) & digit_mask], 1u);
             }
         }
         team_sync<BLOCK>();
-        if (!BLOCK || threadIdx.x < kWave) {                     // one wavefront scans the 256 bins
-            uint32_t c[4];
+        // Scan: every 256-bin chunk has a wavefront of its own (4 bins per lane); the workgroup-wide
+        // select passes the chunk totals through bc[8..].
+        const int chunk = BLOCK ? static_cast<int>(threadIdx.x >> 6) : 0;
+        const bool scanner = chunk < CH;
+        uint32_t c[4] = {0u, 0u, 0u, 0u}, mine = 0, incl = 0, base = 0;
+        if (scanner) {
+            const u32x4 t = *reinterpret_cast<const u32x4*>(h + chunk * 256 + lane * 4);
+            c[0] = t.x; c[1] = t.y; c[2] = t.z; c[3] = t.w;
+            mine = t.x + t.y + t.z + t.w;
+            incl = wave_incl_scan(mine, lane);
+        }
+        if constexpr (BLOCK) {
+            if (scanner) {
+                if (lane == kWave - 1) bc[8 + chunk] = incl;
+            } else {
+                // meanwhile the other wavefronts clear the other histogram for the next pass
+                for (int i = threadIdx.x - CH * kWave; i < BINS; i += kSelThreads - CH * kWave) hist[((pass + 1) & 1) * BINS + i] = 0;
+            }
+            __syncthreads();
+            if (scanner) {
+                const u32x4 t0 = *reinterpret_cast<const u32x4*>(bc + 8), t1 = *reinterpret_cast<const u32x4*>(bc + 12);
+                const uint32_t tot[8] = {t0.x, t0.y, t0.z, t0.w, t1.x, t1.y, t1.z, t1.w};
 #pragma unroll
-            for (int t = 0; t < 4; ++t) c[t] = h[lane * 4 + t];
-            const uint32_t mine = c[0] + c[1] + c[2] + c[3];
-            const uint32_t incl = wave_incl_scan(mine, lane);
-            uint32_t before = incl - mine;
-            if (before < remaining && remaining <= incl) {       // exactly one lane
+                for (int x = 0; x < CH; ++x) base += x < chunk ? tot[x] : 0u;
+            }
+        }
+        if (scanner) {
+            uint32_t before = base + incl - mine;
+            if (before < remaining && remaining <= base + incl) {   // exactly one lane of one chunk
                 int t = 0;
                 while (before + c[t] < remaining) { before += c[t]; ++t; }
-                bc[(pass & 1) * 4 + 0] = static_cast<uint32_t>(lane * 4 + t);   // digit
-                bc[(pass & 1) * 4 + 1] = before;                                // eligible tokens below that digit
-                bc[(pass & 1) * 4 + 2] = c[t];                                  // tokens with that digit
+                bc[(pass & 1) * 4 + 0] = static_cast<uint32_t>(chunk * 256 + lane * 4 + t);   // digit
+                bc[(pass & 1) * 4 + 1] = before;                                                // eligible tokens below that digit
+                bc[(pass & 1) * 4 + 2] = c[t];                                                  // tokens with that digit
             }
         }
         if constexpr (BLOCK) {
-            // the other histogram is cleared for the next pass while this one is scanned
-            if (threadIdx.x >= kWave && threadIdx.x < kWave + 256) hist[((pass + 1) & 1) * 256 + threadIdx.x - kWave] = 0;
             __syncthreads();
         } else {
             team_sync<false>();
-            for (int i = lane; i < 256; i += kWave) hist[i] = 0;      // a wavefront orders its own LDS traffic for free
+            for (int i = lane; i < BINS; i += kWave) hist[i] = 0;     // a wavefront orders its own LDS traffic for free
             team_sync<false>();
         }
         prefix |= bc[(pass & 1) * 4 + 0] << shift;
         remaining -= bc[(pass & 1) * 4 + 1];
         ties = bc[(pass & 1) * 4 + 2];
+        done_shift = shift;
+        if (ties == remaining) break;                            // the whole bin is admitted: its lower bits decide nothing
     }
-    // prefix is now the threshold key; `remaining` of the `ties` tokens that carry it are admitted.
+    // prefix (above done_shift) is now the threshold; `remaining` of the `ties` tokens that carry it are admitted.
 
     if (ties == remaining) {                                     // no contested tie: order does not matter
-        for (int32_t it = 0; it < n_iter; ++it) {
-            const int32_t i = it * TEAM + rank;
-            if (i < reg.count) {
-                const int32_t v = reg.token<CONTIG>(i);
-                if (!(only_unmarked && is_marked(marks, v)) && keys[v] <= prefix) set_mark(marks, v);
+        const uint32_t limit = prefix >> done_shift;
+        if (BLOCK && CONTIG && (reg.base & (kWave - 1)) == 0) {
+            // A wavefront covers 64 consecutive tokens = its own two mark words: one ballot, no atomics.
+            for (int32_t it = 0; it < n_iter; ++it) {
+                const int32_t i = it * TEAM + rank;
+                const int32_t v = reg.base + i;
+                const bool admit = i < reg.count && !(only_unmarked && is_marked(marks, v)) && (keys[v] >> done_shift) <= limit;
+                const uint64_t bal = __ballot(admit);
+                if (lane == 0 && bal) {                          // i - lane < reg.count here, so the words exist
+                    marks[v >> 5] |= static_cast<uint32_t>(bal);
+                    marks[(v >> 5) + 1] |= static_cast<uint32_t>(bal >> 32);
+                }
+            }
+        } else {
+            for (int32_t it = 0; it < n_iter; ++it) {
+                const int32_t i = it * TEAM + rank;
+                if (i < reg.count) {
+                    const int32_t v = reg.token<CONTIG>(i);
+                    if (!(only_unmarked && is_marked(marks, v)) && (keys[v] >> done_shift) <= limit) set_mark(marks, v);
+                }
             }
         }
         team_sync<BLOCK>();
@@ -222,12 +278,12 @@ __device__ void select_first(const uint32_t* keys, uint32_t* marks, uint32_t* hi
 
 __global__ __launch_bounds__(kSelThreads) void select_kernel(SelArgs a)
 {
-    extern __shared__ uint32_t smem[];
-    uint32_t* keys = smem;                                   // [nv_pad]
-    uint32_t* marks = keys + a.nv_pad;                       // [nv_pad / 32]
-    uint32_t* hist = marks + a.nv_pad / 32;                  // [kSelWaves][256]; the workgroup-wide select uses the first 512
+    extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
+    uint32_t* keys = smem;                                   // [nv_pad]; this and the next start on 16-byte boundaries
+    uint32_t* hist = keys + a.nv_pad;                        // [kSelWaves][256]; the workgroup-wide select uses all of it as 2 x 2048
     uint32_t* bcast = hist + kSelWaves * 256;                // [kSelWaves][8]
-    uint32_t* word_prefix = bcast + kSelWaves * 8;           // [nv_pad / 64]
+    uint32_t* marks = bcast + kSelWaves * 8;                 // [nv_pad / 32]
+    uint32_t* word_prefix = marks + a.nv_pad / 32;           // [nv_pad / 64]
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
     const int b = blockIdx.x;
@@ -235,6 +291,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelArgs a)
 
     for (int32_t v = tid; v < a.nv_pad; v += kSelThreads) keys[v] = v < a.nv ? order_key(s[v]) : 0xFFFFFFFFu;
     for (int32_t w = tid; w < a.nv_pad / 32; w += kSelThreads) marks[w] = 0u;
+    // The budget select wants zeroed histograms; the per-wavefront selects before it leave theirs zeroed.
+    for (int i = tid; i < kSelWaves * 256; i += kSelThreads) hist[i] = 0u;
     __syncthreads();
 
     // ---- (1) cell floors
@@ -244,9 +302,10 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelArgs a)
             // are scanned in ascending index with a strict key comparison, which is the tie rule.  The
             // work is cells * floor * size instead of tokens * size for an all-pairs rank.
             const int32_t cells_f = a.cells_y * a.cells_x, cells = a.frames * cells_f;
+            const bool quad_rows = a.cell_w == 4 && (a.width & 3) == 0 && (a.hw & 3) == 0;   // every cell row is an aligned quad of keys
             for (int32_t cell = tid; cell < cells; cell += kSelThreads) {
-                const int32_t f = cell / cells_f, rem = cell - f * cells_f;
-                const int32_t cy = rem / a.cells_x, cx = rem - cy * a.cells_x;
+                const int32_t f = div_magic(cell, a.magic_cells_f), rem = cell - f * cells_f;
+                const int32_t cy = div_magic(rem, a.magic_cells_x), cx = rem - cy * a.cells_x;
                 const int32_t r0 = cy * a.cell_h, c0 = cx * a.cell_w;
                 const int32_t r1 = min(r0 + a.cell_h, a.height), c1 = min(c0 + a.cell_w, a.width);
                 const int32_t base = f * a.hw;
@@ -256,6 +315,33 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelArgs a)
                 for (int32_t k = 0; k < rounds; ++k) {
                     uint32_t best_key = 0xFFFFFFFFu;
                     int32_t best_idx = -1;
+                    if (quad_rows) {
+                        // Four grid rows at a time, one 16-byte LDS read each (consecutive cells read
+                        // consecutive quads, so the wavefront's reads do not collide on banks).  The first
+                        // round has no previous winner to stay behind.
+                        auto scan = [&](auto first_round) {
+                            for (int32_t rr = r0; rr < r1; rr += 4) {
+                                u32x4 kv[4];
+#pragma unroll
+                                for (int y = 0; y < 4; ++y)
+                                    kv[y] = *reinterpret_cast<const u32x4*>(keys + base + min(rr + y, r1 - 1) * a.width + c0);
+#pragma unroll
+                                for (int y = 0; y < 4; ++y) {
+                                    const uint32_t ku[4] = {kv[y].x, kv[y].y, kv[y].z, kv[y].w};
+                                    const bool row_ok = rr + y < r1;
+#pragma unroll
+                                    for (int x = 0; x < 4; ++x) {
+                                        const int32_t u = base + (rr + y) * a.width + c0 + x;
+                                        bool ok = row_ok && (best_idx < 0 || ku[x] < best_key);
+                                        if constexpr (!decltype(first_round)::value)
+                                            ok = ok && (ku[x] > last_key || (ku[x] == last_key && u > last_idx));
+                                        if (ok) { best_key = ku[x]; best_idx = u; }
+                                    }
+                                }
+                            }
+                        };
+                        if (k == 0) scan(std::true_type{}); else scan(std::false_type{});
+                    } else
                     for (int32_t rr = r0; rr < r1; ++rr) {
                         const int32_t u0 = base + rr * a.width;
                         for (int32_t cc = c0; cc < c1; cc += 4) {           // 4 independent LDS reads at a time
@@ -313,7 +399,16 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelArgs a)
     if (lane == kWave - 1) bcast[wave] = incl;
     __syncthreads();
     uint32_t wave_base = 0;
-    for (int x = 0; x < wave; ++x) wave_base += bcast[x];
+    {
+        uint32_t tot[kSelWaves];                             // independent reads; a loop to `wave` would wait on each in turn
+#pragma unroll
+        for (int x = 0; x < kSelWaves; x += 4) {
+            const u32x4 t = *reinterpret_cast<const u32x4*>(bcast + x);
+            tot[x] = t.x; tot[x + 1] = t.y; tot[x + 2] = t.z; tot[x + 3] = t.w;
+        }
+#pragma unroll
+        for (int x = 0; x < kSelWaves; ++x) wave_base += x < wave ? tot[x] : 0u;
+    }
     if (tid < words) word_prefix[tid] = wave_base + incl - pc;
     __syncthreads();
 
@@ -356,6 +451,9 @@ extern "C" int civic_select(const float* scores, int32_t batch, const civic_grid
     a.cells_x = (gi.width + a.cell_w - 1) / a.cell_w;
     a.floor_sum = gi.floor_sum; a.fill = gi.fill; a.kept = gi.kept;
     a.big_cells = static_cast<int64_t>(a.cell_h) * a.cell_w > kSmallCell ? 1 : 0;
+    auto magic = [](int64_t d) { return d <= 1 ? 0u : static_cast<uint32_t>(((int64_t{1} << 32) + d - 1) / d); };
+    a.magic_cells_f = magic(static_cast<int64_t>(a.cells_y) * a.cells_x);
+    a.magic_cells_x = magic(a.cells_x);
 
     const size_t lds = sizeof(uint32_t) * (static_cast<size_t>(a.nv_pad) + a.nv_pad / 32 + kSelWaves * 256 +
                                            kSelWaves * 8 + a.nv_pad / 64 + 2);
