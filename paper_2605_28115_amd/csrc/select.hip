@@ -302,7 +302,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelArgs a)
             // are scanned in ascending index with a strict key comparison, which is the tie rule.  The
             // work is cells * floor * size instead of tokens * size for an all-pairs rank.
             const int32_t cells_f = a.cells_y * a.cells_x, cells = a.frames * cells_f;
-            const bool quad_rows = a.cell_w == 4 && (a.width & 3) == 0 && (a.hw & 3) == 0;   // every cell row is an aligned quad of keys
+            const bool quad_rows = (a.cell_w & 3) == 0 && a.cells_x * a.cell_w == a.width;   // every cell row is made of aligned quads of keys
             for (int32_t cell = tid; cell < cells; cell += kSelThreads) {
                 const int32_t f = div_magic(cell, a.magic_cells_f), rem = cell - f * cells_f;
                 const int32_t cy = div_magic(rem, a.magic_cells_x), cx = rem - cy * a.cells_x;
@@ -316,23 +316,30 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelArgs a)
                     uint32_t best_key = 0xFFFFFFFFu;
                     int32_t best_idx = -1;
                     if (quad_rows) {
-                        // Four grid rows at a time, one 16-byte LDS read each (consecutive cells read
-                        // consecutive quads, so the wavefront's reads do not collide on banks).  The first
-                        // round has no previous winner to stay behind.
+                        // The cell as a row-major list of aligned quads of keys, four 16-byte LDS reads
+                        // at a time (consecutive cells read consecutive quads, so a wavefront's reads do
+                        // not collide on banks).  The first round has no previous winner to stay behind.
                         auto scan = [&](auto first_round) {
-                            for (int32_t rr = r0; rr < r1; rr += 4) {
+                            const int32_t qpr = a.cell_w >> 2, quads = (r1 - r0) * qpr;
+                            int32_t row_u = base + r0 * a.width + c0, q = 0;        // next quad: row start, quad in row
+                            for (int32_t t0 = 0; t0 < quads; t0 += 4) {
                                 u32x4 kv[4];
+                                int32_t u0[4];
 #pragma unroll
-                                for (int y = 0; y < 4; ++y)
-                                    kv[y] = *reinterpret_cast<const u32x4*>(keys + base + min(rr + y, r1 - 1) * a.width + c0);
+                                for (int z = 0; z < 4; ++z) {
+                                    u0[z] = row_u + 4 * q;
+                                    kv[z] = *reinterpret_cast<const u32x4*>(keys + (t0 + z < quads ? u0[z] : row_u));
+                                    if (++q == qpr) { q = 0; row_u += a.width; }
+                                    if (t0 + z + 1 >= quads) { q = 0; row_u = base + r0 * a.width + c0; }   // stay inside the cell
+                                }
 #pragma unroll
-                                for (int y = 0; y < 4; ++y) {
-                                    const uint32_t ku[4] = {kv[y].x, kv[y].y, kv[y].z, kv[y].w};
-                                    const bool row_ok = rr + y < r1;
+                                for (int z = 0; z < 4; ++z) {
+                                    const uint32_t ku[4] = {kv[z].x, kv[z].y, kv[z].z, kv[z].w};
+                                    const bool quad_ok = t0 + z < quads;
 #pragma unroll
                                     for (int x = 0; x < 4; ++x) {
-                                        const int32_t u = base + (rr + y) * a.width + c0 + x;
-                                        bool ok = row_ok && (best_idx < 0 || ku[x] < best_key);
+                                        const int32_t u = u0[z] + x;
+                                        bool ok = quad_ok && (best_idx < 0 || ku[x] < best_key);
                                         if constexpr (!decltype(first_round)::value)
                                             ok = ok && (ku[x] > last_key || (ku[x] == last_key && u > last_idx));
                                         if (ok) { best_key = ku[x]; best_idx = u; }
