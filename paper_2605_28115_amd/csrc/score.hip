@@ -35,27 +35,16 @@ __device__ __forceinline__ uint32_t bf16_rne_bits(float f)
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
-template <bool BF16> struct Chunk;
-template <> struct Chunk<true> {
-    static constexpr int kElems = 8;
-    static __device__ __forceinline__ void unpack(const u32x4& raw, float* x)
-    {
-        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+// The 8 bf16 elements of a 16-byte chunk, widened.
+__device__ __forceinline__ void unpack_bf16(const u32x4& raw, float* x)
+{
+    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            x[2 * i]     = __uint_as_float(w[i] << 16);
-            x[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
-        }
+    for (int i = 0; i < 4; ++i) {
+        x[2 * i]     = __uint_as_float(w[i] << 16);
+        x[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
     }
-};
-template <> struct Chunk<false> {
-    static constexpr int kElems = 4;
-    static __device__ __forceinline__ void unpack(const u32x4& raw, float* x)
-    {
-        x[0] = __uint_as_float(raw.x); x[1] = __uint_as_float(raw.y);
-        x[2] = __uint_as_float(raw.z); x[3] = __uint_as_float(raw.w);
-    }
-};
+}
 
 #ifndef CIVIC_SCORE_THREADS
 #define CIVIC_SCORE_THREADS 512
@@ -70,13 +59,13 @@ constexpr int kScoreBlocksPerCu = CIVIC_SCORE_BLOCKS_PER_CU;
 #endif
 constexpr int kScoreWavesPerSimd = CIVIC_SCORE_WAVES_PER_SIMD;   // register budget of the bf16 kernel: 512 / this
 
-template <int CHUNKS, bool BF16>
-__global__ __launch_bounds__(kScoreThreads, kScoreBlocksPerCu) void score_kernel(const uint8_t* __restrict__ hidden, int64_t n_rows,
-                                                              int64_t row_stride_bytes, int32_t dim,
-                                                              const float* __restrict__ anchor_q, float inv_tau,
-                                                              float* __restrict__ scores)
+// fp32 rows: two passes over a row held in registers.
+template <int CHUNKS>
+__global__ __launch_bounds__(kScoreThreads, kScoreBlocksPerCu) void score_f32_kernel(
+    const uint8_t* __restrict__ hidden, int64_t n_rows, int64_t row_stride_bytes, int32_t dim,
+    const float* __restrict__ anchor_q, float inv_tau, float* __restrict__ scores)
 {
-    constexpr int E = Chunk<BF16>::kElems;
+    constexpr int E = 4;
     extern __shared__ __attribute__((aligned(16))) float q_s[];      // [dim]
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
     const int n_chunks = dim / E;
@@ -101,18 +90,16 @@ __global__ __launch_bounds__(kScoreThreads, kScoreBlocksPerCu) void score_kernel
     __syncthreads();
 
     for (int64_t row = first; row < n_rows; row += step) {
-        // Pass 1: row sum, and the exact "no variance" test (every 32-bit word equals the first one
-        // with its halves equal, i.e. every element carries the same bits).
+        // Pass 1: row sum, and the exact "no variance" test (every element carries the bits of the first).
         const uint32_t w0 = __builtin_amdgcn_readfirstlane(raw[0].x);
-        const bool w0_uniform = !BF16 || (w0 >> 16) == (w0 & 0xFFFFu);
         float sum = 0.f;
-        bool same = w0_uniform;
+        bool same = true;
 #pragma unroll
         for (int c = 0; c < CHUNKS; ++c) {
             const bool live = (c * kWave + lane) < n_chunks;
             same = same && (!live || (raw[c].x == w0 && raw[c].y == w0 && raw[c].z == w0 && raw[c].w == w0));
-            float x[E];
-            Chunk<BF16>::unpack(raw[c], x);                   // dead chunks are zero filled and add nothing
+            const float x[E] = {__uint_as_float(raw[c].x), __uint_as_float(raw[c].y), __uint_as_float(raw[c].z),
+                                __uint_as_float(raw[c].w)};   // dead chunks are zero filled and add nothing
 #pragma unroll
             for (int e = 0; e < E; ++e) sum += x[e];
         }
@@ -123,13 +110,10 @@ __global__ __launch_bounds__(kScoreThreads, kScoreBlocksPerCu) void score_kernel
         for (int c = 0; c < CHUNKS; ++c) {
             const int ch = c * kWave + lane;
             if (ch < n_chunks) {
-                float x[E], q[E];
-                Chunk<BF16>::unpack(raw[c], x);
-#pragma unroll
-                for (int e = 0; e < E; e += 4) {
-                    const float4 t = *reinterpret_cast<const float4*>(q_s + ch * E + e);
-                    q[e] = t.x; q[e + 1] = t.y; q[e + 2] = t.z; q[e + 3] = t.w;
-                }
+                const float x[E] = {__uint_as_float(raw[c].x), __uint_as_float(raw[c].y), __uint_as_float(raw[c].z),
+                                    __uint_as_float(raw[c].w)};
+                const float4 t = *reinterpret_cast<const float4*>(q_s + ch * E);
+                const float q[E] = {t.x, t.y, t.z, t.w};
 #pragma unroll
                 for (int e = 0; e < E; ++e) {
                     const float d = x[e] - mean;
@@ -241,7 +225,7 @@ __global__ __launch_bounds__(kScoreThreads, kScoreWavesPerSimd) void score_bf16_
                 const u32x4 r = src[ch];
                 same = same && r.x == w0 && r.y == w0 && r.z == w0 && r.w == w0;
                 float x[8];
-                Chunk<true>::unpack(r, x);
+                unpack_bf16(r, x);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) s1 += x[e];
             }
@@ -250,9 +234,9 @@ __global__ __launch_bounds__(kScoreThreads, kScoreWavesPerSimd) void score_bf16_
             float n2c = 0.f, dotc = 0.f;
             for (int ch = lane; ch < n_chunks; ch += kWave) {
                 float x[8], qa[8], qb[8];
-                Chunk<true>::unpack(src[ch], x);
-                Chunk<true>::unpack(*reinterpret_cast<const u32x4*>(q_hi + ch * 4), qa);
-                Chunk<true>::unpack(*reinterpret_cast<const u32x4*>(q_lo + ch * 4), qb);
+                unpack_bf16(src[ch], x);
+                unpack_bf16(*reinterpret_cast<const u32x4*>(q_hi + ch * 4), qa);
+                unpack_bf16(*reinterpret_cast<const u32x4*>(q_lo + ch * 4), qb);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const float d = x[e] - mean2;
@@ -283,7 +267,7 @@ static int launch_score(bool bf16, const void* hidden, int64_t n_rows, int64_t r
                            lds + sizeof(float) * rows_per_block, stream, h, n_rows, row_stride_bytes, dim, anchor_q,
                            inv_tau, scores);
     else
-        hipLaunchKernelGGL((score_kernel<CHUNKS, false>), dim3(static_cast<unsigned>(blocks)), dim3(kScoreThreads), lds,
+        hipLaunchKernelGGL((score_f32_kernel<CHUNKS>), dim3(static_cast<unsigned>(blocks)), dim3(kScoreThreads), lds,
                            stream, h, n_rows, row_stride_bytes, dim, anchor_q, inv_tau, scores);
     return check_launch();
 }
