@@ -11,8 +11,10 @@ synchronisations; `value` is compact-prefill tokens/s = batch * S_c * K / time. 
 R independent sets so that consecutive steps do not find their inputs in the last-level cache.
 
 A second pass of the same K steps brackets every stage with HIP events (recorded on the stream the
-kernels run on) and yields the per-stage averages; `roofline` describes the dominant kernel (the
-attention) against the MI355X bf16 MFMA peak.  `cpu_baseline` times the CPU oracle, as it stands, on
+kernels run on); `roofline` describes the dominant kernel (the attention) against the MI355X bf16
+MFMA peak from those in-step durations.  A third pass runs every stage alone, K launches back to
+back, for the per-stage figures under `stages` (`us`; `us_in_step` is the event-bracketed one, which
+carries the 2-3 us an event between two dependent launches costs).  `cpu_baseline` times the CPU oracle, as it stands, on
 a bounded sample of the same workload on this machine's host cores.
 Prints one JSON line.
 """
@@ -219,11 +221,24 @@ def main() -> int:
         d = np.asarray([ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(args.steps)]) * 1e3
         stage_us[name] = {"mean": float(d.mean()), "median": float(np.median(d)), "min": float(d.min())}
 
+    # third pass: every stage alone, K launches back to back over the rotating buffer sets between two events.
+    # An event between two dependent launches costs 2-3 us of its own (the in-step figures above carry it);
+    # back to back the average is the kernel's own duration, which is what the profiler reports.
+    for j, name in enumerate(STAGES):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(args.steps):
+            order[j](sets[i % len(sets)])
+        e1.record()
+        torch.cuda.synchronize()
+        stage_us[name]["alone"] = e0.elapsed_time(e1) * 1e3 / args.steps
+
     work = algorithmic_work(w)
     stages = {}
     for name in STAGES:
-        us = stage_us[name]["mean"]
-        entry = {"us": round(us, 2), "us_median": round(stage_us[name]["median"], 2)}
+        us = stage_us[name]["alone"]
+        entry = {"us": round(us, 2), "us_in_step": round(stage_us[name]["mean"], 2),
+                 "us_in_step_median": round(stage_us[name]["median"], 2)}
         if name in ("attn", "attn_kv"):
             tf = work["attn_flops"] / (us * 1e-6) / 1e12
             entry.update(tflops=round(tf, 1), frac_mfma_peak=round(tf / MFMA_BF16_PEAK_TFLOPS, 4))
@@ -233,7 +248,7 @@ def main() -> int:
             gbs = work[name] / (us * 1e-6) / 1e9
             entry.update(gbs=round(gbs, 1), frac_hbm_peak=round(gbs / HBM_PEAK_GBS, 4))
         stages[name] = entry
-    sg = (work["select"] + work["compact"]) / ((stage_us["select"]["mean"] + stage_us["compact"]["mean"]) * 1e-6) / 1e9
+    sg = (work["select"] + work["compact"]) / ((stage_us["select"]["alone"] + stage_us["compact"]["alone"]) * 1e-6) / 1e9
     stages["select+compact"] = {"gbs": round(sg, 1), "frac_hbm_peak": round(sg / HBM_PEAK_GBS, 4)}
 
     attn_name = "attn" if args.unfused else "attn_kv"
