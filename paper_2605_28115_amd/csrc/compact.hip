@@ -27,7 +27,10 @@ struct FrameTable {
     int32_t start[CIVIC_MAX_FRAMES];    // sequence index of each frame's first token
 };
 
-template <typename V>
+// U > 0: the launch guarantees rows_per_block == U * (kCompactThreads / threads_per_row) and a row
+// length that is a multiple of 2 * threads_per_row vectors, so a block with all its rows (every block
+// but a sample's last) copies them without a per-row or per-column condition.  U == 0: no such promise.
+template <typename V, int U>
 __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
     const uint8_t* __restrict__ hidden, int64_t row_bytes, const int32_t* __restrict__ pos_ids, int32_t batch,
     int32_t seq_len, FrameTable ft, const int32_t* __restrict__ kept_idx, int32_t n_kept, int32_t seq_c,
@@ -44,19 +47,23 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
     const int32_t nrows = min(rows_per_block, seq_c - j0);
     const int32_t* kept = kept_idx + static_cast<int64_t>(b) * n_kept;
     const int32_t F = ft.n, hw = ft.hw;
-    if (tid < F) fstart[tid] = ft.start[tid] - tid * hw;
-
-    __syncthreads();
     // Entries are visited four strided positions per thread at a time, all loads of a batch issued
-    // before any is used (one memory latency per batch instead of one per entry).
-    for (int32_t base = 0; base <= n_kept; base += kCompactThreads * 4) {
-        int32_t cur[4], prev[4];
+    // before any is used (one memory latency per batch instead of one per entry).  The first batch goes
+    // out together with this thread's word of the frame table (a per-thread index into the kernel
+    // arguments is a memory load too), so the block waits for memory once before it knows its rows.
+    int32_t cur[4], prev[4];
+    auto load_batch = [&](int32_t base) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int32_t i = base + u * kCompactThreads + tid;
             cur[u] = i < n_kept ? kept[i] : 0;
             prev[u] = (i > 0 && i <= n_kept) ? kept[i - 1] : 0;
         }
+    };
+    load_batch(0);
+    if (tid < F) fstart[tid] = ft.start[tid] - tid * hw;
+    __syncthreads();
+    for (int32_t base = 0;;) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int32_t i = base + u * kCompactThreads + tid;
@@ -71,6 +78,9 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
             }
             for (int32_t f = f_prev + 1; f <= f_cur; ++f) kb[f] = i;
         }
+        base += kCompactThreads * 4;
+        if (base > n_kept) break;
+        load_batch(base);
     }
     __syncthreads();
 
@@ -107,18 +117,43 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
     const int32_t rr = tid / threads_per_row, c0 = tid - rr * threads_per_row;
     const uint8_t* in_b = hidden + static_cast<int64_t>(b) * seq_len * row_bytes;
     uint8_t* out_b = hidden_c + (static_cast<int64_t>(b) * seq_c + j0) * row_bytes;
+    if (U > 0 && nrows == rows_per_block) {
+        // Straight-line copy: 2 * U independent 16-byte loads per column step, then the stores.  With
+        // conditions around the accesses the compiler cannot count the loads in flight and waits for
+        // all of them, and for the stores before them, at every step.
+        const int Un = U > 0 ? U : 1;
+        int32_t src[Un];
+#pragma unroll
+        for (int u = 0; u < Un; ++u) src[u] = min(max(row_src[u * rows_per_pass + rr], 0), seq_len - 1);
+        for (int32_t c = c0; c < vpr; c += 2 * threads_per_row) {
+            V val[2][Un];
+#pragma unroll
+            for (int u = 0; u < Un; ++u) {
+                const V* in = reinterpret_cast<const V*>(in_b + static_cast<int64_t>(src[u]) * row_bytes) + c;
+                val[0][u] = load_streaming(in);
+                val[1][u] = load_streaming(in + threads_per_row);
+            }
+#pragma unroll
+            for (int u = 0; u < Un; ++u) {
+                V* out = reinterpret_cast<V*>(out_b + static_cast<int64_t>(u * rows_per_pass + rr) * row_bytes) + c;
+                out[0] = val[0][u];
+                out[threads_per_row] = val[1][u];
+            }
+        }
+        return;
+    }
     for (int32_t rbase = 0; rbase < nrows; rbase += rows_per_pass * kCompactUnroll) {
-        const V* in[kCompactUnroll];
-        V* out[kCompactUnroll];
+        // Rows as byte offsets from the two kernel-argument bases plus a flag (a pointer that may be null
+        // would turn every access into a flat one, which the compiler fences off from its neighbours).
+        int64_t in_off[kCompactUnroll], out_off[kCompactUnroll];
+        bool live[kCompactUnroll];
 #pragma unroll
         for (int u = 0; u < kCompactUnroll; ++u) {
             const int32_t r = rbase + u * rows_per_pass + rr;
-            in[u] = nullptr; out[u] = nullptr;
-            if (r < nrows) {
-                const int32_t src = min(max(row_src[r], 0), seq_len - 1);
-                in[u] = reinterpret_cast<const V*>(in_b + static_cast<int64_t>(src) * row_bytes);
-                out[u] = reinterpret_cast<V*>(out_b + static_cast<int64_t>(r) * row_bytes);
-            }
+            live[u] = r < nrows;
+            const int32_t src = live[u] ? min(max(row_src[r], 0), seq_len - 1) : 0;
+            in_off[u] = static_cast<int64_t>(src) * row_bytes;
+            out_off[u] = static_cast<int64_t>(r) * row_bytes;
         }
         // two column steps x kCompactUnroll rows: up to 8 independent 16-byte loads before the first store
         for (int32_t c = c0; c < vpr; c += 2 * threads_per_row) {
@@ -126,18 +161,21 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
             const bool second = c + threads_per_row < vpr;
 #pragma unroll
             for (int u = 0; u < kCompactUnroll; ++u)
-                if (in[u]) {
-                    val[0][u] = load_streaming(in[u] + c);
-                    if (second) val[1][u] = load_streaming(in[u] + c + threads_per_row);
+                if (live[u]) {
+                    const V* in = reinterpret_cast<const V*>(in_b + in_off[u]) + c;
+                    val[0][u] = load_streaming(in);
+                    if (second) val[1][u] = load_streaming(in + threads_per_row);
                 }
 #pragma unroll
             for (int u = 0; u < kCompactUnroll; ++u)
-                if (out[u]) {
-                    out[u][c] = val[0][u];
-                    if (second) out[u][c + threads_per_row] = val[1][u];
+                if (live[u]) {
+                    V* out = reinterpret_cast<V*>(out_b + out_off[u]) + c;
+                    out[0] = val[0][u];
+                    if (second) out[threads_per_row] = val[1][u];
                 }
         }
     }
+
 }
 
 }  // namespace civic
@@ -176,13 +214,16 @@ extern "C" int civic_compact(const void* hidden, int dtype, int32_t dim, const i
     ft.n = gi.frames; ft.hw = gi.hw;
     for (int32_t f = 0; f < CIVIC_MAX_FRAMES; ++f) ft.start[f] = f < gi.frames ? static_cast<int32_t>(frame_start[f]) : 0;
 
-    // Threads per row: the power of two in [16, 256] that wastes the fewest lanes on this row length.
+    // Threads per row: the power of two in [16, 256] that wastes the fewest lanes on this row length; among
+    // equals the largest whose double divides the row, which is what the condition-free copy needs.
     const int64_t vpr = row_bytes / vec;
     int tpr = 256;
     int64_t best = -1;
+    bool best_even = false;
     for (int t = 256; t >= 16; t >>= 1) {
         const int64_t slots = (vpr + t - 1) / t * t;
-        if (best < 0 || slots < best) { best = slots; tpr = t; }
+        const bool even = vpr % (2 * t) == 0;
+        if (best < 0 || slots < best || (slots == best && even && !best_even)) { best = slots; tpr = t; best_even = even; }
     }
     // Rows per block: small blocks win (about 8 per CU on 256 CUs keep more loads in flight, and the
     // per-block pass over kept_idx is a few KB of L2 hits), as long as every thread has a vector to move.
@@ -191,21 +232,35 @@ extern "C" int civic_compact(const void* hidden, int dtype, int32_t dim, const i
     const int64_t min_rows = 256 / tpr > 2 ? 256 / tpr : 2;
     if (rpb < min_rows) rpb = min_rows;
     if (rpb > kCompactMaxRows) rpb = kCompactMaxRows;
+    // Condition-free copy: 1, 2 or 4 passes of 256 / tpr rows per block (more rows per block go the general way).
+    const int64_t rpp = 256 / tpr;
+    int unroll = 0;
+    if (best_even && rpb <= 4 * rpp) {
+        unroll = rpb <= rpp ? 1 : rpb <= 2 * rpp ? 2 : 4;
+        rpb = unroll * rpp;
+    }
     const int64_t blocks = (seq_c + rpb - 1) / rpb;
 
     const uint8_t* h = static_cast<const uint8_t*>(hidden);
     uint8_t* hc = static_cast<uint8_t*>(hidden_c);
     const dim3 g(static_cast<unsigned>(blocks), static_cast<unsigned>(batch)), blk(kCompactThreads);
     hipStream_t s = static_cast<hipStream_t>(stream);
-#define CIVIC_COMPACT_LAUNCH(V)                                                                               \
-    hipLaunchKernelGGL((compact_kernel<V>), g, blk, 0, s, h, row_bytes, pos_ids, batch,                         \
+#define CIVIC_COMPACT_LAUNCH(V, U)                                                                            \
+    hipLaunchKernelGGL((compact_kernel<V, U>), g, blk, 0, s, h, row_bytes, pos_ids, batch,                      \
                        static_cast<int32_t>(seq_len), ft, kept_idx, static_cast<int32_t>(n_kept),               \
                        static_cast<int32_t>(seq_c), static_cast<int32_t>(rpb), tpr, hc, pos_c, src_idx)
     switch (vec) {
-        case 16: CIVIC_COMPACT_LAUNCH(u32x4); break;
-        case 8: CIVIC_COMPACT_LAUNCH(u32x2); break;
-        case 4: CIVIC_COMPACT_LAUNCH(uint32_t); break;
-        default: CIVIC_COMPACT_LAUNCH(uint16_t); break;
+        case 16:
+            switch (unroll) {
+                case 1: CIVIC_COMPACT_LAUNCH(u32x4, 1); break;
+                case 2: CIVIC_COMPACT_LAUNCH(u32x4, 2); break;
+                case 4: CIVIC_COMPACT_LAUNCH(u32x4, 4); break;
+                default: CIVIC_COMPACT_LAUNCH(u32x4, 0); break;
+            }
+            break;
+        case 8: CIVIC_COMPACT_LAUNCH(u32x2, 0); break;
+        case 4: CIVIC_COMPACT_LAUNCH(uint32_t, 0); break;
+        default: CIVIC_COMPACT_LAUNCH(uint16_t, 0); break;
     }
 #undef CIVIC_COMPACT_LAUNCH
     return check_launch();
