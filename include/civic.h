@@ -96,7 +96,11 @@ int civic_anchor_normalize(const float* anchor /* host [dim] */, int32_t dim,
 /* Token scoring.  scores[i] = inv_tau * < anchor_q, Norm(LN(x_i)) > for each of n_rows
  * hidden rows x_i: the pre-softmax logit of Eq. 8 with a single anchor (with one anchor the
  * softmax over tokens is monotone in it).  Norm(LN(x)) = (x - mean) / ||x - mean||; a row
- * without variance scores 0.  fp32 accumulation, two passes over the row held in registers.
+ * without variance scores 0.  fp32 accumulation.  fp32 rows take two passes (mean, then the
+ * centred norm and dot product).  bf16 rows take one pass (sum, sum of squares, dot product;
+ * the anchor is used as two bf16 terms, 16 mantissa bits) whenever |mean| <= the row's
+ * standard deviation, and the two centred passes otherwise; both agree with the fp64 value
+ * to ~1e-6.  Rows whose sum of squares overflows fp32 are outside the supported range.
  *   hidden     [n_rows, row_stride] elements of `dtype`, row_stride >= dim, in elements
  *   anchor_q   device [dim] fp32, zero mean, unit norm (civic_anchor_normalize)
  *   scores     device [n_rows] fp32
