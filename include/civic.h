@@ -25,6 +25,8 @@
  *   - All argument checks happen before the first HIP call, so a rejected call has no
  *     side effect.  On CIVIC_ERR_HIP the outputs are unspecified; no out-of-bounds access
  *     is made in any case.
+ *   - A tensor pointer may be NULL when the tensor it names has no elements (no rows, an
+ *     empty batch, nothing kept and no text); otherwise NULL is CIVIC_ERR_INVALID_ARG.
  *   - dtype: CIVIC_F32 (4-byte IEEE) or CIVIC_BF16 (2-byte bfloat16).
  *   - Re-entrant; no global mutable state except the last HIP error code.
  */

@@ -623,8 +623,9 @@ static int prefill_attn(const void* q, const void* k, const void* v, void* out, 
                         void* k_cache, void* v_cache, int64_t s_max, int64_t pos0, void* stream)
 {
     const int esz = dtype_size(dtype);
-    if (!esz || !q || !k || !v || !out || !q_strides || !kv_strides || !o_strides) return CIVIC_ERR_INVALID_ARG;
+    if (!esz || !q_strides || !kv_strides || !o_strides) return CIVIC_ERR_INVALID_ARG;
     if (batch < 0 || seq < 0 || n_q_heads <= 0 || n_kv_heads <= 0 || head_dim <= 0) return CIVIC_ERR_INVALID_ARG;
+    if (batch > 0 && seq > 0 && (!q || !k || !v || !out)) return CIVIC_ERR_INVALID_ARG;   // no tokens: no tensors
     if (n_q_heads % n_kv_heads) return CIVIC_ERR_INVALID_ARG;
     if (head_dim % 8) return CIVIC_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return CIVIC_ERR_INVALID_ARG;
@@ -683,7 +684,7 @@ extern "C" int civic_prefill_attn_kv(const void* q, const void* k, const void* v
                                      const int64_t* o_strides, int64_t s_max, int64_t pos0, int32_t causal,
                                      float softmax_scale, void* stream)
 {
-    if (!k_cache || !v_cache) return CIVIC_ERR_INVALID_ARG;
+    if ((!k_cache || !v_cache) && batch > 0 && seq > 0) return CIVIC_ERR_INVALID_ARG;
     return civic::prefill_attn(q, k, v, out, dtype, batch, seq, n_q_heads, n_kv_heads, head_dim, q_strides, kv_strides,
                                o_strides, causal, softmax_scale, k_cache, v_cache, s_max, pos0, stream);
 }

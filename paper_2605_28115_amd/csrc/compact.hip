@@ -190,9 +190,12 @@ extern "C" int civic_compact(const void* hidden, int dtype, int32_t dim, const i
     const int esz = dtype_size(dtype);
     GridInfo gi;
     if (grid_info(grid, &gi) != CIVIC_OK) return CIVIC_ERR_INVALID_ARG;
-    if (!esz || !hidden || !pos_ids || !frame_start || !hidden_c || !pos_c || !src_idx) return CIVIC_ERR_INVALID_ARG;
+    if (!esz || !frame_start) return CIVIC_ERR_INVALID_ARG;
     if (dim <= 0 || batch < 0 || seq_len < gi.nv || n_kept < 0 || n_kept > gi.nv) return CIVIC_ERR_INVALID_ARG;
-    if (n_kept > 0 && !kept_idx) return CIVIC_ERR_INVALID_ARG;
+    // a tensor without elements (batch 0; nothing kept and no text) needs no pointer
+    const bool some_out = batch > 0 && seq_len - gi.nv + n_kept > 0;
+    if (batch > 0 && (!hidden || !pos_ids || (n_kept > 0 && !kept_idx))) return CIVIC_ERR_INVALID_ARG;
+    if (some_out && (!hidden_c || !pos_c || !src_idx)) return CIVIC_ERR_INVALID_ARG;
     int64_t prev_end = 0;
     for (int32_t f = 0; f < gi.frames; ++f) {
         if (frame_start[f] < prev_end || frame_start[f] + gi.hw > seq_len) return CIVIC_ERR_INVALID_ARG;

@@ -55,8 +55,9 @@ extern "C" int civic_kv_write(const void* k, const void* v, const int64_t* kv_st
 {
     using namespace civic;
     const int esz = dtype_size(dtype);
-    if (!esz || !k || !v || !k_cache || !v_cache || !kv_strides) return CIVIC_ERR_INVALID_ARG;
+    if (!esz || !kv_strides) return CIVIC_ERR_INVALID_ARG;
     if (batch < 0 || seq < 0 || n_kv_heads <= 0 || head_dim <= 0) return CIVIC_ERR_INVALID_ARG;
+    if (batch > 0 && seq > 0 && (!k || !v || !k_cache || !v_cache)) return CIVIC_ERR_INVALID_ARG;   // else nothing to copy
     if (pos0 < 0 || s_max < 0 || pos0 + seq > s_max) return CIVIC_ERR_INVALID_ARG;
     if ((static_cast<int64_t>(head_dim) * esz) % 16) return CIVIC_ERR_INVALID_ARG;
     if (!aligned16(k) || !aligned16(v) || !aligned16(k_cache) || !aligned16(v_cache)) return CIVIC_ERR_INVALID_ARG;

@@ -279,8 +279,9 @@ extern "C" int civic_score(const void* hidden, int dtype, int64_t n_rows, int64_
 {
     using namespace civic;
     const int esz = dtype_size(dtype);
-    if (!esz || !hidden || !anchor_q || !scores) return CIVIC_ERR_INVALID_ARG;
+    if (!esz || !anchor_q) return CIVIC_ERR_INVALID_ARG;
     if (n_rows < 0 || dim <= 0 || row_stride < dim) return CIVIC_ERR_INVALID_ARG;
+    if (n_rows > 0 && (!hidden || !scores)) return CIVIC_ERR_INVALID_ARG;   // no rows: nothing to point at
     const int elems = 16 / esz;
     if (dim % elems) return CIVIC_ERR_INVALID_ARG;
     if (!aligned16(hidden) || !aligned16(anchor_q) || (row_stride * esz) % 16) return CIVIC_ERR_INVALID_ARG;

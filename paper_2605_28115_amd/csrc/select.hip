@@ -441,8 +441,8 @@ extern "C" int civic_select(const float* scores, int32_t batch, const civic_grid
     (void)workspace; (void)workspace_bytes;
     GridInfo gi;
     if (grid_info(grid, &gi) != CIVIC_OK) return CIVIC_ERR_INVALID_ARG;
-    if (!scores || batch < 0) return CIVIC_ERR_INVALID_ARG;
-    if (gi.kept > 0 && !kept_idx) return CIVIC_ERR_INVALID_ARG;
+    if (batch < 0) return CIVIC_ERR_INVALID_ARG;
+    if (batch > 0 && (!scores || (gi.kept > 0 && !kept_idx))) return CIVIC_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(scores) | reinterpret_cast<uintptr_t>(kept_idx)) & 3u) return CIVIC_ERR_INVALID_ARG;
     if (gi.nv > CIVIC_MAX_VISUAL_TOKENS) return CIVIC_ERR_UNSUPPORTED;
     if (batch == 0) return CIVIC_OK;

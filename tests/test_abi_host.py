@@ -141,6 +141,21 @@ def test_argument_errors_precede_any_hip_call(bd):
     assert attn_kv(kc=None) == I and attn_kv(vc=None) == I and attn_kv(vc=odd) == I
     assert attn_kv(pos0=9) == I and attn_kv(pos0=-1) == I and attn_kv(smax=7) == I
     assert attn_kv(hq=3) == I and attn_kv(d=60) == I and attn_kv(scale=-1.0) == I and attn_kv(ks=None) == I
+    # a tensor without elements needs no pointer: NULL is accepted exactly then
+    OK = bd.CIVIC_OK
+    assert L.civic_score(None, 1, 0, 64, 64, F, 1.0, None, None) == OK and L.civic_score(F, 1, 0, 64, 64, None, 1.0, F, None) == I
+    assert L.civic_select(None, 0, C.byref(g), None, None, None, 0, None) == OK
+    none_kept = bd.make_grid((1, 4, 4, 2, 2, 0, 0, 0))
+    fs0 = np.zeros(1, dtype=np.int64)
+    def compact0(batch, seq_len, n_kept, out):
+        return L.civic_compact(F if batch else None, 1, 64, F if batch else None, batch, seq_len, C.byref(none_kept),
+                               C.c_void_p(fs0.ctypes.data), None, n_kept, out, out, out, None, 0, None)
+    assert compact0(0, 16, 0, None) == OK                # empty batch
+    assert compact0(1, 16, 0, None) == OK                # no text, nothing kept: S_c = 0
+    assert compact0(1, 17, 0, None) == I                 # one text token: outputs are needed
+    assert attn(q=None, k=None, v=None, o=None, s=0) == OK and attn(q=None, k=None, v=None, o=None, b=0) == OK
+    assert kvw(k=None, v=None, kc=None, vc=None, s=0) == OK and kvw(k=None, v=None, kc=None, vc=None, b=0) == OK
+    assert attn_kv(q=None, k=None, v=None, o=None, kc=None, vc=None, s=0) == OK
     wide = (C.c_int64 * 3)(8192, 1024, 512)
     assert attn_kv(d=512, qs=wide, ks=wide, os=wide) == bd.ERR_UNSUPPORTED and attn_kv(s=0) == bd.CIVIC_OK
     assert bd.lib.civic_last_hip_error() == 0

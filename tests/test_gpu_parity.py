@@ -185,6 +185,11 @@ def test_compact_edge_cases(bd):
         pos = rng.integers(0, 1000, (3, 3, seq)).astype(np.int32)
         kept = np.stack([np.sort(rng.choice(np.r_[0:12, 36:60], 9, replace=False)) for _ in range(3)]).astype(np.int32)
         check_compact(bd, hid, pos, grid, fs, kept)
+    # nothing kept and no text: an empty compact sequence (the binding hands over NULL outputs)
+    log("compact empty result")
+    hid0 = rng.integers(0, 60000, (2, 12, 8)).astype(np.uint16)
+    check_compact(bd, hid0, rng.integers(0, 9, (3, 2, 12)).astype(np.int32), (1, 3, 4, 2, 2, 0, 0, 0), np.zeros(1, dtype=np.int64),
+                  np.zeros((2, 0), dtype=np.int32))
     # 128 frames (the documented maximum) of 2x2 tokens, no text at all
     log("compact 128 frames")
     grid = (128, 2, 2, 2, 2, 1, 0, 200)
