@@ -44,6 +44,10 @@ struct AttnArgs {
     int32_t batch, seq, n_q_heads, n_kv_heads, head_dim, causal;
     float scale;                          // softmax scale (natural-exponent domain)
     int32_t heads_per_block, row_tiles;   // MFMA path: block shape and number of 32*rows_per_block tiles
+    // MFMA path, block index -> (head block, kv head, batch) without integer division: q heads per kv head,
+    // head blocks per kv head, log2(heads_per_block), ceil(2^32 / d) for d = head blocks, kv heads (0 for d = 1)
+    int32_t group, head_blocks, hb_shift;
+    uint32_t magic_head_blocks, magic_kv_heads;
     // fused KV-cache write (MFMA path; null = none): caches are dense [batch, n_kv_heads, s_max, head_dim]
     void* k_cache; void* v_cache;
     int64_t s_max, pos0;
@@ -253,21 +257,22 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
-    const int HB = a.heads_per_block, RB = kAttnWaves / HB;   // heads and 32-row sub-tiles per block
-    const int group = a.n_q_heads / a.n_kv_heads;
-    const int head_blocks = group / HB;
+    const int HB = a.heads_per_block, RB = kAttnWaves >> a.hb_shift;   // heads and 32-row sub-tiles per block
+    const int group = a.group, head_blocks = a.head_blocks;
 
-    // blockIdx.x -> (row tile, head block, kv head, batch); the heaviest causal row tiles come first
-    int bid = blockIdx.x;
-    const int per_rt = head_blocks * a.n_kv_heads * a.batch;
-    const int rt = a.row_tiles - 1 - bid / per_rt;
-    bid %= per_rt;
-    const int hb = bid % head_blocks; bid /= head_blocks;
-    const int g = bid % a.n_kv_heads;
-    const int b = bid / a.n_kv_heads;
+    // blockIdx.y -> row tile, the heaviest causal ones first (the linear dispatch order runs through x first);
+    // blockIdx.x -> (head block, kv head, batch).  The quotients come from multiply-high with constants
+    // prepared at launch: a chain of integer divisions here would delay the first load by half a microsecond.
+    auto div_magic = [](uint32_t n, uint32_t magic) { return magic ? __umulhi(n, magic) : n; };
+    const int rt = a.row_tiles - 1 - static_cast<int>(blockIdx.y);
+    const uint32_t bid = blockIdx.x;
+    const uint32_t bid_hb = div_magic(bid, a.magic_head_blocks);      // = kv head + n_kv_heads * batch
+    const int hb = static_cast<int>(bid - bid_hb * head_blocks);
+    const int b = static_cast<int>(div_magic(bid_hb, a.magic_kv_heads));
+    const int g = static_cast<int>(bid_hb) - b * a.n_kv_heads;
 
-    const int h = g * group + hb * HB + (w % HB);
-    const int row0 = (rt * RB + w / HB) * 32;                 // this wavefront's first query row
+    const int h = g * group + hb * HB + (w & (HB - 1));
+    const int row0 = (rt * RB + (w >> a.hb_shift)) * 32;      // this wavefront's first query row
     const int block_row0 = rt * RB * 32;
     const int block_rows_end = min(block_row0 + RB * 32, a.seq);
     const int qi = row0 + col;                                // this lane's query row
@@ -592,15 +597,24 @@ static int launch_mfma(AttnArgs& a, hipStream_t s)
     a.heads_per_block = (group % 4 == 0) ? 4 : (group % 2 == 0) ? 2 : 1;
     const int rows_per_block = 32 * (WAVES / a.heads_per_block);
     a.row_tiles = (a.seq + rows_per_block - 1) / rows_per_block;
-    const int64_t blocks = static_cast<int64_t>(a.row_tiles) * (group / a.heads_per_block) * a.n_kv_heads * a.batch;
-    if (blocks > INT32_MAX) return CIVIC_ERR_UNSUPPORTED;
+    a.group = group;
+    a.head_blocks = group / a.heads_per_block;
+    a.hb_shift = a.heads_per_block == 4 ? 2 : a.heads_per_block == 2 ? 1 : 0;
+    const int64_t per_rt = static_cast<int64_t>(a.head_blocks) * a.n_kv_heads * a.batch;
+    // ceil(2^32 / d) gives exact quotients while n * d < 2^32; n < per_rt here
+    const int64_t d_max = a.head_blocks > a.n_kv_heads ? a.head_blocks : a.n_kv_heads;
+    if (per_rt * d_max >= (int64_t{1} << 32) || a.row_tiles > 65535) return CIVIC_ERR_UNSUPPORTED;
+    auto magic = [](int64_t d) { return d <= 1 ? 0u : static_cast<uint32_t>(((int64_t{1} << 32) + d - 1) / d); };
+    a.magic_head_blocks = magic(a.head_blocks);
+    a.magic_kv_heads = magic(a.n_kv_heads);
     constexpr size_t lds = T::LDS_BYTES;
     if (lds > 64 * 1024) {
         static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<DP, WAVES, STAGES>),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
         if (attr != hipSuccess) return record_hip_error(attr);
     }
-    hipLaunchKernelGGL((attn_mfma_kernel<DP, WAVES, STAGES>), dim3(static_cast<unsigned>(blocks)), dim3(T::THREADS), lds, s, a);
+    hipLaunchKernelGGL((attn_mfma_kernel<DP, WAVES, STAGES>), dim3(static_cast<unsigned>(per_rt), static_cast<unsigned>(a.row_tiles)),
+                       dim3(T::THREADS), lds, s, a);
     return check_launch();
 }
 
@@ -649,6 +663,7 @@ static int prefill_attn(const void* q, const void* k, const void* v, void* out, 
     a.causal = causal ? 1 : 0;
     a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt(static_cast<float>(head_dim));
     a.heads_per_block = 1; a.row_tiles = 0;
+    a.group = n_q_heads / n_kv_heads; a.head_blocks = 0; a.hb_shift = 0; a.magic_head_blocks = 0; a.magic_kv_heads = 0;
     a.k_cache = k_cache; a.v_cache = v_cache; a.s_max = s_max; a.pos0 = pos0;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
