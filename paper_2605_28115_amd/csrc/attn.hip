@@ -284,6 +284,34 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
     const __bf16* vp = static_cast<const __bf16*>(a.v) + b * a.ks[0] + g * a.ks[2];
     const uint32_t row_bytes = static_cast<uint32_t>(a.ks[1]) * 2u;   // K/V token stride
 
+    // Q first: its loads are the longest wait of the prologue, everything else is set up in their shadow.
+    // Q goes through LDS as well (same swizzled layout as a K tile, 32 rows per wavefront), so that the
+    // kernel holds no register-destination global load: the compiler then never emits a vmcnt wait of
+    // its own, which would drain the K/V prefetches along with it.  The staging area is the last ring
+    // stage, which the pipeline first fills after its first barrier, plus a tail behind the ring.
+    constexpr int QW = 32 * PITCHB;                           // bytes of one wavefront's Q tile
+    const uint32_t q_lds = w < 2 ? (kStages - 1) * TILEB + w * QW
+                         : w < 4 ? VBASE + (kStages - 1) * TILEB + (w - 2) * QW
+                                 : 2 * VBASE + (w - 4) * QW;
+    {
+        const char* qb = reinterpret_cast<const char*>(static_cast<const __bf16*>(a.q) + b * a.qs[0] + h * a.qs[2]);
+        const uint64_t qb_bits = reinterpret_cast<uint64_t>(qb);
+        // (the builtin returns a signed int: widen each half as unsigned)
+        const uint32_t qb_hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(qb_bits >> 32)));
+        const uint32_t qb_lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(qb_bits)));
+        const uint64_t qb_uni = (static_cast<uint64_t>(qb_hi) << 32) | qb_lo;
+        const uint32_t q_row_bytes = static_cast<uint32_t>(a.qs[1]) * 2u;
+        const uint32_t q_lds_uni = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds)) + q_lds);
+#pragma unroll
+        for (int j = 0; j < PITCH / 2; ++j) {
+            const int slot = j * kWave + lane;
+            const int row = slot / PITCH;
+            const int c = (slot % PITCH) ^ swz<PITCH>(row);
+            const uint32_t cb = (c * 8 < a.head_dim) ? c * 16 : 0;
+            dma16(reinterpret_cast<const void*>(qb_uni), static_cast<uint32_t>(min(row0 + row, a.seq - 1)) * q_row_bytes + cb,
+                  q_lds_uni + j * kWave * 16);
+        }
+    }
     // Global -> LDS: instruction j of wavefront w fills slots [(w*NI + j)*64, +64) of a tile; slot ->
     // (row, physical chunk); the lane fetches the logical chunk that belongs there.  Every lane always
     // loads (the count of outstanding loads is what the pipeline waits on): rows past the end of the
@@ -317,33 +345,6 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
         }
     };
 
-    // Q goes through LDS as well (same swizzled layout as a K tile, 32 rows per wavefront), so that the
-    // kernel holds no register-destination global load: the compiler then never emits a vmcnt wait of
-    // its own, which would drain the K/V prefetches along with it.  The staging area is the last ring
-    // stage, which the pipeline first fills after its first barrier, plus a tail behind the ring.
-    constexpr int QW = 32 * PITCHB;                           // bytes of one wavefront's Q tile
-    const uint32_t q_lds = w < 2 ? (kStages - 1) * TILEB + w * QW
-                         : w < 4 ? VBASE + (kStages - 1) * TILEB + (w - 2) * QW
-                                 : 2 * VBASE + (w - 4) * QW;
-    {
-        const char* qb = reinterpret_cast<const char*>(static_cast<const __bf16*>(a.q) + b * a.qs[0] + h * a.qs[2]);
-        const uint64_t qb_bits = reinterpret_cast<uint64_t>(qb);
-        // (the builtin returns a signed int: widen each half as unsigned)
-        const uint32_t qb_hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(qb_bits >> 32)));
-        const uint32_t qb_lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(qb_bits)));
-        const uint64_t qb_uni = (static_cast<uint64_t>(qb_hi) << 32) | qb_lo;
-        const uint32_t q_row_bytes = static_cast<uint32_t>(a.qs[1]) * 2u;
-        const uint32_t q_lds_uni = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds)) + q_lds);
-#pragma unroll
-        for (int j = 0; j < PITCH / 2; ++j) {
-            const int slot = j * kWave + lane;
-            const int row = slot / PITCH;
-            const int c = (slot % PITCH) ^ swz<PITCH>(row);
-            const uint32_t cb = (c * 8 < a.head_dim) ? c * 16 : 0;
-            dma16(reinterpret_cast<const void*>(qb_uni), static_cast<uint32_t>(min(row0 + row, a.seq - 1)) * q_row_bytes + cb,
-                  q_lds_uni + j * kWave * 16);
-        }
-    }
     // Start the pipeline: tiles 0 .. kStages-2
 #pragma unroll
     for (int p = 0; p < kStages - 1; ++p)
