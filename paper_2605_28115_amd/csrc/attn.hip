@@ -519,11 +519,13 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
 
     // Fused KV-cache write: the workgroup of the first head block copies the K and V rows of its own
     // query rows (keys block_row0 .. block_rows_end-1, which it has just streamed through LDS, so
-    // the reads hit L2) into the cache; loads go out before the output rows are stored, stores after.  Four 16-byte
-    // pieces per thread cover the usual block (64 rows of 128 channels, K and V); taller blocks take
-    // the rest in a plain loop at the end.
-    constexpr int kKvPieces = 4;
-    u32x4 kv_piece[kKvPieces];
+    // the reads hit L2) into the cache; the loads of the first 64 rows go out before the output rows are
+    // stored and their stores after; taller blocks take the rest in a plain loop at the end.
+    // Copy layout: 8 threads per row, thread t takes row t / 8 of a 64-row group and the 16-byte pieces
+    // t % 8, t % 8 + 8, ... of it, the same piece of K and of V (one address computation for both).
+    constexpr int kKvJ = (DP / 8 + 7) / 8;                     // pieces per thread, row and tensor
+    constexpr int kKvRows = WAVES * kWave / 8;                 // rows per pass of the workgroup (64 with 8 wavefronts)
+    u32x4 kv_piece[2 * kKvJ];
     // opaque copies: they keep the address arithmetic of the epilogue down here, instead of in registers
     // (or spilled) across the main loop
     int tid_late = tid, lane_late = lane;
@@ -531,19 +533,13 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
     const int col_late = lane_late & 31, half_late = lane_late >> 5;
     const bool kv_fused = a.k_cache != nullptr && hb == 0;
     const int kv_cpr = a.head_dim / 8;                         // 16-byte pieces per row
-    const int kv_half = (block_rows_end - block_row0) * kv_cpr;   // pieces of one tensor
-    auto kv_src = [&](int id) {
-        const int which = id >= kv_half;                       // 0: K, 1: V
-        const int rem = id - which * kv_half;
-        const int r = rem / kv_cpr, c = rem - r * kv_cpr;
-        return reinterpret_cast<const u32x4*>((which ? vp : kp) + static_cast<int64_t>(block_row0 + r) * a.ks[1] + c * 8);
-    };
-    auto kv_dst = [&](int id) {
-        const int which = id >= kv_half;
-        const int rem = id - which * kv_half;
-        const int r = rem / kv_cpr, c = rem - r * kv_cpr;
+    const int kv_rows = block_rows_end - block_row0;
+    const int kv_r = tid_late >> 3, kv_c = tid_late & 7;
+    // element offsets of piece (row r, chunk kv_c) from kp / vp and from the cache bases
+    auto kv_src_off = [&](int r) { return static_cast<int64_t>(block_row0 + r) * a.ks[1] + kv_c * 8; };
+    auto kv_dst_off = [&](int r) {
         const int64_t cache_row = (static_cast<int64_t>(b) * a.n_kv_heads + g) * a.s_max + a.pos0 + block_row0 + r;
-        return reinterpret_cast<u32x4*>(static_cast<__bf16*>(which ? a.v_cache : a.k_cache) + cache_row * a.head_dim + c * 8);
+        return cache_row * a.head_dim + kv_c * 8;
     };
     float l_sum = l_run[0] + l_run[1];
     const float l_tot = l_sum + __shfl_xor(l_sum, 32, kWave);
@@ -564,29 +560,56 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
     __builtin_amdgcn_wave_barrier();
     if (kv_fused) {                                           // (the accumulators are dead by now: registers are free)
+        const int64_t so = kv_src_off(kv_r);
 #pragma unroll
-        for (int i = 0; i < kKvPieces; ++i) {
-            const int id = i * (WAVES * kWave) + tid_late;
-            kv_piece[i] = u32x4{0u, 0u, 0u, 0u};
-            if (id < 2 * kv_half) kv_piece[i] = *kv_src(id);
+        for (int j = 0; j < kKvJ; ++j) {
+            kv_piece[2 * j] = kv_piece[2 * j + 1] = u32x4{0u, 0u, 0u, 0u};
+            if (kv_r < kv_rows && kv_c + 8 * j < kv_cpr) {
+                kv_piece[2 * j] = *reinterpret_cast<const u32x4*>(kp + so + 64 * j);
+                kv_piece[2 * j + 1] = *reinterpret_cast<const u32x4*>(vp + so + 64 * j);
+            }
         }
     }
     __bf16* ob = static_cast<__bf16*>(a.out) + b * a.os[0] + h * a.os[2];
+    if (kWave % CPR == 0 && row0 + 32 <= a.seq && a.head_dim == DP) {
+        // whole tile, unpadded head: the lane keeps its column, rows advance by 64 / CPR per store
+        constexpr int RPI = kWave / CPR > 0 ? kWave / CPR : 1;
+        const int r0 = lane_late / CPR, dc = lane_late - r0 * CPR;
+        __bf16* dst = ob + static_cast<int64_t>(row0 + r0) * a.os[1] + dc * 8;
+        const __bf16* src = &o_s[r0 * OROW + dc * 8];
+        const int64_t step = static_cast<int64_t>(RPI) * a.os[1];
 #pragma unroll
-    for (int it = 0; it < 32 * CPR / kWave; ++it) {
-        const int id = it * kWave + lane_late;
-        const int r = id / CPR, dc = id - r * CPR;
-        if (row0 + r < a.seq && dc * 8 < a.head_dim)
-            *reinterpret_cast<bf16x8*>(ob + static_cast<int64_t>(row0 + r) * a.os[1] + dc * 8) =
-                *reinterpret_cast<const bf16x8*>(&o_s[r * OROW + dc * 8]);
+        for (int it = 0; it < 32 * CPR / kWave; ++it)
+            *reinterpret_cast<bf16x8*>(dst + it * step) = *reinterpret_cast<const bf16x8*>(src + it * RPI * OROW);
+    } else {
+#pragma unroll
+        for (int it = 0; it < 32 * CPR / kWave; ++it) {
+            const int id = it * kWave + lane_late;
+            const int r = id / CPR, dc = id - r * CPR;
+            if (row0 + r < a.seq && dc * 8 < a.head_dim)
+                *reinterpret_cast<bf16x8*>(ob + static_cast<int64_t>(row0 + r) * a.os[1] + dc * 8) =
+                    *reinterpret_cast<const bf16x8*>(&o_s[r * OROW + dc * 8]);
+        }
     }
     if (kv_fused) {
+        __bf16* const kc = static_cast<__bf16*>(a.k_cache);
+        __bf16* const vc = static_cast<__bf16*>(a.v_cache);
+        const int64_t d0 = kv_dst_off(kv_r);
 #pragma unroll
-        for (int i = 0; i < kKvPieces; ++i) {
-            const int id = i * (WAVES * kWave) + tid_late;
-            if (id < 2 * kv_half) *kv_dst(id) = kv_piece[i];
+        for (int j = 0; j < kKvJ; ++j)
+            if (kv_r < kv_rows && kv_c + 8 * j < kv_cpr) {
+                *reinterpret_cast<u32x4*>(kc + d0 + 64 * j) = kv_piece[2 * j];
+                *reinterpret_cast<u32x4*>(vc + d0 + 64 * j) = kv_piece[2 * j + 1];
+            }
+        for (int r = kv_r + kKvRows; r < kv_rows; r += kKvRows) {   // taller blocks (fewer than 4 heads per block)
+            const int64_t so = kv_src_off(r), dd = kv_dst_off(r);
+#pragma unroll
+            for (int j = 0; j < kKvJ; ++j)
+                if (kv_c + 8 * j < kv_cpr) {
+                    *reinterpret_cast<u32x4*>(kc + dd + 64 * j) = *reinterpret_cast<const u32x4*>(kp + so + 64 * j);
+                    *reinterpret_cast<u32x4*>(vc + dd + 64 * j) = *reinterpret_cast<const u32x4*>(vp + so + 64 * j);
+                }
         }
-        for (int id = kKvPieces * (WAVES * kWave) + tid_late; id < 2 * kv_half; id += WAVES * kWave) *kv_dst(id) = *kv_src(id);
     }
 }
 
