@@ -430,14 +430,17 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
 
         // mask only where the tile crosses the diagonal or the end of the sequence (wave-uniform)
         if ((a.causal && key0 + kBN - 1 > row0) || key0 + kBN > a.seq) {
+            // The lane sees the tile's keys below `lim` (end of the sequence, and its own row under the causal
+            // mask).  Register r of sub-tile t holds tile key 32 t + 8 (r / 4) + r % 4 + 4 half, so one
+            // per-lane threshold against a constant per register decides: a compare and a select each.
+            int lim = a.seq - key0;
+            if (a.causal) lim = min(lim, qi - key0 + 1);
+            const int thr = lim - 4 * half;
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int kj = key0 + 32 * t + 8 * (r >> 2) + 4 * half + (r & 3);
-                    const bool ok = kj < a.seq && (!a.causal || kj <= qi);
-                    acc_s[t][r] = ok ? acc_s[t][r] : -INFINITY;
-                }
+                for (int r = 0; r < 16; ++r)
+                    acc_s[t][r] = 32 * t + 8 * (r >> 2) + (r & 3) < thr ? acc_s[t][r] : -INFINITY;
         }
         // P = exp2((acc_s - m_run) * scale * log2 e), rounded to bf16, laid out as the B operands; lt = the
         // lane's two partial row sums of the rounded probabilities (what the PV product actually uses).
