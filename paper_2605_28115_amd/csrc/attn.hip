@@ -358,8 +358,12 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
     for (int s = 0; s < KSTEPS; ++s) {
         const bf16x8 t = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
             lds + q_lds + col * PITCHB + (((2 * s + half) ^ swz<PITCH>(col & 15)) << 4));
+        qreg[s] = t;
+    }
+    if (a.head_dim != DP) {                                   // a padded head: the columns past head_dim count as zero
         const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-        qreg[s] = (16 * s + 8 * half < a.head_dim) ? t : zero;
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s) qreg[s] = (16 * s + 8 * half < a.head_dim) ? qreg[s] : zero;
     }
 
     // in registers before the first barrier, after which the staging area is refilled
