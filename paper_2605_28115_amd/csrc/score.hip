@@ -27,14 +27,6 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc)
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), acc, false);
 }
 
-// Round-to-nearest-even bf16 bits of a finite float (NaN stays NaN).
-__device__ __forceinline__ uint32_t bf16_rne_bits(float f)
-{
-    const uint32_t u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0u;
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
-
 // The 8 bf16 elements of a 16-byte chunk, widened.
 __device__ __forceinline__ void unpack_bf16(const u32x4& raw, float* x)
 {
@@ -158,21 +150,24 @@ __global__ __launch_bounds__(kScoreThreads, kScoreWavesPerSimd) void score_bf16_
         for (int c = 0; c < CHUNKS; ++c) fetch_chunk(first, c);
     }
 
-    // Anchor: head = bf16(q), tail = bf16(q - head); sum_q is the sum of what the two words represent.
+    // Anchor: head = bf16(q), tail = bf16(q - head), both rounded to nearest even; sum_q is the sum of what the
+    // two words represent.
     float q_sum = 0.f;
     for (int i = threadIdx.x * 4; i < dim; i += kScoreThreads * 4) {
         const float4 t = *reinterpret_cast<const float4*>(anchor_q + i);
         const float v[4] = {t.x, t.y, t.z, t.w};
-        uint32_t h[4], l[4];
+        uint32_t hw[2], lw[2];                                     // packed pairs (v_cvt_pk_bf16_f32 rounds to nearest even)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            h[e] = bf16_rne_bits(v[e]);
-            const float head = bf16_bits_to_float(h[e]);
-            l[e] = bf16_rne_bits(v[e] - head);
-            q_sum += head + bf16_bits_to_float(l[e]);
+        for (int e = 0; e < 2; ++e) {
+            const bf16x2 hp = {static_cast<__bf16>(v[2 * e]), static_cast<__bf16>(v[2 * e + 1])};
+            hw[e] = __builtin_bit_cast(uint32_t, hp);
+            const float h0 = __uint_as_float(hw[e] << 16), h1 = __uint_as_float(hw[e] & 0xFFFF0000u);
+            const bf16x2 lp = {static_cast<__bf16>(v[2 * e] - h0), static_cast<__bf16>(v[2 * e + 1] - h1)};
+            lw[e] = __builtin_bit_cast(uint32_t, lp);
+            q_sum += (h0 + __uint_as_float(lw[e] << 16)) + (h1 + __uint_as_float(lw[e] & 0xFFFF0000u));
         }
-        *reinterpret_cast<u32x2*>(q_hi + i / 2) = u32x2{h[0] | (h[1] << 16), h[2] | (h[3] << 16)};
-        *reinterpret_cast<u32x2*>(q_lo + i / 2) = u32x2{l[0] | (l[1] << 16), l[2] | (l[3] << 16)};
+        *reinterpret_cast<u32x2*>(q_hi + i / 2) = u32x2{hw[0], hw[1]};
+        *reinterpret_cast<u32x2*>(q_lo + i / 2) = u32x2{lw[0], lw[1]};
     }
     q_sum = wave_sum(q_sum);
     if (lane == 0) q_part[wave] = q_sum;
