@@ -160,7 +160,7 @@ int civic_compact(const void* hidden, int dtype, int32_t dim, const int32_t* pos
  *   softmax_scale  0 means 1/sqrt(head_dim)
  * Pointers and strides*sizeof(element) must be 16-byte aligned; head_dim a multiple of 8
  * and at most CIVIC_MAX_HEAD_DIM; n_q_heads a multiple of n_kv_heads; batch and n_q_heads at
- * most 65535; bf16 with head_dim <= 128: seq at most 2^21 and batch * n_q_heads * n_kv_heads
+ * most 65535; bf16 with head_dim <= 128: seq at most 2^21 and batch * n_q_heads * n_q_heads
  * below 2^32 (CIVIC_ERR_UNSUPPORTED beyond). */
 int civic_prefill_attn(const void* q, const void* k, const void* v, void* out, int dtype,
                        int32_t batch, int32_t seq, int32_t n_q_heads, int32_t n_kv_heads,
