@@ -160,8 +160,9 @@ int civic_compact(const void* hidden, int dtype, int32_t dim, const int32_t* pos
  *   softmax_scale  0 means 1/sqrt(head_dim)
  * Pointers and strides*sizeof(element) must be 16-byte aligned; head_dim a multiple of 8
  * and at most CIVIC_MAX_HEAD_DIM; n_q_heads a multiple of n_kv_heads; batch and n_q_heads at
- * most 65535; bf16 with head_dim <= 128: seq at most 2^21 and batch * n_q_heads * n_q_heads
- * below 2^32 (CIVIC_ERR_UNSUPPORTED beyond). */
+ * most 65535.  The MFMA kernel serves bf16 with head_dim <= 128 while its 32-bit row offsets
+ * and its grid allow (seq * q token stride below 2^31 elements, seq up to 2^22); sizes beyond
+ * that, like fp32 and wider heads, take the plain kernel. */
 int civic_prefill_attn(const void* q, const void* k, const void* v, void* out, int dtype,
                        int32_t batch, int32_t seq, int32_t n_q_heads, int32_t n_kv_heads,
                        int32_t head_dim, const int64_t* q_strides /* host [3] */,

@@ -620,21 +620,30 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
     }
 }
 
+// Block shape and grid of the MFMA kernel for these sizes; false if the grid does not fit (more than 65535
+// row tiles, or a block index too large for the multiply-high decoding: n * d < 2^32 for n < per_rt).
+template <int WAVES>
+static bool mfma_geometry(AttnArgs& a, int64_t* per_rt)
+{
+    const int group = a.n_q_heads / a.n_kv_heads;
+    a.heads_per_block = (group % 4 == 0) ? 4 : (group % 2 == 0) ? 2 : 1;
+    const int rows_per_block = 32 * (WAVES / a.heads_per_block);
+    const int64_t row_tiles = (static_cast<int64_t>(a.seq) + rows_per_block - 1) / rows_per_block;
+    a.row_tiles = static_cast<int32_t>(row_tiles);
+    a.group = group;
+    a.head_blocks = group / a.heads_per_block;
+    a.hb_shift = a.heads_per_block == 4 ? 2 : a.heads_per_block == 2 ? 1 : 0;
+    *per_rt = static_cast<int64_t>(a.head_blocks) * a.n_kv_heads * a.batch;
+    const int64_t d_max = a.head_blocks > a.n_kv_heads ? a.head_blocks : a.n_kv_heads;
+    return *per_rt * d_max < (int64_t{1} << 32) && row_tiles <= 65535;
+}
+
 template <int DP, int WAVES, int STAGES>
 static int launch_mfma(AttnArgs& a, hipStream_t s)
 {
     using T = AttnTile<DP, WAVES, STAGES>;
-    const int group = a.n_q_heads / a.n_kv_heads;
-    a.heads_per_block = (group % 4 == 0) ? 4 : (group % 2 == 0) ? 2 : 1;
-    const int rows_per_block = 32 * (WAVES / a.heads_per_block);
-    a.row_tiles = (a.seq + rows_per_block - 1) / rows_per_block;
-    a.group = group;
-    a.head_blocks = group / a.heads_per_block;
-    a.hb_shift = a.heads_per_block == 4 ? 2 : a.heads_per_block == 2 ? 1 : 0;
-    const int64_t per_rt = static_cast<int64_t>(a.head_blocks) * a.n_kv_heads * a.batch;
-    // ceil(2^32 / d) gives exact quotients while n * d < 2^32; n < per_rt here
-    const int64_t d_max = a.head_blocks > a.n_kv_heads ? a.head_blocks : a.n_kv_heads;
-    if (per_rt * d_max >= (int64_t{1} << 32) || a.row_tiles > 65535) return CIVIC_ERR_UNSUPPORTED;
+    int64_t per_rt = 0;
+    if (!mfma_geometry<WAVES>(a, &per_rt)) return CIVIC_ERR_UNSUPPORTED;      // (the caller has checked)
     auto magic = [](int64_t d) { return d <= 1 ? 0u : static_cast<uint32_t>(((int64_t{1} << 32) + d - 1) / d); };
     a.magic_head_blocks = magic(a.head_blocks);
     a.magic_kv_heads = magic(a.n_kv_heads);
@@ -698,9 +707,12 @@ static int prefill_attn(const void* q, const void* k, const void* v, void* out, 
     a.k_cache = k_cache; a.v_cache = v_cache; a.s_max = s_max; a.pos0 = pos0;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
-    // the MFMA path addresses a K/V tile, and a head's Q rows, with 32-bit per-lane byte offsets
+    // the MFMA path addresses a K/V tile, and a head's Q rows, with 32-bit per-lane byte offsets, and its grid
+    // has limits of its own; whatever falls outside takes the plain kernel
+    int64_t per_rt_unused = 0;
     if (dtype == CIVIC_BF16 && head_dim <= 128 && kv_strides[1] * 2 < (1 << 25) &&
-        static_cast<int64_t>(seq) * q_strides[1] * 2 < (int64_t{1} << 32)) {
+        static_cast<int64_t>(seq) * q_strides[1] * 2 < (int64_t{1} << 32) &&
+        mfma_geometry<CIVIC_ATTN_WAVES>(a, &per_rt_unused)) {
         if (head_dim <= 64) return launch_mfma<64, CIVIC_ATTN_WAVES, CIVIC_ATTN_STAGES>(a, s);
         if (head_dim <= 96) return launch_mfma<96, CIVIC_ATTN_WAVES, CIVIC_ATTN_STAGES>(a, s);
         return launch_mfma<128, CIVIC_ATTN_WAVES, CIVIC_ATTN_STAGES>(a, s);
