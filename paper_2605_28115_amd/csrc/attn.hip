@@ -398,27 +398,23 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
     float l_run[2] = {0.f, 0.f};           // running row sum, two partial accumulators
     const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
 
-    // One tile: wait until it has landed, release the previous one, refill the freed stage, compute.
-    auto tile = [&](int kt, auto stage_c) {
+    // The arithmetic of one tile (stage ST of the ring) for this wavefront: NT = 2 for the whole tile, 1 for
+    // its first 32 keys only.
+    auto tile = [&](int kt, auto stage_c, auto nt_c) {
         constexpr int ST = decltype(stage_c)::value;
-        // Loads retire in order.  Younger than tile kt are the tiles issued after it (at most
-        // kStages-2 of them).
-        wait_tiles<kStages - 2, TLOADS>(min(n_tiles - 1 - kt, kStages - 2));
-        block_barrier();                                      // landed for every wavefront; tile kt-1 is released
-        if (kt + kStages - 1 < n_tiles) issue_tile(kt + kStages - 1, (ST + kStages - 1) % kStages);
-
+        constexpr int NT = decltype(nt_c)::value;
         const int key0 = kt * kBN;
         if (a.causal && key0 > row0 + 31) return;             // no key of the tile is visible to this wavefront
         // S^T tile: rows = keys (two 32-key sub-tiles), columns = this wavefront's 32 queries
-        f32x16 acc_s[2];                                      // raw logits
+        f32x16 acc_s[NT];                                     // raw logits
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+        for (int t = 0; t < NT; ++t)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc_s[t][r] = 0.f;
 #pragma unroll
         for (int s = 0; s < KSTEPS; ++s)
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
+            for (int t = 0; t < NT; ++t) {
                 const bf16x8 ka = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
                     kaddr[s] + ST * TILEB + 32 * t * PITCHB);
                 acc_s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[s], acc_s[t], 0, 0, 0);
@@ -426,7 +422,7 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
         // keep 4 K fragments in flight ahead of the MFMA that consumes them
         __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
 #pragma unroll
-        for (int i = 0; i < 2 * KSTEPS - 4; ++i) {
+        for (int i = 0; i < NT * KSTEPS - 4; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
@@ -441,20 +437,20 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
             if (a.causal) lim = min(lim, qi - key0 + 1);
             const int thr = lim - 4 * half;
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
+            for (int t = 0; t < NT; ++t)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
                     acc_s[t][r] = 32 * t + 8 * (r >> 2) + (r & 3) < thr ? acc_s[t][r] : -INFINITY;
         }
         // P = exp2((acc_s - m_run) * scale * log2 e), rounded to bf16, laid out as the B operands; lt = the
         // lane's two partial row sums of the rounded probabilities (what the PV product actually uses).
-        bf16x8 pb[2][2];
+        bf16x8 pb[NT][2];
         float lt[2];
         auto probs = [&]() __attribute__((always_inline)) {
             const float off = -m_run * sl2;
             lt[0] = 0.f; lt[1] = 0.f;
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
+            for (int t = 0; t < NT; ++t)
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
                     u32x4 packed;
@@ -478,9 +474,9 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
         const bool first = kt == 0;
         if (!first) probs();
         if (first || __any(lt[0] + lt[1] > 1048576.f)) {
-            float mq[4];
+            float mq[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
 #pragma unroll
-            for (int c4 = 0; c4 < 4; ++c4) {
+            for (int c4 = 0; c4 < 2 * NT; ++c4) {
                 const f32x16& x = acc_s[c4 >> 1];
                 const int o = 8 * (c4 & 1);
                 mq[c4] = fmaxf(max3(max3(x[o], x[o + 1], x[o + 2]), x[o + 3], x[o + 4]), max3(x[o + 5], x[o + 6], x[o + 7]));
@@ -502,7 +498,7 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
         l_run[0] += lt[0]; l_run[1] += lt[1];
         // O^T += V^T P^T.  The k-slot (half, e) of step (t, u) is key 32t + 16u + 8(e/4) + 4 half + e%4.
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+        for (int t = 0; t < NT; ++t)
 #pragma unroll
             for (int u = 0; u < 2; ++u)
 #pragma unroll
@@ -516,11 +512,25 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
                 }
     };
 
+    // One step of the pipeline: wait until the tile has landed, release the previous one, refill the freed
+    // stage, compute.  Loads retire in order; younger than tile kt are the tiles issued after it (at most
+    // kStages-2 of them).
+    auto step = [&](int kt, auto stage_c) __attribute__((always_inline)) {
+        constexpr int ST = decltype(stage_c)::value;
+        wait_tiles<kStages - 2, TLOADS>(min(n_tiles - 1 - kt, kStages - 2));
+        block_barrier();                                      // landed for every wavefront; tile kt-1 is released
+        if (kt + kStages - 1 < n_tiles) issue_tile(kt + kStages - 1, (ST + kStages - 1) % kStages);
+        // On the diagonal a wavefront whose rows all precede the tile's second half computes the first half
+        // only: half the MFMAs and exponentials of that tile for half of the wavefronts, which the other
+        // wavefront of the SIMD turns into time.
+        if (a.causal && kt * kBN + 32 > row0 + 31) tile(kt, stage_c, std::integral_constant<int, 1>{});
+        else tile(kt, stage_c, std::integral_constant<int, 2>{});
+    };
     for (int kt = 0; kt < n_tiles; kt += kStages) {
-        tile(kt, std::integral_constant<int, 0>{});
-        if (kt + 1 < n_tiles) tile(kt + 1, std::integral_constant<int, 1>{});
-        if constexpr (kStages > 2) if (kt + 2 < n_tiles) tile(kt + 2, std::integral_constant<int, 2>{});
-        if constexpr (kStages > 3) if (kt + 3 < n_tiles) tile(kt + 3, std::integral_constant<int, 3>{});
+        step(kt, std::integral_constant<int, 0>{});
+        if (kt + 1 < n_tiles) step(kt + 1, std::integral_constant<int, 1>{});
+        if constexpr (kStages > 2) if (kt + 2 < n_tiles) step(kt + 2, std::integral_constant<int, 2>{});
+        if constexpr (kStages > 3) if (kt + 3 < n_tiles) step(kt + 3, std::integral_constant<int, 3>{});
     }
     __syncthreads();                                          // every tile consumed: LDS is free
 
