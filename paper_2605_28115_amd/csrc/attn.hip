@@ -522,8 +522,9 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
         if (kt + kStages - 1 < n_tiles) issue_tile(kt + kStages - 1, (ST + kStages - 1) % kStages);
         // On the diagonal a wavefront whose rows all precede the tile's second half computes the first half
         // only: half the MFMAs and exponentials of that tile for half of the wavefronts, which the other
-        // wavefront of the SIMD turns into time.
-        if (a.causal && kt * kBN + 32 > row0 + 31) tile(kt, stage_c, std::integral_constant<int, 1>{});
+        // wavefront of the SIMD turns into time.  The same holds for a last tile whose second half lies past
+        // the end of the sequence.
+        if ((a.causal && kt * kBN + 32 > row0 + 31) || kt * kBN + 32 >= a.seq) tile(kt, stage_c, std::integral_constant<int, 1>{});
         else tile(kt, stage_c, std::integral_constant<int, 2>{});
     };
     for (int kt = 0; kt < n_tiles; kt += kStages) {
