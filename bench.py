@@ -44,7 +44,7 @@ STAGES_UNFUSED = ("score", "select", "compact", "attn", "kv_write")
 # HBM bytes per attention launch from the profiler's FETCH_SIZE / WRITE_SIZE counters, each scaled by what the
 # same counter reads for a plain copy of known size (profiles/bench_8b_hbm_traffic.txt); measured offline,
 # per workload, and only quoted here.
-MEASURED_ATTN_TRAFFIC_BYTES = {("8b", "attn_kv"): 96.63e6, ("8b", "attn"): 78.10e6}
+MEASURED_ATTN_TRAFFIC_BYTES = {("8b", "attn_kv"): 96.74e6, ("8b", "attn"): 78.10e6}
 
 
 def dev(storage: np.ndarray) -> torch.Tensor:
