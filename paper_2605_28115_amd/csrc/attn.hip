@@ -21,7 +21,12 @@
 //     later only when the row sums show that a tile outgrew it (no per-tile maximum pass).
 //   - fp32 accumulation, row sums taken from the rounded probabilities with v_dot2c_f32_bf16, bf16
 //     output (nearest even) staged through LDS into whole 16-byte row segments.
-//   - Workgroups are ordered heaviest causal row tile first.
+//   - Workgroups are ordered heaviest causal row tile first (row tile on grid y, the rest of the block
+//     index decoded with multiply-high constants from the launch: no integer division ahead of Q's loads).
+//   - Masking costs a compare and a select per score and only on tiles that cross the diagonal or the end
+//     of the sequence; a wavefront that cannot see the second half of such a tile computes the first only.
+//   - civic_prefill_attn_kv: the workgroup of a KV head's first head block also copies the K/V rows of its
+//     own query rows into the caches (8 threads per row, same address for K and V).
 //
 // fp32 path and head sizes the MFMA path does not cover: a plain fp32 kernel, one wavefront per
 // query row (lanes over keys for Q K^T, lanes over channels for P V).
