@@ -33,6 +33,7 @@ int grid_info(const civic_grid* g, GridInfo* out)
     if (rem_c) per_frame += full_r * floor_of(static_cast<int64_t>(g->cell_h) * rem_c);
     if (rem_r) per_frame += full_c * floor_of(rem_r * g->cell_w);
     if (rem_r && rem_c) per_frame += floor_of(rem_r * rem_c);
+    out->cell_kept_frame = static_cast<int32_t>(per_frame);
     const int64_t left = hw - per_frame;
     per_frame += left < g->frame_floor ? left : static_cast<int64_t>(g->frame_floor);
     const int64_t floor_sum = per_frame * g->frames;

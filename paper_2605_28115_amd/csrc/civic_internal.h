@@ -28,6 +28,7 @@ struct GridInfo {
     int32_t frames, height, width, cell_h, cell_w, cell_floor, frame_floor, budget;
     int32_t hw;          // tokens per frame
     int32_t nv;          // visual tokens per sample
+    int32_t cell_kept_frame;   // tokens the cell floors protect in one frame
     int32_t floor_sum;   // tokens the floors protect, per sample
     int32_t kept;        // K = max(budget, floor_sum)
     int32_t fill;        // tokens the budget adds after the floors

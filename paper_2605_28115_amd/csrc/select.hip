@@ -16,13 +16,16 @@
 //           whole (typically the second of three), because the threshold's low bits no longer matter.
 //   output  popcounts of the 64-bit mark words -> LDS prefix scan -> every set bit writes its index
 //           at (prefix of its word + set bits below it): ascending kept_idx without any sort.
+#include <cmath>
+
 #include "civic_internal.h"
 
 namespace civic {
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / kWave;
-constexpr int kSmallCell = 256;        // cells up to this many tokens use the all-pairs rank
+constexpr int kSmallCell = 256;        // cells up to this many tokens are scanned by one thread each
+constexpr int kSelBatch = 4;           // tokens per thread whose LDS reads are in flight together
 
 struct SelArgs {
     const float* scores;
@@ -35,6 +38,9 @@ struct SelArgs {
     int32_t fill;          // tokens the global budget adds after the floors
     int32_t kept;          // K
     int32_t big_cells;     // 1: cells go through the per-wave radix select
+    int32_t cell_kept_frame;   // tokens the cell floors protect in one frame
+    int32_t quad_scores;   // 1: every sample's scores can be read as aligned groups of four
+    int32_t lds_words;     // size of the dynamic LDS allocation in 32-bit words
     uint32_t magic_cells_f, magic_cells_x;   // ceil(2^32 / d) for d = cells per frame, cells per grid row (0 for d = 1)
 };
 
@@ -86,6 +92,25 @@ __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, int)
     return v;
 }
 
+// Reduction over the 64 lanes with an idempotent operation (min, max), result in lane 63: the same DPP
+// moves as the scan above; a lane without a source combines with its own value.
+template <typename Op>
+__device__ __forceinline__ float wave_reduce(float v, Op op)
+{
+    auto step = [&](float x, auto ctrl, auto row_mask) {
+        const int xi = __float_as_int(x);
+        return op(x, __int_as_float(__builtin_amdgcn_update_dpp(xi, xi, decltype(ctrl)::value, decltype(row_mask)::value, 0xF, false)));
+    };
+    using std::integral_constant;
+    v = step(v, integral_constant<int, 0x111>{}, integral_constant<int, 0xF>{});
+    v = step(v, integral_constant<int, 0x112>{}, integral_constant<int, 0xF>{});
+    v = step(v, integral_constant<int, 0x114>{}, integral_constant<int, 0xF>{});
+    v = step(v, integral_constant<int, 0x118>{}, integral_constant<int, 0xF>{});
+    v = step(v, integral_constant<int, 0x142>{}, integral_constant<int, 0xA>{});
+    v = step(v, integral_constant<int, 0x143>{}, integral_constant<int, 0xC>{});
+    return v;
+}
+
 // Orders LDS traffic of the team: a workgroup barrier, or for a single wavefront (whose LDS
 // operations already execute in program order) a compiler-level fence.
 template <bool BLOCK>
@@ -106,64 +131,113 @@ __device__ __forceinline__ void team_sync()
 //   hist  counters owned by the team: 2 x 2048 for the workgroup (double buffered, so the next pass's
 //         clear hides behind the scan; both must be zero on entry and are left dirty), 256 for a
 //         wavefront (cleared here, left zero);  bc  8 words owned by the team, 16 for the workgroup.
+//   smax, range  largest score of the sample and its distance to the smallest one (any value is safe:
+//         they only steer the first pass).
+// First a histogram over buckets that are linear in the score, from the sample's largest down to its
+// smallest, a monotone map that spreads the usual score distributions over all bins (the leading bits of a float
+// key do not: they are sign and exponent).  Everything below the bucket that holds the m-th token is
+// admitted, and when that bucket holds few tokens they are ranked against each other directly, so the
+// select is over after one pass.  Otherwise (few distinct values, an outlier that squeezes everything
+// into one bucket, infinities) an exact radix select over the key digits, high digit first, decides.
 template <bool BLOCK, bool CONTIG>
 __device__ void select_first(const uint32_t* keys, uint32_t* marks, uint32_t* hist, uint32_t* bc, const Region reg,
-                             int32_t m, bool only_unmarked, int32_t eligible)
+                             int32_t m, bool only_unmarked, int32_t eligible, float smax, float range)
 {
     constexpr int TEAM = BLOCK ? kSelThreads : kWave;
     const int rank = BLOCK ? threadIdx.x : (threadIdx.x & (kWave - 1));
     const int lane = threadIdx.x & (kWave - 1);
     const int32_t n_iter = (reg.count + TEAM - 1) / TEAM;
-    if (m <= 0) return;
+    const int32_t n_batch = (n_iter + kSelBatch - 1) / kSelBatch;
+    if (m <= 0 || reg.count <= 0) return;
+
+    // The passes over the region take kSelBatch tokens per thread at a time, with all LDS reads of a
+    // batch issued before the first is used (from clamped indices, so that none is conditional).  A
+    // contiguous region that starts on a multiple of four gives a thread four consecutive tokens: one
+    // 16-byte read for the keys, one mark word, and later one LDS atomic for the four new mark bits;
+    // otherwise the four tokens are a team-width apart.
+    const bool quad = CONTIG && (reg.base & 3) == 0;
+    auto fetch = [&](int32_t bi, int32_t (&tok)[kSelBatch], uint32_t (&key)[kSelBatch], bool (&el)[kSelBatch]) {
+        if (quad) {
+            const int32_t i0 = kSelBatch * (bi * TEAM + rank);
+            const int32_t v0 = reg.base + min(i0, (reg.count - 1) & ~(kSelBatch - 1));   // the array is padded to 64 tokens
+            const u32x4 k = *reinterpret_cast<const u32x4*>(keys + v0);
+            const uint32_t mw = marks[v0 >> 5] >> (v0 & 31);
+            key[0] = k.x; key[1] = k.y; key[2] = k.z; key[3] = k.w;
+#pragma unroll
+            for (int u = 0; u < kSelBatch; ++u) {
+                tok[u] = v0 + u;
+                el[u] = i0 + u < reg.count && !(only_unmarked && ((mw >> u) & 1u));
+            }
+        } else {
+            uint32_t mw[kSelBatch];
+#pragma unroll
+            for (int u = 0; u < kSelBatch; ++u) {
+                const int32_t i = (bi * kSelBatch + u) * TEAM + rank;
+                tok[u] = reg.token<CONTIG>(min(i, reg.count - 1));
+                key[u] = keys[tok[u]];
+                mw[u] = marks[tok[u] >> 5];
+            }
+#pragma unroll
+            for (int u = 0; u < kSelBatch; ++u) {
+                const int32_t i = (bi * kSelBatch + u) * TEAM + rank;
+                el[u] = i < reg.count && !(only_unmarked && ((mw[u] >> (tok[u] & 31)) & 1u));
+            }
+        }
+    };
+    // Sets the mark bits of the batch's admitted tokens (a token is admitted at most once, and a pass
+    // reads a token's own bit only, so the order of reads and writes between tokens does not matter).
+    auto mark = [&](const int32_t (&tok)[kSelBatch], const bool (&adm)[kSelBatch]) {
+        if (quad) {
+            uint32_t nib = 0;
+#pragma unroll
+            for (int u = 0; u < kSelBatch; ++u) nib |= adm[u] ? 1u << u : 0u;
+            if (nib) atomicOr(&marks[tok[0] >> 5], nib << (tok[0] & 31));   // an admitted token means tok[0] was not clamped
+        } else {
+#pragma unroll
+            for (int u = 0; u < kSelBatch; ++u)
+                if (adm[u]) set_mark(marks, tok[u]);
+        }
+    };
+    int32_t tok[kSelBatch];
+    uint32_t key[kSelBatch];
+    bool el[kSelBatch], adm[kSelBatch];
 
     if (!BLOCK && eligible < 0) {                                // wave-uniform count from ballots
         eligible = 0;
-        for (int32_t it = 0; it < n_iter; ++it) {
-            const int32_t i = it * TEAM + rank;
-            bool e = false;
-            if (i < reg.count) { const int32_t v = reg.token<CONTIG>(i); e = !(only_unmarked && is_marked(marks, v)); }
-            eligible += __popcll(__ballot(e));
+        for (int32_t bi = 0; bi < n_batch; ++bi) {
+            fetch(bi, tok, key, el);
+#pragma unroll
+            for (int u = 0; u < kSelBatch; ++u) eligible += __popcll(__ballot(el[u]));
         }
     }
     if (m >= eligible) {                                         // floor covers everything that is left
-        for (int32_t it = 0; it < n_iter; ++it) {
-            const int32_t i = it * TEAM + rank;
-            if (i < reg.count) { const int32_t v = reg.token<CONTIG>(i); if (!(only_unmarked && is_marked(marks, v))) set_mark(marks, v); }
+        for (int32_t bi = 0; bi < n_batch; ++bi) {
+            fetch(bi, tok, key, el);
+            mark(tok, el);
         }
         team_sync<BLOCK>();
         return;
     }
 
-    // Radix select of the m-th smallest key among the eligible tokens, high digit first.
     constexpr int BITS = BLOCK ? 11 : 8;
     constexpr int BINS = 1 << BITS;
     constexpr int PASSES = (32 + BITS - 1) / BITS;
     constexpr int CH = BINS / 256;                               // the scanning wavefront takes 4 bins per lane and chunk
+    constexpr uint32_t CAND = BLOCK ? 256 : 64;                  // tokens of one bucket that are ranked directly
     static_assert(CH <= 8, "chunk totals are read as two quads");
+    static_assert(2 * CAND <= BINS, "the candidates live in a histogram buffer");
     if constexpr (!BLOCK) {                                      // the workgroup's histograms are clear on entry (see the kernel)
         for (int i = rank; i < BINS; i += TEAM) hist[i] = 0;
         team_sync<false>();
     }
-    uint32_t prefix = 0, remaining = static_cast<uint32_t>(m), ties = 0;
-    int done_shift = 0;                                          // key bits below this were never looked at
-#pragma unroll 1
-    for (int pass = 0; pass < PASSES; ++pass) {
-        const int shift = 32 - BITS * (pass + 1) > 0 ? 32 - BITS * (pass + 1) : 0;
-        const int width = 32 - BITS * pass < BITS ? 32 - BITS * pass : BITS;
-        const uint32_t digit_mask = (1u << width) - 1u;
+
+    // Finds the bin that holds the `want`-th counted token of histogram `pass & 1` (the workgroup's; a
+    // wavefront has one): bin, tokens in lower bins, tokens in the bin.  Every 256-bin chunk has a
+    // wavefront of its own (4 bins per lane); the workgroup-wide select passes the chunk totals through
+    // bc[8..] and clears the other histogram meanwhile; a wavefront clears its histogram afterwards.
+    auto scan = [&](int pass, uint32_t want, uint32_t& bin, uint32_t& below, uint32_t& count) {
         uint32_t* h = hist + (BLOCK ? (pass & 1) * BINS : 0);
-        const uint32_t hi_mask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + width));
-        for (int32_t it = 0; it < n_iter; ++it) {
-            const int32_t i = it * TEAM + rank;
-            if (i < reg.count) {
-                const int32_t v = reg.token<CONTIG>(i);
-                const uint32_t k = keys[v];
-                if ((k & hi_mask) == prefix && !(only_unmarked && is_marked(marks, v))) atomicAdd(&h[(k >> shift) & digit_mask], 1u);
-            }
-        }
-        team_sync<BLOCK>();
-        // Scan: every 256-bin chunk has a wavefront of its own (4 bins per lane); the workgroup-wide
-        // select passes the chunk totals through bc[8..].
+        uint32_t* res = bc + (pass & 1) * 4;
         const int chunk = BLOCK ? static_cast<int>(threadIdx.x >> 6) : 0;
         const bool scanner = chunk < CH;
         uint32_t c[4] = {0u, 0u, 0u, 0u}, mine = 0, incl = 0, base = 0;
@@ -177,7 +251,6 @@ __device__ void select_first(const uint32_t* keys, uint32_t* marks, uint32_t* hi
             if (scanner) {
                 if (lane == kWave - 1) bc[8 + chunk] = incl;
             } else {
-                // meanwhile the other wavefronts clear the other histogram for the next pass
                 for (int i = threadIdx.x - CH * kWave; i < BINS; i += kSelThreads - CH * kWave) hist[((pass + 1) & 1) * BINS + i] = 0;
             }
             __syncthreads();
@@ -190,12 +263,13 @@ __device__ void select_first(const uint32_t* keys, uint32_t* marks, uint32_t* hi
         }
         if (scanner) {
             uint32_t before = base + incl - mine;
-            if (before < remaining && remaining <= base + incl) {   // exactly one lane of one chunk
+            if (before < want && want <= base + incl) {          // exactly one lane of one chunk
                 int t = 0;
-                while (before + c[t] < remaining) { before += c[t]; ++t; }
-                bc[(pass & 1) * 4 + 0] = static_cast<uint32_t>(chunk * 256 + lane * 4 + t);   // digit
-                bc[(pass & 1) * 4 + 1] = before;                                                // eligible tokens below that digit
-                bc[(pass & 1) * 4 + 2] = c[t];                                                  // tokens with that digit
+                while (before + c[t] < want) { before += c[t]; ++t; }
+                res[0] = static_cast<uint32_t>(chunk * 256 + lane * 4 + t);
+                res[1] = before;
+                res[2] = c[t];
+                res[3] = 0;                                      // the candidate counter of the first pass
             }
         }
         if constexpr (BLOCK) {
@@ -205,9 +279,93 @@ __device__ void select_first(const uint32_t* keys, uint32_t* marks, uint32_t* hi
             for (int i = lane; i < BINS; i += kWave) hist[i] = 0;     // a wavefront orders its own LDS traffic for free
             team_sync<false>();
         }
-        prefix |= bc[(pass & 1) * 4 + 0] << shift;
-        remaining -= bc[(pass & 1) * 4 + 1];
-        ties = bc[(pass & 1) * 4 + 2];
+        bin = res[0]; below = res[1]; count = res[2];
+    };
+
+    uint32_t remaining = static_cast<uint32_t>(m);
+    int first = 0;                                               // 1: the radix passes start on the second histogram
+    if (range > 0.0f && range < INFINITY) {
+        // ---- one pass over score-linear buckets
+        const float scale = static_cast<float>(BINS) / range;
+        auto bucket = [&](uint32_t k) {                          // never decreases with the key; any input lands inside the histogram
+            const uint32_t asc = ~k;
+            const float s = __uint_as_float((asc & 0x80000000u) ? (asc & 0x7FFFFFFFu) : ~asc);
+            return static_cast<uint32_t>(min(max(static_cast<int32_t>((smax - s) * scale), 0), BINS - 1));
+        };
+        for (int32_t bi = 0; bi < n_batch; ++bi) {
+            fetch(bi, tok, key, el);
+#pragma unroll
+            for (int u = 0; u < kSelBatch; ++u)
+                if (el[u]) atomicAdd(&hist[bucket(key[u])], 1u);
+        }
+        team_sync<BLOCK>();
+        uint32_t bin, below, count;
+        scan(0, remaining, bin, below, count);
+        const uint32_t want = remaining - below;                  // of the `count` tokens in the bucket
+        if (count == want || count <= CAND) {
+            uint32_t* cand = hist + (BLOCK ? BINS : 0);          // (key, token) pairs; this histogram is clear by now
+            for (int32_t bi = 0; bi < n_batch; ++bi) {
+                fetch(bi, tok, key, el);
+#pragma unroll
+                for (int u = 0; u < kSelBatch; ++u) {
+                    const uint32_t bk = bucket(key[u]);
+                    adm[u] = el[u] && (bk < bin || (count == want && bk == bin));
+                    if (count != want && el[u] && bk == bin) {
+                        const uint32_t slot = atomicAdd(&bc[3], 1u);
+                        *reinterpret_cast<u32x2*>(cand + 2 * slot) = u32x2{key[u], static_cast<uint32_t>(tok[u])};
+                    }
+                }
+                mark(tok, adm);
+            }
+            team_sync<BLOCK>();
+            if (count != want) {
+                // Thread j ranks candidate j among all of them by (key, token): the strict order itself.
+                if ((static_cast<uint32_t>(rank) & ~static_cast<uint32_t>(kWave - 1)) < count) {   // wavefronts that own a candidate
+                    const u32x2 me = *reinterpret_cast<const u32x2*>(cand + 2 * min(static_cast<uint32_t>(rank), count - 1));
+                    uint32_t ahead = 0;
+                    for (uint32_t i0 = 0; i0 < count; i0 += 8) {   // eight broadcast reads in flight (a clamped index repeats the last pair)
+                        u32x2 other[8];
+#pragma unroll
+                        for (uint32_t u = 0; u < 8; ++u) other[u] = *reinterpret_cast<const u32x2*>(cand + 2 * min(i0 + u, count - 1));
+#pragma unroll
+                        for (uint32_t u = 0; u < 8; ++u)
+                            ahead += (i0 + u < count && (other[u].x < me.x || (other[u].x == me.x && other[u].y < me.y))) ? 1u : 0u;
+                    }
+                    if (static_cast<uint32_t>(rank) < count && ahead < want) set_mark(marks, static_cast<int32_t>(me.y));
+                }
+                team_sync<BLOCK>();
+                if constexpr (!BLOCK) {
+                    for (int i = lane; i < 2 * static_cast<int>(CAND); i += kWave) hist[i] = 0;
+                    team_sync<false>();
+                }
+            }
+            return;
+        }
+        first = 1;
+    }
+
+    // ---- radix select of the m-th smallest key among the eligible tokens, high digit first
+    uint32_t prefix = 0, ties = 0;
+    int done_shift = 0;                                          // key bits below this were never looked at
+#pragma unroll 1
+    for (int pass = first; pass < first + PASSES; ++pass) {
+        const int digit = pass - first;
+        const int shift = 32 - BITS * (digit + 1) > 0 ? 32 - BITS * (digit + 1) : 0;
+        const int width = 32 - BITS * digit < BITS ? 32 - BITS * digit : BITS;
+        const uint32_t digit_mask = (1u << width) - 1u;
+        uint32_t* h = hist + (BLOCK ? (pass & 1) * BINS : 0);
+        const uint32_t hi_mask = digit == 0 ? 0u : (0xFFFFFFFFu << (shift + width));
+        for (int32_t bi = 0; bi < n_batch; ++bi) {
+            fetch(bi, tok, key, el);
+#pragma unroll
+            for (int u = 0; u < kSelBatch; ++u)
+                if (el[u] && (key[u] & hi_mask) == prefix) atomicAdd(&h[(key[u] >> shift) & digit_mask], 1u);
+        }
+        team_sync<BLOCK>();
+        uint32_t bin, below;
+        scan(pass, remaining, bin, below, ties);
+        prefix |= bin << shift;
+        remaining -= below;
         done_shift = shift;
         if (ties == remaining) break;                            // the whole bin is admitted: its lower bits decide nothing
     }
@@ -215,26 +373,11 @@ __device__ void select_first(const uint32_t* keys, uint32_t* marks, uint32_t* hi
 
     if (ties == remaining) {                                     // no contested tie: order does not matter
         const uint32_t limit = prefix >> done_shift;
-        if (BLOCK && CONTIG && (reg.base & (kWave - 1)) == 0) {
-            // A wavefront covers 64 consecutive tokens = its own two mark words: one ballot, no atomics.
-            for (int32_t it = 0; it < n_iter; ++it) {
-                const int32_t i = it * TEAM + rank;
-                const int32_t v = reg.base + i;
-                const bool admit = i < reg.count && !(only_unmarked && is_marked(marks, v)) && (keys[v] >> done_shift) <= limit;
-                const uint64_t bal = __ballot(admit);
-                if (lane == 0 && bal) {                          // i - lane < reg.count here, so the words exist
-                    marks[v >> 5] |= static_cast<uint32_t>(bal);
-                    marks[(v >> 5) + 1] |= static_cast<uint32_t>(bal >> 32);
-                }
-            }
-        } else {
-            for (int32_t it = 0; it < n_iter; ++it) {
-                const int32_t i = it * TEAM + rank;
-                if (i < reg.count) {
-                    const int32_t v = reg.token<CONTIG>(i);
-                    if (!(only_unmarked && is_marked(marks, v)) && (keys[v] >> done_shift) <= limit) set_mark(marks, v);
-                }
-            }
+        for (int32_t bi = 0; bi < n_batch; ++bi) {
+            fetch(bi, tok, key, el);
+#pragma unroll
+            for (int u = 0; u < kSelBatch; ++u) adm[u] = el[u] && (key[u] >> done_shift) <= limit;
+            mark(tok, adm);
         }
         team_sync<BLOCK>();
         return;
@@ -284,16 +427,53 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelArgs a)
     uint32_t* bcast = hist + kSelWaves * 256;                // [kSelWaves][8]
     uint32_t* marks = bcast + kSelWaves * 8;                 // [nv_pad / 32]
     uint32_t* word_prefix = marks + a.nv_pad / 32;           // [nv_pad / 64]
+    float* extremes = reinterpret_cast<float*>(smem + a.lds_words - 2 * kSelWaves);   // [2][kSelWaves], 16-byte aligned
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
     const int b = blockIdx.x;
     const float* s = a.scores + static_cast<int64_t>(b) * a.nv;
 
-    for (int32_t v = tid; v < a.nv_pad; v += kSelThreads) keys[v] = v < a.nv ? order_key(s[v]) : 0xFFFFFFFFu;
+    // Keys into LDS; on the way the sample's smallest and largest score (NaN ignored), which steer the
+    // first pass of the selects.
+    float lo = INFINITY, hi = -INFINITY;
+    if (a.quad_scores) {                                     // 16-byte loads: the sample starts on a 16-byte boundary, nv % 4 == 0
+        for (int32_t q = tid; q < a.nv / 4; q += kSelThreads) {
+            const float4 x = reinterpret_cast<const float4*>(s)[q];
+            const u32x4 k = {order_key(x.x), order_key(x.y), order_key(x.z), order_key(x.w)};
+            *reinterpret_cast<u32x4*>(keys + 4 * q) = k;
+            lo = fminf(fminf(lo, x.x), fminf(fminf(x.y, x.z), x.w));
+            hi = fmaxf(fmaxf(hi, x.x), fmaxf(fmaxf(x.y, x.z), x.w));
+        }
+        for (int32_t v = a.nv + tid; v < a.nv_pad; v += kSelThreads) keys[v] = 0xFFFFFFFFu;
+    } else {
+        for (int32_t v0 = tid; v0 < a.nv_pad; v0 += kSelBatch * kSelThreads) {
+            float x[kSelBatch];
+#pragma unroll
+            for (int u = 0; u < kSelBatch; ++u) x[u] = s[min(v0 + u * kSelThreads, a.nv - 1)];   // a clamped index repeats a real score
+#pragma unroll
+            for (int u = 0; u < kSelBatch; ++u) {
+                const int32_t v = v0 + u * kSelThreads;
+                if (v < a.nv_pad) keys[v] = v < a.nv ? order_key(x[u]) : 0xFFFFFFFFu;
+                lo = fminf(lo, x[u]);
+                hi = fmaxf(hi, x[u]);
+            }
+        }
+    }
+    lo = wave_reduce(lo, [](float p, float q) { return fminf(p, q); });
+    hi = wave_reduce(hi, [](float p, float q) { return fmaxf(p, q); });
+    if (lane == kWave - 1) { extremes[wave] = lo; extremes[kSelWaves + wave] = hi; }
     for (int32_t w = tid; w < a.nv_pad / 32; w += kSelThreads) marks[w] = 0u;
     // The budget select wants zeroed histograms; the per-wavefront selects before it leave theirs zeroed.
     for (int i = tid; i < kSelWaves * 256; i += kSelThreads) hist[i] = 0u;
     __syncthreads();
+    float smin = INFINITY, smax = -INFINITY;
+#pragma unroll
+    for (int x = 0; x < kSelWaves; x += 4) {
+        const float4 l4 = *reinterpret_cast<const float4*>(extremes + x), h4 = *reinterpret_cast<const float4*>(extremes + kSelWaves + x);
+        smin = fminf(fminf(smin, l4.x), fminf(fminf(l4.y, l4.z), l4.w));
+        smax = fmaxf(fmaxf(smax, h4.x), fmaxf(fmaxf(h4.y, h4.z), h4.w));
+    }
+    const float range = smax - smin;                         // 0, infinite or NaN: the selects go straight to the key digits
 
     // ---- (1) cell floors
     if (a.cell_floor > 0) {
@@ -376,7 +556,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelArgs a)
                 const int32_t r0 = cy * a.cell_h, c0 = cx * a.cell_w;
                 const int32_t hgt = min(a.cell_h, a.height - r0), wid = min(a.cell_w, a.width - c0);
                 const Region reg{f * a.hw + r0 * a.width + c0, wid, a.width, hgt * wid};
-                select_first<false, false>(keys, marks, hist + wave * 256, bcast + wave * 8, reg, a.cell_floor, false, hgt * wid);
+                select_first<false, false>(keys, marks, hist + wave * 256, bcast + wave * 8, reg, a.cell_floor, false, hgt * wid, smax, range);
             }
         }
         __syncthreads();
@@ -386,7 +566,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelArgs a)
     if (a.frame_floor > 0) {
         for (int32_t f = wave; f < a.frames; f += kSelWaves) {
             const Region reg{f * a.hw, a.hw, a.hw, a.hw};
-            select_first<false, true>(keys, marks, hist + wave * 256, bcast + wave * 8, reg, a.frame_floor, true, -1);
+            select_first<false, true>(keys, marks, hist + wave * 256, bcast + wave * 8, reg, a.frame_floor, true,
+                                      a.hw - a.cell_kept_frame, smax, range);
         }
         __syncthreads();
     }
@@ -394,7 +575,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelArgs a)
     // ---- (3) global budget
     if (a.fill > 0) {
         const Region reg{0, a.nv, a.nv, a.nv};
-        select_first<true, true>(keys, marks, hist, bcast, reg, a.fill, true, a.nv - a.floor_sum);
+        select_first<true, true>(keys, marks, hist, bcast, reg, a.fill, true, a.nv - a.floor_sum, smax, range);
     }
     __syncthreads();
 
@@ -420,15 +601,27 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelArgs a)
     __syncthreads();
 
     int32_t* out = a.kept_idx + static_cast<int64_t>(b) * a.kept;
-    for (int32_t v = tid; v < a.nv_pad; v += kSelThreads) {
-        const uint32_t lo = marks[(v >> 6) * 2], hi = marks[(v >> 6) * 2 + 1];
-        const uint64_t word = (static_cast<uint64_t>(hi) << 32) | lo;
-        const bool bit = (word >> lane) & 1ull;
-        if (bit) {
-            const uint32_t pos = word_prefix[v >> 6] + static_cast<uint32_t>(__popcll(word & ((1ull << lane) - 1ull)));
-            if (pos < static_cast<uint32_t>(a.kept)) out[pos] = v;
+    for (int32_t v0 = tid; v0 < a.nv_pad; v0 += kSelBatch * kSelThreads) {
+        u32x2 mw[kSelBatch];
+        uint32_t wp[kSelBatch];
+#pragma unroll
+        for (int u = 0; u < kSelBatch; ++u) {                // a batch of reads from clamped indices, then the stores
+            const int32_t w = min(v0 + u * kSelThreads, a.nv_pad - 1) >> 6;
+            mw[u] = *reinterpret_cast<const u32x2*>(marks + 2 * w);
+            wp[u] = word_prefix[w];
         }
-        if (a.keep_flags && v < a.nv) a.keep_flags[static_cast<int64_t>(b) * a.nv + v] = bit ? 1 : 0;
+#pragma unroll
+        for (int u = 0; u < kSelBatch; ++u) {
+            const int32_t v = v0 + u * kSelThreads;
+            if (v >= a.nv_pad) break;
+            const uint64_t word = (static_cast<uint64_t>(mw[u].y) << 32) | mw[u].x;
+            const bool bit = (word >> lane) & 1ull;
+            if (bit) {
+                const uint32_t pos = wp[u] + static_cast<uint32_t>(__popcll(word & ((1ull << lane) - 1ull)));
+                if (pos < static_cast<uint32_t>(a.kept)) out[pos] = v;
+            }
+            if (a.keep_flags && v < a.nv) a.keep_flags[static_cast<int64_t>(b) * a.nv + v] = bit ? 1 : 0;
+        }
     }
 }
 
@@ -458,12 +651,17 @@ extern "C" int civic_select(const float* scores, int32_t batch, const civic_grid
     a.cells_x = (gi.width + a.cell_w - 1) / a.cell_w;
     a.floor_sum = gi.floor_sum; a.fill = gi.fill; a.kept = gi.kept;
     a.big_cells = static_cast<int64_t>(a.cell_h) * a.cell_w > kSmallCell ? 1 : 0;
+    a.cell_kept_frame = gi.cell_kept_frame;
+    a.quad_scores = (reinterpret_cast<uintptr_t>(scores) & 15u) == 0 && gi.nv % 4 == 0;
     auto magic = [](int64_t d) { return d <= 1 ? 0u : static_cast<uint32_t>(((int64_t{1} << 32) + d - 1) / d); };
     a.magic_cells_f = magic(static_cast<int64_t>(a.cells_y) * a.cells_x);
     a.magic_cells_x = magic(a.cells_x);
 
-    const size_t lds = sizeof(uint32_t) * (static_cast<size_t>(a.nv_pad) + a.nv_pad / 32 + kSelWaves * 256 +
-                                           kSelWaves * 8 + a.nv_pad / 64 + 2);
+    // keys | histograms | per-team words | mark bits | word prefixes, rounded up to 16 bytes | per-wavefront extremes
+    const size_t lds_words = (static_cast<size_t>(a.nv_pad) + kSelWaves * 256 + kSelWaves * 8 + a.nv_pad / 32 + a.nv_pad / 64 + 3) / 4 * 4 +
+                             2 * kSelWaves;
+    a.lds_words = static_cast<int32_t>(lds_words);
+    const size_t lds = sizeof(uint32_t) * lds_words;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel),

@@ -39,8 +39,22 @@ def draw_scores(rng, kind: int, shape) -> np.ndarray:
         s = np.where(rng.random(shape) < 0.3, -rng.random(shape), rng.random(shape) * 1e6)
     elif kind == 6:
         s = np.zeros(shape)
-    else:
+    elif kind == 7:
         s = rng.standard_normal(shape).astype(np.float16).astype(np.float64)   # many exact ties
+    elif kind == 8:                                                            # two outliers squeeze the rest into one bucket
+        s = rng.standard_normal(shape)
+        s.flat[rng.integers(0, s.size)] = 1e30
+        s.flat[rng.integers(0, s.size)] = -1e30
+    elif kind == 9:                                                            # infinities: no finite range
+        s = rng.standard_normal(shape)
+        s[rng.random(shape) < 0.05] = np.inf
+        s[rng.random(shape) < 0.05] = -np.inf
+    elif kind == 10:                                                           # a range that overflows fp32
+        s = rng.choice([-3e38, 3e38, 1.0, -1.0], shape) * rng.random(shape)
+    elif kind == 11:                                                           # 64 distinct values
+        s = np.floor(rng.random(shape) * 64) / 64
+    else:                                                                      # two clusters far apart
+        s = rng.standard_normal(shape) + rng.choice([0.0, 1e4], shape)
     return s.astype(np.float32)
 
 
@@ -61,10 +75,14 @@ def test_select_random_grids(bd):
         budget = int(rng.choice([0, nv // 3, nv // 3, nv // 2, nv, int(rng.integers(0, nv + 1))]))
         grid = (frames, h, w, ch, cw, cell_floor, frame_floor, budget)
         batch = int(rng.choice([1, 2, 4]))
-        s = draw_scores(rng, int(rng.integers(0, 8)), (batch, nv))
+        s = draw_scores(rng, int(rng.integers(0, 13)), (batch, nv))
         if done % 100 == 0:
             log("select random", done, grid, batch)
-        idx, flags = bd.civic_select(torch.from_numpy(s).cuda(), grid, want_flags=True)
+        if rng.random() < 0.2:                                                # a start that is not 16-byte aligned
+            sd = torch.from_numpy(np.concatenate([np.zeros(1, np.float32), s.ravel()])).cuda()[1:].view(batch, nv)
+        else:
+            sd = torch.from_numpy(s).cuda()
+        idx, flags = bd.civic_select(sd, grid, want_flags=True)
         ref_idx, ref_flags = oracle.select(s, grid)
         assert np.array_equal(to_host(idx), ref_idx), (grid, batch)
         assert np.array_equal(to_host(flags), ref_flags), (grid, batch)
