@@ -40,6 +40,7 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
     __shared__ int32_t kb[CIVIC_MAX_FRAMES + 1];
     __shared__ int32_t row_src[kCompactMaxRows];
     __shared__ int32_t fstart[CIVIC_MAX_FRAMES];   // frame_start - f*HW: text tokens before frame f
+    __shared__ int32_t stretch[CIVIC_MAX_FRAMES];  // long lists: the probe at whose entry, or in the P - 1 before it, frame f's boundary lies
 
     const int tid = threadIdx.x;
     const int b = blockIdx.y;
@@ -47,6 +48,65 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
     const int32_t nrows = min(rows_per_block, seq_c - j0);
     const int32_t* kept = kept_idx + static_cast<int64_t>(b) * n_kept;
     const int32_t F = ft.n, hw = ft.hw;
+    auto frame_of = [&](int32_t v) { return min(max(v / hw, 0), F - 1); };
+
+    // Long kept lists (more than one batch below): reading the whole list in every block would cost a
+    // memory round trip per batch and more L2 traffic than the rows themselves.  Two round trips
+    // suffice: (1) every thread probes one entry out of P, which brackets each frame boundary between
+    // two probes, together with the entries that can land in this block's rows (slot j holds entry
+    // j - fstart[f], and fstart only grows with f, so they are a window of nrows plus the text between
+    // the first and the last frame); (2) the bracketed stretches are searched for the boundaries.
+    // Used when the window and the stretches fit one batch; otherwise the full pass below.
+    const int32_t probe_step = (n_kept + kCompactThreads - 1) / kCompactThreads;
+    bool two_level = n_kept > kCompactThreads * 4 && (F - 1) * probe_step <= kCompactThreads * 4;
+    int32_t win_lo = 0, win_hi = 0;
+    if (two_level) {
+        win_lo = max(j0 - (ft.start[F - 1] - (F - 1) * hw), 0);
+        win_hi = min(j0 + nrows - ft.start[0], n_kept);
+        two_level = win_hi - win_lo <= kCompactThreads * 4;
+    }
+    if (two_level) {
+        const int32_t n_probes = (n_kept + probe_step - 1) / probe_step;
+        const int32_t ip = tid * probe_step;
+        int32_t probe = 0, probe_prev = 0, own[4];
+        if (tid < n_probes) { probe = kept[ip]; probe_prev = tid > 0 ? kept[ip - probe_step] : 0; }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int32_t i = win_lo + u * kCompactThreads + tid;
+            own[u] = i < win_hi ? kept[i] : 0;
+        }
+        if (tid < F) { fstart[tid] = ft.start[tid] - tid * hw; stretch[tid] = n_probes; }
+        if (tid <= F) kb[tid] = tid == 0 ? 0 : n_kept;              // a boundary that no entry reaches stays at the end
+        __syncthreads();
+        if (tid < n_probes) {                                        // boundary f lies in (ip - P, ip] for f in (frame before, this frame]
+            const int32_t f_hi = frame_of(probe), f_lo = tid > 0 ? frame_of(probe_prev) : -1;
+            for (int32_t f = f_lo + 1; f <= f_hi; ++f) stretch[f] = tid;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int32_t i = win_lo + u * kCompactThreads + tid;
+            if (i < win_hi) {
+                const int32_t f = frame_of(own[u]), j = fstart[f] + i - j0;
+                if (j >= 0 && j < nrows) row_src[j] = fstart[f] + own[u];
+            }
+        }
+        __syncthreads();
+        int32_t cur[4], prev[4], at[4], fr[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {                                // candidate u of this thread: entry `at` for boundary `fr`
+            const int32_t c = u * kCompactThreads + tid;
+            fr[u] = min(1 + c / probe_step, F - 1);
+            at[u] = probe_step * (stretch[fr[u]] - 1) + 1 + (c - (fr[u] - 1) * probe_step);
+            const bool live = c < (F - 1) * probe_step && at[u] >= 0 && at[u] < n_kept;
+            if (!live) at[u] = -1;
+            cur[u] = live ? kept[at[u]] : 0;
+            prev[u] = live && at[u] > 0 ? kept[at[u] - 1] : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (at[u] >= 0 && fr[u] <= frame_of(cur[u]) && (at[u] == 0 || frame_of(prev[u]) < fr[u])) kb[fr[u]] = at[u];
+        __syncthreads();
+    } else {
     // Entries are visited four strided positions per thread at a time, all loads of a batch issued
     // before any is used (one memory latency per batch instead of one per entry).  The first batch goes
     // out together with this thread's word of the frame table (a per-thread index into the kernel
@@ -83,6 +143,7 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
         load_batch(base);
     }
     __syncthreads();
+    }
 
     for (int32_t r = tid; r < nrows; r += kCompactThreads) {
         const int32_t j = j0 + r;
