@@ -674,12 +674,18 @@ static int launch_mfma(AttnArgs& a, hipStream_t s)
     return check_launch();
 }
 
-#ifndef CIVIC_ATTN_WAVES
-#define CIVIC_ATTN_WAVES 8
-#endif
 #ifndef CIVIC_ATTN_STAGES
 #define CIVIC_ATTN_STAGES 2
 #endif
+constexpr int64_t kComputeUnits = 256;
+
+template <int WAVES>
+static int launch_mfma_for(AttnArgs& a, hipStream_t s)
+{
+    if (a.head_dim <= 64) return launch_mfma<64, WAVES, CIVIC_ATTN_STAGES>(a, s);
+    if (a.head_dim <= 96) return launch_mfma<96, WAVES, CIVIC_ATTN_STAGES>(a, s);
+    return launch_mfma<128, WAVES, CIVIC_ATTN_STAGES>(a, s);
+}
 
 }  // namespace civic
 
@@ -725,13 +731,13 @@ static int prefill_attn(const void* q, const void* k, const void* v, void* out, 
 
     // the MFMA path addresses a K/V tile, and a head's Q rows, with 32-bit per-lane byte offsets, and its grid
     // has limits of its own; whatever falls outside takes the plain kernel
-    int64_t per_rt_unused = 0;
+    // Workgroups of 8 wavefronts (256 query rows x heads) share each K/V tile the most; when they would
+    // leave compute units without work, workgroups of 4 wavefronts, two per unit, fill the chip better.
+    int64_t per_rt = 0;
     if (dtype == CIVIC_BF16 && head_dim <= 128 && kv_strides[1] * 2 < (1 << 25) &&
-        static_cast<int64_t>(seq) * q_strides[1] * 2 < (int64_t{1} << 32) &&
-        mfma_geometry<CIVIC_ATTN_WAVES>(a, &per_rt_unused)) {
-        if (head_dim <= 64) return launch_mfma<64, CIVIC_ATTN_WAVES, CIVIC_ATTN_STAGES>(a, s);
-        if (head_dim <= 96) return launch_mfma<96, CIVIC_ATTN_WAVES, CIVIC_ATTN_STAGES>(a, s);
-        return launch_mfma<128, CIVIC_ATTN_WAVES, CIVIC_ATTN_STAGES>(a, s);
+        static_cast<int64_t>(seq) * q_strides[1] * 2 < (int64_t{1} << 32) && mfma_geometry<8>(a, &per_rt)) {
+        if (per_rt * a.row_tiles >= kComputeUnits || !mfma_geometry<4>(a, &per_rt)) return launch_mfma_for<8>(a, s);
+        return launch_mfma_for<4>(a, s);
     }
     const dim3 grid(static_cast<unsigned>((seq + 3) / 4), static_cast<unsigned>(n_q_heads), static_cast<unsigned>(batch));
     if (dtype == CIVIC_BF16) hipLaunchKernelGGL((attn_plain_kernel<true>), grid, dim3(256), 0, s, a);
