@@ -11,6 +11,9 @@
 //   - in compact space frame f starts at cs[f] = frame_start[f] - f*HW + kb[f] (text before it plus
 //     kept tokens before it); a slot not claimed by a visual token is text and maps back by adding
 //     the visual tokens dropped before it.
+// A kept list of more than 1024 entries is not read whole by every block: a probe of one entry out of
+// P brackets each frame boundary, the entries that can land in the block's rows are a small window,
+// and a second round trip searches the bracketed stretches (see the kernel).
 // The rows are then moved with the widest vector the row size allows (16 bytes for every Qwen3-VL
 // shape), several rows in flight per thread so that loads are issued back to back before any store.
 #include "civic_internal.h"

@@ -7,13 +7,14 @@
 // onto +0).
 //   cells   small cells: one thread per cell picks the cell's best remaining member cell_floor times
 //           (members scanned in index order, strict key comparison = the tie rule).
-//           large cells: one wavefront per cell runs the radix select below.
-//   frames  one wavefront per frame: radix select (digits of 8 bits, high first, over a per-wave LDS
-//           histogram) finds the key of the frame_floor-th unmarked token; equal keys are admitted
-//           in index order with ballot prefix counts.
-//   budget  the same radix select run by the whole workgroup over the unmarked tokens of the sample,
-//           with digits of 11 bits.  A select stops after the first digit whose bin is admitted
-//           whole (typically the second of three), because the threshold's low bits no longer matter.
+//           large cells: one wavefront per cell runs the select below.
+//   frames  one wavefront per frame: the select below over the frame's unmarked tokens (256 bins).
+//   budget  the same select run by the whole workgroup over the unmarked tokens of the sample (2048
+//           bins).
+//   select  one histogram pass over buckets that are linear in the score, a scan for the bucket that
+//           holds the m-th token, one marking pass; the few tokens of that bucket are ranked against
+//           each other directly.  Degenerate score distributions fall back to an exact radix select
+//           over the key digits (see select_first).
 //   output  popcounts of the 64-bit mark words -> LDS prefix scan -> every set bit writes its index
 //           at (prefix of its word + set bits below it): ascending kept_idx without any sort.
 #include <cmath>
