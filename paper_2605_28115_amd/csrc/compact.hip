@@ -33,7 +33,9 @@ struct FrameTable {
 // U > 0: the launch guarantees rows_per_block == U * (kCompactThreads / threads_per_row) and a row
 // length that is a multiple of 2 * threads_per_row vectors, so a block with all its rows (every block
 // but a sample's last) copies them without a per-row or per-column condition.  U == 0: no such promise.
-template <typename V, int U>
+// LONG: the kept list is searched in two round trips instead of read whole (the launch guarantees
+// that the probes' stretches and a block's window of entries each fit one batch of 4 per thread).
+template <typename V, int U, bool LONG>
 __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
     const uint8_t* __restrict__ hidden, int64_t row_bytes, const int32_t* __restrict__ pos_ids, int32_t batch,
     int32_t seq_len, FrameTable ft, const int32_t* __restrict__ kept_idx, int32_t n_kept, int32_t seq_c,
@@ -59,16 +61,11 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
     // two probes, together with the entries that can land in this block's rows (slot j holds entry
     // j - fstart[f], and fstart only grows with f, so they are a window of nrows plus the text between
     // the first and the last frame); (2) the bracketed stretches are searched for the boundaries.
-    // Used when the window and the stretches fit one batch; otherwise the full pass below.
-    const int32_t probe_step = (n_kept + kCompactThreads - 1) / kCompactThreads;
-    bool two_level = n_kept > kCompactThreads * 4 && (F - 1) * probe_step <= kCompactThreads * 4;
-    int32_t win_lo = 0, win_hi = 0;
-    if (two_level) {
-        win_lo = max(j0 - (ft.start[F - 1] - (F - 1) * hw), 0);
-        win_hi = min(j0 + nrows - ft.start[0], n_kept);
-        two_level = win_hi - win_lo <= kCompactThreads * 4;
-    }
-    if (two_level) {
+    // Used when the window and the stretches fit one batch (decided at launch); otherwise the full pass below.
+    if constexpr (LONG) {
+        const int32_t probe_step = (n_kept + kCompactThreads - 1) / kCompactThreads;
+        const int32_t win_lo = max(j0 - (ft.start[F - 1] - (F - 1) * hw), 0);
+        const int32_t win_hi = min(j0 + nrows - ft.start[0], n_kept);
         const int32_t n_probes = (n_kept + probe_step - 1) / probe_step;
         const int32_t ip = tid * probe_step;
         int32_t probe = 0, probe_prev = 0, own[4];
@@ -307,27 +304,43 @@ extern "C" int civic_compact(const void* hidden, int dtype, int32_t dim, const i
         rpb = unroll * rpp;
     }
     const int64_t blocks = (seq_c + rpb - 1) / rpb;
+    // Long kept lists (more than one batch of 4 entries per thread) are searched instead of read whole when
+    // the stretches between the probes, (frames - 1) * ceil(n_kept / 256) entries, and the entries that can land
+    // in one block, its rows plus the text between the first and the last frame, each fit one batch.
+    const int64_t probe_step = (n_kept + kCompactThreads - 1) / kCompactThreads;
+    const int64_t text_between = (frame_start[gi.frames - 1] - frame_start[0]) - static_cast<int64_t>(gi.frames - 1) * gi.hw;
+    const bool long_list = vec == 16 && n_kept > 4 * kCompactThreads && (gi.frames - 1) * probe_step <= 4 * kCompactThreads &&
+                           rpb + text_between <= 4 * kCompactThreads;
 
     const uint8_t* h = static_cast<const uint8_t*>(hidden);
     uint8_t* hc = static_cast<uint8_t*>(hidden_c);
     const dim3 g(static_cast<unsigned>(blocks), static_cast<unsigned>(batch)), blk(kCompactThreads);
     hipStream_t s = static_cast<hipStream_t>(stream);
-#define CIVIC_COMPACT_LAUNCH(V, U)                                                                            \
-    hipLaunchKernelGGL((compact_kernel<V, U>), g, blk, 0, s, h, row_bytes, pos_ids, batch,                      \
+#define CIVIC_COMPACT_LAUNCH(V, U, LONG)                                                                      \
+    hipLaunchKernelGGL((compact_kernel<V, U, LONG>), g, blk, 0, s, h, row_bytes, pos_ids, batch,                \
                        static_cast<int32_t>(seq_len), ft, kept_idx, static_cast<int32_t>(n_kept),               \
                        static_cast<int32_t>(seq_c), static_cast<int32_t>(rpb), tpr, hc, pos_c, src_idx)
     switch (vec) {
         case 16:
-            switch (unroll) {
-                case 1: CIVIC_COMPACT_LAUNCH(u32x4, 1); break;
-                case 2: CIVIC_COMPACT_LAUNCH(u32x4, 2); break;
-                case 4: CIVIC_COMPACT_LAUNCH(u32x4, 4); break;
-                default: CIVIC_COMPACT_LAUNCH(u32x4, 0); break;
+            if (long_list) {
+                switch (unroll) {
+                    case 1: CIVIC_COMPACT_LAUNCH(u32x4, 1, true); break;
+                    case 2: CIVIC_COMPACT_LAUNCH(u32x4, 2, true); break;
+                    case 4: CIVIC_COMPACT_LAUNCH(u32x4, 4, true); break;
+                    default: CIVIC_COMPACT_LAUNCH(u32x4, 0, true); break;
+                }
+            } else {
+                switch (unroll) {
+                    case 1: CIVIC_COMPACT_LAUNCH(u32x4, 1, false); break;
+                    case 2: CIVIC_COMPACT_LAUNCH(u32x4, 2, false); break;
+                    case 4: CIVIC_COMPACT_LAUNCH(u32x4, 4, false); break;
+                    default: CIVIC_COMPACT_LAUNCH(u32x4, 0, false); break;
+                }
             }
             break;
-        case 8: CIVIC_COMPACT_LAUNCH(u32x2, 0); break;
-        case 4: CIVIC_COMPACT_LAUNCH(uint32_t, 0); break;
-        default: CIVIC_COMPACT_LAUNCH(uint16_t, 0); break;
+        case 8: CIVIC_COMPACT_LAUNCH(u32x2, 0, false); break;
+        case 4: CIVIC_COMPACT_LAUNCH(uint32_t, 0, false); break;
+        default: CIVIC_COMPACT_LAUNCH(uint16_t, 0, false); break;
     }
 #undef CIVIC_COMPACT_LAUNCH
     return check_launch();
