@@ -732,11 +732,13 @@ static int prefill_attn(const void* q, const void* k, const void* v, void* out, 
     // the MFMA path addresses a K/V tile, and a head's Q rows, with 32-bit per-lane byte offsets, and its grid
     // has limits of its own; whatever falls outside takes the plain kernel
     // Workgroups of 8 wavefronts (256 query rows x heads) share each K/V tile the most; when they would
-    // leave compute units without work, workgroups of 4 wavefronts, two per unit, fill the chip better.
+    // leave at least half of the compute units without work, workgroups of 4 wavefronts spread it over twice
+    // as many (measured: 32 workgroups of 8 wavefronts 15.4 us, 64 of 4 12.2 us; but 192 of 8 37.9 us against
+    // 384 of 4, two per unit, 39.7 us).
     int64_t per_rt = 0;
     if (dtype == CIVIC_BF16 && head_dim <= 128 && kv_strides[1] * 2 < (1 << 25) &&
         static_cast<int64_t>(seq) * q_strides[1] * 2 < (int64_t{1} << 32) && mfma_geometry<8>(a, &per_rt)) {
-        if (per_rt * a.row_tiles >= kComputeUnits || !mfma_geometry<4>(a, &per_rt)) return launch_mfma_for<8>(a, s);
+        if (2 * per_rt * a.row_tiles > kComputeUnits || !mfma_geometry<4>(a, &per_rt)) return launch_mfma_for<8>(a, s);
         return launch_mfma_for<4>(a, s);
     }
     const dim3 grid(static_cast<unsigned>((seq + 3) / 4), static_cast<unsigned>(n_q_heads), static_cast<unsigned>(batch));
