@@ -199,6 +199,40 @@ def test_compact_edge_cases(bd):
     check_compact(bd, hid, pos, grid, np.arange(128, dtype=np.int64) * 4, kept)
 
 
+def test_compact_long_kept_lists(bd):
+    # More than 1024 kept tokens per sample: the kernel brackets the frame boundaries with 256 probes (one entry
+    # out of P = ceil(K / 256)) and searches between them.  Boundaries on and next to probe positions, frames
+    # without a kept token, everything in the first or the last frame, with and without text around the frames.
+    frames, h, w = 8, 32, 32
+    hw, rng = h * w, np.random.default_rng(21)
+
+    def take(per_frame):                                       # per_frame[f] tokens of frame f, at random positions
+        return np.concatenate([f * hw + np.sort(rng.choice(hw, n, replace=False)) for f, n in enumerate(per_frame)]).astype(np.int32)
+
+    lists = {
+        "boundary on a probe (P = 10)": take([1024, 256, 0, 1024, 256, 0, 0, 0]),
+        "boundary one past a probe": take([1024, 257, 0, 1024, 255, 0, 0, 0]),
+        "boundary one before a probe": take([1024, 255, 0, 0, 0, 0, 257, 1024]),
+        "whole frames 2, 3 and 5": take([0, 0, 1024, 1024, 0, 1024, 0, 0]),
+        "first frame only": take([1024, 1, 0, 0, 0, 0, 0, 0]),
+        "last frame only": take([0, 0, 0, 0, 0, 0, 1, 1024]),
+        "one token per boundary": take([1018, 1, 1, 1, 1, 1, 1, 1]),
+        "every other token": np.arange(0, frames * hw, 2, dtype=np.int32),
+        "everything": np.arange(frames * hw, dtype=np.int32),
+    }
+    for gaps in ([0] * 9, [5, 0, 300, 0, 0, 17, 1, 0, 40], [0, 900, 0, 0, 0, 0, 0, 200, 0]):   # the last: too much text between the frames, full pass
+        fs, t = [], gaps[0]
+        for f in range(frames):
+            fs.append(t)
+            t += hw + gaps[f + 1]
+        seq, fs = t, np.asarray(fs, dtype=np.int64)
+        hid = rng.integers(0, 60000, (1, seq, 64)).astype(np.uint16)
+        pos = rng.integers(0, 100000, (3, 1, seq)).astype(np.int32)
+        for name, kept in lists.items():
+            log("compact long list:", name, "K", kept.size, "text", gaps[:3])
+            check_compact(bd, hid, pos, (frames, h, w, 1, 1, 0, 0, int(kept.size)), fs, kept.reshape(1, -1))
+
+
 # ------------------------------------------------------------------------------------- attention
 def attn_tol(ref: np.ndarray, dtype: str) -> float:
     return (2e-2 if dtype == "bf16" else 1e-4) * max(1.0, float(np.nanmax(np.abs(ref))))
