@@ -148,6 +148,38 @@ def test_select_at_the_size_limit(bd):
     check_select(bd, np.zeros((1, 32768), dtype=np.float32), grid)
 
 
+def test_select_with_nan_scores_keeps_its_shape(bd):
+    # NaN scores are a caller error and the oracle rejects them, so there is no expected kept set; what the kernel
+    # promises is a well-formed answer: exactly K distinct in-range indices in ascending order, flags that agree
+    # with them, and every cell and frame still holding its floor.
+    rng = np.random.default_rng(8)
+    for grid in ((2, 32, 32, 4, 4, 1, 0, 682), (3, 10, 7, 3, 2, 2, 5, 70), (16, 24, 24, 4, 4, 1, 16, 3072), (1, 64, 64, 8, 8, 1, 0, 1365)):
+        frames, h, w, ch, cw, cell_floor, frame_floor, _ = grid
+        nv = frames * h * w
+        for frac, sign in ((0.01, 1.0), (0.3, -1.0), (1.0, 1.0)):
+            s = rng.standard_normal((2, nv)).astype(np.float32)
+            s[rng.random((2, nv)) < frac] = np.float32(np.nan) * sign
+            log("select with NaN", grid, frac)
+            idx, flags = bd.civic_select(torch.from_numpy(s).cuda(), grid, want_flags=True)
+            idx, flags = to_host(idx), to_host(flags)
+            k = bd.civic_kept_count(grid)
+            assert idx.shape == (2, k)
+            for b in range(2):
+                assert (np.diff(idx[b]) > 0).all() and idx[b, 0] >= 0 and idx[b, -1] < nv
+                mask = np.zeros(nv, dtype=np.uint8)
+                mask[idx[b]] = 1
+                assert np.array_equal(mask, flags[b])
+                m = mask.reshape(frames, h, w)
+                for f in range(frames):
+                    cells = 0
+                    for r0 in range(0, h, ch):
+                        for c0 in range(0, w, cw):
+                            cell = m[f, r0:r0 + ch, c0:c0 + cw]
+                            assert cell.sum() >= min(cell_floor, cell.size), (grid, f, r0, c0)
+                            cells += min(cell_floor, cell.size)
+                    assert m[f].sum() >= min(cells + frame_floor, h * w), (grid, f)
+
+
 # --------------------------------------------------------------------------------------- compact
 def check_compact(bd, hid, pos, grid, fs, kept):
     hc, pc, si = bd.civic_compact(to_dev(hid), torch.from_numpy(pos).cuda(), grid, fs, torch.from_numpy(kept).cuda())
