@@ -15,6 +15,19 @@ int record_hip_error(hipError_t e)
     return CIVIC_ERR_HIP;
 }
 
+int allow_dynamic_lds(const void* kernel, size_t bytes, std::atomic<uint64_t>* done)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return record_hip_error(e);
+    const uint64_t bit = dev >= 0 && dev < 64 ? uint64_t{1} << dev : 0;   // devices beyond 63 set it on every call
+    if (bit && (done->load(std::memory_order_acquire) & bit)) return CIVIC_OK;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes));
+    if (e != hipSuccess) return record_hip_error(e);
+    done->fetch_or(bit, std::memory_order_release);
+    return CIVIC_OK;
+}
+
 int grid_info(const civic_grid* g, GridInfo* out)
 {
     if (!g || !out) return CIVIC_ERR_INVALID_ARG;

@@ -665,9 +665,9 @@ static int launch_mfma(AttnArgs& a, hipStream_t s)
     a.magic_kv_heads = magic(a.n_kv_heads);
     constexpr size_t lds = T::LDS_BYTES;
     if (lds > 64 * 1024) {
-        static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<DP, WAVES, STAGES>),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-        if (attr != hipSuccess) return record_hip_error(attr);
+        static std::atomic<uint64_t> allowed{0};
+        const int rc = allow_dynamic_lds(reinterpret_cast<const void*>(attn_mfma_kernel<DP, WAVES, STAGES>), lds, &allowed);
+        if (rc != CIVIC_OK) return rc;
     }
     hipLaunchKernelGGL((attn_mfma_kernel<DP, WAVES, STAGES>), dim3(static_cast<unsigned>(per_rt), static_cast<unsigned>(a.row_tiles)),
                        dim3(T::THREADS), lds, s, a);

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
 #include <type_traits>
 
 #include "civic.h"
@@ -12,6 +13,10 @@ namespace civic {
 
 // Records a failing HIP status for civic_last_hip_error() and maps it to the ABI code.
 int record_hip_error(hipError_t e);
+
+// Raises a kernel's dynamic LDS limit to `bytes` on the current device; the attribute belongs to the device's
+// copy of the kernel, so it is set once per device (bit d of *done: device d has it).  CIVIC_OK or an error code.
+int allow_dynamic_lds(const void* kernel, size_t bytes, std::atomic<uint64_t>* done);
 
 static inline int check_launch()
 {

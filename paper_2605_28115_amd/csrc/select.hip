@@ -729,10 +729,13 @@ extern "C" int civic_select(const float* scores, int32_t batch, const civic_grid
     a.lds_words = static_cast<int32_t>(lds_words);
     const size_t lds = sizeof(uint32_t) * lds_words;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-        if (e != hipSuccess) return record_hip_error(e);
+    if (lds > 64 * 1024) {                                   // allowed once per device, for the largest sample there is
+        constexpr size_t max_pad = (CIVIC_MAX_VISUAL_TOKENS + 63) / 64 * 64;
+        constexpr size_t max_lds = sizeof(uint32_t) * ((max_pad + kSelWaves * 256 + kSelWaves * 8 + max_pad / 32 + max_pad / 64 + 3) / 4 * 4 +
+                                                       2 * kSelWaves);
+        static std::atomic<uint64_t> allowed{0};
+        const int rc = allow_dynamic_lds(reinterpret_cast<const void*>(select_kernel), max_lds, &allowed);
+        if (rc != CIVIC_OK) return rc;
     }
     hipLaunchKernelGGL(select_kernel, dim3(static_cast<unsigned>(batch)), dim3(kSelThreads), lds, s, a);
     return check_launch();
