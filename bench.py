@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the compact-prefill path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 8b] [--sets R] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 8b] [--sets R] [--layers N] [--no-cpu]
 
 A step is one pass of the whole path over one batch of synthetic input already resident in HBM:
 civic_score -> civic_select -> civic_compact -> civic_prefill_attn_kv (attention and the KV-cache
@@ -148,7 +148,9 @@ def cpu_baseline(w: wl.Workload, target_seconds: float = 20.0) -> dict:
     vc = np.zeros_like(kc)
     t0 = time.perf_counter(); oracle.kv_write(k, v, kc, vc, 0); t["kv_write"] = time.perf_counter() - t0
     total = sum(t.values())
+    model = next((l.split(":", 1)[1].strip() for l in open("/proc/cpuinfo") if l.startswith("model name")), "unknown")
     return {"value": w.batch * w.seq_compact / total, "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
+            "cpu_model": model,
             "sample": (f"workload {w.name}: score, select, compact and kv_write in full; attention on every "
                        f"{row_step}-th query row, its time scaled by {row_step}"),
             "stage_ms": {s: round(1e3 * x, 3) for s, x in t.items()}}
@@ -162,6 +164,9 @@ def main() -> int:
     ap.add_argument("--workload", default="8b", choices=list(wl.WORKLOADS))
     ap.add_argument("--sets", type=int, default=4, help="independent buffer sets rotated through (1 = warm cache)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--layers", type=int, default=28,
+                    help="transformer layers N_l of the amortised figure: score, select and compact once, attention and "
+                         "KV write per layer (28 = the layer count the paper's Table 1 KV sizes imply for its 2B model)")
     ap.add_argument("--unfused", action="store_true", help="attention and KV write as two calls")
     ap.add_argument("--calibrate", action="store_true",
                     help="run only a device-to-device copy of 256 MiB (the known-size kernel the HBM byte counters "
@@ -284,6 +289,12 @@ def main() -> int:
         "stages": stages,
         "roofline": roofline,
     }
+    # the selection runs once per prompt, the attention and the KV write once per layer: one measured step plus
+    # layers - 1 further attention launches (in-step duration)
+    per_layer_us = attn_us + (stage_us["kv_write"]["mean"] if args.unfused else 0.0)
+    amortised_us = 1e3 * ms_per_step + (args.layers - 1) * per_layer_us
+    result["amortised"] = {"layers": args.layers, "us": round(amortised_us, 2),
+                           "tokens_per_s": round(tokens / (amortised_us * 1e-6), 1)}
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(result), flush=True)
