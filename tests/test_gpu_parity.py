@@ -315,6 +315,27 @@ def test_attention_large_logits_stay_finite(bd):
     check_attn(bd, q, k, v, False, "bf16")
 
 
+def test_attention_long_sequence_sampled_rows(bd):
+    # 20000 tokens (313 key tiles per workgroup, 20 MB between a head's first and last row): the oracle computes
+    # every 613-th query row; the fused call must also have written all 20000 cache rows and nothing before them.
+    rng = np.random.default_rng(17)
+    b, s, hq, hkv, d = 1, 20000, 4, 2, 128
+    log("attention long sequence", (b, s, hq, hkv, d))
+    q, k, v = (wl.quantize(rng.standard_normal((b, s, h, d)).astype(np.float32), "bf16")[0] for h in (hq, hkv, hkv))
+    qd, kd, vd = to_dev(q), to_dev(k), to_dev(v)
+    kc = torch.zeros((b, hkv, s + 3, d), dtype=qd.dtype, device="cuda")
+    vc = torch.zeros_like(kc)
+    for causal in (True, False):
+        out = bd.civic_prefill_attn_kv(qd, kd, vd, kc, vc, 3, causal, 0.0)
+        ref = oracle.attention(widen(q), widen(k), widen(v), causal, scale=None, row_step=613)[:, ::613]
+        got = widen(to_host(out)).astype(np.float64)[:, ::613]
+        err = float(np.abs(got - ref).max())
+        log("   causal", causal, "max abs err", err, "tol", attn_tol(ref, "bf16"))
+        assert np.isfinite(widen(to_host(out))).all() and err <= attn_tol(ref, "bf16")
+        assert torch.equal(kc[:, :, 3:], kd.permute(0, 2, 1, 3)) and torch.equal(vc[:, :, 3:], vd.permute(0, 2, 1, 3))
+        assert not kc[:, :, :3].any() and not vc[:, :, :3].any()
+
+
 @pytest.mark.parametrize("causal", [True, False])
 def test_attention_logits_growing_along_the_sequence(bd, causal):
     """Keys whose logits grow steadily with the key index: every later tile outgrows the softmax
