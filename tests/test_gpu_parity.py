@@ -91,6 +91,22 @@ def test_score_edge_rows_and_strides(bd):
     assert np.abs(s - oracle.score(np.ascontiguousarray(x32[:, 64:128]), q, 1.0)).max() <= 2e-5
 
 
+def test_score_many_rows_per_wavefront(bd):
+    # Far more rows than resident wavefronts (4096): every wavefront walks a dozen rows, refilling its registers
+    # with the next row while it reduces the current one; a third of the rows take the centred two-pass branch.
+    rng = np.random.default_rng(3)
+    for dtype, dim, rows in (("bf16", 1024, 50001), ("bf16", 72, 70000), ("fp32", 512, 30011)):
+        log("score many rows", dtype, dim, rows)
+        x = rng.standard_normal((rows, dim)).astype(np.float32)
+        x[::3] += 5.0
+        x[7] = 0.0
+        st, x32 = wl.quantize(x, dtype)
+        q = bd.civic_anchor_normalize(rng.standard_normal(dim).astype(np.float32))
+        s = to_host(bd.civic_score(to_dev(st), torch.from_numpy(q).cuda(), 3.0))
+        ref = oracle.score(x32, q, 3.0)
+        assert s[7] == 0.0 and np.isfinite(s).all() and np.abs(s - ref).max() <= 4e-5 * 3.0
+
+
 # ---------------------------------------------------------------------------------------- select
 def check_select(bd, scores: np.ndarray, grid):
     idx, flags = bd.civic_select(torch.from_numpy(scores).cuda(), grid, want_flags=True)
@@ -229,6 +245,26 @@ def test_compact_edge_cases(bd):
     pos = rng.integers(0, 1000, (3, 2, 512)).astype(np.int32)
     kept, _ = oracle.select(rng.standard_normal((2, 512)).astype(np.float32), grid)
     check_compact(bd, hid, pos, grid, np.arange(128, dtype=np.int64) * 4, kept)
+
+
+def test_compact_many_rows_per_block(bd):
+    # 200 000 compact rows: blocks own the maximum of 64 rows each and walk them in several passes; row sizes that
+    # use the 16-, 8- and 2-byte copies.
+    rng = np.random.default_rng(33)
+    frames, h, w = 8, 64, 64
+    hw, batch = h * w, 4
+    gaps = [700, 0, 1500, 3, 0, 900, 64, 1, 2500]
+    fs, t = [], gaps[0]
+    for f in range(frames):
+        fs.append(t)
+        t += hw + gaps[f + 1]
+    seq, fs = t, np.asarray(fs, dtype=np.int64)
+    for dim, dtype, k in ((64, np.uint16, frames * hw), (20, np.uint16, 20000), (3, np.uint16, 29000)):
+        log("compact many rows", dim, k, "seq", seq)
+        kept = np.stack([np.sort(rng.choice(frames * hw, k, replace=False)) for _ in range(batch)]).astype(np.int32)
+        hid = rng.integers(0, 60000, (batch, seq, dim)).astype(dtype)
+        pos = rng.integers(0, 100000, (3, batch, seq)).astype(np.int32)
+        check_compact(bd, hid, pos, (frames, h, w, 1, 1, 0, 0, k), fs, kept)
 
 
 def test_compact_long_kept_lists(bd):
