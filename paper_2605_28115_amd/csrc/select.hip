@@ -640,6 +640,30 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelArgs a)
 
     // ---- (4) ascending output
     const int32_t words = a.nv_pad / 64;                     // <= 512, one per thread
+    int32_t* out = a.kept_idx + static_cast<int64_t>(b) * a.kept;
+    if (words <= kWave) {
+        // Up to 4096 tokens: the mark words fit one per lane, so every wavefront scans all of them itself and
+        // takes the prefixes of its own words from the scan's lanes; nothing goes through LDS, no barrier.
+        const u32x2 mine = *reinterpret_cast<const u32x2*>(marks + 2 * min(lane, words - 1));
+        const uint32_t cnt = lane < words ? __popc(mine.x) + __popc(mine.y) : 0u;
+        const uint32_t before = wave_incl_scan(cnt, lane) - cnt;
+#pragma unroll
+        for (int u = 0; u < kWave / kSelWaves; ++u) {        // the wavefront's tokens: 64 per 1024, word wave + 16 u
+            const int w = wave + u * kSelWaves;
+            if (w >= words) break;
+            const uint32_t lo = __builtin_amdgcn_readlane(mine.x, w), hi = __builtin_amdgcn_readlane(mine.y, w);
+            const uint32_t base = __builtin_amdgcn_readlane(before, w);
+            const uint64_t word = (static_cast<uint64_t>(hi) << 32) | lo;
+            const int32_t v = w * kWave + lane;
+            const bool bit = (word >> lane) & 1ull;
+            if (bit) {
+                const uint32_t pos = base + static_cast<uint32_t>(__popcll(word & ((1ull << lane) - 1ull)));
+                if (pos < static_cast<uint32_t>(a.kept)) out[pos] = v;
+            }
+            if (a.keep_flags && v < a.nv) a.keep_flags[static_cast<int64_t>(b) * a.nv + v] = bit ? 1 : 0;
+        }
+        return;
+    }
     uint32_t pc = 0;
     if (tid < words) pc = __popc(marks[2 * tid]) + __popc(marks[2 * tid + 1]);
     const uint32_t incl = wave_incl_scan(pc, lane);
@@ -659,7 +683,6 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelArgs a)
     if (tid < words) word_prefix[tid] = wave_base + incl - pc;
     __syncthreads();
 
-    int32_t* out = a.kept_idx + static_cast<int64_t>(b) * a.kept;
     for (int32_t v0 = tid; v0 < a.nv_pad; v0 += kSelBatch * kSelThreads) {
         u32x2 mw[kSelBatch];
         uint32_t wp[kSelBatch];
