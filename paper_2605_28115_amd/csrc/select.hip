@@ -129,8 +129,9 @@ __device__ __forceinline__ void team_sync()
 
 // Marks the first m tokens, in (key, index) order, among the eligible tokens of `reg`; eligible means
 // not marked yet when only_unmarked is set.  Run by one wavefront (BLOCK = false) or by the whole
-// workgroup (BLOCK = true; every thread must call it with the same arguments, and `eligible` must be
-// given).  eligible < 0 (wavefront only): counted here.
+// workgroup (BLOCK = true; every thread must call it with the same arguments, `eligible` must be
+// given, and the caller synchronises the workgroup before anyone reads the marks: the function ends
+// without a barrier of its own).  eligible < 0 (wavefront only): counted here.
 //   hist  counters owned by the team: 2 x 2048 for the workgroup (double buffered, so the next pass's
 //         clear hides behind the scan; both must be zero on entry and are left dirty), 256 for a
 //         wavefront (cleared here, left zero);  bc  8 words owned by the team, 16 for the workgroup.
@@ -218,7 +219,7 @@ __device__ void select_first(const uint32_t* keys, uint32_t* marks, uint32_t* hi
             fetch(bi, tok, key, el);
             mark(tok, el);
         }
-        team_sync<BLOCK>();
+        team_sync<false>();
         return;
     }
 
@@ -320,8 +321,9 @@ __device__ void select_first(const uint32_t* keys, uint32_t* marks, uint32_t* hi
                 }
                 mark(tok, adm);
             }
+            if (count == want) { team_sync<false>(); return; }
             team_sync<BLOCK>();
-            if (count != want) {
+            {
                 // Thread j ranks candidate j among all of them by (key, token): the strict order itself.
                 if ((static_cast<uint32_t>(rank) & ~static_cast<uint32_t>(kWave - 1)) < count) {   // wavefronts that own a candidate
                     const u32x2 me = *reinterpret_cast<const u32x2*>(cand + 2 * min(static_cast<uint32_t>(rank), count - 1));
@@ -336,7 +338,7 @@ __device__ void select_first(const uint32_t* keys, uint32_t* marks, uint32_t* hi
                     }
                     if (static_cast<uint32_t>(rank) < count && ahead < want) set_mark(marks, static_cast<int32_t>(me.y));
                 }
-                team_sync<BLOCK>();
+                team_sync<false>();
                 if constexpr (!BLOCK) {
                     for (int i = lane; i < 2 * static_cast<int>(CAND); i += kWave) hist[i] = 0;
                     team_sync<false>();
@@ -382,7 +384,7 @@ __device__ void select_first(const uint32_t* keys, uint32_t* marks, uint32_t* hi
             for (int u = 0; u < kSelBatch; ++u) adm[u] = el[u] && (key[u] >> done_shift) <= limit;
             mark(tok, adm);
         }
-        team_sync<BLOCK>();
+        team_sync<false>();
         return;
     }
 
@@ -419,7 +421,7 @@ __device__ void select_first(const uint32_t* keys, uint32_t* marks, uint32_t* hi
             running += static_cast<uint32_t>(__popcll(bal));
         }
     }
-    team_sync<BLOCK>();
+    team_sync<false>();
 }
 
 __global__ __launch_bounds__(kSelThreads) void select_kernel(SelArgs a)
