@@ -30,6 +30,8 @@
 //
 // fp32 path and head sizes the MFMA path does not cover: a plain fp32 kernel, one wavefront per
 // query row (lanes over keys for Q K^T, lanes over channels for P V).
+#include <algorithm>
+#include <array>
 #include <cmath>
 #include <type_traits>
 
@@ -49,6 +51,7 @@ struct AttnArgs {
     int32_t batch, seq, n_q_heads, n_kv_heads, head_dim, causal;
     float scale;                          // softmax scale (natural-exponent domain)
     int32_t heads_per_block, row_tiles;   // MFMA path: block shape and number of 32*rows_per_block tiles
+    int32_t paired;                       // MFMA path: a workgroup walks two row tiles, a heavy and a light one
     // MFMA path, block index -> (head block, kv head, batch) without integer division: q heads per kv head,
     // head blocks per kv head, log2(heads_per_block), ceil(2^32 / d) for d = head blocks, kv heads (0 for d = 1)
     int32_t group, head_blocks, hb_shift;
@@ -184,13 +187,30 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) char lds_char;
 
 // 16 bytes per lane from global memory (scalar base + per-lane byte offset) straight into LDS at
-// lds_addr + lane * 16 (lds_addr wave-uniform).  Issued as inline assembly on purpose: the pipeline
+// lds_addr + LDS_IMM + lane * 16 (lds_addr wave-uniform).  Issued as inline assembly on purpose: the pipeline
 // tracks these loads with explicit s_waitcnt vmcnt(N), and an LDS read the compiler could see racing
-// with an asynchronous LDS write would make it drain the whole load queue first.
+// with an asynchronous LDS write would make it drain the whole load queue first.  m0 is written and not
+// declared: the register is reserved (the compiler rejects it as a clobber), never allocated, and set by the
+// compiler only directly in front of an instruction that reads it, of which this file has none.
+template <int LDS_IMM>
 __device__ __forceinline__ void dma16(const void* base, uint32_t byte_off, uint32_t lds_addr)
 {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(lds_addr), "v"(byte_off), "s"(base) : "memory");
+    // (the LDS address is lds_addr + LDS_IMM, added here so that one scalar register serves every instruction
+    // of a tile instead of one register per instruction)
+    asm volatile("s_add_u32 m0, %0, %3\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(byte_off), "s"(base), "n"(LDS_IMM) : "memory", "scc");
+}
+
+// dma16 with the LDS immediate BASE_IMM + j * 1024 for a loop index j that is a constant after unrolling
+// (at most 16 instructions per wavefront and tile).
+template <int BASE_IMM, int J = 0>
+__device__ __forceinline__ void dma16_at(const void* base, uint32_t byte_off, uint32_t lds_addr,
+                                         std::integral_constant<int, BASE_IMM> imm, int j)
+{
+    if constexpr (J < 16) {
+        if (j == J) dma16<BASE_IMM + J * kWave * 16>(base, byte_off, lds_addr);
+        else dma16_at<BASE_IMM, J + 1>(base, byte_off, lds_addr, imm, j);
+    }
 }
 
 // Workgroup barrier without the memory fence __syncthreads() implies (which would wait for every
@@ -233,10 +253,14 @@ struct AttnTile {
     static constexpr int NI = kBN * PITCH / THREADS;       // global->LDS instructions per wavefront, tile and tensor
     static constexpr int TLOADS = 2 * NI;                  // ... per tile (K and V)
     static constexpr int VBASE = STAGES * TILEB;           // byte offset of the V stages
-    // K ring, V ring, and a tail that stages Q for the wavefronts the last ring stage has no room for
-    static constexpr int LDS_BYTES = (2 * STAGES + (WAVES > 4 ? 2 : 0)) * TILEB;
-    static_assert(WAVES == 4 || WAVES == 8, "Q staging places wavefronts 0-3 in the last ring stage");
-    static_assert(STAGES >= 2 && STAGES <= 4 && (STAGES - 1) * TLOADS <= 63, "vmcnt is a 6-bit counter");
+    static constexpr int OROW = DP + 8;                    // elements per staged output row (padded against bank conflicts)
+    // behind the rings every wavefront owns an area that first stages its Q tile (32 rows in the K tile layout)
+    // and later its 32 x DP output tile
+    static constexpr int QW = 32 * PITCHB;
+    static constexpr int WAREA = QW > 32 * OROW * 2 ? QW : 32 * OROW * 2;
+    static constexpr int LDS_BYTES = 2 * STAGES * TILEB + WAVES * WAREA;
+    static_assert(WAVES == 4 || WAVES == 8, "block shapes are 4 or 8 wavefronts");
+    static_assert(STAGES == 2, "every wait below is for all outstanding loads, which fits a ring of two");
 };
 
 // Waits until at most `younger` tiles' worth of loads (TL per tile) are outstanding, younger <= MAXY.
@@ -258,18 +282,23 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
     constexpr int KSTEPS = T::KSTEPS, DT = T::DT, PITCH = T::PITCH, PITCHB = T::PITCHB, TILEB = T::TILEB;
     constexpr int NI = T::NI, TLOADS = T::TLOADS, VBASE = T::VBASE;
     extern __shared__ __attribute__((aligned(16))) __bf16 smem[];
-    lds_char* const lds = (lds_char*)smem;    // K stages at [0, VBASE), V stages at [VBASE, 2 VBASE)
+    lds_char* const lds = (lds_char*)smem;    // K stages at [0, VBASE), V stages at [VBASE, 2 VBASE), then the wavefronts' areas
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
     const int HB = a.heads_per_block, RB = kAttnWaves >> a.hb_shift;   // heads and 32-row sub-tiles per block
     const int group = a.group, head_blocks = a.head_blocks;
 
-    // blockIdx.y -> row tile, the heaviest causal ones first (the linear dispatch order runs through x first);
-    // blockIdx.x -> (head block, kv head, batch).  The quotients come from multiply-high with constants
-    // prepared at launch: a chain of integer divisions here would delay the first load by half a microsecond.
+    // blockIdx.y -> the workgroup's row tiles, the heaviest causal ones first (the linear dispatch order runs
+    // through x first); blockIdx.x -> (head block, kv head, batch).  The quotients come from multiply-high with
+    // constants prepared at launch: a chain of integer divisions here would delay the first load by half a
+    // microsecond.  A paired launch gives workgroup y the row tiles n-1-y and then y (y-1 when n is odd, where
+    // the heaviest tile stays alone): under the causal mask tile t has t+1 key tiles, so every workgroup gets
+    // the same number of them, one workgroup per compute unit covers the launch, and the second tile's Q and
+    // first K/V tile are fetched under the first one's last tiles and output stores.
     auto div_magic = [](uint32_t n, uint32_t magic) { return magic ? __umulhi(n, magic) : n; };
-    const int rt = a.row_tiles - 1 - static_cast<int>(blockIdx.y);
+    int rt = a.row_tiles - 1 - static_cast<int>(blockIdx.y);
+    int rt_next = a.paired ? static_cast<int>(blockIdx.y) - (a.row_tiles & 1) : -1;
     const uint32_t bid = blockIdx.x;
     const uint32_t bid_hb = div_magic(bid, a.magic_head_blocks);      // = kv head + n_kv_heads * batch
     const int hb = static_cast<int>(bid - bid_hb * head_blocks);
@@ -277,53 +306,73 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
     const int g = static_cast<int>(bid_hb) - b * a.n_kv_heads;
 
     const int h = g * group + hb * HB + (w & (HB - 1));
-    const int row0 = (rt * RB + (w >> a.hb_shift)) * 32;      // this wavefront's first query row
-    const int block_row0 = rt * RB * 32;
-    const int block_rows_end = min(block_row0 + RB * 32, a.seq);
-    const int qi = row0 + col;                                // this lane's query row
+    const int wrow = (w >> a.hb_shift) * 32;                  // this wavefront's first query row inside a row tile
     const float sl2 = a.scale * 1.4426950408889634f;          // scale * log2(e)
 
-    const int kv_end = a.causal ? block_rows_end : a.seq;     // keys [0, kv_end) are visible to the block
-    const int n_tiles = (kv_end + kBN - 1) / kBN;
+    // geometry of the row tile being computed
+    int row0, block_row0, block_rows_end, qi, n_tiles;
+    auto set_rows = [&](int t) {
+        block_row0 = t * RB * 32;
+        row0 = block_row0 + wrow;                             // this wavefront's first query row
+        block_rows_end = min(block_row0 + RB * 32, a.seq);
+        qi = row0 + col;                                      // this lane's query row
+        const int kv_end = a.causal ? block_rows_end : a.seq; // keys [0, kv_end) are visible to the block
+        n_tiles = (kv_end + kBN - 1) / kBN;
+    };
+    set_rows(rt);
     const __bf16* kp = static_cast<const __bf16*>(a.k) + b * a.ks[0] + g * a.ks[2];
     const __bf16* vp = static_cast<const __bf16*>(a.v) + b * a.ks[0] + g * a.ks[2];
     const uint32_t row_bytes = static_cast<uint32_t>(a.ks[1]) * 2u;   // K/V token stride
 
     // Q first: its loads are the longest wait of the prologue, everything else is set up in their shadow.
-    // Q goes through LDS as well (same swizzled layout as a K tile, 32 rows per wavefront), so that the
-    // kernel holds no register-destination global load: the compiler then never emits a vmcnt wait of
-    // its own, which would drain the K/V prefetches along with it.  The staging area is the last ring
-    // stage, which the pipeline first fills after its first barrier, plus a tail behind the ring.
-    constexpr int QW = 32 * PITCHB;                           // bytes of one wavefront's Q tile
-    const uint32_t q_lds = w < 2 ? (kStages - 1) * TILEB + w * QW
-                         : w < 4 ? VBASE + (kStages - 1) * TILEB + (w - 2) * QW
-                                 : 2 * VBASE + (w - 4) * QW;
-    {
-        const char* qb = reinterpret_cast<const char*>(static_cast<const __bf16*>(a.q) + b * a.qs[0] + h * a.qs[2]);
-        const uint64_t qb_bits = reinterpret_cast<uint64_t>(qb);
-        // (the builtin returns a signed int: widen each half as unsigned)
-        const uint32_t qb_hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(qb_bits >> 32)));
-        const uint32_t qb_lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(qb_bits)));
-        const uint64_t qb_uni = (static_cast<uint64_t>(qb_hi) << 32) | qb_lo;
-        const uint32_t q_row_bytes = static_cast<uint32_t>(a.qs[1]) * 2u;
-        const uint32_t q_lds_uni = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds)) + q_lds);
+    // Q goes through LDS as well (same swizzled layout as a K tile, 32 rows per wavefront, in the wavefront's
+    // own area behind the rings), so that the main loop holds no register-destination global load: the
+    // compiler then never emits a vmcnt wait of its own there.
+    const uint32_t q_lds = 2 * VBASE + w * T::WAREA;
+    const char* qb = reinterpret_cast<const char*>(static_cast<const __bf16*>(a.q) + b * a.qs[0] + h * a.qs[2]);
+    const uint64_t qb_bits = reinterpret_cast<uint64_t>(qb);
+    // (the builtin returns a signed int: widen each half as unsigned)
+    const uint32_t qb_hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(qb_bits >> 32)));
+    const uint32_t qb_lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(qb_bits)));
+    const uint64_t qb_uni = (static_cast<uint64_t>(qb_hi) << 32) | qb_lo;
+    const uint32_t q_row_bytes = static_cast<uint32_t>(a.qs[1]) * 2u;
+    const uint32_t q_lds_uni = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds)) + q_lds);
+    // Slot -> (row, physical chunk) as for a K tile: instruction j covers rows 4j .. 4j+3 when a row has 16
+    // chunks (8j .. 8j+7 when it has 8), and the chunk swizzle repeats every 16 rows, so instructions j and
+    // j + 16/rows-per-instruction differ by a constant row offset only.
+    auto q_slot_off = [&](int j, int first_row, bool clamp) {
+        const int slot = j * kWave + lane;
+        const int row = slot / PITCH;
+        const int c = (slot % PITCH) ^ swz<PITCH>(row);
+        const uint32_t cb = (c * 8 < a.head_dim) ? c * 16 : 0;
+        const int r = clamp ? min(first_row + row, a.seq - 1) : first_row + row;
+        return static_cast<uint32_t>(r) * q_row_bytes + cb;
+    };
+    auto issue_q = [&](int first_row) {                       // any row tile: rows past the sequence re-read its last row
 #pragma unroll
-        for (int j = 0; j < PITCH / 2; ++j) {
-            const int slot = j * kWave + lane;
-            const int row = slot / PITCH;
-            const int c = (slot % PITCH) ^ swz<PITCH>(row);
-            const uint32_t cb = (c * 8 < a.head_dim) ? c * 16 : 0;
-            dma16(reinterpret_cast<const void*>(qb_uni), static_cast<uint32_t>(min(row0 + row, a.seq - 1)) * q_row_bytes + cb,
-                  q_lds_uni + j * kWave * 16);
-        }
-    }
+        for (int j = 0; j < PITCH / 2; ++j)
+            dma16_at(reinterpret_cast<const void*>(qb_uni), q_slot_off(j, first_row, true), q_lds_uni, std::integral_constant<int, 0>{}, j);
+    };
+    // The Q rows of a workgroup's second row tile, which is never the last of the sequence (no clamping): the
+    // offsets of the first 16 rows stay in registers, the tile's first row enters through the scalar base.
+    constexpr int QJ = 16 * PITCH / kWave;                    // instructions per 16 rows
+    uint32_t q_voff[QJ];
+#pragma unroll
+    for (int j = 0; j < QJ; ++j) q_voff[j] = q_slot_off(j, 0, false);
+    auto issue_q_next = [&](int first_row) {
+        const char* base0 = uniform_ptr(reinterpret_cast<const char*>(qb_uni) + static_cast<int64_t>(first_row) * q_row_bytes);
+        const char* base1 = uniform_ptr(base0 + 16 * static_cast<int64_t>(q_row_bytes));
+#pragma unroll
+        for (int j = 0; j < PITCH / 2; ++j)
+            dma16_at(j < QJ ? base0 : base1, q_voff[j % QJ], q_lds_uni, std::integral_constant<int, 0>{}, j);
+    };
+    issue_q(row0);
     // Global -> LDS: instruction j of wavefront w fills slots [(w*NI + j)*64, +64) of a tile; slot ->
     // (row, physical chunk); the lane fetches the logical chunk that belongs there.  Every lane always
-    // loads (the count of outstanding loads is what the pipeline waits on): rows past the end of the
-    // sequence re-read the last row (their scores are masked), chunks past head_dim re-read chunk 0
-    // (they meet zero-filled Q columns, or produce output columns that are never stored).  The tile's
-    // first key enters through the scalar base, so the per-lane offsets are loop invariant; only the
-    // tile that holds the end of the sequence needs the clamped set.
+    // loads: rows past the end of the sequence re-read the last row (their scores are masked), chunks past
+    // head_dim re-read chunk 0 (they meet zero-filled Q columns, or produce output columns that are never
+    // stored).  The tile's first key enters through the scalar base, so the per-lane offsets are loop
+    // invariant; only the tile that holds the end of the sequence needs the clamped set.
     uint32_t ld_voff[NI], ld_voff_tail[NI];
     const int tail_tile = (a.seq - 1) / kBN;                  // the tile that may run past the sequence
 #pragma unroll
@@ -337,42 +386,43 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
     }
     const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(
         static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds)) + w * NI * kWave * 16);
-    auto issue_tile = [&](int kt, int st) {
-        const char* kb = reinterpret_cast<const char*>(kp) + static_cast<int64_t>(kt) * kBN * row_bytes;
-        const char* vb = reinterpret_cast<const char*>(vp) + static_cast<int64_t>(kt) * kBN * row_bytes;
+    auto issue_tile = [&](int kt, auto stage_c) {
+        constexpr int st = decltype(stage_c)::value;
+        // (wave-uniform by construction; made so explicitly because the load takes its base in scalar registers)
+        const char* kb = uniform_ptr(reinterpret_cast<const char*>(kp) + static_cast<int64_t>(kt) * kBN * row_bytes);
+        const char* vb = uniform_ptr(reinterpret_cast<const char*>(vp) + static_cast<int64_t>(kt) * kBN * row_bytes);
         const bool tail = kt == tail_tile;
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
             const uint32_t off = tail ? ld_voff_tail[j] : ld_voff[j];
-            const uint32_t la = lds_wave + st * TILEB + j * kWave * 16;
-            dma16(kb, off, la);
-            dma16(vb, off, la + VBASE);
+            dma16_at(kb, off, lds_wave, std::integral_constant<int, st * TILEB>{}, j);
+            dma16_at(vb, off, lds_wave, std::integral_constant<int, st * TILEB + VBASE>{}, j);
         }
     };
 
-    // Start the pipeline: tiles 0 .. kStages-2
-#pragma unroll
-    for (int p = 0; p < kStages - 1; ++p)
-        if (p < n_tiles) issue_tile(p, p);
+    // Start the pipeline: tile 0 (the ring runs one tile ahead of the one being consumed)
+    issue_tile(0, std::integral_constant<int, 0>{});
 
-    // Q^T as B operand: lane (col, half) holds Q[qi][16 s + 8 half .. +7] for every k-step s.  Loads
-    // retire in order and Q was issued first: wait until only the tile loads are outstanding.
-    wait_tiles<kStages - 1, TLOADS>(min(n_tiles, kStages - 1));
+    // Q^T as B operand: lane (col, half) holds Q[qi][16 s + 8 half .. +7] for every k-step s.
     bf16x8 qreg[KSTEPS];
+    auto read_q = [&]() {
 #pragma unroll
-    for (int s = 0; s < KSTEPS; ++s) {
-        const bf16x8 t = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
-            lds + q_lds + col * PITCHB + (((2 * s + half) ^ swz<PITCH>(col & 15)) << 4));
-        qreg[s] = t;
-    }
-    if (a.head_dim != DP) {                                   // a padded head: the columns past head_dim count as zero
-        const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+        for (int s = 0; s < KSTEPS; ++s) {
+            const bf16x8 t = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
+                lds + q_lds + col * PITCHB + (((2 * s + half) ^ swz<PITCH>(col & 15)) << 4));
+            qreg[s] = t;
+        }
+        if (a.head_dim != DP) {                               // a padded head: the columns past head_dim count as zero
+            const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-        for (int s = 0; s < KSTEPS; ++s) qreg[s] = (16 * s + 8 * half < a.head_dim) ? qreg[s] : zero;
-    }
-
-    // in registers before the first barrier, after which the staging area is refilled
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            for (int s = 0; s < KSTEPS; ++s) qreg[s] = (16 * s + 8 * half < a.head_dim) ? qreg[s] : zero;
+        }
+        // in registers before the area is written again
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    };
+    // Loads retire in order and Q was issued first: wait until only the tile's loads are outstanding.
+    wait_vmcnt<TLOADS>();
+    read_q();
 
     // Per-lane LDS read addresses (bytes) inside stage 0; stage, t, u add compile-time immediates.
     lds_char* kaddr[KSTEPS];              // K: row col, logical chunk 2s + half
@@ -395,12 +445,8 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
         }
 
     f32x16 acc_o[DT];
-#pragma unroll
-    for (int t = 0; t < DT; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc_o[t][r] = 0.f;
-    float m_run = 0.f;                     // offset subtracted from the raw logits (a recent row maximum)
-    float l_run[2] = {0.f, 0.f};           // running row sum, two partial accumulators
+    float m_run;                           // offset subtracted from the raw logits (a recent row maximum)
+    float l_run[2];                        // running row sum, two partial accumulators
     const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
 
     // The arithmetic of one tile (stage ST of the ring) for this wavefront: NT = 2 for the whole tile, 1 for
@@ -515,16 +561,26 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
                     const s16x8 v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                     acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, v8), pb[t][u], acc_o[dt], 0, 0, 0);
                 }
+        // keep the V fragments of 4 MFMAs (two transposing reads each) in flight ahead of their consumer
+        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+        for (int i = 0; i < NT * 2 * DT - 4; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
     };
 
     // One step of the pipeline: wait until the tile has landed, release the previous one, refill the freed
-    // stage, compute.  Loads retire in order; younger than tile kt are the tiles issued after it (at most
-    // kStages-2 of them).
+    // stage, compute.  At step q_issue the Q rows of the workgroup's next row tile are requested as well (their
+    // area has been free since Q moved into registers); they land with a later tile.
+    int q_issue = -1, next_row0 = 0;
     auto step = [&](int kt, auto stage_c) __attribute__((always_inline)) {
         constexpr int ST = decltype(stage_c)::value;
-        wait_tiles<kStages - 2, TLOADS>(min(n_tiles - 1 - kt, kStages - 2));
+        wait_vmcnt<0>();
         block_barrier();                                      // landed for every wavefront; tile kt-1 is released
-        if (kt + kStages - 1 < n_tiles) issue_tile(kt + kStages - 1, (ST + kStages - 1) % kStages);
+        if (kt + 1 < n_tiles) issue_tile(kt + 1, std::integral_constant<int, (ST + 1) % kStages>{});
+        if (kt == q_issue) issue_q_next(next_row0);
         // On the diagonal a wavefront whose rows all precede the tile's second half computes the first half
         // only: half the MFMAs and exponentials of that tile for half of the wavefronts, which the other
         // wavefront of the SIMD turns into time.  The same holds for a last tile whose second half lies past
@@ -532,107 +588,132 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
         if ((a.causal && kt * kBN + 32 > row0 + 31) || kt * kBN + 32 >= a.seq) tile(kt, stage_c, std::integral_constant<int, 1>{});
         else tile(kt, stage_c, std::integral_constant<int, 2>{});
     };
-    for (int kt = 0; kt < n_tiles; kt += kStages) {
-        step(kt, std::integral_constant<int, 0>{});
-        if (kt + 1 < n_tiles) step(kt + 1, std::integral_constant<int, 1>{});
-        if constexpr (kStages > 2) if (kt + 2 < n_tiles) step(kt + 2, std::integral_constant<int, 2>{});
-        if constexpr (kStages > 3) if (kt + 3 < n_tiles) step(kt + 3, std::integral_constant<int, 3>{});
-    }
-    __syncthreads();                                          // every tile consumed: LDS is free
 
-    // Fused KV-cache write: the workgroup of the first head block copies the K and V rows of its own
-    // query rows (keys block_row0 .. block_rows_end-1, which it has just streamed through LDS, so
-    // the reads hit L2) into the cache; the loads of the first 64 rows go out before the output rows are
-    // stored and their stores after; taller blocks take the rest in a plain loop at the end.
-    // Copy layout: 8 threads per row, thread t takes row t / 8 of a 64-row group and the 16-byte pieces
-    // t % 8, t % 8 + 8, ... of it, the same piece of K and of V (one address computation for both).
+    constexpr int OROW = T::OROW;
+    constexpr int CPR = DP / 8;
     constexpr int kKvJ = (DP / 8 + 7) / 8;                     // pieces per thread, row and tensor
     constexpr int kKvRows = WAVES * kWave / 8;                 // rows per pass of the workgroup (64 with 8 wavefronts)
-    u32x4 kv_piece[2 * kKvJ];
-    // opaque copies: they keep the address arithmetic of the epilogue down here, instead of in registers
-    // (or spilled) across the main loop
-    int tid_late = tid, lane_late = lane;
-    asm volatile("" : "+v"(tid_late), "+v"(lane_late));
-    const int col_late = lane_late & 31, half_late = lane_late >> 5;
-    const bool kv_fused = a.k_cache != nullptr && hb == 0;
-    const int kv_cpr = a.head_dim / 8;                         // 16-byte pieces per row
-    const int kv_rows = block_rows_end - block_row0;
-    const int kv_r = tid_late >> 3, kv_c = tid_late & 7;
-    // element offsets of piece (row r, chunk kv_c) from kp / vp and from the cache bases
-    auto kv_src_off = [&](int r) { return static_cast<int64_t>(block_row0 + r) * a.ks[1] + kv_c * 8; };
-    auto kv_dst_off = [&](int r) {
-        const int64_t cache_row = (static_cast<int64_t>(b) * a.n_kv_heads + g) * a.s_max + a.pos0 + block_row0 + r;
-        return cache_row * a.head_dim + kv_c * 8;
-    };
-    float l_sum = l_run[0] + l_run[1];
-    const float l_tot = l_sum + __shfl_xor(l_sum, 32, kWave);
-    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    // Stage the wavefront's 32 x DP output tile in LDS and write it out as whole 16-byte row segments.
-    constexpr int OROW = DP + 8;
-    constexpr int CPR = DP / 8;
-    __bf16* o_s = smem + w * 32 * OROW;
+    __bf16* const o_s = reinterpret_cast<__bf16*>(smem) + q_lds / 2;   // the wavefront's area, now its output tile
+
+    for (;;) {
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
+        for (int t = 0; t < DT; ++t)
 #pragma unroll
-        for (int rq = 0; rq < 4; ++rq) {
-            bf16x4 o4;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o4[e] = static_cast<__bf16>(acc_o[dt][4 * rq + e] * inv);
-            *reinterpret_cast<bf16x4*>(&o_s[col_late * OROW + 32 * dt + 8 * rq + 4 * half_late]) = o4;
+            for (int r = 0; r < 16; ++r) acc_o[t][r] = 0.f;
+        m_run = 0.f; l_run[0] = 0.f; l_run[1] = 0.f;
+        const bool has_next = rt_next >= 0;
+        q_issue = has_next ? max(n_tiles - 3, 0) : -1;
+        next_row0 = rt_next * RB * 32 + wrow;
+
+        for (int kt = 0; kt < n_tiles; kt += kStages) {
+            step(kt, std::integral_constant<int, 0>{});
+            if (kt + 1 < n_tiles) step(kt + 1, std::integral_constant<int, 1>{});
         }
-    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    if (kv_fused) {                                           // (the accumulators are dead by now: registers are free)
-        const int64_t so = kv_src_off(kv_r);
+        if (has_next) wait_vmcnt<0>();                        // the next Q rows (a one-tile pass waits nowhere else)
+        __syncthreads();                                      // every tile consumed: the rings are free
+
+        // what the epilogue needs of the tile just computed
+        const int e_row0 = row0, e_block_row0 = block_row0, e_rows_end = block_rows_end;
+        float l_sum = l_run[0] + l_run[1];
+        const float l_tot = l_sum + __shfl_xor(l_sum, 32, kWave);
+        const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+        if (has_next) {
+            // the next row tile starts here: its first K/V tile flies while this one's output is stored, and
+            // its Q rows move into registers before the area takes the output tile
+            set_rows(rt_next);
+            issue_tile(0, std::integral_constant<int, 0>{});
+            read_q();
+        }
+
+        // Fused KV-cache write: the workgroup of the first head block copies the K and V rows of its own
+        // query rows (which it has just streamed through LDS, so the reads hit L2) into the cache; the loads
+        // of the first 64 rows go out before the output rows are stored and their stores after; taller blocks
+        // take the rest in a plain loop at the end.
+        // Copy layout: 8 threads per row, thread t takes row t / 8 of a 64-row group and the 16-byte pieces
+        // t % 8, t % 8 + 8, ... of it, the same piece of K and of V (one address computation for both).
+        u32x4 kv_piece[2 * kKvJ];
+        // opaque copies: they keep the address arithmetic of the epilogue down here, instead of in registers
+        // (or spilled) across the main loop
+        int tid_late = tid, lane_late = lane;
+        asm volatile("" : "+v"(tid_late), "+v"(lane_late));
+        const int col_late = lane_late & 31, half_late = lane_late >> 5;
+        const bool kv_fused = a.k_cache != nullptr && hb == 0;
+        const int kv_cpr = a.head_dim / 8;                     // 16-byte pieces per row
+        const int kv_rows = e_rows_end - e_block_row0;
+        const int kv_r = tid_late >> 3, kv_c = tid_late & 7;
+        // element offsets of piece (row r, chunk kv_c) from kp / vp and from the cache bases
+        auto kv_src_off = [&](int r) { return static_cast<int64_t>(e_block_row0 + r) * a.ks[1] + kv_c * 8; };
+        auto kv_dst_off = [&](int r) {
+            const int64_t cache_row = (static_cast<int64_t>(b) * a.n_kv_heads + g) * a.s_max + a.pos0 + e_block_row0 + r;
+            return cache_row * a.head_dim + kv_c * 8;
+        };
+        // Stage the wavefront's 32 x DP output tile in LDS and write it out as whole 16-byte row segments.
 #pragma unroll
-        for (int j = 0; j < kKvJ; ++j) {
-            kv_piece[2 * j] = kv_piece[2 * j + 1] = u32x4{0u, 0u, 0u, 0u};
-            if (kv_r < kv_rows && kv_c + 8 * j < kv_cpr) {
-                kv_piece[2 * j] = *reinterpret_cast<const u32x4*>(kp + so + 64 * j);
-                kv_piece[2 * j + 1] = *reinterpret_cast<const u32x4*>(vp + so + 64 * j);
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                bf16x4 o4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o4[e] = static_cast<__bf16>(acc_o[dt][4 * rq + e] * inv);
+                *reinterpret_cast<bf16x4*>(&o_s[col_late * OROW + 32 * dt + 8 * rq + 4 * half_late]) = o4;
+            }
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        if (kv_fused) {                                       // (the accumulators are dead by now: registers are free)
+            const int64_t so = kv_src_off(kv_r);
+#pragma unroll
+            for (int j = 0; j < kKvJ; ++j) {
+                kv_piece[2 * j] = kv_piece[2 * j + 1] = u32x4{0u, 0u, 0u, 0u};
+                if (kv_r < kv_rows && kv_c + 8 * j < kv_cpr) {
+                    kv_piece[2 * j] = *reinterpret_cast<const u32x4*>(kp + so + 64 * j);
+                    kv_piece[2 * j + 1] = *reinterpret_cast<const u32x4*>(vp + so + 64 * j);
+                }
             }
         }
-    }
-    __bf16* ob = static_cast<__bf16*>(a.out) + b * a.os[0] + h * a.os[2];
-    if (kWave % CPR == 0 && row0 + 32 <= a.seq && a.head_dim == DP) {
-        // whole tile, unpadded head: the lane keeps its column, rows advance by 64 / CPR per store
-        constexpr int RPI = kWave / CPR > 0 ? kWave / CPR : 1;
-        const int r0 = lane_late / CPR, dc = lane_late - r0 * CPR;
-        __bf16* dst = ob + static_cast<int64_t>(row0 + r0) * a.os[1] + dc * 8;
-        const __bf16* src = &o_s[r0 * OROW + dc * 8];
-        const int64_t step = static_cast<int64_t>(RPI) * a.os[1];
+        __bf16* ob = static_cast<__bf16*>(a.out) + b * a.os[0] + h * a.os[2];
+        if (kWave % CPR == 0 && e_row0 + 32 <= a.seq && a.head_dim == DP) {
+            // whole tile, unpadded head: the lane keeps its column, rows advance by 64 / CPR per store
+            constexpr int RPI = kWave / CPR > 0 ? kWave / CPR : 1;
+            const int r0 = lane_late / CPR, dc = lane_late - r0 * CPR;
+            __bf16* dst = ob + static_cast<int64_t>(e_row0 + r0) * a.os[1] + dc * 8;
+            const __bf16* src = &o_s[r0 * OROW + dc * 8];
+            const int64_t stride = static_cast<int64_t>(RPI) * a.os[1];
 #pragma unroll
-        for (int it = 0; it < 32 * CPR / kWave; ++it)
-            *reinterpret_cast<bf16x8*>(dst + it * step) = *reinterpret_cast<const bf16x8*>(src + it * RPI * OROW);
-    } else {
+            for (int it = 0; it < 32 * CPR / kWave; ++it)
+                *reinterpret_cast<bf16x8*>(dst + it * stride) = *reinterpret_cast<const bf16x8*>(src + it * RPI * OROW);
+        } else {
 #pragma unroll
-        for (int it = 0; it < 32 * CPR / kWave; ++it) {
-            const int id = it * kWave + lane_late;
-            const int r = id / CPR, dc = id - r * CPR;
-            if (row0 + r < a.seq && dc * 8 < a.head_dim)
-                *reinterpret_cast<bf16x8*>(ob + static_cast<int64_t>(row0 + r) * a.os[1] + dc * 8) =
-                    *reinterpret_cast<const bf16x8*>(&o_s[r * OROW + dc * 8]);
-        }
-    }
-    if (kv_fused) {
-        __bf16* const kc = static_cast<__bf16*>(a.k_cache);
-        __bf16* const vc = static_cast<__bf16*>(a.v_cache);
-        const int64_t d0 = kv_dst_off(kv_r);
-#pragma unroll
-        for (int j = 0; j < kKvJ; ++j)
-            if (kv_r < kv_rows && kv_c + 8 * j < kv_cpr) {
-                *reinterpret_cast<u32x4*>(kc + d0 + 64 * j) = kv_piece[2 * j];
-                *reinterpret_cast<u32x4*>(vc + d0 + 64 * j) = kv_piece[2 * j + 1];
+            for (int it = 0; it < 32 * CPR / kWave; ++it) {
+                const int id = it * kWave + lane_late;
+                const int r = id / CPR, dc = id - r * CPR;
+                if (e_row0 + r < a.seq && dc * 8 < a.head_dim)
+                    *reinterpret_cast<bf16x8*>(ob + static_cast<int64_t>(e_row0 + r) * a.os[1] + dc * 8) =
+                        *reinterpret_cast<const bf16x8*>(&o_s[r * OROW + dc * 8]);
             }
-        for (int r = kv_r + kKvRows; r < kv_rows; r += kKvRows) {   // taller blocks (fewer than 4 heads per block)
-            const int64_t so = kv_src_off(r), dd = kv_dst_off(r);
+        }
+        if (kv_fused) {
+            __bf16* const kc = static_cast<__bf16*>(a.k_cache);
+            __bf16* const vc = static_cast<__bf16*>(a.v_cache);
+            const int64_t d0 = kv_dst_off(kv_r);
 #pragma unroll
             for (int j = 0; j < kKvJ; ++j)
-                if (kv_c + 8 * j < kv_cpr) {
-                    *reinterpret_cast<u32x4*>(kc + dd + 64 * j) = *reinterpret_cast<const u32x4*>(kp + so + 64 * j);
-                    *reinterpret_cast<u32x4*>(vc + dd + 64 * j) = *reinterpret_cast<const u32x4*>(vp + so + 64 * j);
+                if (kv_r < kv_rows && kv_c + 8 * j < kv_cpr) {
+                    *reinterpret_cast<u32x4*>(kc + d0 + 64 * j) = kv_piece[2 * j];
+                    *reinterpret_cast<u32x4*>(vc + d0 + 64 * j) = kv_piece[2 * j + 1];
                 }
+            for (int r = kv_r + kKvRows; r < kv_rows; r += kKvRows) {   // taller blocks (fewer than 4 heads per block)
+                const int64_t so = kv_src_off(r), dd = kv_dst_off(r);
+#pragma unroll
+                for (int j = 0; j < kKvJ; ++j)
+                    if (kv_c + 8 * j < kv_cpr) {
+                        *reinterpret_cast<u32x4*>(kc + dd + 64 * j) = *reinterpret_cast<const u32x4*>(kp + so + 64 * j);
+                        *reinterpret_cast<u32x4*>(vc + dd + 64 * j) = *reinterpret_cast<const u32x4*>(vp + so + 64 * j);
+                    }
+            }
         }
+        if (!has_next) break;
+        rt = rt_next;
+        rt_next = -1;
     }
 }
 
@@ -654,6 +735,65 @@ static bool mfma_geometry(AttnArgs& a, int64_t* per_rt)
     return *per_rt * d_max < (int64_t{1} << 32) && row_tiles <= 65535;
 }
 
+constexpr int64_t kComputeUnits = 256;
+
+// Time (in arbitrary units) until the last workgroup of a causal launch ends when every compute unit runs one
+// workgroup at a time and takes the next in dispatch order.  `paired`: workgroup y walks row tiles n-1-y and
+// its partner (see the kernel).  A key tile costs 1.9 and a workgroup 5.5 around its tiles, 2 more for a
+// second row tile whose start hides under the first one's end (microseconds measured on the 8B-shaped
+// launch).  Only the ratio of the two results is used.
+static double causal_makespan(int n_row_tiles, int64_t per_rt, int rows_per_block, int seq, bool paired)
+{
+    auto tiles_of = [&](int rt) {
+        const int64_t end = std::min<int64_t>(static_cast<int64_t>(rt + 1) * rows_per_block, seq);
+        return static_cast<double>((end + kBN - 1) / kBN);
+    };
+    const int items = paired ? (n_row_tiles + 1) / 2 : n_row_tiles;
+    std::array<double, kComputeUnits> free_at;                // a min-heap of the units' free times
+    free_at.fill(0.0);
+    auto cmp = [](double x, double y) { return x > y; };
+    double last = 0.0;
+    for (int y = 0; y < items; ++y) {
+        double cost = 5.5 + 1.9 * tiles_of(n_row_tiles - 1 - y);
+        if (paired) {
+            const int light = y - (n_row_tiles & 1);
+            if (light >= 0) cost += 2.0 + 1.9 * tiles_of(light);
+        }
+        for (int64_t x = 0; x < per_rt; ++x) {
+            std::pop_heap(free_at.begin(), free_at.end(), cmp);
+            const double t = free_at.back() + cost;
+            free_at.back() = t;
+            std::push_heap(free_at.begin(), free_at.end(), cmp);
+            if (t > last) last = t;
+        }
+    }
+    return last;
+}
+
+// Whether the launch gives every workgroup two row tiles.  It pays under the causal mask when the row tiles
+// do not all run at once anyway: the pairs are equally heavy, there are half as many workgroup starts, and a
+// pair's second start is hidden.  Decided with the model above for grids small enough that the answer depends
+// on how the workgroups fall onto the compute units; larger grids always pair.  The last answer is kept per
+// thread so that a loop over layers does not model the same launch again.
+static bool choose_paired(const AttnArgs& a, int64_t per_rt, int rows_per_block)
+{
+#ifdef CIVIC_ATTN_FORCE_PAIRED
+    return CIVIC_ATTN_FORCE_PAIRED && a.row_tiles >= 2;           // build-time override for A/B measurements
+#endif
+    if (!a.causal || a.row_tiles < 2) return false;
+    const int64_t blocks = per_rt * a.row_tiles;
+    if (blocks <= kComputeUnits) return false;                // one generation as it is
+    if (blocks > 16 * kComputeUnits) return true;
+    struct Memo { int32_t row_tiles, rows_per_block, seq; int64_t per_rt; bool paired; };
+    static thread_local Memo memo = {0, 0, 0, 0, false};
+    if (memo.row_tiles == a.row_tiles && memo.rows_per_block == rows_per_block && memo.seq == a.seq && memo.per_rt == per_rt)
+        return memo.paired;
+    const bool paired = causal_makespan(a.row_tiles, per_rt, rows_per_block, a.seq, true) <
+                        causal_makespan(a.row_tiles, per_rt, rows_per_block, a.seq, false);
+    memo = {a.row_tiles, rows_per_block, a.seq, per_rt, paired};
+    return paired;
+}
+
 template <int DP, int WAVES, int STAGES>
 static int launch_mfma(AttnArgs& a, hipStream_t s)
 {
@@ -663,13 +803,15 @@ static int launch_mfma(AttnArgs& a, hipStream_t s)
     auto magic = [](int64_t d) { return d <= 1 ? 0u : static_cast<uint32_t>(((int64_t{1} << 32) + d - 1) / d); };
     a.magic_head_blocks = magic(a.head_blocks);
     a.magic_kv_heads = magic(a.n_kv_heads);
+    a.paired = choose_paired(a, per_rt, 32 * (WAVES / a.heads_per_block)) ? 1 : 0;
+    const unsigned grid_y = static_cast<unsigned>(a.paired ? (a.row_tiles + 1) / 2 : a.row_tiles);
     constexpr size_t lds = T::LDS_BYTES;
     if (lds > 64 * 1024) {
         static std::atomic<uint64_t> allowed{0};
         const int rc = allow_dynamic_lds(reinterpret_cast<const void*>(attn_mfma_kernel<DP, WAVES, STAGES>), lds, &allowed);
         if (rc != CIVIC_OK) return rc;
     }
-    hipLaunchKernelGGL((attn_mfma_kernel<DP, WAVES, STAGES>), dim3(static_cast<unsigned>(per_rt), static_cast<unsigned>(a.row_tiles)),
+    hipLaunchKernelGGL((attn_mfma_kernel<DP, WAVES, STAGES>), dim3(static_cast<unsigned>(per_rt), grid_y),
                        dim3(T::THREADS), lds, s, a);
     return check_launch();
 }
@@ -677,8 +819,6 @@ static int launch_mfma(AttnArgs& a, hipStream_t s)
 #ifndef CIVIC_ATTN_STAGES
 #define CIVIC_ATTN_STAGES 2
 #endif
-constexpr int64_t kComputeUnits = 256;
-
 template <int WAVES>
 static int launch_mfma_for(AttnArgs& a, hipStream_t s)
 {
@@ -724,7 +864,7 @@ static int prefill_attn(const void* q, const void* k, const void* v, void* out, 
     a.batch = batch; a.seq = seq; a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads; a.head_dim = head_dim;
     a.causal = causal ? 1 : 0;
     a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt(static_cast<float>(head_dim));
-    a.heads_per_block = 1; a.row_tiles = 0;
+    a.heads_per_block = 1; a.row_tiles = 0; a.paired = 0;
     a.group = n_q_heads / n_kv_heads; a.head_blocks = 0; a.hb_shift = 0; a.magic_head_blocks = 0; a.magic_kv_heads = 0;
     a.k_cache = k_cache; a.v_cache = v_cache; a.s_max = s_max; a.pos0 = pos0;
     hipStream_t s = static_cast<hipStream_t>(stream);
