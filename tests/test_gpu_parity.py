@@ -45,15 +45,16 @@ def test_score_matches_oracle(bd, name):
     w = wl.WORKLOADS[name]
     log("score", name)
     rows = min(w.batch * w.seq_len, 3000)
-    hid, hid32 = wl.hidden(w, 0)
-    hid = hid.reshape(-1, w.dim)[:rows]
-    hid32 = hid32.reshape(-1, w.dim)[:rows]
-    q = bd.civic_anchor_normalize(wl.anchor(w, 0))
-    assert np.abs(q - oracle.anchor_normalize(wl.anchor(w, 0))).max() < 1e-7
-    for inv_tau in (1.0, 14.0):
-        s = to_host(bd.civic_score(to_dev(hid), torch.from_numpy(q).cuda(), inv_tau))
-        ref = oracle.score(hid32, q, inv_tau)
-        assert s.shape == ref.shape and np.abs(s - ref).max() <= 2e-5 * inv_tau
+    for trial in range(5):
+        hid, hid32 = wl.hidden(w, trial)
+        hid = hid.reshape(-1, w.dim)[:rows]
+        hid32 = hid32.reshape(-1, w.dim)[:rows]
+        q = bd.civic_anchor_normalize(wl.anchor(w, trial))
+        assert np.abs(q - oracle.anchor_normalize(wl.anchor(w, trial))).max() < 1e-7
+        for inv_tau in (1.0, 14.0):
+            s = to_host(bd.civic_score(to_dev(hid), torch.from_numpy(q).cuda(), inv_tau))
+            ref = oracle.score(hid32, q, inv_tau)
+            assert s.shape == ref.shape and np.abs(s - ref).max() <= 2e-5 * inv_tau
 
 
 def test_score_edge_rows_and_strides(bd):
@@ -66,7 +67,7 @@ def test_score_edge_rows_and_strides(bd):
         q = bd.civic_anchor_normalize(rng.standard_normal(dim).astype(np.float32))
         s = to_host(bd.civic_score(to_dev(st), torch.from_numpy(q).cuda(), 2.0))
         ref = oracle.score(x32, q, 2.0)
-        assert s[0] == 0.0 and np.abs(s - ref).max() <= 4e-5
+        assert s[0] == 0.0 and np.abs(s - ref).max() <= 2e-5 * 2.0
     # offsets on both sides of |mean| = standard deviation, where the bf16 kernel changes from its one-pass
     # sums to the centred two passes; magnitudes far from 1; all-zero and constant rows in between
     for dim in (256, 4096):
@@ -104,7 +105,7 @@ def test_score_many_rows_per_wavefront(bd):
         q = bd.civic_anchor_normalize(rng.standard_normal(dim).astype(np.float32))
         s = to_host(bd.civic_score(to_dev(st), torch.from_numpy(q).cuda(), 3.0))
         ref = oracle.score(x32, q, 3.0)
-        assert s[7] == 0.0 and np.isfinite(s).all() and np.abs(s - ref).max() <= 4e-5 * 3.0
+        assert s[7] == 0.0 and np.isfinite(s).all() and np.abs(s - ref).max() <= 2e-5 * 3.0
 
 
 # ---------------------------------------------------------------------------------------- select
@@ -208,7 +209,7 @@ def check_compact(bd, hid, pos, grid, fs, kept):
 @pytest.mark.parametrize("name", list(wl.WORKLOADS))
 def test_compact_matches_oracle_on_workloads(bd, name):
     w = wl.WORKLOADS[name]
-    for trial in range(2):
+    for trial in range(5):
         log("compact", name, trial)
         hid, _ = wl.hidden(w, trial)
         kept, _ = oracle.select(wl.scores(w, trial), w.grid_tuple())
@@ -316,12 +317,61 @@ def check_attn(bd, q, k, v, causal, dtype, row_step=1, scale=0.0):
     assert np.isfinite(got).all() and err <= attn_tol(ref, dtype)
 
 
-@pytest.mark.parametrize("name,row_step", [("tiny", 1), ("2b", 1), ("8b", 7), ("vit", 11), ("video", 61)])
+@pytest.mark.parametrize("name,row_step", [("tiny", 1), ("2b", 1), ("8b", 1), ("vit", 1), ("video", 13)])
 def test_attention_matches_oracle_on_workloads(bd, name, row_step):
+    """Every output row of every head against the oracle, five seeds; the video workload (105 GFLOP in the
+    oracle's scalar loops) on every 13th query row, 276 of 3584, every head."""
     w = wl.WORKLOADS[name]
-    log("attention", name)
-    (q, _), (k, _), (v, _) = wl.qkv(w, 0)
-    check_attn(bd, q, k, v, w.causal, w.dtype, row_step)
+    for trial in range(5):
+        log("attention", name, "trial", trial)
+        (q, _), (k, _), (v, _) = wl.qkv(w, trial)
+        check_attn(bd, q, k, v, w.causal, w.dtype, row_step)
+
+
+def peaked_qkv(rng, b, s, hq, hkv, d, causal, sharp=3.0):
+    """Q, K, V for which every query attends to ONE key, at a random visible position: K ~ N(0,1), V ~ N(0,1)
+    (distinct per key), q_i = sharp * k_j(i).  The matching logit is about sharp * sqrt(d) standard deviations
+    above the others, so out_i = V[j(i)] up to a few percent, at full magnitude: a key tile lost, read from the
+    wrong ring stage or put into the wrong lane changes the output by O(1), not by the softmax average's O(0.03)."""
+    k = rng.standard_normal((b, s, hkv, d)).astype(np.float32)
+    v = rng.standard_normal((b, s, hkv, d)).astype(np.float32)
+    group = hq // hkv
+    q = np.empty((b, s, hq, d), dtype=np.float32)
+    rows = np.arange(s)
+    for bi in range(b):
+        for h in range(hq):
+            hi = np.minimum((rng.random(s) * (rows + 1 if causal else s)).astype(np.int64), rows if causal else s - 1)
+            q[bi, :, h] = sharp * k[bi, hi, h // group]
+    return (wl.quantize(x, "bf16")[0] for x in (q, k, v))
+
+
+# The first four shapes are the sizes that matter (the 8B-shaped workload, 4096 and 20000 tokens, the encoder's
+# head size); the others are causal launches with more workgroups than compute units, where a workgroup walks two
+# row tiles (a heavy and a light one): odd and even numbers of row tiles, a full and a ragged last tile, 2 and 4
+# heads per workgroup, padded heads, and the KV-cache copy in the same launch.
+@pytest.mark.parametrize("shape,row_step", [((4, 938, 32, 8, 128), 1), ((1, 4096, 8, 2, 128), 1), ((1, 1365, 4, 4, 72), 1),
+                                            ((1, 20000, 4, 2, 128), 41), ((4, 896, 32, 8, 128), 1), ((5, 961, 32, 8, 128), 1),
+                                            ((8, 700, 16, 8, 128), 1), ((16, 1100, 12, 4, 96), 1), ((20, 1000, 8, 8, 64), 1),
+                                            ((40, 130, 32, 8, 128), 1), ((3, 2049, 16, 4, 72), 1)])
+@pytest.mark.parametrize("causal", [True, False])
+def test_attention_one_key_per_query(bd, shape, row_step, causal):
+    b, s, hq, hkv, d = shape
+    log("attention, one key per query", shape, "causal", causal)
+    q, k, v = peaked_qkv(np.random.default_rng(s + d), b, s, hq, hkv, d, causal)
+    dq, dk, dv = to_dev(q), to_dev(k), to_dev(v)
+    kc = torch.zeros((b, hkv, s + 2, d), dtype=dq.dtype, device="cuda")
+    vc = torch.zeros_like(kc)
+    out = bd.civic_prefill_attn_kv(dq, dk, dv, kc, vc, 1, causal, 0.0)
+    assert torch.equal(kc[:, :, 1:s + 1], dk.permute(0, 2, 1, 3)) and torch.equal(vc[:, :, 1:s + 1], dv.permute(0, 2, 1, 3))
+    assert not kc[:, :, 0].any() and not kc[:, :, s + 1].any() and not vc[:, :, 0].any() and not vc[:, :, s + 1].any()
+    assert torch.equal(out, bd.civic_prefill_attn(dq, dk, dv, causal, 0.0))
+    out = to_host(out)
+    ref = oracle.attention(widen(q), widen(k), widen(v), causal, row_step=row_step)[:, ::row_step]
+    got = widen(out).astype(np.float64)[:, ::row_step]
+    err = float(np.abs(got - ref).max())
+    log("   max abs err", err, "tol", attn_tol(ref, "bf16"), "mean |ref|", float(np.abs(ref).mean()))
+    assert np.abs(ref).mean() > 0.5                          # the outputs really are single V rows, not averages
+    assert np.isfinite(got).all() and err <= attn_tol(ref, "bf16")
 
 
 @pytest.mark.parametrize("shape", [
@@ -397,17 +447,18 @@ def test_attention_logits_growing_along_the_sequence(bd, causal):
 @pytest.mark.parametrize("name", ["tiny", "2b", "8b", "video"])
 def test_kv_write_matches_oracle(bd, name):
     w = wl.WORKLOADS[name]
-    log("kv_write", name)
-    _, (k, _), (v, _) = wl.qkv(w, 1)
-    seq = k.shape[1]
-    for s_max, pos0 in ((seq, 0), (seq + 37, 21)):
-        fill = 0x7B7B if k.dtype == np.uint16 else 123.0
-        kc = np.full((w.batch, w.n_kv_heads, s_max, w.head_dim), fill, dtype=k.dtype)
-        vc = kc.copy()
-        dk, dv = to_dev(kc), to_dev(vc)
-        bd.civic_kv_write(to_dev(k), to_dev(v), dk, dv, pos0)
-        oracle.kv_write(k, v, kc, vc, pos0)
-        assert np.array_equal(to_host(dk), kc) and np.array_equal(to_host(dv), vc)   # includes the untouched rows
+    for trial in range(5):
+        log("kv_write", name, trial)
+        _, (k, _), (v, _) = wl.qkv(w, trial)
+        seq = k.shape[1]
+        for s_max, pos0 in ((seq, 0), (seq + 37, 21)):
+            fill = 0x7B7B if k.dtype == np.uint16 else 123.0
+            kc = np.full((w.batch, w.n_kv_heads, s_max, w.head_dim), fill, dtype=k.dtype)
+            vc = kc.copy()
+            dk, dv = to_dev(kc), to_dev(vc)
+            bd.civic_kv_write(to_dev(k), to_dev(v), dk, dv, pos0)
+            oracle.kv_write(k, v, kc, vc, pos0)
+            assert np.array_equal(to_host(dk), kc) and np.array_equal(to_host(dv), vc)   # includes the untouched rows
 
 
 @pytest.mark.parametrize("shape,causal,dtype", [
@@ -433,13 +484,16 @@ def test_fused_attention_kv_write_equals_the_two_calls(bd, shape, causal, dtype)
     out2 = bd.civic_prefill_attn_kv(dq, dk, dv, kc2, vc2, pos0, causal)
     assert np.array_equal(to_host(out1), to_host(out2))
     assert np.array_equal(to_host(kc1), to_host(kc2)) and np.array_equal(to_host(vc1), to_host(vc2))
+    ref = oracle.attention(widen(q), widen(k), widen(v), causal)                    # the fused call against the oracle itself
+    err = float(np.abs(widen(to_host(out2)).astype(np.float64) - ref).max())
+    assert err <= attn_tol(ref, dtype), err
     ref_k, ref_v = cache.copy(), cache.copy()
     oracle.kv_write(k, v, ref_k, ref_v, pos0)
     assert np.array_equal(to_host(kc2), ref_k) and np.array_equal(to_host(vc2), ref_v)
 
 
 # -------------------------------------------------------------------------------------- the path
-@pytest.mark.parametrize("name", ["tiny", "2b", "8b", "video"])
+@pytest.mark.parametrize("name", ["tiny", "2b", "8b", "vit", "video"])
 def test_whole_path_chained(bd, name):
     """score -> select -> compact -> attention -> KV write on device, each stage fed by the previous
     one's device output.  Selection parity is defined on a given score array, so the oracle selects on
@@ -476,7 +530,7 @@ def test_whole_path_chained(bd, name):
     r32 = widen(rhc)
     rq = r32.reshape(w.batch, s_c, w.n_q_heads, w.head_dim)
     rkv = r32[:, :, :w.n_kv_heads * w.head_dim].reshape(w.batch, s_c, w.n_kv_heads, w.head_dim)
-    step = 1 if s_c < 600 else 13 if s_c < 2000 else 97
+    step = 1 if s_c < 2000 else 29                        # video: 124 of 3584 query rows, every head
     ref = oracle.attention(rq, rkv, rkv, w.causal, row_step=step)[:, ::step]
     got = widen(to_host(out)).astype(np.float64)[:, ::step]
     assert np.abs(got - ref).max() <= attn_tol(ref, w.dtype)

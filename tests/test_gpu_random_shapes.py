@@ -157,7 +157,7 @@ def test_attention_random_shapes(bd):
             assert torch.equal(vc[:, :, pos0:pos0 + s], vd.permute(0, 2, 1, 3)), (b, s, hq, hkv, d)
         else:
             out = bd.civic_prefill_attn(qd, kd, vd, causal, 0.0)
-        step = 1 if s <= 128 else 3
+        step = 1
         ref = oracle.attention(widen(q), widen(k), widen(v), causal, scale=None, row_step=step)[:, ::step]
         got = widen(to_host(out)).astype(np.float64)[:, ::step]
         err, tol = float(np.abs(got - ref).max()), attn_tol(ref, dtype)
@@ -191,7 +191,7 @@ def test_score_random_rows(bd):
             log("score random", done, dtype, dim, rows, inv_tau)
         s = to_host(bd.civic_score(to_dev(st), torch.from_numpy(q).cuda(), inv_tau))
         ref = oracle.score(x32, q, inv_tau)
-        err, tol = float(np.abs(s - ref).max()), 4e-5 * max(inv_tau, 1.0)
+        err, tol = float(np.abs(s - ref).max()), 2e-5 * inv_tau
         worst = max(worst, err / tol)
         assert np.isfinite(s).all() and err <= tol, (dtype, dim, rows, inv_tau, err)
         if rows > 3:
