@@ -4,20 +4,26 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 8b] [--sets R] [--layers N] [--no-cpu]
 
 A step is one pass of the whole path over one batch of synthetic input already resident in HBM:
-civic_score -> civic_select -> civic_compact -> civic_prefill_attn_kv (attention and the KV-cache
-write of the same K/V as one call; --unfused runs civic_prefill_attn -> civic_kv_write instead),
-back to back on one stream, for one transformer layer.  The timed region runs exactly K steps between device
-synchronisations; `value` is compact-prefill tokens/s = batch * S_c * K / time.  Buffers rotate over
-R independent sets so that consecutive steps do not find their inputs in the last-level cache.
+civic_score_visual (the visual rows scored where they lie in the dense sequence) -> civic_select (on
+the scores just written) -> civic_compact -> civic_prefill_attn_kv (attention and the KV-cache write
+of the same K/V as one call; --unfused runs civic_prefill_attn -> civic_kv_write instead), back to
+back on one stream, for one transformer layer.  Buffers rotate over R independent sets so that
+consecutive steps do not find their inputs in the last-level cache.
+
+Order of a run: an untimed pre-warm of full steps for --prewarm-ms of wall time (the chip's clock
+governor needs tens of milliseconds of load before the clocks settle; reported as `prewarm_ms`), W
+untimed warm-up steps, then exactly K timed steps between device synchronisations: `value` is
+compact-prefill tokens/s = batch * S_c * K / time.
 
 A second pass of the same K steps brackets every stage with HIP events (recorded on the stream the
 kernels run on); `roofline` describes the dominant kernel (the attention) against the MI355X bf16
-MFMA peak from those in-step durations.  A third pass runs every HBM-bound stage alone, K launches
-back to back, for the per-stage figures under `stages` (`us`; `us_in_step` is the event-bracketed
-one, which carries the 2-3 us an event between two short dependent launches costs).  `cpu_baseline` times the CPU oracle, as it stands, on
-a bounded sample of the same workload on this machine's host cores.
-The defaults (500 warm-up steps, 2000 timed) are sized for the chip's clock governor: from idle the
-first ~300 steps (25 ms) run up to 6 % slower than the steady state that follows.
+MFMA peak from those in-step durations.  A third pass times every stage alone as a GPU number: a
+spin kernel holds the stream while --stage-launches launches of the stage are queued behind it, and
+two events bracket them, so the figure under `stages` (`us`) is the kernels' own back-to-back time
+and carries no host launch cost (`us_in_step` is the event-bracketed one, which carries the 2-3 us
+an event between two short dependent launches costs).  `decode` reports the decode-step attention
+over the cache the step has just written (one query per sequence, HBM-bound).  `cpu_baseline` times
+the CPU oracle, as it stands, on a bounded sample of the same workload on this machine's host cores.
 Prints one JSON line.
 """
 from __future__ import annotations
@@ -41,10 +47,21 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 STAGES_FUSED = ("score", "select", "compact", "attn_kv")
 STAGES_UNFUSED = ("score", "select", "compact", "attn", "kv_write")
-# HBM bytes per attention launch from the profiler's FETCH_SIZE / WRITE_SIZE counters, each scaled by what the
-# same counter reads for a plain copy of known size (profiles/bench_8b_hbm_traffic.txt); measured offline,
-# per workload, and only quoted here.
-MEASURED_ATTN_TRAFFIC_BYTES = {("8b", "attn_kv"): 96.74e6, ("8b", "attn"): 78.10e6}
+
+
+def measured_traffic(workload: str, stage: str):
+    """HBM bytes per launch of a stage as the profiler's FETCH_SIZE / WRITE_SIZE counters gave them (scaled by
+    what the same counters read for a copy of known size): the line `traffic_bytes_per_launch <stage> <bytes>`
+    of profiles/bench_<workload>_hbm_traffic.txt, written by the profiled run.  None when no profile says."""
+    path = os.path.join(ROOT, "profiles", f"bench_{workload}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) == 3 and f[0] == "traffic_bytes_per_launch" and f[1] == stage:
+                return float(f[2])
+    except OSError:
+        pass
+    return None
 
 
 def dev(storage: np.ndarray) -> torch.Tensor:
@@ -57,20 +74,16 @@ class BufferSet:
     """Device inputs and outputs of one step (one independent copy per rotation slot)."""
 
     def __init__(self, bd, w: wl.Workload, trial: int):
-        hw = w.height * w.width
-        fs = wl.frame_starts(w)
         hid, _ = wl.hidden(w, trial)
         self.hidden = dev(hid)
-        # the scored rows are the visual rows of the dense sequence, gathered once (input preparation)
-        self.visual = torch.cat([self.hidden[:, s:s + hw] for s in fs], dim=1).contiguous()
         self.pos = torch.from_numpy(wl.position_ids(w)).cuda()
         (q, _), (k, _), (v, _) = wl.qkv(w, trial)
         self.q, self.k, self.v = dev(q), dev(k), dev(v)
         self.anchor_q = torch.from_numpy(bd.civic_anchor_normalize(wl.anchor(w, trial))).cuda()
         b, sc = w.batch, w.seq_compact
         dt = self.hidden.dtype
-        # civic_select is measured on the workload's own score distribution; civic_score writes its
-        # logits into a separate buffer of the same shape
+        # in a step civic_select reads what civic_score_visual has just written; the workload's own score
+        # distribution (scores_in) is what the selection is timed on when it runs alone
         self.scores_in = torch.from_numpy(wl.scores(w, trial)).cuda()
         self.scores = torch.empty((b, w.n_visual), dtype=torch.float32, device="cuda")
         self.kept = torch.empty((b, w.kept), dtype=torch.int32, device="cuda")
@@ -86,9 +99,12 @@ def make_stage_calls(bd, w: wl.Workload, fs):
     grid = bd.make_grid(w.grid_tuple())
 
     def score(s):
-        bd.civic_score(s.visual, s.anchor_q, 1.0, scores=s.scores)
+        bd.civic_score_visual(s.hidden, grid, fs, s.anchor_q, 1.0, scores=s.scores)
 
     def select(s):
+        bd.civic_select(s.scores, grid, kept_idx=s.kept)
+
+    def select_dist(s):
         bd.civic_select(s.scores_in, grid, kept_idx=s.kept)
 
     def compact(s):
@@ -103,7 +119,8 @@ def make_stage_calls(bd, w: wl.Workload, fs):
     def attn_kv(s):
         bd.civic_prefill_attn_kv(s.q, s.k, s.v, s.k_cache, s.v_cache, 0, w.causal, 0.0, out=s.out)
 
-    return dict(score=score, select=select, compact=compact, attn=attn, kv_write=kv_write, attn_kv=attn_kv)
+    return dict(score=score, select=select, select_dist=select_dist, compact=compact, attn=attn, kv_write=kv_write,
+                attn_kv=attn_kv)
 
 
 def algorithmic_work(w: wl.Workload) -> dict:
@@ -131,12 +148,12 @@ def cpu_baseline(w: wl.Workload, target_seconds: float = 20.0) -> dict:
     hid, hid32 = wl.hidden(w, 0)
     vis32 = np.ascontiguousarray(np.concatenate([hid32[:, s:s + hw] for s in fs], axis=1).reshape(-1, w.dim))
     q_anchor = oracle.anchor_normalize(wl.anchor(w, 0)).astype(np.float32)
-    sc_in = wl.scores(w, 0)
     pos = wl.position_ids(w)
     (q, q32), (k, k32), (v, v32) = wl.qkv(w, 0)
     t = {}
-    t0 = time.perf_counter(); oracle.score(vis32, q_anchor, 1.0); t["score"] = time.perf_counter() - t0
-    t0 = time.perf_counter(); kept, _ = oracle.select(sc_in, grid); t["select"] = time.perf_counter() - t0
+    t0 = time.perf_counter(); sc = oracle.score(vis32, q_anchor, 1.0); t["score"] = time.perf_counter() - t0
+    sc = sc.reshape(w.batch, w.n_visual)                   # the selection reads the scores just computed, as on the GPU
+    t0 = time.perf_counter(); kept, _ = oracle.select(sc, grid); t["select"] = time.perf_counter() - t0
     t0 = time.perf_counter(); oracle.compact(hid, pos, grid, fs, kept); t["compact"] = time.perf_counter() - t0
     # choose the attention sample from a short probe so the whole leg stays near target_seconds
     t0 = time.perf_counter(); oracle.attention(q32, k32, v32, w.causal, row_step=256); probe = time.perf_counter() - t0
@@ -159,8 +176,8 @@ def cpu_baseline(w: wl.Workload, target_seconds: float = 20.0) -> dict:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=500)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="8b", choices=list(wl.WORKLOADS))
     ap.add_argument("--sets", type=int, default=4, help="independent buffer sets rotated through (1 = warm cache)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
@@ -168,6 +185,10 @@ def main() -> int:
                     help="transformer layers N_l of the amortised figure: score, select and compact once, attention and "
                          "KV write per layer (28 = the layer count the paper's Table 1 KV sizes imply for its 2B model)")
     ap.add_argument("--unfused", action="store_true", help="attention and KV write as two calls")
+    ap.add_argument("--prewarm-ms", type=float, default=150.0,
+                    help="untimed full steps for this much wall time ahead of --warmup (0 = none)")
+    ap.add_argument("--stage-launches", type=int, default=200,
+                    help="launches per stage of the stage-alone pass (queued behind a spin kernel, bracketed by two events)")
     ap.add_argument("--calibrate", action="store_true",
                     help="run only a device-to-device copy of 256 MiB (the known-size kernel the HBM byte counters "
                          "of a profiler run are scaled by) and exit")
@@ -203,6 +224,14 @@ def main() -> int:
         for c in order:
             c(s)
 
+    # untimed pre-warm by wall time: the clocks settle under load, whatever --warmup and --steps are
+    prewarm_steps, t_pre = 0, time.perf_counter()
+    while (time.perf_counter() - t_pre) * 1e3 < args.prewarm_ms:
+        for _ in range(20):
+            step(prewarm_steps)
+            prewarm_steps += 1
+        torch.cuda.synchronize()
+    prewarm_ms = (time.perf_counter() - t_pre) * 1e3
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -228,22 +257,37 @@ def main() -> int:
         d = np.asarray([ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(args.steps)]) * 1e3
         stage_us[name] = {"mean": float(d.mean()), "median": float(np.median(d)), "min": float(d.min())}
 
-    # third pass: every stage alone, K launches back to back over the rotating buffer sets between two events.
-    # An event between two dependent launches costs 2-3 us of its own (the in-step figures above carry it);
-    # back to back the average is the kernel's own duration, which is what the profiler reports.
-    for j, name in enumerate(STAGES):
-        if name in ("attn", "attn_kv"):
-            # 50 us of MFMA work hides the event's cost (in-step time = profiler time), and attention launches
-            # back to back run slower than in a step (the chip holds a lower clock under sustained MFMA load)
-            stage_us[name]["alone"] = stage_us[name]["mean"]
-            continue
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for i in range(args.steps):
-            order[j](sets[i % len(sets)])
-        e1.record()
+    # third pass: every stage alone as a GPU number.  A spin kernel occupies the stream while the host queues
+    # the launches behind it, so that the two events bracket kernels that start back to back, without the
+    # ~8 us of host time a launch from Python costs; the average is the kernel's duration plus the gap the
+    # hardware leaves between two dependent launches.
+    spin_cycles = 1_000_000
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(); torch.cuda._sleep(spin_cycles); e1.record(); torch.cuda.synchronize()
+    spin_ms = max(e0.elapsed_time(e1), 1e-3)
+    n_alone = max(1, args.stage_launches)
+    hold_cycles = int(spin_cycles * (n_alone * 0.012 + 1.0) / spin_ms)     # 12 us of host time per launch, and 1 ms
+
+    def alone(call):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
-        stage_us[name]["alone"] = e0.elapsed_time(e1) * 1e3 / args.steps
+        torch.cuda._sleep(hold_cycles)
+        a.record()
+        for i in range(n_alone):
+            call(sets[i % len(sets)])
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e3 / n_alone
+
+    for name in STAGES:
+        if name in ("attn", "attn_kv"):
+            # attention launches back to back run slower than in a step (the chip holds a lower clock under
+            # sustained MFMA load), and 40 us of MFMA work hides the event's cost: the in-step time is the kernel time
+            stage_us[name]["alone"] = stage_us[name]["mean"]
+            stage_us[name]["back_to_back"] = alone(calls[name])
+            continue
+        stage_us[name]["alone"] = alone(calls[name])
+    select_dist_us = alone(calls["select_dist"])
 
     work = algorithmic_work(w)
     stages = {}
@@ -251,6 +295,8 @@ def main() -> int:
         us = stage_us[name]["alone"]
         entry = {"us": round(us, 2), "us_in_step": round(stage_us[name]["mean"], 2),
                  "us_in_step_median": round(stage_us[name]["median"], 2)}
+        if "back_to_back" in stage_us[name]:
+            entry["us_back_to_back"] = round(stage_us[name]["back_to_back"], 2)
         if name in ("attn", "attn_kv"):
             tf = work["attn_flops"] / (us * 1e-6) / 1e12
             entry.update(tflops=round(tf, 1), frac_mfma_peak=round(tf / MFMA_BF16_PEAK_TFLOPS, 4))
@@ -260,6 +306,7 @@ def main() -> int:
             gbs = work[name] / (us * 1e-6) / 1e9
             entry.update(gbs=round(gbs, 1), frac_hbm_peak=round(gbs / HBM_PEAK_GBS, 4))
         stages[name] = entry
+    stages["select"]["us_on_workload_scores"] = round(select_dist_us, 2)   # the configuration's own score distribution
     sg = (work["select"] + work["compact"]) / ((stage_us["select"]["alone"] + stage_us["compact"]["alone"]) * 1e-6) / 1e9
     stages["select+compact"] = {"gbs": round(sg, 1), "frac_hbm_peak": round(sg / HBM_PEAK_GBS, 4)}
 
@@ -269,7 +316,7 @@ def main() -> int:
     if w.dtype == "bf16":
         roofline = {"bound": "mfma", "kernel": f"attn_mfma_kernel (civic_prefill_{attn_name})", "achieved": round(attn_tf, 2),
                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(attn_tf / MFMA_BF16_PEAK_TFLOPS, 4),
-                    "traffic": MEASURED_ATTN_TRAFFIC_BYTES.get((w.name, attn_name)), "launch_us": round(attn_us, 2), "flops_per_launch": work["attn_flops"]}
+                    "traffic": measured_traffic(w.name, attn_name), "launch_us": round(attn_us, 2), "flops_per_launch": work["attn_flops"]}
     else:
         roofline = {"bound": "alu", "kernel": f"attn_plain_kernel (civic_prefill_{attn_name})", "achieved": round(attn_tf, 3),
                     "peak": 157.3, "unit": "TFLOP/s", "frac": round(attn_tf / 157.3, 5), "traffic": None,
@@ -277,14 +324,15 @@ def main() -> int:
 
     result = {
         "metric": "compact-prefill tokens/s", "value": round(tokens / (ms_per_step * 1e-3), 1), "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "prewarm_ms": round(prewarm_ms, 1),
+        "prewarm_steps": prewarm_steps, "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": f"Qwen3-VL-{w.name}-shaped" if w.name in ("2b", "8b") else w.name,
                    "batch": w.batch, "seq_dense": w.seq_len, "seq_compact": w.seq_compact, "visual_tokens": w.n_visual,
                    "kept_visual": w.kept, "hidden": w.dim, "heads": f"{w.n_q_heads}q/{w.n_kv_heads}kv x {w.head_dim}",
                    "causal": w.causal, "layers_timed": 1, "buffer_sets": len(sets),
-                   "calls": "+".join(STAGES)},
+                   "calls": "+".join(STAGES).replace("score", "score_visual"), "stage_launches": n_alone},
         "dense_equivalent_tokens_per_s": round(w.batch * w.seq_len / (ms_per_step * 1e-3), 1),
         "stages": stages,
         "roofline": roofline,

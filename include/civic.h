@@ -3,7 +3,8 @@
  * inference for vision-language models) for AMD MI355X (gfx950).
  *
  * The path, in call order:
- *   civic_score        per visual token, the anchor logit of Eq. 8
+ *   civic_score        per visual token, the anchor logit of Eq. 8 (civic_score_visual: the same on
+ *                      the frame spans of the dense sequence, in place)
  *   civic_select       kept set under a global token budget and spatial retention floors
  *   civic_compact      Merge of Eq. 13: one contiguous, order-preserving sequence with the
  *                      position ids carried along (sentence after Eq. 14)
@@ -28,7 +29,8 @@
  *   - A tensor pointer may be NULL when the tensor it names has no elements (no rows, an
  *     empty batch, nothing kept and no text); otherwise NULL is CIVIC_ERR_INVALID_ARG.
  *   - dtype: CIVIC_F32 (4-byte IEEE) or CIVIC_BF16 (2-byte bfloat16).
- *   - Re-entrant; no global mutable state except the last HIP error code.
+ *   - Re-entrant.  Global mutable state: the last HIP error code, and per kernel and device one flag
+ *     that its dynamic LDS limit has been raised (set once, never cleared).
  */
 #ifndef CIVIC_H
 #define CIVIC_H
@@ -110,6 +112,20 @@ int civic_anchor_normalize(const float* anchor /* host [dim] */, int32_t dim,
  * it for fp32); hidden and row_stride*sizeof(element) must be 16-byte aligned. */
 int civic_score(const void* hidden, int dtype, int64_t n_rows, int64_t row_stride, int32_t dim,
                 const float* anchor_q, float inv_tau, float* scores, void* stream);
+
+/* civic_score on the visual tokens where they lie: frame f of batch item b occupies rows
+ * [frame_start[f], frame_start[f] + height*width) of that item's dense sequence (the "dense visual
+ * placeholder spans" that Eq. 13 merges from), with text rows in between, so the visual rows are not at
+ * one uniform stride and a single civic_score call cannot address them.  One launch scores them all:
+ * scores[b, f*height*width + t] is the civic_score value of row frame_start[f] + t of item b.
+ *   hidden      device [batch, seq_len, dim] of `dtype`, dense
+ *   frame_start host [grid->frames] int64, ascending, spans inside [0, seq_len), disjoint
+ *   scores      device [batch, N_v] fp32, N_v = frames*height*width
+ * Arithmetic, accuracy and dim limits are civic_score's; grid->frames <= CIVIC_MAX_FRAMES,
+ * batch * frames <= 65535, seq_len < 2^31. */
+int civic_score_visual(const void* hidden, int dtype, int32_t batch, int64_t seq_len, int32_t dim,
+                       const civic_grid* grid /* host */, const int64_t* frame_start /* host */,
+                       const float* anchor_q, float inv_tau, float* scores, void* stream);
 
 /* Token selection.  With the strict order "higher score first, equal scores (IEEE ==, so
  * -0 equals +0) to the lower index", per sample:

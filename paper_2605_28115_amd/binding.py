@@ -21,7 +21,7 @@ CIVIC_F32, CIVIC_BF16 = 0, 1
 MAX_VISUAL_TOKENS, MAX_FRAMES, MAX_SCORE_DIM, MAX_HEAD_DIM = 32768, 128, 8192, 256
 
 EXPORTS = ("civic_last_hip_error", "civic_kept_count", "civic_select_workspace_bytes",
-           "civic_compact_workspace_bytes", "civic_anchor_normalize", "civic_score", "civic_select",
+           "civic_compact_workspace_bytes", "civic_anchor_normalize", "civic_score", "civic_score_visual", "civic_select",
            "civic_compact", "civic_prefill_attn", "civic_kv_write", "civic_prefill_attn_kv")
 
 
@@ -59,6 +59,8 @@ lib.civic_anchor_normalize.restype = C.c_int
 lib.civic_anchor_normalize.argtypes = [_P, C.c_int32, _P]
 lib.civic_score.restype = C.c_int
 lib.civic_score.argtypes = [_P, C.c_int, C.c_int64, C.c_int64, C.c_int32, _P, C.c_float, _P, _P]
+lib.civic_score_visual.restype = C.c_int
+lib.civic_score_visual.argtypes = [_P, C.c_int, C.c_int32, C.c_int64, C.c_int32, C.POINTER(Grid), _P, _P, C.c_float, _P, _P]
 lib.civic_select.restype = C.c_int
 lib.civic_select.argtypes = [_P, C.c_int32, C.POINTER(Grid), _P, _P, _P, C.c_size_t, _P]
 lib.civic_compact.restype = C.c_int
@@ -147,6 +149,24 @@ def civic_score(hidden: torch.Tensor, anchor_q: torch.Tensor, inv_tau: float = 1
         scores = torch.empty(hidden.shape[:-1], dtype=torch.float32, device=hidden.device)
     _check("civic_score", lib.civic_score(_dev(rows), _dtype_code(rows), rows.shape[0], rows.stride(0), dim,
                                           _dev(anchor_q), float(inv_tau), _dev(scores), _stream(stream)))
+    return scores
+
+
+def civic_score_visual(hidden: torch.Tensor, grid, frame_start: Sequence[int], anchor_q: torch.Tensor, inv_tau: float = 1.0,
+                       scores: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """hidden [batch, S, dim] contiguous; the frames' rows are scored where they lie -> fp32 scores [batch, N_v]."""
+    g = make_grid(grid)
+    if hidden.dim() != 3 or not hidden.is_contiguous():
+        raise ValueError("hidden must be contiguous [batch, S, dim]")
+    batch, seq_len, dim = hidden.shape
+    fs = np.ascontiguousarray(np.asarray(frame_start, dtype=np.int64))
+    if fs.shape != (g.frames,):
+        raise ValueError("frame_start must have one entry per frame")
+    if scores is None:
+        scores = torch.empty((batch, g.n_visual), dtype=torch.float32, device=hidden.device)
+    _check("civic_score_visual", lib.civic_score_visual(_dev(hidden), _dtype_code(hidden), batch, seq_len, dim, C.byref(g),
+                                                        C.c_void_p(fs.ctypes.data), _dev(anchor_q), float(inv_tau),
+                                                        _dev(scores), _stream(stream)))
     return scores
 
 

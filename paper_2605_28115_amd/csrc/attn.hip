@@ -881,6 +881,9 @@ static int prefill_attn(const void* q, const void* k, const void* v, void* out, 
         if (2 * per_rt * a.row_tiles > kComputeUnits || !mfma_geometry<4>(a, &per_rt)) return launch_mfma_for<8>(a, s);
         return launch_mfma_for<4>(a, s);
     }
+    // (the limit of the separate KV-write launch that follows, checked before anything is launched)
+    if (k_cache && static_cast<int64_t>(seq) * n_kv_heads * (static_cast<int64_t>(head_dim) * esz / 16) > INT32_MAX)
+        return CIVIC_ERR_UNSUPPORTED;
     const dim3 grid(static_cast<unsigned>((seq + 3) / 4), static_cast<unsigned>(n_q_heads), static_cast<unsigned>(batch));
     if (dtype == CIVIC_BF16) hipLaunchKernelGGL((attn_plain_kernel<true>), grid, dim3(256), 0, s, a);
     else hipLaunchKernelGGL((attn_plain_kernel<false>), grid, dim3(256), 0, s, a);

@@ -51,12 +51,36 @@ constexpr int kScoreBlocksPerCu = CIVIC_SCORE_BLOCKS_PER_CU;
 #endif
 constexpr int kScoreWavesPerSimd = CIVIC_SCORE_WAVES_PER_SIMD;   // register budget of the bf16 kernel: 512 / this
 
+// Where the rows of a launch live.  PlainRows: n_rows rows at a uniform stride from `hidden` (grid y = 1).
+// SpanRows (civic_score_visual): grid y runs over (batch item, frame); a block scores rows of ONE frame span
+// of the dense sequence, so all it needs is that span's first row, found once per block, and the kernels below
+// stay what they are: a uniform-stride walk over n_rows = height * width rows.
+struct PlainRows {
+    static constexpr bool kSpans = false;
+};
+struct SpanRows {
+    static constexpr bool kSpans = true;
+    int32_t frames;                     // per sample
+    int32_t hw;                         // tokens per frame
+    int64_t seq_len;                    // rows per sample in the dense sequence
+    int32_t start[CIVIC_MAX_FRAMES];    // sequence index of each frame's first token
+    __device__ __forceinline__ int64_t first_row(uint32_t y) const
+    {
+        const uint32_t b = y / static_cast<uint32_t>(frames), f = y - b * static_cast<uint32_t>(frames);
+        return static_cast<int64_t>(b) * seq_len + start[f];
+    }
+};
+
 // fp32 rows: two passes over a row held in registers.
-template <int CHUNKS>
+template <int CHUNKS, typename MAP>
 __global__ __launch_bounds__(kScoreThreads, kScoreBlocksPerCu) void score_f32_kernel(
     const uint8_t* __restrict__ hidden, int64_t n_rows, int64_t row_stride_bytes, int32_t dim,
-    const float* __restrict__ anchor_q, float inv_tau, float* __restrict__ scores)
+    const float* __restrict__ anchor_q, float inv_tau, float* __restrict__ scores, MAP map)
 {
+    if constexpr (MAP::kSpans) {
+        hidden += map.first_row(blockIdx.y) * row_stride_bytes;
+        scores += static_cast<int64_t>(blockIdx.y) * map.hw;
+    }
     constexpr int E = 4;
     extern __shared__ __attribute__((aligned(16))) float q_s[];      // [dim]
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
@@ -123,11 +147,15 @@ __global__ __launch_bounds__(kScoreThreads, kScoreBlocksPerCu) void score_f32_ke
 
 // bf16 rows, one pass on packed words (see the file header).  LDS: q_hi[dim/2] and q_lo[dim/2] words
 // (element pairs packed like the row's own words), then the per-wave partial sums of q.
-template <int CHUNKS>
+template <int CHUNKS, typename MAP>
 __global__ __launch_bounds__(kScoreThreads, kScoreWavesPerSimd) void score_bf16_kernel(
     const uint8_t* __restrict__ hidden, int64_t n_rows, int64_t row_stride_bytes, int32_t dim,
-    const float* __restrict__ anchor_q, float inv_tau, float* __restrict__ scores)
+    const float* __restrict__ anchor_q, float inv_tau, float* __restrict__ scores, MAP map)
 {
+    if constexpr (MAP::kSpans) {
+        hidden += map.first_row(blockIdx.y) * row_stride_bytes;
+        scores += static_cast<int64_t>(blockIdx.y) * map.hw;
+    }
     constexpr int kWaves = kScoreThreads / kWave;
     extern __shared__ __attribute__((aligned(16))) uint32_t q_w[];
     uint32_t* q_hi = q_w;
@@ -246,25 +274,49 @@ __global__ __launch_bounds__(kScoreThreads, kScoreWavesPerSimd) void score_bf16_
     }
 }
 
-template <int CHUNKS>
-static int launch_score(bool bf16, const void* hidden, int64_t n_rows, int64_t row_stride_bytes, int32_t dim,
-                        const float* anchor_q, float inv_tau, float* scores, hipStream_t stream)
+// n_rows rows per grid-y slice (`slices` of them: 1 for a plain call, batch * frames for the spans of a dense
+// sequence).
+template <int CHUNKS, typename MAP>
+static int launch_score(bool bf16, const void* hidden, int64_t n_rows, int64_t slices, int64_t row_stride_bytes, int32_t dim,
+                        const float* anchor_q, float inv_tau, float* scores, const MAP& map, hipStream_t stream)
 {
     // Two 8-wave blocks per CU on 256 CUs; a wavefront loops over its rows with the next row's loads in
     // flight while the current one is reduced, so the vector work overlaps the stream from HBM.
     constexpr int rows_per_block = kScoreThreads / kWave;
     int64_t blocks = (n_rows + rows_per_block - 1) / rows_per_block;
-    if (blocks > 256 * kScoreBlocksPerCu) blocks = 256 * kScoreBlocksPerCu;
+    int64_t cap = 256 * kScoreBlocksPerCu / slices;
+    if (cap < 1) cap = 1;
+    if (blocks > cap) blocks = cap;
     const uint8_t* h = static_cast<const uint8_t*>(hidden);
     const size_t lds = sizeof(float) * static_cast<size_t>(dim);
+    const dim3 grid(static_cast<unsigned>(blocks), static_cast<unsigned>(slices));
     if (bf16)
-        hipLaunchKernelGGL((score_bf16_kernel<CHUNKS>), dim3(static_cast<unsigned>(blocks)), dim3(kScoreThreads),
+        hipLaunchKernelGGL((score_bf16_kernel<CHUNKS, MAP>), grid, dim3(kScoreThreads),
                            lds + sizeof(float) * rows_per_block, stream, h, n_rows, row_stride_bytes, dim, anchor_q,
-                           inv_tau, scores);
+                           inv_tau, scores, map);
     else
-        hipLaunchKernelGGL((score_f32_kernel<CHUNKS>), dim3(static_cast<unsigned>(blocks)), dim3(kScoreThreads), lds,
-                           stream, h, n_rows, row_stride_bytes, dim, anchor_q, inv_tau, scores);
+        hipLaunchKernelGGL((score_f32_kernel<CHUNKS, MAP>), grid, dim3(kScoreThreads), lds,
+                           stream, h, n_rows, row_stride_bytes, dim, anchor_q, inv_tau, scores, map);
     return check_launch();
+}
+
+// Shared by civic_score and civic_score_visual once their own arguments are checked.
+template <typename MAP>
+static int score_rows(const void* hidden, int dtype, int64_t n_rows, int64_t slices, int64_t row_stride, int32_t dim,
+                      const float* anchor_q, float inv_tau, float* scores, const MAP& map, void* stream)
+{
+    const int esz = dtype_size(dtype);
+    const int elems = 16 / esz;
+    const int chunks = (dim / elems + kWave - 1) / kWave;   // 16-byte chunks per lane
+    const bool bf16 = dtype == CIVIC_BF16;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t rsb = row_stride * esz;
+#define CIVIC_SCORE_CASE(N) \
+    if (chunks <= N) return launch_score<N, MAP>(bf16, hidden, n_rows, slices, rsb, dim, anchor_q, inv_tau, scores, map, s)
+    CIVIC_SCORE_CASE(1); CIVIC_SCORE_CASE(2); CIVIC_SCORE_CASE(3); CIVIC_SCORE_CASE(4);
+    CIVIC_SCORE_CASE(6); CIVIC_SCORE_CASE(8); CIVIC_SCORE_CASE(12); CIVIC_SCORE_CASE(16);
+#undef CIVIC_SCORE_CASE
+    return CIVIC_ERR_UNSUPPORTED;
 }
 
 }  // namespace civic
@@ -284,14 +336,35 @@ extern "C" int civic_score(const void* hidden, int dtype, int64_t n_rows, int64_
     if (static_cast<int64_t>(dim) * esz > static_cast<int64_t>(CIVIC_MAX_SCORE_DIM) * 2) return CIVIC_ERR_UNSUPPORTED;
     if (n_rows == 0) return CIVIC_OK;
 
-    const int chunks = (dim / elems + kWave - 1) / kWave;   // 16-byte chunks per lane
-    const bool bf16 = dtype == CIVIC_BF16;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const int64_t rsb = row_stride * esz;
-#define CIVIC_SCORE_CASE(N) \
-    if (chunks <= N) return launch_score<N>(bf16, hidden, n_rows, rsb, dim, anchor_q, inv_tau, scores, s)
-    CIVIC_SCORE_CASE(1); CIVIC_SCORE_CASE(2); CIVIC_SCORE_CASE(3); CIVIC_SCORE_CASE(4);
-    CIVIC_SCORE_CASE(6); CIVIC_SCORE_CASE(8); CIVIC_SCORE_CASE(12); CIVIC_SCORE_CASE(16);
-#undef CIVIC_SCORE_CASE
-    return CIVIC_ERR_UNSUPPORTED;
+    return score_rows(hidden, dtype, n_rows, 1, row_stride, dim, anchor_q, inv_tau, scores, PlainRows{}, stream);
+}
+
+extern "C" int civic_score_visual(const void* hidden, int dtype, int32_t batch, int64_t seq_len, int32_t dim,
+                                  const civic_grid* grid, const int64_t* frame_start, const float* anchor_q,
+                                  float inv_tau, float* scores, void* stream)
+{
+    using namespace civic;
+    const int esz = dtype_size(dtype);
+    GridInfo gi;
+    if (grid_info(grid, &gi) != CIVIC_OK) return CIVIC_ERR_INVALID_ARG;
+    if (!esz || !anchor_q || !frame_start) return CIVIC_ERR_INVALID_ARG;
+    if (batch < 0 || dim <= 0 || seq_len < gi.nv) return CIVIC_ERR_INVALID_ARG;
+    if (batch > 0 && (!hidden || !scores)) return CIVIC_ERR_INVALID_ARG;
+    int64_t prev_end = 0;
+    for (int32_t f = 0; f < gi.frames; ++f) {
+        if (frame_start[f] < prev_end || frame_start[f] + gi.hw > seq_len) return CIVIC_ERR_INVALID_ARG;
+        prev_end = frame_start[f] + gi.hw;
+    }
+    const int elems = 16 / esz;
+    if (dim % elems) return CIVIC_ERR_INVALID_ARG;
+    if (!aligned16(hidden) || !aligned16(anchor_q)) return CIVIC_ERR_INVALID_ARG;
+    if (!(inv_tau == inv_tau)) return CIVIC_ERR_INVALID_ARG;
+    if (static_cast<int64_t>(dim) * esz > static_cast<int64_t>(CIVIC_MAX_SCORE_DIM) * 2) return CIVIC_ERR_UNSUPPORTED;
+    const int64_t slices = static_cast<int64_t>(batch) * gi.frames;
+    if (gi.frames > CIVIC_MAX_FRAMES || seq_len > INT32_MAX || slices > 65535) return CIVIC_ERR_UNSUPPORTED;
+    if (batch == 0) return CIVIC_OK;
+    SpanRows map;
+    map.frames = gi.frames; map.hw = gi.hw; map.seq_len = seq_len;
+    for (int32_t f = 0; f < CIVIC_MAX_FRAMES; ++f) map.start[f] = f < gi.frames ? static_cast<int32_t>(frame_start[f]) : 0;
+    return score_rows(hidden, dtype, gi.hw, slices, dim, dim, anchor_q, inv_tau, scores, map, stream);
 }

@@ -94,6 +94,19 @@ def test_argument_errors_precede_any_hip_call(bd):
     assert L.civic_score(F, 1, -1, 64, 64, F, 1.0, F, None) == I
     assert L.civic_score(F, 1, 4, 16384, 16384, F, 1.0, F, None) == bd.ERR_UNSUPPORTED
     assert L.civic_score(F, 1, 0, 64, 64, F, 1.0, F, None) == bd.CIVIC_OK          # nothing to do
+    # civic_score_visual: the same checks plus the frame spans
+    def score_vis(fs, seq_len=40, grid=g, hidden=F, dim=64, batch=1, dt=1, scores=F, anchor=F):
+        arr = np.asarray(fs, dtype=np.int64)
+        return L.civic_score_visual(hidden, dt, batch, seq_len, dim, C.byref(grid), C.c_void_p(arr.ctypes.data), anchor,
+                                    C.c_float(1.0), scores, None)
+    assert score_vis([30]) == I and score_vis([-1]) == I and score_vis([0], seq_len=15) == I
+    assert score_vis([0], hidden=None) == I and score_vis([0], hidden=odd) == I and score_vis([0], dim=60) == I
+    assert score_vis([0], dt=5) == I and score_vis([0], scores=None) == I and score_vis([0], anchor=None) == I
+    assert score_vis([0], batch=-1) == I and score_vis([0], batch=0, hidden=None, scores=None) == bd.CIVIC_OK
+    assert score_vis([0], dim=16384) == bd.ERR_UNSUPPORTED and score_vis([0], batch=70000) == bd.ERR_UNSUPPORTED
+    two = bd.make_grid((2, 4, 4, 2, 2, 1, 0, 5))
+    assert score_vis([0, 8], grid=two) == I and score_vis([20, 0], grid=two) == I
+    assert L.civic_score_visual(F, 1, 1, 40, 64, C.byref(g), None, F, C.c_float(1.0), F, None) == I
     # civic_select: null scores / output, too many tokens
     assert L.civic_select(None, 1, C.byref(g), F, None, None, 0, None) == I
     assert L.civic_select(F, 1, C.byref(g), None, None, None, 0, None) == I

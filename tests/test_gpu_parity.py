@@ -92,6 +92,54 @@ def test_score_edge_rows_and_strides(bd):
     assert np.abs(s - oracle.score(np.ascontiguousarray(x32[:, 64:128]), q, 1.0)).max() <= 2e-5
 
 
+@pytest.mark.parametrize("name", list(wl.WORKLOADS))
+def test_score_visual_scores_the_frame_spans_in_place(bd, name):
+    """civic_score_visual on the dense sequence against the oracle on the gathered visual rows, and bit for bit
+    against civic_score on the same rows gathered by hand (same kernel, same order of summation)."""
+    w = wl.WORKLOADS[name]
+    fs, grid, hw = wl.frame_starts(w), w.grid_tuple(), w.height * w.width
+    for trial in (0, 3):
+        log("score_visual", name, trial)
+        hid, hid32 = wl.hidden(w, trial)
+        d_hid = to_dev(hid)
+        q = bd.civic_anchor_normalize(wl.anchor(w, trial))
+        dq = torch.from_numpy(q).cuda()
+        s = bd.civic_score_visual(d_hid, grid, fs, dq, 2.0)
+        vis = torch.cat([d_hid[:, f:f + hw] for f in fs], dim=1).contiguous()
+        assert torch.equal(s, bd.civic_score(vis, dq, 2.0))
+        vis32 = np.concatenate([hid32[:, f:f + hw] for f in fs], axis=1).reshape(-1, w.dim)
+        ref = oracle.score(vis32, q, 2.0).reshape(w.batch, -1)
+        assert s.shape == ref.shape and np.abs(to_host(s) - ref).max() <= 2e-5 * 2.0
+
+
+def test_score_visual_scattered_frames(bd):
+    # frames separated by text of every length, a frame at row 0 and one ending at the last row; more (batch, frame)
+    # slices than blocks fit; rows that take the centred two-pass branch
+    rng = np.random.default_rng(12)
+    for frames, h, wd, dim, batch, dtype in ((5, 3, 4, 64, 3, "bf16"), (128, 2, 2, 8, 2, "bf16"), (7, 9, 5, 260, 2, "fp32"),
+                                             (3, 40, 40, 1152, 40, "bf16")):
+        hw = h * wd
+        gaps = rng.integers(0, 9, frames + 1)
+        gaps[0] = 0
+        gaps[-1] = 0
+        fs, t = [], 0
+        for f in range(frames):
+            t += int(gaps[f])
+            fs.append(t)
+            t += hw
+        seq = t
+        log("score_visual scattered", frames, h, wd, dim, batch, dtype, "seq", seq)
+        x = rng.standard_normal((batch, seq, dim)).astype(np.float32)
+        x[:, ::5] += 4.0
+        st, x32 = wl.quantize(x, dtype)
+        q = bd.civic_anchor_normalize(rng.standard_normal(dim).astype(np.float32))
+        grid = (frames, h, wd, 2, 2, 0, 0, 0)
+        s = to_host(bd.civic_score_visual(to_dev(st), grid, fs, torch.from_numpy(q).cuda(), 1.0))
+        vis32 = np.concatenate([x32[:, f:f + hw] for f in fs], axis=1).reshape(-1, dim)
+        ref = oracle.score(vis32, q, 1.0).reshape(batch, -1)
+        assert s.shape == ref.shape and np.abs(s - ref).max() <= 2e-5
+
+
 def test_score_many_rows_per_wavefront(bd):
     # Far more rows than resident wavefronts (4096): every wavefront walks a dozen rows, refilling its registers
     # with the next row while it reduces the current one; a third of the rows take the centred two-pass branch.
@@ -506,8 +554,7 @@ def test_whole_path_chained(bd, name):
     hw = w.height * w.width
     d_hid = to_dev(hid)
     q_anchor = bd.civic_anchor_normalize(wl.anchor(w, 4))
-    vis = torch.cat([d_hid[:, s:s + hw] for s in fs], dim=1).contiguous()          # [batch, N_v, dim]
-    scores = bd.civic_score(vis, torch.from_numpy(q_anchor).cuda(), 1.0)
+    scores = bd.civic_score_visual(d_hid, grid, fs, torch.from_numpy(q_anchor).cuda(), 1.0)   # on the dense sequence, in place
     kept, _ = bd.civic_select(scores, grid)
     hc, pc, si = bd.civic_compact(d_hid, torch.from_numpy(pos).cuda(), grid, fs, kept)
     s_c = hc.shape[1]
