@@ -59,6 +59,9 @@ def lib() -> C.CDLL:
         L.oracle_kv_write.restype = C.c_int64
         L.oracle_kv_write.argtypes = [P, P, P, P, P, C.c_int32, C.c_int32, C.c_int32, C.c_int64,
                                       C.c_int64, C.c_int64]
+        L.oracle_decode_attention.restype = None
+        L.oracle_decode_attention.argtypes = [P, P, P, P, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int64,
+                                              C.c_int64, C.c_double]
         _lib = L
     return _lib
 
@@ -176,3 +179,20 @@ def kv_write(k: np.ndarray, v: np.ndarray, k_cache: np.ndarray, v_cache: np.ndar
     st = np.asarray(k.strides[:3], dtype=np.int64)
     return int(lib().oracle_kv_write(_ptr(k), _ptr(v), _ptr(st), _ptr(k_cache), _ptr(v_cache), batch, seq, hkv,
                                      d * k.dtype.itemsize, s_max, int(pos0)))
+
+
+def decode_attention(q: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray, n_ctx: int,
+                     scale: Optional[float] = None) -> np.ndarray:
+    """q [batch, H_q, d]; k_cache, v_cache [batch, H_kv, s_max, d] (fp32 widening of what the caches hold,
+    C-contiguous); attends to cache rows [0, n_ctx) -> float64 [batch, H_q, d]."""
+    q = np.ascontiguousarray(q, dtype=np.float32)
+    kc = np.ascontiguousarray(k_cache, dtype=np.float32)
+    vc = np.ascontiguousarray(v_cache, dtype=np.float32)
+    batch, hq, d = q.shape
+    assert kc.shape == vc.shape and kc.ndim == 4 and kc.shape[0] == batch and kc.shape[3] == d
+    hkv, s_max = kc.shape[1], kc.shape[2]
+    assert hq % hkv == 0 and 1 <= n_ctx <= s_max
+    out = np.empty((batch, hq, d), dtype=np.float64)
+    sc = (1.0 / np.sqrt(d)) if scale is None else float(scale)
+    lib().oracle_decode_attention(_ptr(q), _ptr(kc), _ptr(vc), _ptr(out), batch, hq, hkv, d, s_max, int(n_ctx), sc)
+    return out

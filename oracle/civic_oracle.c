@@ -22,6 +22,9 @@
  *   oracle_attention         softmax(Q K^T / sqrt(d)) V per head, grouped-query, optional
  *                            causal mask: the "LLM prefill attention" term of Eq. 2 / Eq. 7
  *   oracle_kv_write          the "KV-cache storage" term of Eq. 2 / Eq. 7: contiguous rows
+ *   oracle_decode_attention  one generated token attending to the whole compact prompt in
+ *                            the cache: the per-token work inside the autoregressive decoding
+ *                            cost C_dec of Eq. 2 / Eq. 7 (decode column of the latency table)
  *
  * OpenMP is used on the outermost independent loop only (rows, batch items, query rows);
  * every inner computation is a sequential loop in the order the definition states.
@@ -329,4 +332,41 @@ int64_t oracle_kv_write(const uint8_t *k, const uint8_t *v, const int64_t *kv_st
                 written += 2 * head_bytes;
             }
     return written;
+}
+
+/* ---------------------------------------------- Eq. 2 / Eq. 7: decode-step attention   */
+/* One query per (batch item, query head) against the first n_ctx rows of the contiguous
+ * caches [batch, H_kv, s_max, head_dim] (the layout oracle_kv_write fills):
+ *   out[b, h, :] = sum_{j < n_ctx} softmax_j(scale * <q[b,h,:], K[b,g,j,:]>) V[b,g,j,:],
+ * g = h / (H_q / H_kv).  Rows at or beyond n_ctx are never read.  q is dense
+ * [batch, H_q, head_dim]; output double, same shape.  n_ctx >= 1. */
+void oracle_decode_attention(const float *q, const float *k_cache, const float *v_cache,
+                             double *out, int32_t batch, int32_t n_q_heads, int32_t n_kv_heads,
+                             int32_t head_dim, int64_t s_max, int64_t n_ctx, double scale)
+{
+    const int32_t group = n_q_heads / n_kv_heads;
+#pragma omp parallel for schedule(static)
+    for (int64_t w = 0; w < (int64_t)batch * n_q_heads; ++w) {
+        const int32_t b = (int32_t)(w / n_q_heads), h = (int32_t)(w % n_q_heads);
+        const int32_t g = h / group;
+        const float *qv = q + w * head_dim;
+        const float *kb = k_cache + ((int64_t)b * n_kv_heads + g) * s_max * head_dim;
+        const float *vb = v_cache + ((int64_t)b * n_kv_heads + g) * s_max * head_dim;
+        double *z = (double *)malloc(sizeof(double) * (size_t)n_ctx);
+        double zmax = -INFINITY, denom = 0.0;
+        for (int64_t j = 0; j < n_ctx; ++j) {
+            double acc = 0.0;
+            for (int32_t c = 0; c < head_dim; ++c) acc += (double)qv[c] * (double)kb[j * head_dim + c];
+            z[j] = scale * acc;
+            if (z[j] > zmax) zmax = z[j];
+        }
+        for (int64_t j = 0; j < n_ctx; ++j) { z[j] = exp(z[j] - zmax); denom += z[j]; }
+        double *o = out + w * head_dim;
+        for (int32_t c = 0; c < head_dim; ++c) o[c] = 0.0;
+        for (int64_t j = 0; j < n_ctx; ++j) {
+            const double p = z[j] / denom;
+            for (int32_t c = 0; c < head_dim; ++c) o[c] += p * (double)vb[j * head_dim + c];
+        }
+        free(z);
+    }
 }
