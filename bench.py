@@ -337,12 +337,51 @@ def main() -> int:
         "stages": stages,
         "roofline": roofline,
     }
+    # Decode-step attention over the cache the step has just written (n_ctx = S_c, one query per sequence): the
+    # per-token work of the decoding phase.  The workload's own batch is a launch of a few microseconds; the
+    # same shape at batch 64 (labelled) shows the bandwidth the kernel reaches once the chip is covered.
+    def decode_figures(batch):
+        e = 2 if w.dtype == "bf16" else 4
+        dt = sets[0].hidden.dtype
+        sc = w.seq_compact
+        reps = max(1, min(len(sets), 1 + (1 << 30) // max(1, batch * w.n_kv_heads * sc * w.head_dim * e * 2)))
+        kcs = [torch.randn((batch, w.n_kv_heads, sc, w.head_dim), device="cuda").to(dt) for _ in range(reps)]
+        vcs = [torch.randn((batch, w.n_kv_heads, sc, w.head_dim), device="cuda").to(dt) for _ in range(reps)]
+        qd = torch.randn((batch, w.n_q_heads, w.head_dim), device="cuda").to(dt)
+        od = torch.empty_like(qd)
+        need = bd.civic_decode_attn_workspace_bytes(dt, batch, w.n_q_heads, w.n_kv_heads, w.head_dim, sc)
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+        def call(i):
+            bd.civic_decode_attn(qd, kcs[i % reps], vcs[i % reps], sc, 0.0, out=od, workspace=ws)
+        for i in range(20):
+            call(i)
+        a, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        torch.cuda._sleep(hold_cycles)
+        a.record()
+        for i in range(n_alone):
+            call(i)
+        b_.record()
+        torch.cuda.synchronize()
+        us = a.elapsed_time(b_) * 1e3 / n_alone
+        nbytes = batch * (2 * w.n_kv_heads * sc * w.head_dim * e + 2 * w.n_q_heads * w.head_dim * e)
+        gbs = nbytes / (us * 1e-6) / 1e9
+        return {"batch": batch, "n_ctx": sc, "us": round(us, 2), "bytes": nbytes, "gbs": round(gbs, 1),
+                "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4), "workspace_bytes": need, "cache_sets": reps}
+
+    decode = None
+    if w.n_kv_heads != w.n_q_heads or w.causal:              # the encoder-side workload keeps no cache
+        decode = {"kernel": "decode_partial_kernel + decode_merge_kernel (civic_decode_attn)", "bound": "hbm",
+                  "unit": "GB/s", "peak": HBM_PEAK_GBS, "workload": decode_figures(w.batch), "batch_64": decode_figures(64)}
+
     # the selection runs once per prompt, the attention and the KV write once per layer: one measured step plus
     # layers - 1 further attention launches (in-step duration)
     per_layer_us = attn_us + (stage_us["kv_write"]["mean"] if args.unfused else 0.0)
     amortised_us = 1e3 * ms_per_step + (args.layers - 1) * per_layer_us
     result["amortised"] = {"layers": args.layers, "us": round(amortised_us, 2),
                            "tokens_per_s": round(tokens / (amortised_us * 1e-6), 1)}
+    if decode is not None:
+        result["decode"] = decode
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(result), flush=True)

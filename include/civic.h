@@ -13,6 +13,8 @@
  *   civic_kv_write     contiguous, un-paged KV-cache rows (the gamma * N_l * (L+M_p) * D_l
  *                      term of Eq. 7, ratio of Eq. 14)
  *   civic_prefill_attn_kv  the last two as one call (the K/V rows are read once)
+ * and, after the prefill, per generated token:
+ *   civic_decode_attn  one query per sequence against the compact cache (inside C_dec of Eq. 7)
  *
  * Conventions shared by every call
  *   - Plain C.  Every function that launches work returns int: CIVIC_OK or a negative
@@ -212,6 +214,29 @@ int civic_prefill_attn_kv(const void* q, const void* k, const void* v, void* out
                           const int64_t* o_strides /* host [3] */,
                           int64_t s_max, int64_t pos0, int32_t causal, float softmax_scale,
                           void* stream);
+
+/* Decode-step attention over the compact cache: the work one generated token adds to the autoregressive
+ * decoding cost C_dec of Eq. 2 / Eq. 7, in which "every generated text token must attend to the entire visual
+ * prompt" (latency decomposition, decode column of the latency table) - here to the compact one that
+ * civic_kv_write left in the contiguous caches.
+ *   out[b, h, :] = sum_{j < n_ctx} softmax_j(scale * <q[b,h,:], k_cache[b,g,j,:]>) v_cache[b,g,j,:],
+ * g = h / (n_q_heads / n_kv_heads).  Rows at or beyond n_ctx are not read.  fp32 logits and accumulation
+ * (exp2 of logits scaled by log2 e); the output is rounded to `dtype` (nearest even for bf16).
+ *   q, out            device [batch, n_q_heads, head_dim] of `dtype`, dense
+ *   k_cache, v_cache  device [batch, n_kv_heads, s_max, head_dim] of `dtype`, dense
+ *   n_ctx             rows of every cache that hold the context, 1..s_max (the same for every batch item:
+ *                     compact sequences of one grid have one length)
+ *   softmax_scale     0 means 1/sqrt(head_dim)
+ *   workspace         device, 16-byte aligned, at least civic_decode_attn_workspace_bytes(same sizes) bytes:
+ *                     partial (max, sum, output) per split of the context; may be NULL when that is 0.
+ *                     Contents need no initialisation and mean nothing afterwards.
+ * Pointers 16-byte aligned; head_dim * sizeof(element) a multiple of 16 and at most 1024 bytes; batch at most
+ * 65535.  CIVIC_ERR_WORKSPACE if the workspace is missing or too small. */
+size_t civic_decode_attn_workspace_bytes(int dtype, int32_t batch, int32_t n_q_heads, int32_t n_kv_heads,
+                                         int32_t head_dim, int64_t n_ctx);
+int civic_decode_attn(const void* q, const void* k_cache, const void* v_cache, void* out, int dtype,
+                      int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int64_t s_max,
+                      int64_t n_ctx, float softmax_scale, void* workspace, size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -22,7 +22,8 @@ MAX_VISUAL_TOKENS, MAX_FRAMES, MAX_SCORE_DIM, MAX_HEAD_DIM = 32768, 128, 8192, 2
 
 EXPORTS = ("civic_last_hip_error", "civic_kept_count", "civic_select_workspace_bytes",
            "civic_compact_workspace_bytes", "civic_anchor_normalize", "civic_score", "civic_score_visual", "civic_select",
-           "civic_compact", "civic_prefill_attn", "civic_kv_write", "civic_prefill_attn_kv")
+           "civic_compact", "civic_prefill_attn", "civic_kv_write", "civic_prefill_attn_kv",
+           "civic_decode_attn_workspace_bytes", "civic_decode_attn")
 
 
 class CivicError(RuntimeError):
@@ -75,6 +76,13 @@ lib.civic_kv_write.argtypes = [_P, _P, _P, C.c_int, _P, _P, C.c_int32, C.c_int32
 lib.civic_prefill_attn_kv.restype = C.c_int
 lib.civic_prefill_attn_kv.argtypes = [_P, _P, _P, _P, _P, _P, C.c_int, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                       _P, _P, _P, C.c_int64, C.c_int64, C.c_int32, C.c_float, _P]
+
+
+lib.civic_decode_attn_workspace_bytes.restype = C.c_size_t
+lib.civic_decode_attn_workspace_bytes.argtypes = [C.c_int, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int64]
+lib.civic_decode_attn.restype = C.c_int
+lib.civic_decode_attn.argtypes = [_P, _P, _P, _P, C.c_int, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int64,
+                                  C.c_float, _P, C.c_size_t, _P]
 
 
 def _check(call: str, rc: int) -> None:
@@ -263,4 +271,37 @@ def civic_prefill_attn_kv(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, k_c
         _dev(q), _dev(k), _dev(v), _dev(out), _dev(k_cache), _dev(v_cache), _dtype_code(q), batch, seq, hq, hkv, d,
         _strides3(q), _strides3(k), _strides3(out), k_cache.shape[2], int(pos0), int(bool(causal)), float(softmax_scale),
         _stream(stream)))
+    return out
+
+
+def civic_decode_attn_workspace_bytes(dtype: torch.dtype, batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int,
+                                      n_ctx: int) -> int:
+    code = CIVIC_F32 if dtype == torch.float32 else CIVIC_BF16
+    return int(lib.civic_decode_attn_workspace_bytes(code, batch, n_q_heads, n_kv_heads, head_dim, n_ctx))
+
+
+def _decode_shapes(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor):
+    if q.dim() != 3 or not q.is_contiguous() or not k_cache.is_contiguous() or not v_cache.is_contiguous():
+        raise ValueError("q [batch, H_q, d] and the caches [batch, H_kv, s_max, d] must be contiguous")
+    if k_cache.shape != v_cache.shape or k_cache.dim() != 4 or k_cache.dtype != q.dtype or v_cache.dtype != q.dtype:
+        raise ValueError("caches must share shape and q's dtype")
+    batch, hq, d = q.shape
+    if k_cache.shape[0] != batch or k_cache.shape[3] != d:
+        raise ValueError("caches must be [batch, H_kv, s_max, d]")
+    return batch, hq, k_cache.shape[1], d, k_cache.shape[2]
+
+
+def civic_decode_attn(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, n_ctx: int, softmax_scale: float = 0.0,
+                      out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """q [batch, H_q, d] against rows [0, n_ctx) of the caches [batch, H_kv, s_max, d] -> out [batch, H_q, d]."""
+    batch, hq, hkv, d, s_max = _decode_shapes(q, k_cache, v_cache)
+    if out is None:
+        out = torch.empty_like(q)
+    if workspace is None:
+        need = civic_decode_attn_workspace_bytes(q.dtype, batch, hq, hkv, d, n_ctx)
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device) if need else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check("civic_decode_attn", lib.civic_decode_attn(_dev(q), _dev(k_cache), _dev(v_cache), _dev(out), _dtype_code(q), batch,
+                                                      hq, hkv, d, s_max, int(n_ctx), float(softmax_scale), _dev(workspace),
+                                                      ws_bytes, _stream(stream)))
     return out

@@ -154,6 +154,21 @@ def test_argument_errors_precede_any_hip_call(bd):
     assert attn_kv(kc=None) == I and attn_kv(vc=None) == I and attn_kv(vc=odd) == I
     assert attn_kv(pos0=9) == I and attn_kv(pos0=-1) == I and attn_kv(smax=7) == I
     assert attn_kv(hq=3) == I and attn_kv(d=60) == I and attn_kv(scale=-1.0) == I and attn_kv(ks=None) == I
+    # civic_decode_attn: context outside the cache, empty context, head mismatch, alignment, workspace
+    def dec(**kw):
+        a = dict(q=F, kc=F, vc=F, o=F, dt=1, b=2, hq=4, hkv=2, d=64, smax=100, n=50, scale=0.0, ws=F, wsb=1 << 30)
+        a.update(kw)
+        return L.civic_decode_attn(a["q"], a["kc"], a["vc"], a["o"], a["dt"], a["b"], a["hq"], a["hkv"], a["d"], a["smax"],
+                                   a["n"], C.c_float(a["scale"]), a["ws"], a["wsb"], None)
+    assert dec(n=101) == I and dec(n=0) == I and dec(n=-1) == I and dec(hq=3) == I and dec(d=60) == I
+    assert dec(q=None) == I and dec(kc=odd) == I and dec(o=None) == I and dec(dt=3) == I and dec(scale=-1.0) == I
+    assert dec(d=1024) == bd.ERR_UNSUPPORTED and dec(b=0, q=None, kc=None, vc=None, o=None) == bd.CIVIC_OK
+    need = bd.civic_decode_attn_workspace_bytes(__import__("torch").bfloat16, 2, 4, 2, 64, 50)
+    assert need == 0                                        # 50 rows are one round of one workgroup: nothing to combine
+    need = bd.civic_decode_attn_workspace_bytes(__import__("torch").bfloat16, 2, 4, 2, 64, 5000)
+    assert need > 0 and need % 4 == 0
+    assert dec(smax=6000, n=5000, ws=None, wsb=0) == bd.ERR_WORKSPACE
+    assert dec(smax=6000, n=5000, wsb=need - 4) == bd.ERR_WORKSPACE and dec(smax=6000, n=5000, ws=odd) == bd.ERR_WORKSPACE
     # a tensor without elements needs no pointer: NULL is accepted exactly then
     OK = bd.CIVIC_OK
     assert L.civic_score(None, 1, 0, 64, 64, F, 1.0, None, None) == OK and L.civic_score(F, 1, 0, 64, 64, None, 1.0, F, None) == I
