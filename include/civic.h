@@ -238,6 +238,20 @@ int civic_decode_attn(const void* q, const void* k_cache, const void* v_cache, v
                       int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int64_t s_max,
                       int64_t n_ctx, float softmax_scale, void* workspace, size_t workspace_bytes, void* stream);
 
+/* civic_decode_attn for callers that cannot allocate or hand over a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the workspace, same kernels,
+ * same results bit for bit; the partial results of the splits live in an array inside the library's code
+ * object, of CIVIC_DECODE_NOALLOC_MAX_BYTES on every GPU that runs the library, held until the process ends.
+ * The call allocates and frees nothing (device or pinned memory) and needs no initialisation call.
+ * CIVIC_ERR_WORKSPACE when civic_decode_attn_workspace_bytes(same sizes) exceeds that maximum.
+ * All calls on one GPU share the array: calls that may overlap on one GPU (different streams, different
+ * threads) race on it and must be serialised by the caller; civic_decode_attn with separate workspaces has no
+ * such limit. */
+#define CIVIC_DECODE_NOALLOC_MAX_BYTES (4u << 20)
+int civic_decode_attn_noalloc(const void* q, const void* k_cache, const void* v_cache, void* out, int dtype,
+                              int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int64_t s_max,
+                              int64_t n_ctx, float softmax_scale, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,7 @@ MAX_VISUAL_TOKENS, MAX_FRAMES, MAX_SCORE_DIM, MAX_HEAD_DIM = 32768, 128, 8192, 2
 EXPORTS = ("civic_last_hip_error", "civic_kept_count", "civic_select_workspace_bytes",
            "civic_compact_workspace_bytes", "civic_anchor_normalize", "civic_score", "civic_score_visual", "civic_select",
            "civic_compact", "civic_prefill_attn", "civic_kv_write", "civic_prefill_attn_kv",
-           "civic_decode_attn_workspace_bytes", "civic_decode_attn")
+           "civic_decode_attn_workspace_bytes", "civic_decode_attn", "civic_decode_attn_noalloc")
 
 
 class CivicError(RuntimeError):
@@ -83,6 +83,10 @@ lib.civic_decode_attn_workspace_bytes.argtypes = [C.c_int, C.c_int32, C.c_int32,
 lib.civic_decode_attn.restype = C.c_int
 lib.civic_decode_attn.argtypes = [_P, _P, _P, _P, C.c_int, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int64,
                                   C.c_float, _P, C.c_size_t, _P]
+lib.civic_decode_attn_noalloc.restype = C.c_int
+lib.civic_decode_attn_noalloc.argtypes = [_P, _P, _P, _P, C.c_int, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int64,
+                                          C.c_float, _P]
+DECODE_NOALLOC_MAX_BYTES = 4 << 20
 
 
 def _check(call: str, rc: int) -> None:
@@ -304,4 +308,14 @@ def civic_decode_attn(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Ten
     _check("civic_decode_attn", lib.civic_decode_attn(_dev(q), _dev(k_cache), _dev(v_cache), _dev(out), _dtype_code(q), batch,
                                                       hq, hkv, d, s_max, int(n_ctx), float(softmax_scale), _dev(workspace),
                                                       ws_bytes, _stream(stream)))
+    return out
+
+
+def civic_decode_attn_noalloc(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, n_ctx: int, out: torch.Tensor,
+                              softmax_scale: float = 0.0, stream=None) -> torch.Tensor:
+    """civic_decode_attn without a workspace argument (the library's own static scratch); `out` is the caller's."""
+    batch, hq, hkv, d, s_max = _decode_shapes(q, k_cache, v_cache)
+    _check("civic_decode_attn_noalloc", lib.civic_decode_attn_noalloc(_dev(q), _dev(k_cache), _dev(v_cache), _dev(out),
+                                                                      _dtype_code(q), batch, hq, hkv, d, s_max, int(n_ctx),
+                                                                      float(softmax_scale), _stream(stream)))
     return out

@@ -387,7 +387,57 @@ static int decode_check(const void* q, const void* k_cache, const void* v_cache,
     return CIVIC_OK;
 }
 
+// ------------------------------------------------------------------------------ no allocation at all
+// civic_decode_attn_noalloc keeps the partial results of the splits in a buffer that belongs to the library's
+// code object instead of one the caller brings: every GPU that loads the library holds its own copy of this
+// array, at its own address, until the process ends.
+constexpr size_t kDecStaticBytes = CIVIC_DECODE_NOALLOC_MAX_BYTES;
+static __device__ __align__(256) unsigned char dec_static_scratch[kDecStaticBytes];
+
+// The array's address on the current device.  In host code the array's name stands for the symbol, not for
+// device memory: its address is asked for once per device, with that device current, and kept.
+static int static_scratch_ptr(void** ptr)
+{
+    constexpr int kMaxDevices = 64;
+    static std::atomic<void*> cached[kMaxDevices];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return record_hip_error(e);
+    if (dev >= 0 && dev < kMaxDevices) {
+        void* p = cached[dev].load(std::memory_order_acquire);
+        if (p) { *ptr = p; return CIVIC_OK; }
+    }
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(dec_static_scratch));
+    if (e != hipSuccess || !p) return record_hip_error(e != hipSuccess ? e : hipErrorInvalidSymbol);
+    if (dev >= 0 && dev < kMaxDevices) cached[dev].store(p, std::memory_order_release);
+    *ptr = p;
+    return CIVIC_OK;
+}
+
 }  // namespace civic
+
+extern "C" int civic_decode_attn_noalloc(const void* q, const void* k_cache, const void* v_cache, void* out, int dtype,
+                                         int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                         int64_t s_max, int64_t n_ctx, float softmax_scale, void* stream)
+{
+    using namespace civic;
+    DecodePlan p;
+    bool nothing = false;
+    const int rc = decode_check(q, k_cache, v_cache, out, dtype, batch, n_q_heads, n_kv_heads, head_dim, s_max, n_ctx,
+                                softmax_scale, &p, &nothing);
+    if (rc != CIVIC_OK || nothing) return rc;
+    if (p.ws_bytes > kDecStaticBytes) return CIVIC_ERR_WORKSPACE;      // more partial results than the array holds
+    void* scratch = nullptr;
+    if (p.ws_bytes > 0) {
+        const int rs = static_scratch_ptr(&scratch);
+        if (rs != CIVIC_OK) return rs;
+    }
+    // every element of the array that the combine launch reads is written by this call's first launch: nothing
+    // has to start at zero
+    return decode_attn(q, k_cache, v_cache, out, dtype, batch, n_q_heads, n_kv_heads, head_dim, s_max, n_ctx, softmax_scale,
+                       p, static_cast<float*>(scratch), stream);
+}
 
 extern "C" size_t civic_decode_attn_workspace_bytes(int dtype, int32_t batch, int32_t n_q_heads, int32_t n_kv_heads,
                                                     int32_t head_dim, int64_t n_ctx)
