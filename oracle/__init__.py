@@ -59,6 +59,10 @@ def lib() -> C.CDLL:
         L.oracle_kv_write.restype = C.c_int64
         L.oracle_kv_write.argtypes = [P, P, P, P, P, C.c_int32, C.c_int32, C.c_int32, C.c_int64,
                                       C.c_int64, C.c_int64]
+        L.oracle_mrope_table.restype = None
+        L.oracle_mrope_table.argtypes = [P, C.c_int32, C.c_int64, C.c_int32, P, P, P]
+        L.oracle_mrope_apply.restype = None
+        L.oracle_mrope_apply.argtypes = [P, P, C.c_int32, C.c_int64, C.c_int32, C.c_int32, P, P]
         L.oracle_decode_attention.restype = None
         L.oracle_decode_attention.argtypes = [P, P, P, P, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int64,
                                               C.c_int64, C.c_double]
@@ -195,4 +199,31 @@ def decode_attention(q: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray, n_
     out = np.empty((batch, hq, d), dtype=np.float64)
     sc = (1.0 / np.sqrt(d)) if scale is None else float(scale)
     lib().oracle_decode_attention(_ptr(q), _ptr(kc), _ptr(vc), _ptr(out), batch, hq, hkv, d, s_max, int(n_ctx), sc)
+    return out
+
+
+def mrope_table(pos_ids: np.ndarray, axis_of_pair: np.ndarray, inv_freq: np.ndarray) -> np.ndarray:
+    """pos_ids int32 [3, batch, seq]; axis_of_pair int32 [n_pairs] in {0,1,2}; inv_freq fp32 [n_pairs]
+    -> float64 [batch, seq, n_pairs, 2] holding (cos, sin) of pos[axis[i]] * inv_freq[i]."""
+    p = np.ascontiguousarray(pos_ids, dtype=np.int32)
+    ax = np.ascontiguousarray(axis_of_pair, dtype=np.int32)
+    fr = np.ascontiguousarray(inv_freq, dtype=np.float32)
+    assert p.ndim == 3 and p.shape[0] == 3 and ax.shape == fr.shape and ax.ndim == 1
+    assert ax.min() >= 0 and ax.max() <= 2
+    _, batch, seq = p.shape
+    out = np.empty((batch, seq, ax.shape[0], 2), dtype=np.float64)
+    lib().oracle_mrope_table(_ptr(p), batch, seq, ax.shape[0], _ptr(ax), _ptr(fr), _ptr(out))
+    return out
+
+
+def mrope_apply(x: np.ndarray, cos_sin: np.ndarray) -> np.ndarray:
+    """x fp32 view [batch, seq, heads, d] (strides honoured on the first three axes); cos_sin float64
+    [batch, seq, d/2, 2] -> float64 [batch, seq, heads, d], pairs (i, i + d/2) rotated."""
+    assert x.dtype == np.float32 and x.ndim == 4 and x.strides[3] == 4
+    batch, seq, heads, d = x.shape
+    cs = np.ascontiguousarray(cos_sin, dtype=np.float64)
+    assert d % 2 == 0 and cs.shape == (batch, seq, d // 2, 2)
+    st = np.asarray([s // 4 for s in x.strides[:3]], dtype=np.int64)
+    out = np.empty((batch, seq, heads, d), dtype=np.float64)
+    lib().oracle_mrope_apply(_ptr(x), _ptr(st), batch, seq, heads, d // 2, _ptr(cs), _ptr(out))
     return out

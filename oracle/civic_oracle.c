@@ -22,6 +22,13 @@
  *   oracle_attention         softmax(Q K^T / sqrt(d)) V per head, grouped-query, optional
  *                            causal mask: the "LLM prefill attention" term of Eq. 2 / Eq. 7
  *   oracle_kv_write          the "KV-cache storage" term of Eq. 2 / Eq. 7: contiguous rows
+ *   oracle_mrope_table /     rotary position embedding driven by the position ids that the compact
+ *   oracle_mrope_apply       merge carries along ("text positions are preserved, compact visual
+ *                            positions are inherited", sentence after Eq. 14).  The paper does not
+ *                            print the rotary form: three-axis rotary embedding as published for
+ *                            the Qwen-VL family, pairs (i, i + d/2), axis and frequency per pair
+ *                            given by the caller: PARITY UNPINNED BY THE PAPER, pinned by the
+ *                            complex-multiplication form and the relative-position property.
  *   oracle_decode_attention  one generated token attending to the whole compact prompt in
  *                            the cache: the per-token work inside the autoregressive decoding
  *                            cost C_dec of Eq. 2 / Eq. 7 (decode column of the latency table)
@@ -368,5 +375,51 @@ void oracle_decode_attention(const float *q, const float *k_cache, const float *
             for (int32_t c = 0; c < head_dim; ++c) o[c] += p * (double)vb[j * head_dim + c];
         }
         free(z);
+    }
+}
+
+/* ------------------------------------------- position ids -> rotary angles (M-RoPE)    */
+/* cos_sin[b, t, i, 0..1] = (cos, sin) of angle = pos_ids[axis_of_pair[i], b, t] * inv_freq[i]
+ * for every frequency pair i < n_pairs; pos_ids is int32 [3, batch, seq] (temporal, height,
+ * width), axis_of_pair[i] in {0, 1, 2}.  inv_freq is taken as the fp32 values given. */
+void oracle_mrope_table(const int32_t *pos_ids, int32_t batch, int64_t seq, int32_t n_pairs,
+                        const int32_t *axis_of_pair, const float *inv_freq, double *cos_sin)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t w = 0; w < (int64_t)batch * seq; ++w) {
+        const int32_t b = (int32_t)(w / seq);
+        const int64_t t = w % seq;
+        for (int32_t i = 0; i < n_pairs; ++i) {
+            const double p = (double)pos_ids[((int64_t)axis_of_pair[i] * batch + b) * seq + t];
+            const double angle = p * (double)inv_freq[i];
+            cos_sin[(w * n_pairs + i) * 2] = cos(angle);
+            cos_sin[(w * n_pairs + i) * 2 + 1] = sin(angle);
+        }
+    }
+}
+
+/* Rotates every head row of x [batch, seq, heads, head_dim] (element strides for batch, token,
+ * head; head_dim contiguous, head_dim = 2 * n_pairs): pair i is (x[i], x[i + n_pairs]),
+ *   out[i]           = x[i] * cos - x[i + n_pairs] * sin
+ *   out[i + n_pairs] = x[i + n_pairs] * cos + x[i] * sin
+ * with the (cos, sin) of the row's token.  Output double, dense [batch, seq, heads, head_dim]. */
+void oracle_mrope_apply(const float *x, const int64_t *x_strides, int32_t batch, int64_t seq,
+                        int32_t heads, int32_t n_pairs, const double *cos_sin, double *out)
+{
+    const int32_t d = 2 * n_pairs;
+#pragma omp parallel for schedule(static)
+    for (int64_t w = 0; w < (int64_t)batch * seq; ++w) {
+        const int32_t b = (int32_t)(w / seq);
+        const int64_t t = w % seq;
+        for (int32_t h = 0; h < heads; ++h) {
+            const float *row = x + b * x_strides[0] + t * x_strides[1] + h * x_strides[2];
+            double *o = out + (w * heads + h) * d;
+            for (int32_t i = 0; i < n_pairs; ++i) {
+                const double c = cos_sin[(w * n_pairs + i) * 2], sn = cos_sin[(w * n_pairs + i) * 2 + 1];
+                const double x0 = (double)row[i], x1 = (double)row[i + n_pairs];
+                o[i] = x0 * c - x1 * sn;
+                o[i + n_pairs] = x1 * c + x0 * sn;
+            }
+        }
     }
 }

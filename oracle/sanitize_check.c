@@ -35,6 +35,11 @@ void oracle_decode_attention(const float *q, const float *k_cache, const float *
                              int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int64_t s_max, int64_t n_ctx,
                              double scale);
 
+void oracle_mrope_table(const int32_t *pos_ids, int32_t batch, int64_t seq, int32_t n_pairs, const int32_t *axis_of_pair,
+                        const float *inv_freq, double *cos_sin);
+void oracle_mrope_apply(const float *x, const int64_t *x_strides, int32_t batch, int64_t seq, int32_t heads, int32_t n_pairs,
+                        const double *cos_sin, double *out);
+
 static uint64_t rng_state = 0x9E3779B97F4A7C15ull;
 static float rnd(void)
 {
@@ -133,6 +138,22 @@ int main(void)
         oracle_decode_attention(q, kc, vc, od, b, hq, hkv, d, s_max, s_max, 0.3);
         CHECK(isfinite(od[b * hq * d - 1]));
         free(q); free(k); free(v); free(o); free(kc); free(vc); free(od);
+    }
+    /* rotary embedding: rows embedded in wider rows, ids on three axes */
+    {
+        const int32_t b = 2, heads = 3, np_ = 5, d = 10;
+        const int64_t s = 7, xs[3] = {s * heads * (d + 3), heads * (d + 3), d + 3};
+        float *x = rand_floats((size_t)((b - 1) * xs[0] + (s - 1) * xs[1] + (heads - 1) * xs[2] + d));
+        int32_t *pos = (int32_t *)malloc(sizeof(int32_t) * (size_t)(3 * b * s));
+        for (int64_t i = 0; i < 3 * b * s; ++i) pos[i] = (int32_t)(i * 37 % 1000);
+        const int32_t axis[5] = {0, 1, 2, 1, 0};
+        const float inv[5] = {1.0f, 0.5f, 0.1f, 0.01f, 0.001f};
+        double *cs = (double *)malloc(sizeof(double) * (size_t)(b * s * np_ * 2));
+        double *o = (double *)malloc(sizeof(double) * (size_t)(b * s * heads * d));
+        oracle_mrope_table(pos, b, s, np_, axis, inv, cs);
+        oracle_mrope_apply(x, xs, b, s, heads, np_, cs, o);
+        CHECK(fabs(cs[0] * cs[0] + cs[1] * cs[1] - 1.0) < 1e-12 && isfinite(o[b * s * heads * d - 1]));
+        free(x); free(pos); free(cs); free(o);
     }
     printf("sanitize_check OK\n");
     return 0;
