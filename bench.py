@@ -374,6 +374,44 @@ def main() -> int:
         decode = {"kernel": "decode_partial_kernel + decode_merge_kernel (civic_decode_attn)", "bound": "hbm",
                   "unit": "GB/s", "peak": HBM_PEAK_GBS, "workload": decode_figures(w.batch), "batch_64": decode_figures(64)}
 
+    # Rotary embedding from the carried ids: the table once per prompt; per layer K rotated on its way into the
+    # cache (civic_kv_write_rope) and Q rotated inside the attention launch (civic_prefill_attn_rope reading K and
+    # V from the cache).  civic_mrope_apply on Q is what the fused attention saves.
+    rope = None
+    if w.head_dim % 32 == 0 and w.dtype == "bf16":
+        n_pairs = w.head_dim // 2
+        inv_freq = (1.0e6 ** (-np.arange(n_pairs, dtype=np.float64) / n_pairs)).astype(np.float32)
+        axis = (np.arange(n_pairs) % 3).astype(np.int32)
+        e = 2
+        for s_ in sets:
+            s_.cos_sin = torch.empty((w.batch, w.seq_compact, n_pairs, 2), dtype=torch.float32, device="cuda")
+            s_.q_rot = torch.empty_like(s_.q)
+        def rope_table(s_):
+            bd.civic_mrope_table(s_.pos_c, axis, inv_freq, cos_sin=s_.cos_sin)
+        def kv_rope(s_):
+            bd.civic_kv_write_rope(s_.k, s_.v, s_.cos_sin, s_.k_cache, s_.v_cache, 0)
+        def attn_rope(s_):
+            bd.civic_prefill_attn_rope(s_.q, s_.k_cache.permute(0, 2, 1, 3), s_.v_cache.permute(0, 2, 1, 3), s_.cos_sin, w.causal,
+                                       0.0, out=s_.out)
+        def attn_cache(s_):
+            bd.civic_prefill_attn(s_.q, s_.k_cache.permute(0, 2, 1, 3), s_.v_cache.permute(0, 2, 1, 3), w.causal, 0.0, out=s_.out)
+        def apply_q(s_):
+            bd.civic_mrope_apply(s_.q, s_.cos_sin, out=s_.q_rot)
+        for s_ in sets:
+            compact_call = calls["compact"]; compact_call(s_); rope_table(s_); kv_rope(s_)
+        torch.cuda.synchronize()
+        table_bytes = w.batch * w.seq_compact * n_pairs * 8
+        t_table, t_kv, t_attn_rope, t_attn_cache, t_apply = (alone(f) for f in (rope_table, kv_rope, attn_rope, attn_cache, apply_q))
+        kv_bytes = work["kv_write"] + table_bytes
+        q_bytes = 2 * w.batch * w.seq_compact * w.n_q_heads * w.head_dim * e + table_bytes
+        rope = {"table_us": round(t_table, 2),
+                "kv_write_rope": {"us": round(t_kv, 2), "bytes": kv_bytes, "gbs": round(kv_bytes / t_kv / 1e3, 1),
+                                  "frac_hbm_peak": round(kv_bytes / t_kv / 1e3 / HBM_PEAK_GBS, 4)},
+                "prefill_attn_rope_us_back_to_back": round(t_attn_rope, 2),
+                "prefill_attn_on_cache_us_back_to_back": round(t_attn_cache, 2),
+                "mrope_apply_q": {"us": round(t_apply, 2), "bytes": q_bytes, "gbs": round(q_bytes / t_apply / 1e3, 1),
+                                  "frac_hbm_peak": round(q_bytes / t_apply / 1e3 / HBM_PEAK_GBS, 4)}}
+
     # the selection runs once per prompt, the attention and the KV write once per layer: one measured step plus
     # layers - 1 further attention launches (in-step duration)
     per_layer_us = attn_us + (stage_us["kv_write"]["mean"] if args.unfused else 0.0)
@@ -382,6 +420,8 @@ def main() -> int:
                            "tokens_per_s": round(tokens / (amortised_us * 1e-6), 1)}
     if decode is not None:
         result["decode"] = decode
+    if rope is not None:
+        result["rope"] = rope
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(result), flush=True)

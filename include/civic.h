@@ -215,6 +215,53 @@ int civic_prefill_attn_kv(const void* q, const void* k, const void* v, void* out
                           int64_t s_max, int64_t pos0, int32_t causal, float softmax_scale,
                           void* stream);
 
+/* Rotary position embedding from the carried position ids.  The compact merge copies the three ids of every
+ * token unchanged ("text positions are preserved, compact visual positions are inherited", sentence after
+ * Eq. 14); this is where they are consumed.  The paper prints no rotary formula: the form is the published
+ * three-axis rotary embedding of the Qwen-VL family in rotate-half layout.  Frequency pair i of a head row is
+ * (x[i], x[i + head_dim/2]); it is turned by angle(t, i) = pos_ids[axis_of_pair[i], b, t] * inv_freq[i]:
+ *   y[i] = x[i] cos - x[i + head_dim/2] sin,   y[i + head_dim/2] = x[i + head_dim/2] cos + x[i] sin.
+ * Which id axis (0 temporal, 1 height, 2 width) and which frequency a pair uses are the caller's tables, so
+ * sectioned and interleaved splits and any base are covered.
+ *
+ * civic_mrope_table: (cos, sin) of every angle, once per prefill (all layers and heads share them).
+ *   pos_ids       device [3, batch, seq] int32 (civic_compact's pos_c)
+ *   axis_of_pair  host [n_pairs] int32 in {0, 1, 2};  inv_freq  host [n_pairs] fp32, finite
+ *   cos_sin       device [batch, seq, n_pairs, 2] fp32, 16-byte aligned
+ * Angles are formed and reduced in double precision.  n_pairs <= CIVIC_MAX_HEAD_DIM / 2. */
+int civic_mrope_table(const int32_t* pos_ids, int32_t batch, int64_t seq, int32_t n_pairs,
+                      const int32_t* axis_of_pair /* host */, const float* inv_freq /* host */,
+                      float* cos_sin, void* stream);
+
+/* Rotates every head row of x into out (out may be x): fp32 arithmetic, output rounded to `dtype`.
+ *   x, out   device [batch, seq, heads, head_dim], element strides (batch, token, head) in x_strides /
+ *            out_strides (host int64[3]), head_dim contiguous
+ *   cos_sin  device [batch, seq, head_dim/2, 2] fp32 (civic_mrope_table with n_pairs = head_dim/2)
+ * head_dim/2 * sizeof(element) must be a multiple of 16; pointers and strides*sizeof(element) 16-byte aligned. */
+int civic_mrope_apply(const void* x, void* out, int dtype, int32_t batch, int64_t seq, int32_t heads, int32_t head_dim,
+                      const int64_t* x_strides /* host [3] */, const int64_t* out_strides /* host [3] */,
+                      const float* cos_sin, void* stream);
+
+/* civic_kv_write with K rotated on its way into the cache (V is copied as it is): the keys enter the cache
+ * with their positions applied once, which is what civic_decode_attn and civic_prefill_attn_rope expect to
+ * find there.  Arguments as civic_kv_write plus cos_sin [batch, seq, head_dim/2, 2] for the seq tokens written;
+ * head_dim/2 * sizeof(element) a multiple of 16. */
+int civic_kv_write_rope(const void* k, const void* v, const int64_t* kv_strides /* host [3] */, int dtype,
+                        const float* cos_sin, void* k_cache, void* v_cache, int32_t batch, int32_t seq,
+                        int32_t n_kv_heads, int32_t head_dim, int64_t s_max, int64_t pos0, void* stream);
+
+/* civic_prefill_attn with the rotary embedding of Q applied on the fly (in registers, from q_cos_sin
+ * [batch, seq, head_dim/2, 2]); k is taken as given, i.e. already rotated - typically the cache rows
+ * civic_kv_write_rope has just written, addressed through kv_strides (batch: n_kv_heads*s_max*head_dim,
+ * token: head_dim, head: s_max*head_dim).  No separate pass over Q is made.  Everything else as
+ * civic_prefill_attn; the rotated query is rounded to `dtype` before the products, as a separate
+ * civic_mrope_apply would.  head_dim a multiple of 4; the MFMA kernel serves head_dim 64, 96 and 128. */
+int civic_prefill_attn_rope(const void* q, const void* k, const void* v, void* out, int dtype,
+                            int32_t batch, int32_t seq, int32_t n_q_heads, int32_t n_kv_heads,
+                            int32_t head_dim, const int64_t* q_strides /* host [3] */,
+                            const int64_t* kv_strides /* host [3] */, const int64_t* o_strides /* host [3] */,
+                            int32_t causal, float softmax_scale, const float* q_cos_sin, void* stream);
+
 /* Decode-step attention over the compact cache: the work one generated token adds to the autoregressive
  * decoding cost C_dec of Eq. 2 / Eq. 7, in which "every generated text token must attend to the entire visual
  * prompt" (latency decomposition, decode column of the latency table) - here to the compact one that

@@ -23,7 +23,8 @@ MAX_VISUAL_TOKENS, MAX_FRAMES, MAX_SCORE_DIM, MAX_HEAD_DIM = 32768, 128, 8192, 2
 EXPORTS = ("civic_last_hip_error", "civic_kept_count", "civic_select_workspace_bytes",
            "civic_compact_workspace_bytes", "civic_anchor_normalize", "civic_score", "civic_score_visual", "civic_select",
            "civic_compact", "civic_prefill_attn", "civic_kv_write", "civic_prefill_attn_kv",
-           "civic_decode_attn_workspace_bytes", "civic_decode_attn", "civic_decode_attn_noalloc")
+           "civic_decode_attn_workspace_bytes", "civic_decode_attn", "civic_decode_attn_noalloc",
+           "civic_mrope_table", "civic_mrope_apply", "civic_kv_write_rope", "civic_prefill_attn_rope")
 
 
 class CivicError(RuntimeError):
@@ -87,6 +88,16 @@ lib.civic_decode_attn_noalloc.restype = C.c_int
 lib.civic_decode_attn_noalloc.argtypes = [_P, _P, _P, _P, C.c_int, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int64,
                                           C.c_float, _P]
 DECODE_NOALLOC_MAX_BYTES = 4 << 20
+lib.civic_mrope_table.restype = C.c_int
+lib.civic_mrope_table.argtypes = [_P, C.c_int32, C.c_int64, C.c_int32, _P, _P, _P, _P]
+lib.civic_mrope_apply.restype = C.c_int
+lib.civic_mrope_apply.argtypes = [_P, _P, C.c_int, C.c_int32, C.c_int64, C.c_int32, C.c_int32, _P, _P, _P, _P]
+lib.civic_kv_write_rope.restype = C.c_int
+lib.civic_kv_write_rope.argtypes = [_P, _P, _P, C.c_int, _P, _P, _P, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int64,
+                                    C.c_int64, _P]
+lib.civic_prefill_attn_rope.restype = C.c_int
+lib.civic_prefill_attn_rope.argtypes = [_P, _P, _P, _P, C.c_int, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                        _P, _P, _P, C.c_int32, C.c_float, _P, _P]
 
 
 def _check(call: str, rc: int) -> None:
@@ -318,4 +329,67 @@ def civic_decode_attn_noalloc(q: torch.Tensor, k_cache: torch.Tensor, v_cache: t
     _check("civic_decode_attn_noalloc", lib.civic_decode_attn_noalloc(_dev(q), _dev(k_cache), _dev(v_cache), _dev(out),
                                                                       _dtype_code(q), batch, hq, hkv, d, s_max, int(n_ctx),
                                                                       float(softmax_scale), _stream(stream)))
+    return out
+
+
+def civic_mrope_table(pos_ids: torch.Tensor, axis_of_pair, inv_freq, cos_sin: Optional[torch.Tensor] = None,
+                      stream=None) -> torch.Tensor:
+    """pos_ids int32 [3, batch, seq] (device); axis_of_pair / inv_freq host arrays [n_pairs] -> fp32 [batch, seq, n_pairs, 2]."""
+    if pos_ids.dim() != 3 or pos_ids.shape[0] != 3 or pos_ids.dtype != torch.int32 or not pos_ids.is_contiguous():
+        raise ValueError("pos_ids must be contiguous int32 [3, batch, seq]")
+    ax = np.ascontiguousarray(np.asarray(axis_of_pair, dtype=np.int32))
+    fr = np.ascontiguousarray(np.asarray(inv_freq, dtype=np.float32))
+    if ax.ndim != 1 or ax.shape != fr.shape:
+        raise ValueError("axis_of_pair and inv_freq must be 1-D of one length")
+    _, batch, seq = pos_ids.shape
+    if cos_sin is None:
+        cos_sin = torch.empty((batch, seq, ax.shape[0], 2), dtype=torch.float32, device=pos_ids.device)
+    _check("civic_mrope_table", lib.civic_mrope_table(_dev(pos_ids), batch, seq, ax.shape[0], C.c_void_p(ax.ctypes.data),
+                                                      C.c_void_p(fr.ctypes.data), _dev(cos_sin), _stream(stream)))
+    return cos_sin
+
+
+def civic_mrope_apply(x: torch.Tensor, cos_sin: torch.Tensor, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """x [batch, seq, heads, d] (strided views are fine) rotated into out (default: a new dense tensor; may be x itself)."""
+    batch, seq, heads, d = x.shape
+    if out is None:
+        out = torch.empty((batch, seq, heads, d), dtype=x.dtype, device=x.device)
+    if not cos_sin.is_contiguous() or tuple(cos_sin.shape) != (batch, seq, d // 2, 2) or cos_sin.dtype != torch.float32:
+        raise ValueError("cos_sin must be contiguous fp32 [batch, seq, d/2, 2]")
+    _check("civic_mrope_apply", lib.civic_mrope_apply(_dev(x), _dev(out), _dtype_code(x), batch, seq, heads, d, _strides3(x),
+                                                      _strides3(out), _dev(cos_sin), _stream(stream)))
+    return out
+
+
+def civic_kv_write_rope(k: torch.Tensor, v: torch.Tensor, cos_sin: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                        pos0: int = 0, stream=None) -> None:
+    """civic_kv_write with K rotated by cos_sin [batch, seq, d/2, 2] on its way into the cache."""
+    if k.shape != v.shape or k.stride() != v.stride() or k.dtype != v.dtype:
+        raise ValueError("k and v must share shape, strides and dtype")
+    batch, seq, hkv, d = k.shape
+    if (not k_cache.is_contiguous() or not v_cache.is_contiguous() or k_cache.shape != v_cache.shape
+            or k_cache.dtype != k.dtype or v_cache.dtype != k.dtype
+            or k_cache.shape[0] != batch or k_cache.shape[1] != hkv or k_cache.shape[3] != d):
+        raise ValueError("caches must be contiguous [batch, H_kv, s_max, d] of the inputs' dtype")
+    if not cos_sin.is_contiguous() or tuple(cos_sin.shape) != (batch, seq, d // 2, 2) or cos_sin.dtype != torch.float32:
+        raise ValueError("cos_sin must be contiguous fp32 [batch, seq, d/2, 2]")
+    _check("civic_kv_write_rope", lib.civic_kv_write_rope(_dev(k), _dev(v), _strides3(k), _dtype_code(k), _dev(cos_sin),
+                                                          _dev(k_cache), _dev(v_cache), batch, seq, hkv, d, k_cache.shape[2],
+                                                          int(pos0), _stream(stream)))
+
+
+def civic_prefill_attn_rope(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, q_cos_sin: torch.Tensor, causal: bool = True,
+                            softmax_scale: float = 0.0, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """civic_prefill_attn with Q rotated on the fly; k (already rotated) and v [batch, seq, H_kv, d] may be views of the caches."""
+    if k.shape != v.shape or k.stride() != v.stride() or q.dtype != k.dtype or q.dtype != v.dtype:
+        raise ValueError("k and v must share shape, strides and dtype with q's dtype")
+    batch, seq, hq, d = q.shape
+    if not q_cos_sin.is_contiguous() or tuple(q_cos_sin.shape) != (batch, seq, d // 2, 2) or q_cos_sin.dtype != torch.float32:
+        raise ValueError("q_cos_sin must be contiguous fp32 [batch, seq, d/2, 2]")
+    if out is None:
+        out = torch.empty((batch, seq, hq, d), dtype=q.dtype, device=q.device)
+    _check("civic_prefill_attn_rope", lib.civic_prefill_attn_rope(_dev(q), _dev(k), _dev(v), _dev(out), _dtype_code(q), batch, seq,
+                                                                  hq, k.shape[2], d, _strides3(q), _strides3(k), _strides3(out),
+                                                                  int(bool(causal)), float(softmax_scale), _dev(q_cos_sin),
+                                                                  _stream(stream)))
     return out

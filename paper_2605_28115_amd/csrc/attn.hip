@@ -59,6 +59,8 @@ struct AttnArgs {
     // fused KV-cache write (MFMA path; null = none): caches are dense [batch, n_kv_heads, s_max, head_dim]
     void* k_cache; void* v_cache;
     int64_t s_max, pos0;
+    // rotary embedding of Q from a (cos, sin) table [batch, seq, head_dim / 2] (null = none): civic_prefill_attn_rope
+    const float2* q_cs;
 };
 
 // ------------------------------------------------------------------------------------ fp32 ALU path
@@ -90,6 +92,16 @@ __global__ __launch_bounds__(256) void attn_plain_kernel(AttnArgs a)
     for (int c = lane; c < d; c += kWave) q_s[w][c] = load_elem<BF16>(a.q, q_off + c) * a.scale;
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
     __builtin_amdgcn_wave_barrier();
+    if (a.q_cs) {                                             // rotary embedding: pairs (c, c + d/2) of the query row
+        const float2* cs = a.q_cs + (static_cast<int64_t>(b) * a.seq + i) * (d / 2);
+        for (int c = lane; c < d / 2; c += kWave) {
+            const float x0 = q_s[w][c], x1 = q_s[w][c + d / 2];
+            const float2 t = cs[c];
+            rope_pair(x0, x1, t.x, t.y, q_s[w][c], q_s[w][c + d / 2]);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
 
     float acc[CIVIC_MAX_HEAD_DIM / kWave];
 #pragma unroll
@@ -419,6 +431,33 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
         }
         // in registers before the area is written again
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        if (a.q_cs != nullptr) {
+            // Rotary embedding of the query row in registers: the lane holds elements 16 s + 8 half + j, and with
+            // head_dim a multiple of 32 the partner of an element, head_dim / 2 further on, sits KSTEPS / 2
+            // k-steps later in the same lane.  (cos, sin) of the row's 8 consecutive pairs come as four 16-byte loads.
+            constexpr int HS = KSTEPS / 2;
+            const float2* cs_row = a.q_cs + (static_cast<int64_t>(b) * a.seq + min(qi, a.seq - 1)) * (DP / 2) + 8 * half;
+#pragma unroll
+            for (int s = 0; s < HS; ++s) {
+                float2 cs[8];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float4 t = reinterpret_cast<const float4*>(cs_row + 16 * s)[v];
+                    cs[2 * v] = make_float2(t.x, t.y);
+                    cs[2 * v + 1] = make_float2(t.z, t.w);
+                }
+                bf16x8 lo = qreg[s], hi = qreg[s + HS];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const float x0 = static_cast<float>(lo[j]), x1 = static_cast<float>(hi[j]);
+                    float r0, r1;
+                    rope_pair(x0, x1, cs[j].x, cs[j].y, r0, r1);
+                    lo[j] = static_cast<__bf16>(r0);
+                    hi[j] = static_cast<__bf16>(r1);
+                }
+                qreg[s] = lo; qreg[s + HS] = hi;
+            }
+        }
     };
     // Loads retire in order and Q was issued first: wait until only the tile's loads are outstanding.
     wait_vmcnt<TLOADS>();
@@ -836,7 +875,7 @@ namespace civic {
 static int prefill_attn(const void* q, const void* k, const void* v, void* out, int dtype, int32_t batch, int32_t seq,
                         int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, const int64_t* q_strides,
                         const int64_t* kv_strides, const int64_t* o_strides, int32_t causal, float softmax_scale,
-                        void* k_cache, void* v_cache, int64_t s_max, int64_t pos0, void* stream)
+                        void* k_cache, void* v_cache, int64_t s_max, int64_t pos0, const float* q_cos_sin, void* stream)
 {
     const int esz = dtype_size(dtype);
     if (!esz || !q_strides || !kv_strides || !o_strides) return CIVIC_ERR_INVALID_ARG;
@@ -855,6 +894,7 @@ static int prefill_attn(const void* q, const void* k, const void* v, void* out, 
         if (pos0 < 0 || s_max < 0 || pos0 + seq > s_max) return CIVIC_ERR_INVALID_ARG;
         if (kv_strides[2] < head_dim && n_kv_heads > 1) return CIVIC_ERR_INVALID_ARG;
     }
+    if (q_cos_sin && (!aligned16(q_cos_sin) || head_dim % 4)) return CIVIC_ERR_INVALID_ARG;
     if (head_dim > CIVIC_MAX_HEAD_DIM || batch > 65535 || n_q_heads > 65535) return CIVIC_ERR_UNSUPPORTED;
     if (batch == 0 || seq == 0) return CIVIC_OK;
 
@@ -867,6 +907,7 @@ static int prefill_attn(const void* q, const void* k, const void* v, void* out, 
     a.heads_per_block = 1; a.row_tiles = 0; a.paired = 0;
     a.group = n_q_heads / n_kv_heads; a.head_blocks = 0; a.hb_shift = 0; a.magic_head_blocks = 0; a.magic_kv_heads = 0;
     a.k_cache = k_cache; a.v_cache = v_cache; a.s_max = s_max; a.pos0 = pos0;
+    a.q_cs = reinterpret_cast<const float2*>(q_cos_sin);
     hipStream_t s = static_cast<hipStream_t>(stream);
 
     // the MFMA path addresses a K/V tile, and a head's Q rows, with 32-bit per-lane byte offsets, and its grid
@@ -876,7 +917,9 @@ static int prefill_attn(const void* q, const void* k, const void* v, void* out, 
     // as many (measured: 32 workgroups of 8 wavefronts 15.4 us, 64 of 4 12.2 us; but 192 of 8 37.9 us against
     // 384 of 4, two per unit, 39.7 us).
     int64_t per_rt = 0;
-    if (dtype == CIVIC_BF16 && head_dim <= 128 && kv_strides[1] * 2 < (1 << 25) &&
+    // (with a rotary table the MFMA kernel needs an unpadded head whose halves are whole k-step pairs)
+    const bool rope_fits = !q_cos_sin || head_dim == 64 || head_dim == 96 || head_dim == 128;
+    if (dtype == CIVIC_BF16 && head_dim <= 128 && rope_fits && kv_strides[1] * 2 < (1 << 25) &&
         static_cast<int64_t>(seq) * q_strides[1] * 2 < (int64_t{1} << 32) && mfma_geometry<8>(a, &per_rt)) {
         if (2 * per_rt * a.row_tiles > kComputeUnits || !mfma_geometry<4>(a, &per_rt)) return launch_mfma_for<8>(a, s);
         return launch_mfma_for<4>(a, s);
@@ -900,7 +943,17 @@ extern "C" int civic_prefill_attn(const void* q, const void* k, const void* v, v
                                   int32_t causal, float softmax_scale, void* stream)
 {
     return civic::prefill_attn(q, k, v, out, dtype, batch, seq, n_q_heads, n_kv_heads, head_dim, q_strides, kv_strides,
-                               o_strides, causal, softmax_scale, nullptr, nullptr, 0, 0, stream);
+                               o_strides, causal, softmax_scale, nullptr, nullptr, 0, 0, nullptr, stream);
+}
+
+extern "C" int civic_prefill_attn_rope(const void* q, const void* k, const void* v, void* out, int dtype, int32_t batch,
+                                       int32_t seq, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                       const int64_t* q_strides, const int64_t* kv_strides, const int64_t* o_strides,
+                                       int32_t causal, float softmax_scale, const float* q_cos_sin, void* stream)
+{
+    if (!q_cos_sin && batch > 0 && seq > 0) return CIVIC_ERR_INVALID_ARG;
+    return civic::prefill_attn(q, k, v, out, dtype, batch, seq, n_q_heads, n_kv_heads, head_dim, q_strides, kv_strides,
+                               o_strides, causal, softmax_scale, nullptr, nullptr, 0, 0, q_cos_sin, stream);
 }
 
 extern "C" int civic_prefill_attn_kv(const void* q, const void* k, const void* v, void* out, void* k_cache, void* v_cache,
@@ -911,5 +964,5 @@ extern "C" int civic_prefill_attn_kv(const void* q, const void* k, const void* v
 {
     if ((!k_cache || !v_cache) && batch > 0 && seq > 0) return CIVIC_ERR_INVALID_ARG;
     return civic::prefill_attn(q, k, v, out, dtype, batch, seq, n_q_heads, n_kv_heads, head_dim, q_strides, kv_strides,
-                               o_strides, causal, softmax_scale, k_cache, v_cache, s_max, pos0, stream);
+                               o_strides, causal, softmax_scale, k_cache, v_cache, s_max, pos0, nullptr, stream);
 }

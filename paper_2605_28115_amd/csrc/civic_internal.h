@@ -72,6 +72,14 @@ __device__ __forceinline__ float wave_sum(float v)
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
+// One frequency pair of the rotary embedding: (x0, x1) turned by the angle whose (cos, sin) is (c, s).  Written
+// with explicit fused multiply-adds so that every kernel that rotates rounds the same way.
+__device__ __forceinline__ void rope_pair(float x0, float x1, float c, float s, float& y0, float& y1)
+{
+    y0 = __builtin_fmaf(x0, c, -(x1 * s));
+    y1 = __builtin_fmaf(x1, c, x0 * s);
+}
+
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
 
 }  // namespace civic

@@ -169,6 +169,34 @@ def test_argument_errors_precede_any_hip_call(bd):
     assert need > 0 and need % 4 == 0
     assert dec(smax=6000, n=5000, ws=None, wsb=0) == bd.ERR_WORKSPACE
     assert dec(smax=6000, n=5000, wsb=need - 4) == bd.ERR_WORKSPACE and dec(smax=6000, n=5000, ws=odd) == bd.ERR_WORKSPACE
+    # rotary calls: tables, head sizes, alignment, cache bounds
+    ax = np.asarray([0, 1, 2, 1], dtype=np.int32); fr = np.asarray([1.0, 0.5, 0.25, 0.1], dtype=np.float32)
+    def table(axis=ax, freq=fr, n=4, pos=F, out=F, b=1, s=8):
+        return L.civic_mrope_table(pos, b, s, n, C.c_void_p(axis.ctypes.data) if axis is not None else None,
+                                   C.c_void_p(freq.ctypes.data) if freq is not None else None, out, None)
+    assert table(axis=None) == I and table(freq=None) == I and table(n=0) == I and table(pos=None) == I and table(out=odd) == I
+    assert table(axis=np.asarray([0, 3, 0, 0], dtype=np.int32)) == I
+    assert table(freq=np.asarray([1.0, np.inf, 0.0, 0.0], dtype=np.float32)) == I
+    assert table(n=129, axis=np.zeros(129, dtype=np.int32), freq=np.zeros(129, dtype=np.float32)) == bd.ERR_UNSUPPORTED
+    assert table(s=0, pos=None, out=None) == bd.CIVIC_OK
+    def apply(**kw):
+        a = dict(x=F, o=F, dt=1, b=1, s=8, h=2, d=64, xs=st, os=st, cs=F)
+        a.update(kw)
+        return L.civic_mrope_apply(a["x"], a["o"], a["dt"], a["b"], a["s"], a["h"], a["d"], a["xs"], a["os"], a["cs"], None)
+    assert apply(d=24) == I and apply(d=63) == I and apply(x=None) == I and apply(cs=None) == I and apply(o=odd) == I
+    assert apply(xs=None) == I and apply(dt=9) == I and apply(d=512) == bd.ERR_UNSUPPORTED and apply(s=0, x=None, o=None, cs=None) == bd.CIVIC_OK
+    def kvr(**kw):
+        a = dict(k=F, v=F, st=st, dt=1, cs=F, kc=F, vc=F, b=1, s=8, h=2, d=64, smax=16, pos0=0)
+        a.update(kw)
+        return L.civic_kv_write_rope(a["k"], a["v"], a["st"], a["dt"], a["cs"], a["kc"], a["vc"], a["b"], a["s"], a["h"], a["d"],
+                                     a["smax"], a["pos0"], None)
+    assert kvr(pos0=9) == I and kvr(d=24) == I and kvr(cs=None) == I and kvr(kc=None) == I and kvr(cs=odd) == I and kvr(s=0) == bd.CIVIC_OK
+    def attn_rope(**kw):
+        a = dict(q=F, k=F, v=F, o=F, dt=1, b=1, s=8, hq=4, hkv=2, d=64, qs=st, ks=st, os=st, causal=1, scale=0.0, cs=F)
+        a.update(kw)
+        return L.civic_prefill_attn_rope(a["q"], a["k"], a["v"], a["o"], a["dt"], a["b"], a["s"], a["hq"], a["hkv"], a["d"],
+                                         a["qs"], a["ks"], a["os"], a["causal"], C.c_float(a["scale"]), a["cs"], None)
+    assert attn_rope(cs=None) == I and attn_rope(cs=odd) == I and attn_rope(hq=3) == I and attn_rope(s=0, cs=None) == bd.CIVIC_OK
     # a tensor without elements needs no pointer: NULL is accepted exactly then
     OK = bd.CIVIC_OK
     assert L.civic_score(None, 1, 0, 64, 64, F, 1.0, None, None) == OK and L.civic_score(F, 1, 0, 64, 64, None, 1.0, F, None) == I
