@@ -59,6 +59,13 @@ def lib() -> C.CDLL:
         L.oracle_kv_write.restype = C.c_int64
         L.oracle_kv_write.argtypes = [P, P, P, P, P, C.c_int32, C.c_int32, C.c_int32, C.c_int64,
                                       C.c_int64, C.c_int64]
+        L.oracle_anchor_aggregate.restype = None
+        L.oracle_anchor_aggregate.argtypes = [P, P, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_double, C.c_double, P, P]
+        L.oracle_kv_compress.restype = None
+        L.oracle_kv_compress.argtypes = [P, P, C.c_int32, C.c_int32, C.c_int32, C.c_int32, P]
+        L.oracle_cross_attention.restype = None
+        L.oracle_cross_attention.argtypes = [P, P, P, P, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                             C.c_double]
         L.oracle_mrope_table.restype = None
         L.oracle_mrope_table.argtypes = [P, C.c_int32, C.c_int64, C.c_int32, P, P, P]
         L.oracle_mrope_apply.restype = None
@@ -226,4 +233,44 @@ def mrope_apply(x: np.ndarray, cos_sin: np.ndarray) -> np.ndarray:
     st = np.asarray([s // 4 for s in x.strides[:3]], dtype=np.int64)
     out = np.empty((batch, seq, heads, d), dtype=np.float64)
     lib().oracle_mrope_apply(_ptr(x), _ptr(st), batch, seq, heads, d // 2, _ptr(cs), _ptr(out))
+    return out
+
+
+def anchor_aggregate(x0: np.ndarray, anchors: np.ndarray, inv_tau: float = 1.0, eps: float = 1e-6,
+                     want_col_sum: bool = False):
+    """Eq. 8: x0 fp32 [batch, T, D], anchors fp32 [M, D] -> z0 float64 [batch, M, D] (and, if asked, the total
+    weight every dense token receives, float64 [batch, T])."""
+    x = np.ascontiguousarray(x0, dtype=np.float32)
+    a = np.ascontiguousarray(anchors, dtype=np.float32)
+    batch, t, d = x.shape
+    m = a.shape[0]
+    assert a.shape == (m, d)
+    z = np.empty((batch, m, d), dtype=np.float64)
+    cs = np.empty((batch, t), dtype=np.float64) if want_col_sum else None
+    lib().oracle_anchor_aggregate(_ptr(x), _ptr(a), batch, t, m, d, float(inv_tau), float(eps), _ptr(z),
+                                  _ptr(cs) if cs is not None else None)
+    return (z, cs) if want_col_sum else z
+
+
+def kv_compress(x: np.ndarray, r: np.ndarray) -> np.ndarray:
+    """Eq. 9: x fp32 [batch, M, width], r fp32 [M, S] -> Rbar^T x, float64 [batch, S, width] (Rbar = r with every
+    column divided by its sum)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    r = np.ascontiguousarray(r, dtype=np.float32)
+    batch, m, width = x.shape
+    assert r.ndim == 2 and r.shape[0] == m
+    out = np.empty((batch, r.shape[1], width), dtype=np.float64)
+    lib().oracle_kv_compress(_ptr(x), _ptr(r), batch, m, r.shape[1], width, _ptr(out))
+    return out
+
+
+def cross_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: Optional[float] = None) -> np.ndarray:
+    """q fp32 [batch, n_q, H_q, d]; k, v fp32 [batch, n_kv, H_kv, d]; no mask -> float64 [batch, n_q, H_q, d]."""
+    q, k, v = (np.ascontiguousarray(a, dtype=np.float32) for a in (q, k, v))
+    batch, n_q, hq, d = q.shape
+    n_kv, hkv = k.shape[1], k.shape[2]
+    assert k.shape == v.shape and k.shape[0] == batch and k.shape[3] == d and hq % hkv == 0
+    out = np.empty((batch, n_q, hq, d), dtype=np.float64)
+    sc = (1.0 / np.sqrt(d)) if scale is None else float(scale)
+    lib().oracle_cross_attention(_ptr(q), _ptr(k), _ptr(v), _ptr(out), batch, n_q, n_kv, hq, hkv, d, sc)
     return out

@@ -29,6 +29,12 @@
  *                            the Qwen-VL family, pairs (i, i + d/2), axis and frequency per pair
  *                            given by the caller: PARITY UNPINNED BY THE PAPER, pinned by the
  *                            complex-multiplication form and the relative-position property.
+ *   oracle_anchor_aggregate  Z_0 = softmax(Q_A K_0^T / tau) X_0, K_0 = Norm(LN(X_0)), Q_A = Norm(LN(A)),
+ *                            softmax over the dense tokens (Eq. 8 in full)
+ *   oracle_kv_compress       K_c = Rbar^T K, V_c = Rbar^T V with the column-normalised assignment
+ *                            matrix (Eq. 9); "column-normalised" is read as every column divided by
+ *                            its sum (the rows of K_c are weighted means): PARITY UNPINNED BY THE PAPER
+ *   oracle_cross_attention   softmax(Q K_c^T / sqrt(d)) V_c, queries and keys of different counts (Eq. 9)
  *   oracle_decode_attention  one generated token attending to the whole compact prompt in
  *                            the cache: the per-token work inside the autoregressive decoding
  *                            cost C_dec of Eq. 2 / Eq. 7 (decode column of the latency table)
@@ -421,5 +427,128 @@ void oracle_mrope_apply(const float *x, const int64_t *x_strides, int32_t batch,
                 o[i + n_pairs] = x1 * c + x0 * sn;
             }
         }
+    }
+}
+
+/* --------------------------------------------------------- Eq. 8: anchor aggregation   */
+/* For every batch item: K_0 = Norm(LN(X_0)) and Q_A = Norm(LN(A)) row by row (LN without
+ * affine, epsilon eps; Norm = division by the l2 norm, a zero row stays zero), logits
+ * Q_A K_0^T * inv_tau, softmax over the T dense tokens for every anchor, Z_0 = W_A X_0.
+ *   x0 [batch, T, D], anchors [M, D] -> z0 [batch, M, D] (double);
+ *   col_sum [batch, T] (may be NULL): sum over the anchors of W_A[a, i], the total weight a
+ *   dense token receives. */
+static void ln_norm_row(const float *x, int32_t dim, double eps, double *out)
+{
+    double mean = 0.0, var = 0.0, nrm = 0.0;
+    for (int32_t j = 0; j < dim; ++j) mean += (double)x[j];
+    mean /= dim;
+    for (int32_t j = 0; j < dim; ++j) { double c = (double)x[j] - mean; var += c * c; }
+    var /= dim;
+    for (int32_t j = 0; j < dim; ++j) { out[j] = ((double)x[j] - mean) / sqrt(var + eps); nrm += out[j] * out[j]; }
+    nrm = sqrt(nrm);
+    for (int32_t j = 0; j < dim; ++j) out[j] = nrm > 0.0 ? out[j] / nrm : 0.0;
+}
+
+void oracle_anchor_aggregate(const float *x0, const float *anchors, int32_t batch, int32_t n_tokens,
+                             int32_t n_anchors, int32_t dim, double inv_tau, double eps, double *z0,
+                             double *col_sum)
+{
+    double *qa = (double *)malloc(sizeof(double) * (size_t)n_anchors * dim);
+    for (int32_t a = 0; a < n_anchors; ++a) ln_norm_row(anchors + (int64_t)a * dim, dim, eps, qa + (int64_t)a * dim);
+    for (int32_t b = 0; b < batch; ++b) {
+        const float *xb = x0 + (int64_t)b * n_tokens * dim;
+        double *k0 = (double *)malloc(sizeof(double) * (size_t)n_tokens * dim);
+        double *w = (double *)malloc(sizeof(double) * (size_t)n_anchors * n_tokens);
+#pragma omp parallel for schedule(static)
+        for (int32_t i = 0; i < n_tokens; ++i) ln_norm_row(xb + (int64_t)i * dim, dim, eps, k0 + (int64_t)i * dim);
+#pragma omp parallel for schedule(static)
+        for (int32_t a = 0; a < n_anchors; ++a) {
+            double *wa = w + (int64_t)a * n_tokens;
+            double zmax = -INFINITY, denom = 0.0;
+            for (int32_t i = 0; i < n_tokens; ++i) {
+                double acc = 0.0;
+                for (int32_t j = 0; j < dim; ++j) acc += qa[(int64_t)a * dim + j] * k0[(int64_t)i * dim + j];
+                wa[i] = acc * inv_tau;
+                if (wa[i] > zmax) zmax = wa[i];
+            }
+            for (int32_t i = 0; i < n_tokens; ++i) { wa[i] = exp(wa[i] - zmax); denom += wa[i]; }
+            for (int32_t i = 0; i < n_tokens; ++i) wa[i] /= denom;
+            double *z = z0 + ((int64_t)b * n_anchors + a) * dim;
+            for (int32_t j = 0; j < dim; ++j) z[j] = 0.0;
+            for (int32_t i = 0; i < n_tokens; ++i)
+                for (int32_t j = 0; j < dim; ++j) z[j] += wa[i] * (double)xb[(int64_t)i * dim + j];
+        }
+        if (col_sum)
+            for (int32_t i = 0; i < n_tokens; ++i) {
+                double t = 0.0;
+                for (int32_t a = 0; a < n_anchors; ++a) t += w[(int64_t)a * n_tokens + i];
+                col_sum[(int64_t)b * n_tokens + i] = t;
+            }
+        free(k0);
+        free(w);
+    }
+    free(qa);
+}
+
+/* ------------------------------------------------- Eq. 9: compressed keys and values   */
+/* out[b, s, :] = sum_m Rbar[m, s] * x[b, m, :] with Rbar[m, s] = R[m, s] / sum_m' R[m', s]
+ * (a column whose sum is zero gives a zero row).  x [batch, M, width] (width = heads *
+ * head_dim), r [M, S] shared by the batch, out [batch, S, width] double. */
+void oracle_kv_compress(const float *x, const float *r, int32_t batch, int32_t n_rows, int32_t n_mem,
+                        int32_t width, double *out)
+{
+    double *colsum = (double *)calloc((size_t)n_mem, sizeof(double));
+    for (int32_t m = 0; m < n_rows; ++m)
+        for (int32_t s = 0; s < n_mem; ++s) colsum[s] += (double)r[(int64_t)m * n_mem + s];
+#pragma omp parallel for schedule(static)
+    for (int64_t w = 0; w < (int64_t)batch * n_mem; ++w) {
+        const int32_t b = (int32_t)(w / n_mem), s = (int32_t)(w % n_mem);
+        double *o = out + w * width;
+        for (int32_t c = 0; c < width; ++c) o[c] = 0.0;
+        if (colsum[s] == 0.0) continue;
+        for (int32_t m = 0; m < n_rows; ++m) {
+            const double wgt = (double)r[(int64_t)m * n_mem + s] / colsum[s];
+            const float *row = x + ((int64_t)b * n_rows + m) * width;
+            for (int32_t c = 0; c < width; ++c) o[c] += wgt * (double)row[c];
+        }
+    }
+    free(colsum);
+}
+
+/* out[b, i, h, :] = sum_{j < n_kv} softmax_j(scale * <q[b,i,h], k[b,j,g]>) v[b,j,g], g = h /
+ * (H_q / H_kv): every query sees every key.  q [batch, n_q, H_q, d], k and v [batch, n_kv,
+ * H_kv, d], all dense; out double [batch, n_q, H_q, d]. */
+void oracle_cross_attention(const float *q, const float *k, const float *v, double *out, int32_t batch,
+                            int32_t n_q, int32_t n_kv, int32_t n_q_heads, int32_t n_kv_heads,
+                            int32_t head_dim, double scale)
+{
+    const int32_t group = n_q_heads / n_kv_heads;
+#pragma omp parallel
+    {
+        double *z = (double *)malloc(sizeof(double) * (size_t)n_kv);
+#pragma omp for schedule(static)
+        for (int64_t w = 0; w < (int64_t)batch * n_q * n_q_heads; ++w) {
+            const int32_t h = (int32_t)(w % n_q_heads);
+            const int32_t b = (int32_t)(w / ((int64_t)n_q * n_q_heads));
+            const int32_t g = h / group;
+            const float *qi = q + w * head_dim;
+            double zmax = -INFINITY, denom = 0.0;
+            for (int32_t j = 0; j < n_kv; ++j) {
+                const float *kj = k + (((int64_t)b * n_kv + j) * n_kv_heads + g) * head_dim;
+                double acc = 0.0;
+                for (int32_t c = 0; c < head_dim; ++c) acc += (double)qi[c] * (double)kj[c];
+                z[j] = scale * acc;
+                if (z[j] > zmax) zmax = z[j];
+            }
+            for (int32_t j = 0; j < n_kv; ++j) { z[j] = exp(z[j] - zmax); denom += z[j]; }
+            double *o = out + w * head_dim;
+            for (int32_t c = 0; c < head_dim; ++c) o[c] = 0.0;
+            for (int32_t j = 0; j < n_kv; ++j) {
+                const float *vj = v + (((int64_t)b * n_kv + j) * n_kv_heads + g) * head_dim;
+                const double p = z[j] / denom;
+                for (int32_t c = 0; c < head_dim; ++c) o[c] += p * (double)vj[c];
+            }
+        }
+        free(z);
     }
 }
