@@ -412,6 +412,35 @@ def main() -> int:
                 "mrope_apply_q": {"us": round(t_apply, 2), "bytes": q_bytes, "gbs": round(q_bytes / t_apply / 1e3, 1),
                                   "frac_hbm_peak": round(q_bytes / t_apply / 1e3 / HBM_PEAK_GBS, 4)}}
 
+    # Encoder-side compaction (the paper's own soft route), timed on the encoder-shaped workload: Eq. 8 from the
+    # dense patch grid to K anchors, and Eq. 9 (KV compression to S memory anchors + attention over them).
+    encoder = None
+    if w.name == "vit":
+        t_e, m_e, d_v, s_mem = w.n_visual, w.kept, w.dim, 256
+        x0 = sets[0].hidden[:, :t_e].contiguous()
+        anchors = torch.randn((m_e, d_v), device="cuda").to(x0.dtype)
+        z0 = torch.empty((w.batch, m_e, d_v), dtype=x0.dtype, device="cuda")
+        ws_a = torch.empty(int(bd.lib.civic_anchor_aggregate_workspace_bytes(w.batch, t_e, m_e, d_v)), dtype=torch.uint8, device="cuda")
+        kq = sets[0].k[:, :m_e].contiguous(); vq = sets[0].v[:, :m_e].contiguous(); qq = sets[0].q[:, :m_e].contiguous()
+        r = torch.rand((m_e, s_mem), device="cuda") ** 4
+        kc = torch.empty((w.batch, s_mem, w.n_kv_heads, w.head_dim), dtype=x0.dtype, device="cuda"); vc = torch.empty_like(kc)
+        ws_c = torch.empty(int(bd.lib.civic_kv_compress_workspace_bytes(w.batch, m_e, s_mem, w.n_kv_heads * w.head_dim)), dtype=torch.uint8, device="cuda")
+        oc = torch.empty_like(qq)
+        t_agg = alone(lambda s_: bd.civic_anchor_aggregate(x0, anchors, 14.0, z0=z0, workspace=ws_a))
+        t_cmp = alone(lambda s_: bd.civic_kv_compress(kq, vq, r, k_c=kc, v_c=vc, workspace=ws_c))
+        t_x = alone(lambda s_: bd.civic_cross_attn(qq, kc, vc, out=oc))
+        t_full = alone(lambda s_: bd.civic_prefill_attn(qq, kq, vq, False, out=oc))
+        f_agg = 4.0 * m_e * t_e * d_v * w.batch
+        f_cmp = 4.0 * s_mem * m_e * w.n_kv_heads * w.head_dim * w.batch
+        f_x = 4.0 * w.n_q_heads * w.head_dim * m_e * s_mem * w.batch
+        encoder = {"tokens": t_e, "anchors": m_e, "dim": d_v, "memory_anchors": s_mem,
+                   "anchor_aggregate": {"us": round(t_agg, 2), "flops": f_agg, "tflops": round(f_agg / t_agg / 1e6, 1),
+                                        "frac_mfma_peak": round(f_agg / t_agg / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4),
+                                        "workspace_bytes": ws_a.numel(), "launches": 6},
+                   "kv_compress": {"us": round(t_cmp, 2), "flops": f_cmp, "tflops": round(f_cmp / t_cmp / 1e6, 1)},
+                   "cross_attn": {"us": round(t_x, 2), "flops": f_x, "tflops": round(f_x / t_x / 1e6, 1)},
+                   "uncompressed_attn_us": round(t_full, 2)}
+
     # the selection runs once per prompt, the attention and the KV write once per layer: one measured step plus
     # layers - 1 further attention launches (in-step duration)
     per_layer_us = attn_us + (stage_us["kv_write"]["mean"] if args.unfused else 0.0)
@@ -422,6 +451,8 @@ def main() -> int:
         result["decode"] = decode
     if rope is not None:
         result["rope"] = rope
+    if encoder is not None:
+        result["encoder"] = encoder
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(result), flush=True)

@@ -262,6 +262,46 @@ int civic_prefill_attn_rope(const void* q, const void* k, const void* v, void* o
                             const int64_t* kv_strides /* host [3] */, const int64_t* o_strides /* host [3] */,
                             int32_t causal, float softmax_scale, const float* q_cos_sin, void* stream);
 
+/* Soft anchor aggregation, Eq. 8 in full - the paper's own, learned route from T_e dense patch embeddings to M_e
+ * compact tokens, before the visual encoder:
+ *   K_0 = Norm(LN(X_0)),  Q_A = Norm(LN(A)),  W_A = softmax(Q_A K_0^T / tau) over the dense tokens,  Z_0 = W_A X_0.
+ * LN without affine (its epsilon cancels under Norm); a row without variance normalises to zero.  K_0, Q_A and
+ * W_A are rounded to bf16 for the two contractions (bf16 MFMA, fp32 accumulation); the softmax is fp32.
+ *   x0            device [batch, n_tokens, dim] bf16, dense
+ *   anchors       device [n_anchors, dim] bf16: A itself, not normalised (shared by the batch)
+ *   z0            device [batch, n_anchors, dim] bf16
+ *   token_weight  device [batch, n_tokens] fp32 or NULL: sum over the anchors of W_A[a, i], the weight each dense
+ *                 token receives (a multi-anchor importance score that civic_select accepts)
+ *   workspace     device, 16-byte aligned, civic_anchor_aggregate_workspace_bytes(same sizes) bytes: normalised
+ *                 rows, logits, weights, X_0 transposed; no initialisation needed
+ * dtype must be CIVIC_BF16 and dim a multiple of 64 (else CIVIC_ERR_UNSUPPORTED); inv_tau >= 0, finite. */
+size_t civic_anchor_aggregate_workspace_bytes(int32_t batch, int32_t n_tokens, int32_t n_anchors, int32_t dim);
+int civic_anchor_aggregate(const void* x0, const void* anchors, int dtype, int32_t batch, int32_t n_tokens,
+                           int32_t n_anchors, int32_t dim, float inv_tau, void* z0, float* token_weight,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* KV compression of the compact visual encoder, Eq. 9: K_c = Rbar^T K and V_c = Rbar^T V, where R [n_rows, n_mem]
+ * assigns the n_rows compact tokens to n_mem memory anchors and Rbar is R "column-normalised", read here as every
+ * column divided by its sum (each compressed key is a weighted mean of keys; a column that sums to zero gives a
+ * zero row).  The paper does not say how R is produced; it is an input.
+ *   k, v      device [batch, n_rows, width] bf16, dense (width = heads * head_dim)
+ *   r         device [n_rows, n_mem] fp32, shared by the batch
+ *   k_c, v_c  device [batch, n_mem, width] bf16
+ *   workspace device, 16-byte aligned, civic_kv_compress_workspace_bytes(same sizes) bytes
+ * Rbar is rounded to bf16 for the contraction (bf16 MFMA, fp32 accumulation).  dtype must be CIVIC_BF16. */
+size_t civic_kv_compress_workspace_bytes(int32_t batch, int32_t n_rows, int32_t n_mem, int32_t width);
+int civic_kv_compress(const void* k, const void* v, int dtype, const float* r, int32_t batch, int32_t n_rows,
+                      int32_t n_mem, int32_t width, void* k_c, void* v_c, void* workspace, size_t workspace_bytes,
+                      void* stream);
+
+/* Attention of n_q queries over n_kv keys without a mask, out = softmax(Q K^T * scale) V: with the compressed
+ * K_c, V_c of civic_kv_compress this is the compact visual attention of Eq. 9 (score size M_e x S instead of
+ * M_e x M_e).  Same kernels, layouts, strides and limits as civic_prefill_attn; k and v hold n_kv tokens. */
+int civic_cross_attn(const void* q, const void* k, const void* v, void* out, int dtype, int32_t batch, int32_t n_q,
+                     int32_t n_kv, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                     const int64_t* q_strides /* host [3] */, const int64_t* kv_strides /* host [3] */,
+                     const int64_t* o_strides /* host [3] */, float softmax_scale, void* stream);
+
 /* Decode-step attention over the compact cache: the work one generated token adds to the autoregressive
  * decoding cost C_dec of Eq. 2 / Eq. 7, in which "every generated text token must attend to the entire visual
  * prompt" (latency decomposition, decode column of the latency table) - here to the compact one that

@@ -24,7 +24,9 @@ EXPORTS = ("civic_last_hip_error", "civic_kept_count", "civic_select_workspace_b
            "civic_compact_workspace_bytes", "civic_anchor_normalize", "civic_score", "civic_score_visual", "civic_select",
            "civic_compact", "civic_prefill_attn", "civic_kv_write", "civic_prefill_attn_kv",
            "civic_decode_attn_workspace_bytes", "civic_decode_attn", "civic_decode_attn_noalloc",
-           "civic_mrope_table", "civic_mrope_apply", "civic_kv_write_rope", "civic_prefill_attn_rope")
+           "civic_mrope_table", "civic_mrope_apply", "civic_kv_write_rope", "civic_prefill_attn_rope",
+           "civic_anchor_aggregate_workspace_bytes", "civic_anchor_aggregate", "civic_kv_compress_workspace_bytes",
+           "civic_kv_compress", "civic_cross_attn")
 
 
 class CivicError(RuntimeError):
@@ -88,6 +90,18 @@ lib.civic_decode_attn_noalloc.restype = C.c_int
 lib.civic_decode_attn_noalloc.argtypes = [_P, _P, _P, _P, C.c_int, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int64,
                                           C.c_float, _P]
 DECODE_NOALLOC_MAX_BYTES = 4 << 20
+lib.civic_anchor_aggregate_workspace_bytes.restype = C.c_size_t
+lib.civic_anchor_aggregate_workspace_bytes.argtypes = [C.c_int32] * 4
+lib.civic_anchor_aggregate.restype = C.c_int
+lib.civic_anchor_aggregate.argtypes = [_P, _P, C.c_int, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_float, _P, _P, _P,
+                                       C.c_size_t, _P]
+lib.civic_kv_compress_workspace_bytes.restype = C.c_size_t
+lib.civic_kv_compress_workspace_bytes.argtypes = [C.c_int32] * 4
+lib.civic_kv_compress.restype = C.c_int
+lib.civic_kv_compress.argtypes = [_P, _P, C.c_int, _P, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _P, _P, _P, C.c_size_t, _P]
+lib.civic_cross_attn.restype = C.c_int
+lib.civic_cross_attn.argtypes = [_P, _P, _P, _P, C.c_int, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                 _P, _P, _P, C.c_float, _P]
 lib.civic_mrope_table.restype = C.c_int
 lib.civic_mrope_table.argtypes = [_P, C.c_int32, C.c_int64, C.c_int32, _P, _P, _P, _P]
 lib.civic_mrope_apply.restype = C.c_int
@@ -392,4 +406,59 @@ def civic_prefill_attn_rope(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, q
                                                                   hq, k.shape[2], d, _strides3(q), _strides3(k), _strides3(out),
                                                                   int(bool(causal)), float(softmax_scale), _dev(q_cos_sin),
                                                                   _stream(stream)))
+    return out
+
+
+def civic_anchor_aggregate(x0: torch.Tensor, anchors: torch.Tensor, inv_tau: float = 1.0, want_token_weight: bool = False,
+                           z0: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None):
+    """Eq. 8: x0 [batch, T, D], anchors [M, D] (bf16) -> z0 [batch, M, D] (and the per-token weight [batch, T] fp32)."""
+    if x0.dim() != 3 or anchors.dim() != 2 or not x0.is_contiguous() or not anchors.is_contiguous() or x0.dtype != anchors.dtype:
+        raise ValueError("x0 [batch, T, D] and anchors [M, D] must be contiguous and of one dtype")
+    batch, t, d = x0.shape
+    m = anchors.shape[0]
+    if anchors.shape[1] != d:
+        raise ValueError("anchors must be [M, D]")
+    if z0 is None:
+        z0 = torch.empty((batch, m, d), dtype=x0.dtype, device=x0.device)
+    tw = torch.empty((batch, t), dtype=torch.float32, device=x0.device) if want_token_weight else None
+    if workspace is None:
+        workspace = torch.empty(int(lib.civic_anchor_aggregate_workspace_bytes(batch, t, m, d)), dtype=torch.uint8, device=x0.device)
+    _check("civic_anchor_aggregate", lib.civic_anchor_aggregate(_dev(x0), _dev(anchors), _dtype_code(x0), batch, t, m, d,
+                                                                float(inv_tau), _dev(z0), _dev(tw), _dev(workspace),
+                                                                workspace.numel(), _stream(stream)))
+    return (z0, tw) if want_token_weight else z0
+
+
+def civic_kv_compress(k: torch.Tensor, v: torch.Tensor, r: torch.Tensor, k_c: Optional[torch.Tensor] = None,
+                      v_c: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None):
+    """Eq. 9: k, v [batch, M, ...] (trailing axes flattened to the width), r fp32 [M, S] -> k_c, v_c [batch, S, ...]."""
+    if k.shape != v.shape or not k.is_contiguous() or not v.is_contiguous() or not r.is_contiguous() or r.dtype != torch.float32:
+        raise ValueError("k and v must be contiguous of one shape, r contiguous fp32 [M, S]")
+    batch, m = k.shape[0], k.shape[1]
+    width = int(np.prod(k.shape[2:]))
+    if r.shape[0] != m:
+        raise ValueError("r must be [M, S]")
+    s_mem = r.shape[1]
+    if k_c is None:
+        k_c = torch.empty((batch, s_mem) + tuple(k.shape[2:]), dtype=k.dtype, device=k.device)
+    if v_c is None:
+        v_c = torch.empty_like(k_c)
+    if workspace is None:
+        workspace = torch.empty(int(lib.civic_kv_compress_workspace_bytes(batch, m, s_mem, width)), dtype=torch.uint8, device=k.device)
+    _check("civic_kv_compress", lib.civic_kv_compress(_dev(k), _dev(v), _dtype_code(k), _dev(r), batch, m, s_mem, width, _dev(k_c),
+                                                      _dev(v_c), _dev(workspace), workspace.numel(), _stream(stream)))
+    return k_c, v_c
+
+
+def civic_cross_attn(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, softmax_scale: float = 0.0,
+                     out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """q [batch, n_q, H_q, d] over k, v [batch, n_kv, H_kv, d], no mask."""
+    if k.shape != v.shape or k.stride() != v.stride() or q.dtype != k.dtype or q.dtype != v.dtype:
+        raise ValueError("k and v must share shape, strides and dtype with q's dtype")
+    batch, n_q, hq, d = q.shape
+    if out is None:
+        out = torch.empty((batch, n_q, hq, d), dtype=q.dtype, device=q.device)
+    _check("civic_cross_attn", lib.civic_cross_attn(_dev(q), _dev(k), _dev(v), _dev(out), _dtype_code(q), batch, n_q, k.shape[1], hq,
+                                                    k.shape[2], d, _strides3(q), _strides3(k), _strides3(out), float(softmax_scale),
+                                                    _stream(stream)))
     return out

@@ -49,6 +49,7 @@ struct AttnArgs {
     const void* q; const void* k; const void* v; void* out;
     int64_t qs[3], ks[3], os[3];          // element strides: batch, token, head
     int32_t batch, seq, n_q_heads, n_kv_heads, head_dim, causal;
+    int32_t kv_seq;                       // keys per sample (= seq except for civic_cross_attn, which has no mask)
     float scale;                          // softmax scale (natural-exponent domain)
     int32_t heads_per_block, row_tiles;   // MFMA path: block shape and number of 32*rows_per_block tiles
     int32_t paired;                       // MFMA path: a workgroup walks two row tiles, a heavy and a light one
@@ -107,7 +108,7 @@ __global__ __launch_bounds__(256) void attn_plain_kernel(AttnArgs a)
 #pragma unroll
     for (int t = 0; t < CIVIC_MAX_HEAD_DIM / kWave; ++t) acc[t] = 0.f;
     float m = -INFINITY, l = 0.f;
-    const int last = a.causal ? i : a.seq - 1;
+    const int last = a.causal ? i : a.kv_seq - 1;
     for (int j0 = 0; j0 <= last; j0 += kWave) {
         const int j = j0 + lane;
         float z = -INFINITY;
@@ -328,7 +329,7 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
         row0 = block_row0 + wrow;                             // this wavefront's first query row
         block_rows_end = min(block_row0 + RB * 32, a.seq);
         qi = row0 + col;                                      // this lane's query row
-        const int kv_end = a.causal ? block_rows_end : a.seq; // keys [0, kv_end) are visible to the block
+        const int kv_end = a.causal ? block_rows_end : a.kv_seq; // keys [0, kv_end) are visible to the block
         n_tiles = (kv_end + kBN - 1) / kBN;
     };
     set_rows(rt);
@@ -386,7 +387,7 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
     // stored).  The tile's first key enters through the scalar base, so the per-lane offsets are loop
     // invariant; only the tile that holds the end of the sequence needs the clamped set.
     uint32_t ld_voff[NI], ld_voff_tail[NI];
-    const int tail_tile = (a.seq - 1) / kBN;                  // the tile that may run past the sequence
+    const int tail_tile = (a.kv_seq - 1) / kBN;               // the tile that may run past the keys
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
         const int slot = (w * NI + j) * kWave + lane;
@@ -394,7 +395,7 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
         const int c = (slot % PITCH) ^ swz<PITCH>(row);
         const uint32_t cb = (c * 8 < a.head_dim) ? c * 16 : 0;
         ld_voff[j] = row * row_bytes + cb;
-        ld_voff_tail[j] = (min(tail_tile * kBN + row, a.seq - 1) - tail_tile * kBN) * row_bytes + cb;
+        ld_voff_tail[j] = (min(tail_tile * kBN + row, a.kv_seq - 1) - tail_tile * kBN) * row_bytes + cb;
     }
     const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(
         static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds)) + w * NI * kWave * 16);
@@ -519,11 +520,11 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
         __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
 
         // mask only where the tile crosses the diagonal or the end of the sequence (wave-uniform)
-        if ((a.causal && key0 + kBN - 1 > row0) || key0 + kBN > a.seq) {
+        if ((a.causal && key0 + kBN - 1 > row0) || key0 + kBN > a.kv_seq) {
             // The lane sees the tile's keys below `lim` (end of the sequence, and its own row under the causal
             // mask).  Register r of sub-tile t holds tile key 32 t + 8 (r / 4) + r % 4 + 4 half, so one
             // per-lane threshold against a constant per register decides: a compare and a select each.
-            int lim = a.seq - key0;
+            int lim = a.kv_seq - key0;
             if (a.causal) lim = min(lim, qi - key0 + 1);
             const int thr = lim - 4 * half;
 #pragma unroll
@@ -624,7 +625,7 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
         // only: half the MFMAs and exponentials of that tile for half of the wavefronts, which the other
         // wavefront of the SIMD turns into time.  The same holds for a last tile whose second half lies past
         // the end of the sequence.
-        if ((a.causal && kt * kBN + 32 > row0 + 31) || kt * kBN + 32 >= a.seq) tile(kt, stage_c, std::integral_constant<int, 1>{});
+        if ((a.causal && kt * kBN + 32 > row0 + 31) || kt * kBN + 32 >= a.kv_seq) tile(kt, stage_c, std::integral_constant<int, 1>{});
         else tile(kt, stage_c, std::integral_constant<int, 2>{});
     };
 
@@ -873,13 +874,15 @@ namespace civic {
 // Attention, and the KV-cache write when k_cache is not null (inside the attention kernel where the
 // MFMA path runs, as a second launch otherwise).
 static int prefill_attn(const void* q, const void* k, const void* v, void* out, int dtype, int32_t batch, int32_t seq,
-                        int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, const int64_t* q_strides,
+                        int32_t kv_seq, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, const int64_t* q_strides,
                         const int64_t* kv_strides, const int64_t* o_strides, int32_t causal, float softmax_scale,
                         void* k_cache, void* v_cache, int64_t s_max, int64_t pos0, const float* q_cos_sin, void* stream)
 {
     const int esz = dtype_size(dtype);
     if (!esz || !q_strides || !kv_strides || !o_strides) return CIVIC_ERR_INVALID_ARG;
-    if (batch < 0 || seq < 0 || n_q_heads <= 0 || n_kv_heads <= 0 || head_dim <= 0) return CIVIC_ERR_INVALID_ARG;
+    if (batch < 0 || seq < 0 || kv_seq < 0 || n_q_heads <= 0 || n_kv_heads <= 0 || head_dim <= 0) return CIVIC_ERR_INVALID_ARG;
+    if (causal && kv_seq != seq) return CIVIC_ERR_INVALID_ARG;
+    if (seq > 0 && kv_seq == 0) return CIVIC_ERR_INVALID_ARG;                             // a softmax over no key has no value
     if (batch > 0 && seq > 0 && (!q || !k || !v || !out)) return CIVIC_ERR_INVALID_ARG;   // no tokens: no tensors
     if (n_q_heads % n_kv_heads) return CIVIC_ERR_INVALID_ARG;
     if (head_dim % 8) return CIVIC_ERR_INVALID_ARG;
@@ -901,7 +904,7 @@ static int prefill_attn(const void* q, const void* k, const void* v, void* out, 
     AttnArgs a;
     a.q = q; a.k = k; a.v = v; a.out = out;
     for (int i = 0; i < 3; ++i) { a.qs[i] = q_strides[i]; a.ks[i] = kv_strides[i]; a.os[i] = o_strides[i]; }
-    a.batch = batch; a.seq = seq; a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads; a.head_dim = head_dim;
+    a.batch = batch; a.seq = seq; a.kv_seq = kv_seq; a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads; a.head_dim = head_dim;
     a.causal = causal ? 1 : 0;
     a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt(static_cast<float>(head_dim));
     a.heads_per_block = 1; a.row_tiles = 0; a.paired = 0;
@@ -942,7 +945,7 @@ extern "C" int civic_prefill_attn(const void* q, const void* k, const void* v, v
                                   const int64_t* q_strides, const int64_t* kv_strides, const int64_t* o_strides,
                                   int32_t causal, float softmax_scale, void* stream)
 {
-    return civic::prefill_attn(q, k, v, out, dtype, batch, seq, n_q_heads, n_kv_heads, head_dim, q_strides, kv_strides,
+    return civic::prefill_attn(q, k, v, out, dtype, batch, seq, seq, n_q_heads, n_kv_heads, head_dim, q_strides, kv_strides,
                                o_strides, causal, softmax_scale, nullptr, nullptr, 0, 0, nullptr, stream);
 }
 
@@ -952,7 +955,7 @@ extern "C" int civic_prefill_attn_rope(const void* q, const void* k, const void*
                                        int32_t causal, float softmax_scale, const float* q_cos_sin, void* stream)
 {
     if (!q_cos_sin && batch > 0 && seq > 0) return CIVIC_ERR_INVALID_ARG;
-    return civic::prefill_attn(q, k, v, out, dtype, batch, seq, n_q_heads, n_kv_heads, head_dim, q_strides, kv_strides,
+    return civic::prefill_attn(q, k, v, out, dtype, batch, seq, seq, n_q_heads, n_kv_heads, head_dim, q_strides, kv_strides,
                                o_strides, causal, softmax_scale, nullptr, nullptr, 0, 0, q_cos_sin, stream);
 }
 
@@ -963,6 +966,14 @@ extern "C" int civic_prefill_attn_kv(const void* q, const void* k, const void* v
                                      float softmax_scale, void* stream)
 {
     if ((!k_cache || !v_cache) && batch > 0 && seq > 0) return CIVIC_ERR_INVALID_ARG;
-    return civic::prefill_attn(q, k, v, out, dtype, batch, seq, n_q_heads, n_kv_heads, head_dim, q_strides, kv_strides,
+    return civic::prefill_attn(q, k, v, out, dtype, batch, seq, seq, n_q_heads, n_kv_heads, head_dim, q_strides, kv_strides,
                                o_strides, causal, softmax_scale, k_cache, v_cache, s_max, pos0, nullptr, stream);
+}
+
+extern "C" int civic_cross_attn(const void* q, const void* k, const void* v, void* out, int dtype, int32_t batch, int32_t n_q,
+                                int32_t n_kv, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, const int64_t* q_strides,
+                                const int64_t* kv_strides, const int64_t* o_strides, float softmax_scale, void* stream)
+{
+    return civic::prefill_attn(q, k, v, out, dtype, batch, n_q, n_kv, n_q_heads, n_kv_heads, head_dim, q_strides, kv_strides,
+                               o_strides, 0, softmax_scale, nullptr, nullptr, 0, 0, nullptr, stream);
 }

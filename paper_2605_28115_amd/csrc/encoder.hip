@@ -1,0 +1,547 @@
+// Encoder-side compaction of CIVIC, the paper's own (learned, soft) route to a compact sequence:
+//   civic_anchor_aggregate  Eq. 8: Z_0 = softmax(Q_A K_0^T / tau) X_0 with K_0 = Norm(LN(X_0)), Q_A = Norm(LN(A)),
+//                           softmax over the dense tokens
+//   civic_kv_compress       Eq. 9: K_c = Rbar^T K, V_c = Rbar^T V with the column-normalised assignment matrix
+// (the attention over the compressed keys, softmax(Q K_c^T / sqrt(d)) V_c, is civic_cross_attn in attn.hip).
+//
+// Both are dense contractions and run on the bf16 MFMA pipe through one kernel, C = alpha * A B^T with both
+// operands stored with the contraction index contiguous ("NT").  Operands whose contraction index is the slow
+// one in the caller's layout (X_0 in Z_0 = W_A X_0; K, V and R in Eq. 9) are first transposed into scratch with
+// the contraction length zero-padded to a multiple of 64, so the GEMM has no tail in that direction; row and
+// column tails are clamped loads and masked stores.
+//   - 128 x 128 output tile per 256-thread workgroup, 64 x 64 per wavefront (2 x 2 blocks of
+//     v_mfma_f32_32x32x16_bf16, fp32 accumulators), 64 contraction elements per LDS tile.
+//   - A and B tiles go from global memory straight into a two-stage LDS ring (global_load_lds_dwordx4), rows at a
+//     128-byte pitch with the 16-byte chunks XOR-swizzled by the row, so that the 128-bit operand reads of 32
+//     adjacent rows fall on distinct banks; one tile ahead, explicit vmcnt waits, fence-free barriers.  Two
+//     workgroups share a compute unit.  (A four-stage ring, 128 KB and one workgroup per unit, was slower, 46.6
+//     against 35.3 us on the 1365 x 4096 x 1152 logits: the kernel is bound by the L2 -> LDS traffic of its 128 x 128
+//     tiles, 64 FLOP per byte, not by the latency of a tile.)
+// The softmax of Eq. 8 runs over rows of 4096 logits and more, too long for a fused epilogue: the logits go to
+// scratch in fp32, a row kernel turns them into bf16 weights, the second GEMM consumes those.
+#include <cmath>
+
+#include "civic_internal.h"
+
+namespace civic {
+
+typedef __bf16 enc_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float enc_f32x16 __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) char enc_lds_char;
+
+constexpr int kGemmBM = 128, kGemmBN = 128, kGemmBK = 64;
+constexpr int kGemmThreads = 256;
+constexpr int kGemmTileBytes = kGemmBM * kGemmBK * 2;         // one operand tile: 16 KB
+constexpr int kGemmStages = 2;                                 // tiles in the LDS ring (2 or 4): all but one in flight ahead of the one consumed
+constexpr int kGemmLds = 2 * kGemmStages * kGemmTileBytes;     // A ring, then B ring
+
+struct GemmArgs {
+    const __bf16* a; const __bf16* b; void* c;
+    int64_t lda, ldb, ldc;             // elements between rows
+    int64_t sa, sb, sc;                // elements between batch items (0 = shared)
+    int32_t m, n, k;                   // k a multiple of 64
+    float alpha;
+};
+
+template <int LDS_IMM>
+__device__ __forceinline__ void enc_dma16(const void* base, uint32_t byte_off, uint32_t lds_addr)
+{
+    // 16 bytes per lane from base + byte_off (scalar base, per-lane offset) into LDS at lds_addr + LDS_IMM + lane * 16
+    asm volatile("s_add_u32 m0, %0, %3\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(byte_off), "s"(base), "n"(LDS_IMM) : "memory", "scc");
+}
+
+__device__ __forceinline__ const char* enc_uniform(const void* p)
+{
+    const uint64_t bits = reinterpret_cast<uint64_t>(p);
+    const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(bits >> 32)));
+    const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(bits)));
+    return reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | lo);
+}
+
+// physical chunk = logical chunk ^ swz(row): rows 0..31 of a 128-byte-pitch tile, same logical chunk -> 32 banks groups
+__device__ __forceinline__ int enc_swz(int row) { return (((row >> 1) & 1) << 2) | ((row >> 2) & 3); }
+
+template <bool C_BF16>
+__global__ __launch_bounds__(kGemmThreads, 2) void gemm_nt_kernel(GemmArgs g)
+{
+    extern __shared__ __attribute__((aligned(16))) char gemm_lds[];
+    enc_lds_char* const lds = (enc_lds_char*)gemm_lds;       // the A stages, then the B stages
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid >> 6;
+    const int col = lane & 31, half = lane >> 5;
+    const int wm = w >> 1, wn = w & 1;                        // the wavefront's 64 x 64 quadrant
+    const int m0 = blockIdx.y * kGemmBM, n0 = blockIdx.x * kGemmBN;
+    const int64_t bz = blockIdx.z;
+
+    // global -> LDS: instruction j of wavefront w fills slots [(4 w + j) * 64, +64) of a tile; slot -> (row, physical chunk)
+    const char* a_base = reinterpret_cast<const char*>(g.a + bz * g.sa + static_cast<int64_t>(m0) * g.lda);
+    const char* b_base = reinterpret_cast<const char*>(g.b + bz * g.sb + static_cast<int64_t>(n0) * g.ldb);
+    uint32_t a_off[4], b_off[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int slot = (w * 4 + j) * kWave + lane;
+        const int row = slot >> 3;
+        const int c = (slot & 7) ^ enc_swz(row);
+        a_off[j] = static_cast<uint32_t>(min(row, g.m - 1 - m0)) * static_cast<uint32_t>(g.lda * 2) + c * 16;
+        b_off[j] = static_cast<uint32_t>(min(row, g.n - 1 - n0)) * static_cast<uint32_t>(g.ldb * 2) + c * 16;
+    }
+    const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds)) + w * 4 * kWave * 16);
+    auto issue = [&](int kt, auto stage_c) {
+        constexpr int st = decltype(stage_c)::value;
+        const char* ab = enc_uniform(a_base + static_cast<int64_t>(kt) * kGemmBK * 2);
+        const char* bb = enc_uniform(b_base + static_cast<int64_t>(kt) * kGemmBK * 2);
+        enc_dma16<st * kGemmTileBytes + 0 * 1024>(ab, a_off[0], lds_wave);
+        enc_dma16<st * kGemmTileBytes + 1 * 1024>(ab, a_off[1], lds_wave);
+        enc_dma16<st * kGemmTileBytes + 2 * 1024>(ab, a_off[2], lds_wave);
+        enc_dma16<st * kGemmTileBytes + 3 * 1024>(ab, a_off[3], lds_wave);
+        enc_dma16<(kGemmStages + st) * kGemmTileBytes + 0 * 1024>(bb, b_off[0], lds_wave);
+        enc_dma16<(kGemmStages + st) * kGemmTileBytes + 1 * 1024>(bb, b_off[1], lds_wave);
+        enc_dma16<(kGemmStages + st) * kGemmTileBytes + 2 * 1024>(bb, b_off[2], lds_wave);
+        enc_dma16<(kGemmStages + st) * kGemmTileBytes + 3 * 1024>(bb, b_off[3], lds_wave);
+    };
+
+    // operand reads: row (quadrant row 32 i + col), logical chunk 2 s + half; the swizzle depends on row bits 1..3 only,
+    // so the second row block is the first plus a constant
+    enc_lds_char* a_addr[4];
+    enc_lds_char* b_addr[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        a_addr[s] = lds + (wm * 64 + col) * 128 + (((2 * s + half) ^ enc_swz(col)) << 4);
+        b_addr[s] = lds + kGemmStages * kGemmTileBytes + (wn * 64 + col) * 128 + (((2 * s + half) ^ enc_swz(col)) << 4);
+        asm volatile("" : "+v"(a_addr[s]), "+v"(b_addr[s]));
+    }
+
+    enc_f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int n_tiles = g.k / kGemmBK;
+    issue(0, std::integral_constant<int, 0>{});
+    if constexpr (kGemmStages == 4) {
+        if (n_tiles > 1) issue(1, std::integral_constant<int, 1>{});
+        if (n_tiles > 2) issue(2, std::integral_constant<int, 2>{});
+    }
+    // Loads retire in order, 8 per tile and wavefront: tile kt has landed once at most 8 * (tiles issued after it)
+    // loads are outstanding.
+    auto wait_landed = [&](int younger) {
+        if (younger >= 2) __builtin_amdgcn_s_waitcnt(0x0F70 | 16);       // vmcnt(16)
+        else if (younger == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | 8);   // vmcnt(8)
+        else __builtin_amdgcn_s_waitcnt(0x0F70);                         // vmcnt(0)
+    };
+    auto step = [&](int kt, auto stage_c) __attribute__((always_inline)) {
+        constexpr int st = decltype(stage_c)::value;
+        wait_landed(min(n_tiles - 1 - kt, kGemmStages - 2));
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();                         // landed for every wavefront; the stage of tile kt - 1 is free
+        asm volatile("" ::: "memory");
+        if (kt + kGemmStages - 1 < n_tiles) issue(kt + kGemmStages - 1, std::integral_constant<int, (st + kGemmStages - 1) % kGemmStages>{});
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            enc_bf16x8 af[2], bf[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                af[i] = *reinterpret_cast<const __attribute__((address_space(3))) enc_bf16x8*>(a_addr[s] + st * kGemmTileBytes + i * 32 * 128);
+                bf[i] = *reinterpret_cast<const __attribute__((address_space(3))) enc_bf16x8*>(b_addr[s] + st * kGemmTileBytes + i * 32 * 128);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+        }
+        // the operands of one k-step (four reads) stay in flight ahead of the MFMAs that consume them
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+        for (int i = 0; i < 12; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+    };
+    for (int kt = 0; kt < n_tiles; kt += kGemmStages) {
+        step(kt, std::integral_constant<int, 0>{});
+        if (kt + 1 < n_tiles) step(kt + 1, std::integral_constant<int, 1>{});
+        if constexpr (kGemmStages == 4) {
+            if (kt + 2 < n_tiles) step(kt + 2, std::integral_constant<int, 2>{});
+            if (kt + 3 < n_tiles) step(kt + 3, std::integral_constant<int, 3>{});
+        }
+    }
+
+    // register r of block (i, j): row 32 i + 8 (r / 4) + r % 4 + 4 half, column 32 j + col
+    char* c_base = static_cast<char*>(g.c) + (bz * g.sc) * (C_BF16 ? 2 : 4);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = m0 + wm * 64 + 32 * i + 8 * (r >> 2) + (r & 3) + 4 * half;
+                const int cc = n0 + wn * 64 + 32 * j + col;
+                if (row < g.m && cc < g.n) {
+                    const float val = acc[i][j][r] * g.alpha;
+                    const int64_t idx = static_cast<int64_t>(row) * g.ldc + cc;
+                    if constexpr (C_BF16) reinterpret_cast<__bf16*>(c_base)[idx] = static_cast<__bf16>(val);
+                    else reinterpret_cast<float*>(c_base)[idx] = val;
+                }
+            }
+}
+
+static int launch_gemm_nt(const GemmArgs& g, int batch, bool c_bf16, hipStream_t s)
+{
+    const dim3 grid(static_cast<unsigned>((g.n + kGemmBN - 1) / kGemmBN), static_cast<unsigned>((g.m + kGemmBM - 1) / kGemmBM),
+                    static_cast<unsigned>(batch));
+    static std::atomic<uint64_t> allowed_bf16{0}, allowed_f32{0};
+    const int rc = c_bf16 ? allow_dynamic_lds(reinterpret_cast<const void*>(gemm_nt_kernel<true>), kGemmLds, &allowed_bf16)
+                          : allow_dynamic_lds(reinterpret_cast<const void*>(gemm_nt_kernel<false>), kGemmLds, &allowed_f32);
+    if (rc != CIVIC_OK) return rc;
+    if (c_bf16) hipLaunchKernelGGL((gemm_nt_kernel<true>), grid, dim3(kGemmThreads), kGemmLds, s, g);
+    else hipLaunchKernelGGL((gemm_nt_kernel<false>), grid, dim3(kGemmThreads), kGemmLds, s, g);
+    return check_launch();
+}
+
+// ------------------------------------------------------------------------------------------ row kernels
+template <bool BF16>
+__device__ __forceinline__ float enc_load(const void* p, int64_t i)
+{
+    if constexpr (BF16) return bf16_bits_to_float(static_cast<const uint16_t*>(p)[i]);
+    else return static_cast<const float*>(p)[i];
+}
+
+// out[row, :] = Norm(LN(x[row, :])) = (x - mean) / ||x - mean|| as bf16 (a row without variance gives zeros); one
+// wavefront per row, three passes over a row that stays in L1/L2 after the first.
+template <bool BF16>
+__global__ __launch_bounds__(256) void ln_norm_rows_kernel(const void* __restrict__ x, int64_t rows, int32_t dim, int64_t ld_in,
+                                                           __bf16* __restrict__ out, int64_t ld_out)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const int64_t base = row * ld_in;
+    float sum = 0.f;
+    for (int j = lane; j < dim; j += kWave) sum += enc_load<BF16>(x, base + j);
+    const float mean = wave_sum(sum) / static_cast<float>(dim);
+    float n2 = 0.f;
+    for (int j = lane; j < dim; j += kWave) { const float c = enc_load<BF16>(x, base + j) - mean; n2 = fmaf(c, c, n2); }
+    n2 = wave_sum(n2);
+    const float inv = n2 > 0.f ? 1.0f / sqrtf(n2) : 0.f;
+    for (int j = lane; j < dim; j += kWave) out[row * ld_out + j] = static_cast<__bf16>((enc_load<BF16>(x, base + j) - mean) * inv);
+}
+
+// p[row, 0..cols) = softmax(s[row, 0..cols)) as bf16, p[row, cols..ld_p) = 0; one wavefront per row.  Rows of up to
+// 64 * 4 * CH logits (ld_s a multiple of 4) stay in registers between the maximum, the exponentials and the store: one
+// trip to memory; longer rows take the three-pass loop.
+template <int CH>
+__global__ __launch_bounds__(256) void row_softmax_kernel(const float* __restrict__ s, int64_t rows, int32_t cols, int64_t ld_s,
+                                                          __bf16* __restrict__ p, int64_t ld_p)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const float* src = s + row * ld_s;
+    __bf16* dst = p + row * ld_p;
+    if constexpr (CH > 0) {
+        float4 v[CH];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            const int j = (c * kWave + lane) * 4;
+            v[c] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+            if (j < cols) v[c] = *reinterpret_cast<const float4*>(src + j);   // (ld_s is padded: the vector stays inside the row)
+            if (j + 1 >= cols) v[c].y = -INFINITY;
+            if (j + 2 >= cols) v[c].z = -INFINITY;
+            if (j + 3 >= cols) v[c].w = -INFINITY;
+            mx = fmaxf(mx, fmaxf(fmaxf(v[c].x, v[c].y), fmaxf(v[c].z, v[c].w)));
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+        float sum = 0.f;
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            v[c].x = __expf(v[c].x - mx); v[c].y = __expf(v[c].y - mx); v[c].z = __expf(v[c].z - mx); v[c].w = __expf(v[c].w - mx);
+            sum += (v[c].x + v[c].y) + (v[c].z + v[c].w);
+        }
+        const float inv = 1.0f / wave_sum(sum);
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            const int j = (c * kWave + lane) * 4;
+            if (j < ld_p) {                                                   // (ld_p is a multiple of 64)
+                const __bf16 o[4] = {static_cast<__bf16>(v[c].x * inv), static_cast<__bf16>(v[c].y * inv),
+                                     static_cast<__bf16>(v[c].z * inv), static_cast<__bf16>(v[c].w * inv)};
+                u32x2 packed;
+                packed.x = static_cast<uint32_t>(__builtin_bit_cast(uint16_t, o[0])) | (static_cast<uint32_t>(__builtin_bit_cast(uint16_t, o[1])) << 16);
+                packed.y = static_cast<uint32_t>(__builtin_bit_cast(uint16_t, o[2])) | (static_cast<uint32_t>(__builtin_bit_cast(uint16_t, o[3])) << 16);
+                *reinterpret_cast<u32x2*>(dst + j) = packed;
+            }
+        }
+    } else {
+        float mx = -INFINITY;
+        for (int j = lane; j < cols; j += kWave) mx = fmaxf(mx, src[j]);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+        float sum = 0.f;
+        for (int j = lane; j < cols; j += kWave) sum += __expf(src[j] - mx);
+        const float inv = 1.0f / wave_sum(sum);
+        for (int j = lane; j < ld_p; j += kWave) dst[j] = static_cast<__bf16>(j < cols ? __expf(src[j] - mx) * inv : 0.f);
+    }
+}
+
+// out[b, j] = sum over rows of p[b, row, j]: the weight a dense token receives from all anchors together.
+__global__ __launch_bounds__(256) void col_sum_kernel(const __bf16* __restrict__ p, int32_t rows, int32_t cols, int64_t ld_p,
+                                                      int64_t batch_stride, float* __restrict__ out)
+{
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t b = blockIdx.y;
+    if (j >= cols) return;
+    const __bf16* src = p + b * batch_stride + j;
+    float acc = 0.f;
+    for (int r = 0; r < rows; ++r) acc += static_cast<float>(src[static_cast<int64_t>(r) * ld_p]);
+    out[b * cols + j] = acc;
+}
+
+// out[b, c, r] = in[b, r, c] * scale[c] (scale may be null) for r < rows, 0 for rows <= r < ld_out; 32 x 32 tiles through LDS.
+template <typename TIN>
+__global__ __launch_bounds__(256) void transpose_pad_kernel(const TIN* __restrict__ in, int32_t rows, int32_t cols, int64_t ld_in,
+                                                            int64_t in_batch, const float* __restrict__ scale,
+                                                            __bf16* __restrict__ out, int64_t ld_out, int64_t out_batch)
+{
+    __shared__ float tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
+    const int r0 = blockIdx.x * 32, c0 = blockIdx.y * 32;
+    const int64_t b = blockIdx.z;
+    for (int k = ty; k < 32; k += 8) {
+        const int r = r0 + k, c = c0 + tx;
+        float v = 0.f;
+        if (r < rows && c < cols) {
+            if constexpr (std::is_same<TIN, float>::value) v = in[b * in_batch + static_cast<int64_t>(r) * ld_in + c];
+            else v = static_cast<float>(in[b * in_batch + static_cast<int64_t>(r) * ld_in + c]);
+        }
+        tile[k][tx] = v;
+    }
+    __syncthreads();
+    for (int k = ty; k < 32; k += 8) {
+        const int c = c0 + k, r = r0 + tx;
+        if (c < cols && r < ld_out) {
+            const float sc = scale ? scale[c] : 1.0f;
+            out[b * out_batch + static_cast<int64_t>(c) * ld_out + r] = static_cast<__bf16>(tile[tx][k] * sc);
+        }
+    }
+}
+
+// Column sums of r [rows, cols] in two steps: block (x, y) adds the rows y, y + gridDim.y, ... of 64 columns (its four
+// wavefronts four rows apart, coalesced 256-byte reads, meeting in LDS) into part[y, c]; the second kernel turns the
+// partial sums of a column into inv[c] = 1 / sum (0 for a column that sums to zero).
+constexpr int kColParts = 32;
+__global__ __launch_bounds__(256) void col_part_sum_kernel(const float* __restrict__ r, int32_t rows, int32_t cols, float* __restrict__ part)
+{
+    __shared__ float lds_part[4][kWave];
+    const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
+    const int c = blockIdx.x * kWave + lane;
+    float acc = 0.f;
+    if (c < cols)
+        for (int m = blockIdx.y * 4 + wv; m < rows; m += 4 * kColParts) acc += r[static_cast<int64_t>(m) * cols + c];
+    lds_part[wv][lane] = acc;
+    __syncthreads();
+    if (wv == 0 && c < cols)
+        part[static_cast<int64_t>(blockIdx.y) * cols + c] = (lds_part[0][lane] + lds_part[1][lane]) + (lds_part[2][lane] + lds_part[3][lane]);
+}
+
+__global__ __launch_bounds__(256) void col_inv_kernel(const float* __restrict__ part, int32_t cols, float* __restrict__ inv)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= cols) return;
+    float t = 0.f;
+#pragma unroll
+    for (int p = 0; p < kColParts; ++p) t += part[static_cast<int64_t>(p) * cols + c];
+    inv[c] = t != 0.f ? 1.0f / t : 0.f;
+}
+
+static int64_t pad64(int64_t x) { return (x + 63) / 64 * 64; }
+static size_t align256(size_t x) { return (x + 255) / 256 * 256; }
+
+struct AggPlan {                         // byte offsets into the workspace of civic_anchor_aggregate
+    int64_t t_pad;
+    size_t qa, k0, s, p, xt, total;
+};
+
+static void agg_plan(int32_t batch, int32_t n_tokens, int32_t n_anchors, int32_t dim, AggPlan* p)
+{
+    p->t_pad = pad64(n_tokens);
+    size_t off = 0;
+    p->qa = off; off += align256(static_cast<size_t>(n_anchors) * dim * 2);
+    p->k0 = off; off += align256(static_cast<size_t>(batch) * n_tokens * dim * 2);
+    p->s = off;  off += align256(static_cast<size_t>(batch) * n_anchors * p->t_pad * 4);
+    p->p = off;  off += align256(static_cast<size_t>(batch) * n_anchors * p->t_pad * 2);
+    p->xt = off; off += align256(static_cast<size_t>(batch) * dim * p->t_pad * 2);
+    p->total = off;
+}
+
+struct CompressPlan {                    // byte offsets into the workspace of civic_kv_compress
+    int64_t m_pad;
+    size_t inv, part, rt, xt, total;
+};
+
+static void compress_plan(int32_t batch, int32_t n_rows, int32_t n_mem, int32_t width, CompressPlan* p)
+{
+    p->m_pad = pad64(n_rows);
+    size_t off = 0;
+    p->inv = off; off += align256(static_cast<size_t>(n_mem) * 4);
+    p->part = off; off += align256(static_cast<size_t>(n_mem) * 4 * kColParts);
+    p->rt = off;  off += align256(static_cast<size_t>(n_mem) * p->m_pad * 2);
+    p->xt = off;  off += align256(static_cast<size_t>(batch) * width * p->m_pad * 2);
+    p->total = off;
+}
+
+static bool agg_sizes_ok(int32_t batch, int32_t n_tokens, int32_t n_anchors, int32_t dim)
+{
+    return batch >= 0 && n_tokens > 0 && n_anchors > 0 && dim > 0;
+}
+
+}  // namespace civic
+
+extern "C" size_t civic_anchor_aggregate_workspace_bytes(int32_t batch, int32_t n_tokens, int32_t n_anchors, int32_t dim)
+{
+    if (!civic::agg_sizes_ok(batch, n_tokens, n_anchors, dim)) return 0;
+    civic::AggPlan p;
+    civic::agg_plan(batch, n_tokens, n_anchors, dim, &p);
+    return p.total;
+}
+
+extern "C" int civic_anchor_aggregate(const void* x0, const void* anchors, int dtype, int32_t batch, int32_t n_tokens,
+                                      int32_t n_anchors, int32_t dim, float inv_tau, void* z0, float* token_weight,
+                                      void* workspace, size_t workspace_bytes, void* stream)
+{
+    using namespace civic;
+    const int esz = dtype_size(dtype);
+    if (!esz || !agg_sizes_ok(batch, n_tokens, n_anchors, dim)) return CIVIC_ERR_INVALID_ARG;
+    if (!(inv_tau >= 0.f) || std::isinf(inv_tau)) return CIVIC_ERR_INVALID_ARG;
+    if (batch > 0 && (!x0 || !anchors || !z0)) return CIVIC_ERR_INVALID_ARG;
+    if (!aligned16(x0) || !aligned16(anchors) || !aligned16(z0) || (reinterpret_cast<uintptr_t>(token_weight) & 3u)) return CIVIC_ERR_INVALID_ARG;
+    if (dim % 64) return CIVIC_ERR_UNSUPPORTED;                          // the first contraction runs over dim in tiles of 64
+    if (dtype != CIVIC_BF16) return CIVIC_ERR_UNSUPPORTED;               // z0 leaves the MFMA path as bf16
+    if (batch > 65535 || static_cast<int64_t>(n_tokens) * dim * 2 >= (int64_t{1} << 32) ||
+        static_cast<int64_t>(n_anchors) * pad64(n_tokens) * 2 >= (int64_t{1} << 32))
+        return CIVIC_ERR_UNSUPPORTED;                                     // 32-bit row offsets inside one batch item
+    AggPlan p;
+    agg_plan(batch, n_tokens, n_anchors, dim, &p);
+    if (!workspace || workspace_bytes < p.total || !aligned16(workspace)) return CIVIC_ERR_WORKSPACE;
+    if (batch == 0) return CIVIC_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* ws = static_cast<char*>(workspace);
+    __bf16* qa = reinterpret_cast<__bf16*>(ws + p.qa);
+    __bf16* k0 = reinterpret_cast<__bf16*>(ws + p.k0);
+    float* sl = reinterpret_cast<float*>(ws + p.s);
+    __bf16* pw = reinterpret_cast<__bf16*>(ws + p.p);
+    __bf16* xt = reinterpret_cast<__bf16*>(ws + p.xt);
+    const int64_t rows_x = static_cast<int64_t>(batch) * n_tokens;
+
+    // Q_A = Norm(LN(A)), K_0 = Norm(LN(X_0))
+    hipLaunchKernelGGL((ln_norm_rows_kernel<true>), dim3(static_cast<unsigned>((n_anchors + 3) / 4)), dim3(256), 0, s, anchors,
+                       static_cast<int64_t>(n_anchors), dim, static_cast<int64_t>(dim), qa, static_cast<int64_t>(dim));
+    hipLaunchKernelGGL((ln_norm_rows_kernel<true>), dim3(static_cast<unsigned>((rows_x + 3) / 4)), dim3(256), 0, s, x0, rows_x, dim,
+                       static_cast<int64_t>(dim), k0, static_cast<int64_t>(dim));
+    // X_0^T with the token axis zero-padded to a multiple of 64
+    hipLaunchKernelGGL((transpose_pad_kernel<__bf16>), dim3(static_cast<unsigned>(p.t_pad / 32), static_cast<unsigned>((dim + 31) / 32),
+                                                            static_cast<unsigned>(batch)),
+                       dim3(256), 0, s, static_cast<const __bf16*>(x0), n_tokens, dim, static_cast<int64_t>(dim),
+                       static_cast<int64_t>(n_tokens) * dim, static_cast<const float*>(nullptr), xt, p.t_pad, static_cast<int64_t>(dim) * p.t_pad);
+    int rc = check_launch();
+    if (rc != CIVIC_OK) return rc;
+    // logits = Q_A K_0^T / tau  [n_anchors x n_tokens] per batch item, fp32
+    GemmArgs g1;
+    g1.a = qa; g1.b = k0; g1.c = sl;
+    g1.lda = dim; g1.ldb = dim; g1.ldc = p.t_pad;
+    g1.sa = 0; g1.sb = static_cast<int64_t>(n_tokens) * dim; g1.sc = static_cast<int64_t>(n_anchors) * p.t_pad;
+    g1.m = n_anchors; g1.n = n_tokens; g1.k = dim; g1.alpha = inv_tau;
+    rc = launch_gemm_nt(g1, batch, false, s);
+    if (rc != CIVIC_OK) return rc;
+    // W_A = softmax over the dense tokens, bf16, zero in the padding
+    const int64_t rows_w = static_cast<int64_t>(batch) * n_anchors;
+    {
+        const dim3 grid(static_cast<unsigned>((rows_w + 3) / 4));
+        const int chunks = static_cast<int>((p.t_pad / 4 + kWave - 1) / kWave);       // float4 per lane
+#define CIVIC_SOFTMAX_CASE(N) hipLaunchKernelGGL((row_softmax_kernel<N>), grid, dim3(256), 0, s, sl, rows_w, n_tokens, p.t_pad, pw, p.t_pad)
+        if (chunks <= 4) CIVIC_SOFTMAX_CASE(4);
+        else if (chunks <= 8) CIVIC_SOFTMAX_CASE(8);
+        else if (chunks <= 16) CIVIC_SOFTMAX_CASE(16);
+        else if (chunks <= 32) CIVIC_SOFTMAX_CASE(32);
+        else CIVIC_SOFTMAX_CASE(0);
+#undef CIVIC_SOFTMAX_CASE
+    }
+    if (token_weight)
+        hipLaunchKernelGGL(col_sum_kernel, dim3(static_cast<unsigned>((n_tokens + 255) / 256), static_cast<unsigned>(batch)), dim3(256), 0, s,
+                           pw, n_anchors, n_tokens, p.t_pad, static_cast<int64_t>(n_anchors) * p.t_pad, token_weight);
+    rc = check_launch();
+    if (rc != CIVIC_OK) return rc;
+    // Z_0 = W_A X_0 = W_A (X_0^T)^T
+    GemmArgs g2;
+    g2.a = pw; g2.b = xt; g2.c = z0;
+    g2.lda = p.t_pad; g2.ldb = p.t_pad; g2.ldc = dim;
+    g2.sa = static_cast<int64_t>(n_anchors) * p.t_pad; g2.sb = static_cast<int64_t>(dim) * p.t_pad; g2.sc = static_cast<int64_t>(n_anchors) * dim;
+    g2.m = n_anchors; g2.n = dim; g2.k = static_cast<int32_t>(p.t_pad); g2.alpha = 1.0f;
+    return launch_gemm_nt(g2, batch, true, s);
+}
+
+extern "C" size_t civic_kv_compress_workspace_bytes(int32_t batch, int32_t n_rows, int32_t n_mem, int32_t width)
+{
+    if (batch < 0 || n_rows <= 0 || n_mem <= 0 || width <= 0) return 0;
+    civic::CompressPlan p;
+    civic::compress_plan(batch, n_rows, n_mem, width, &p);
+    return p.total;
+}
+
+extern "C" int civic_kv_compress(const void* k, const void* v, int dtype, const float* r, int32_t batch, int32_t n_rows,
+                                 int32_t n_mem, int32_t width, void* k_c, void* v_c, void* workspace, size_t workspace_bytes,
+                                 void* stream)
+{
+    using namespace civic;
+    const int esz = dtype_size(dtype);
+    if (!esz || batch < 0 || n_rows <= 0 || n_mem <= 0 || width <= 0) return CIVIC_ERR_INVALID_ARG;
+    if (!r || (batch > 0 && (!k || !v || !k_c || !v_c))) return CIVIC_ERR_INVALID_ARG;
+    if (!aligned16(k) || !aligned16(v) || !aligned16(k_c) || !aligned16(v_c) || !aligned16(r)) return CIVIC_ERR_INVALID_ARG;
+    if (dtype != CIVIC_BF16) return CIVIC_ERR_UNSUPPORTED;
+    if (batch > 65535 || pad64(n_rows) * static_cast<int64_t>(width) * 2 >= (int64_t{1} << 32) ||
+        pad64(n_rows) * static_cast<int64_t>(n_mem) * 2 >= (int64_t{1} << 32))
+        return CIVIC_ERR_UNSUPPORTED;
+    CompressPlan p;
+    compress_plan(batch, n_rows, n_mem, width, &p);
+    if (!workspace || workspace_bytes < p.total || !aligned16(workspace)) return CIVIC_ERR_WORKSPACE;
+    if (batch == 0) return CIVIC_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* ws = static_cast<char*>(workspace);
+    float* inv = reinterpret_cast<float*>(ws + p.inv);
+    __bf16* rt = reinterpret_cast<__bf16*>(ws + p.rt);
+    __bf16* xt = reinterpret_cast<__bf16*>(ws + p.xt);
+    // Rbar^T [n_mem x m_pad]: every column of R over its sum, transposed, zero beyond n_rows
+    float* part = reinterpret_cast<float*>(ws + p.part);
+    hipLaunchKernelGGL(col_part_sum_kernel, dim3(static_cast<unsigned>((n_mem + kWave - 1) / kWave), kColParts), dim3(256), 0, s, r, n_rows,
+                       n_mem, part);
+    hipLaunchKernelGGL(col_inv_kernel, dim3(static_cast<unsigned>((n_mem + 255) / 256)), dim3(256), 0, s, part, n_mem, inv);
+    hipLaunchKernelGGL((transpose_pad_kernel<float>), dim3(static_cast<unsigned>(p.m_pad / 32), static_cast<unsigned>((n_mem + 31) / 32), 1u),
+                       dim3(256), 0, s, r, n_rows, n_mem, static_cast<int64_t>(n_mem), int64_t{0}, inv, rt, p.m_pad, int64_t{0});
+    int rc = check_launch();
+    if (rc != CIVIC_OK) return rc;
+    const void* src[2] = {k, v};
+    void* dst[2] = {k_c, v_c};
+    for (int t = 0; t < 2; ++t) {
+        // X^T [width x m_pad] per batch item, then X_c = Rbar^T X = Rbar^T (X^T)^T
+        hipLaunchKernelGGL((transpose_pad_kernel<__bf16>), dim3(static_cast<unsigned>(p.m_pad / 32), static_cast<unsigned>((width + 31) / 32),
+                                                                static_cast<unsigned>(batch)),
+                           dim3(256), 0, s, static_cast<const __bf16*>(src[t]), n_rows, width, static_cast<int64_t>(width),
+                           static_cast<int64_t>(n_rows) * width, static_cast<const float*>(nullptr), xt, p.m_pad,
+                           static_cast<int64_t>(width) * p.m_pad);
+        rc = check_launch();
+        if (rc != CIVIC_OK) return rc;
+        GemmArgs g;
+        g.a = rt; g.b = xt; g.c = dst[t];
+        g.lda = p.m_pad; g.ldb = p.m_pad; g.ldc = width;
+        g.sa = 0; g.sb = static_cast<int64_t>(width) * p.m_pad; g.sc = static_cast<int64_t>(n_mem) * width;
+        g.m = n_mem; g.n = width; g.k = static_cast<int32_t>(p.m_pad); g.alpha = 1.0f;
+        rc = launch_gemm_nt(g, batch, true, s);
+        if (rc != CIVIC_OK) return rc;
+    }
+    return CIVIC_OK;
+}

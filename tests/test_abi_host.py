@@ -197,6 +197,29 @@ def test_argument_errors_precede_any_hip_call(bd):
         return L.civic_prefill_attn_rope(a["q"], a["k"], a["v"], a["o"], a["dt"], a["b"], a["s"], a["hq"], a["hkv"], a["d"],
                                          a["qs"], a["ks"], a["os"], a["causal"], C.c_float(a["scale"]), a["cs"], None)
     assert attn_rope(cs=None) == I and attn_rope(cs=odd) == I and attn_rope(hq=3) == I and attn_rope(s=0, cs=None) == bd.CIVIC_OK
+    # encoder-side calls
+    def agg(**kw):
+        a = dict(x=F, a=F, dt=1, b=1, t=100, m=10, d=64, tau=1.0, z=F, tw=None, ws=F, wsb=1 << 40)
+        a.update(kw)
+        return L.civic_anchor_aggregate(a["x"], a["a"], a["dt"], a["b"], a["t"], a["m"], a["d"], C.c_float(a["tau"]), a["z"], a["tw"],
+                                        a["ws"], a["wsb"], None)
+    assert agg(x=None) == I and agg(a=odd) == I and agg(t=0) == I and agg(m=0) == I and agg(tau=-1.0) == I and agg(dt=4) == I
+    assert agg(d=72) == bd.ERR_UNSUPPORTED and agg(dt=0) == bd.ERR_UNSUPPORTED
+    assert agg(ws=None) == bd.ERR_WORKSPACE and agg(wsb=1000) == bd.ERR_WORKSPACE
+    assert bd.lib.civic_anchor_aggregate_workspace_bytes(1, 100, 10, 64) > 0 and bd.lib.civic_anchor_aggregate_workspace_bytes(1, 0, 10, 64) == 0
+    assert agg(b=0, x=None, z=None) == bd.CIVIC_OK
+    def comp(**kw):
+        a = dict(k=F, v=F, dt=1, r=F, b=1, m=100, s=10, w=64, kc=F, vc=F, ws=F, wsb=1 << 40)
+        a.update(kw)
+        return L.civic_kv_compress(a["k"], a["v"], a["dt"], a["r"], a["b"], a["m"], a["s"], a["w"], a["kc"], a["vc"], a["ws"], a["wsb"], None)
+    assert comp(k=None) == I and comp(r=None) == I and comp(m=0) == I and comp(s=0) == I and comp(vc=odd) == I
+    assert comp(dt=0) == bd.ERR_UNSUPPORTED and comp(ws=None) == bd.ERR_WORKSPACE and comp(wsb=10) == bd.ERR_WORKSPACE
+    def cross(**kw):
+        a = dict(q=F, k=F, v=F, o=F, dt=1, b=1, nq=8, nkv=5, hq=4, hkv=2, d=64, qs=st, ks=st, os=st, scale=0.0)
+        a.update(kw)
+        return L.civic_cross_attn(a["q"], a["k"], a["v"], a["o"], a["dt"], a["b"], a["nq"], a["nkv"], a["hq"], a["hkv"], a["d"],
+                                  a["qs"], a["ks"], a["os"], C.c_float(a["scale"]), None)
+    assert cross(nkv=0) == I and cross(nkv=-1) == I and cross(hq=3) == I and cross(k=None) == I and cross(nq=0, nkv=0) == bd.CIVIC_OK
     # a tensor without elements needs no pointer: NULL is accepted exactly then
     OK = bd.CIVIC_OK
     assert L.civic_score(None, 1, 0, 64, 64, F, 1.0, None, None) == OK and L.civic_score(F, 1, 0, 64, 64, None, 1.0, F, None) == I
