@@ -23,6 +23,9 @@ namespace civic {
 constexpr int kCompactThreads = 256;
 constexpr int kCompactMaxRows = 64;   // compact rows per block (LDS table size)
 constexpr int kCompactUnroll = 4;
+#ifndef CIVIC_COMPACT_BLOCKS_PER_CU
+#define CIVIC_COMPACT_BLOCKS_PER_CU 8   // target number of workgroups per compute unit (a build-time knob for A/B runs)
+#endif
 
 struct FrameTable {
     int32_t n;                          // frames
@@ -55,6 +58,18 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
     const int32_t F = ft.n, hw = ft.hw;
     auto frame_of = [&](int32_t v) { return min(max(v / hw, 0), F - 1); };
 
+    // A block whose rows all lie before the first frame or behind the last kept visual token holds text only,
+    // and the sources of such rows follow from the counts alone (nothing is dropped before the first frame,
+    // everything that is dropped lies before the text at the end): no look at the list.  These blocks start
+    // to move rows at once, which fills the memory system while the others are still reading the list.
+    const int32_t first_vis = ft.start[0];
+    const int32_t after_vis = ft.start[F - 1] - (F - 1) * hw + n_kept;
+    const bool text_only = j0 + nrows <= first_vis || j0 >= after_vis;
+    if (text_only) {
+        const int32_t shift = j0 >= after_vis ? F * hw - n_kept : 0;
+        for (int32_t r = tid; r < nrows; r += kCompactThreads) row_src[r] = j0 + r + shift;
+        __syncthreads();
+    } else {
     // Long kept lists (more than one batch below): reading the whole list in every block would cost a
     // memory round trip per batch and more L2 traffic than the rows themselves.  Two round trips
     // suffice: (1) every thread probes one entry out of P, which brackets each frame boundary between
@@ -162,6 +177,7 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
         }
     }
     __syncthreads();
+    }
 
     for (int32_t r = tid; r < nrows; r += kCompactThreads) {
         const int32_t src = min(max(row_src[r], 0), seq_len - 1);
@@ -292,7 +308,7 @@ extern "C" int civic_compact(const void* hidden, int dtype, int32_t dim, const i
     // Rows per block: small blocks win (about 8 per CU on 256 CUs keep more loads in flight, and the
     // per-block pass over kept_idx is a few KB of L2 hits), as long as every thread has a vector to move.
     const int64_t total_rows = seq_c * batch;
-    int64_t rpb = total_rows / (256 * 8);
+    int64_t rpb = total_rows / (256 * CIVIC_COMPACT_BLOCKS_PER_CU);
     const int64_t min_rows = 256 / tpr > 2 ? 256 / tpr : 2;
     if (rpb < min_rows) rpb = min_rows;
     if (rpb > kCompactMaxRows) rpb = kCompactMaxRows;
