@@ -7,7 +7,9 @@ A step is one pass of the whole path over one batch of synthetic input already r
 civic_score_visual (the visual rows scored where they lie in the dense sequence) -> civic_select (on
 the scores just written) -> civic_compact -> civic_prefill_attn_kv (attention and the KV-cache write
 of the same K/V as one call; --unfused runs civic_prefill_attn -> civic_kv_write instead), back to
-back on one stream, for one transformer layer.  Buffers rotate over R independent sets so that
+back on one stream, for one transformer layer.  The timed step issues the first three through
+civic_compact_prefill, the library's one-call front (the same three kernels, one crossing from Python;
+--separate-calls issues them one by one).  Buffers rotate over R independent sets so that
 consecutive steps do not find their inputs in the last-level cache.
 
 Order of a run: an untimed pre-warm of full steps for --prewarm-ms of wall time (the chip's clock
@@ -110,6 +112,10 @@ def make_stage_calls(bd, w: wl.Workload, fs):
     def compact(s):
         bd.civic_compact(s.hidden, s.pos, grid, fs, s.kept, hidden_c=s.hidden_c, pos_c=s.pos_c, src_idx=s.src_idx)
 
+    def front(s):
+        bd.civic_compact_prefill(s.hidden, s.pos, grid, fs, s.anchor_q, 1.0, scores=s.scores, kept_idx=s.kept,
+                                 hidden_c=s.hidden_c, pos_c=s.pos_c, src_idx=s.src_idx)
+
     def attn(s):
         bd.civic_prefill_attn(s.q, s.k, s.v, w.causal, 0.0, out=s.out)
 
@@ -119,8 +125,8 @@ def make_stage_calls(bd, w: wl.Workload, fs):
     def attn_kv(s):
         bd.civic_prefill_attn_kv(s.q, s.k, s.v, s.k_cache, s.v_cache, 0, w.causal, 0.0, out=s.out)
 
-    return dict(score=score, select=select, select_dist=select_dist, compact=compact, attn=attn, kv_write=kv_write,
-                attn_kv=attn_kv)
+    return dict(score=score, select=select, select_dist=select_dist, compact=compact, front=front, attn=attn,
+                kv_write=kv_write, attn_kv=attn_kv)
 
 
 def algorithmic_work(w: wl.Workload) -> dict:
@@ -185,6 +191,8 @@ def main() -> int:
                     help="transformer layers N_l of the amortised figure: score, select and compact once, attention and "
                          "KV write per layer (28 = the layer count the paper's Table 1 KV sizes imply for its 2B model)")
     ap.add_argument("--unfused", action="store_true", help="attention and KV write as two calls")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="the timed step calls score_visual, select and compact one by one instead of civic_compact_prefill")
     ap.add_argument("--prewarm-ms", type=float, default=150.0,
                     help="untimed full steps for this much wall time ahead of --warmup (0 = none)")
     ap.add_argument("--stage-launches", type=int, default=200,
@@ -219,9 +227,13 @@ def main() -> int:
     STAGES = STAGES_UNFUSED if args.unfused else STAGES_FUSED
     order = [calls[s] for s in STAGES]
 
+    # the timed step: the front of the path as one library call (the same three kernels; one crossing from Python
+    # instead of three), then attention and the KV write
+    step_calls = order if args.separate_calls else [calls["front"]] + order[3:]
+
     def step(i):
         s = sets[i % len(sets)]
-        for c in order:
+        for c in step_calls:
             c(s)
 
     # untimed pre-warm by wall time: the clocks settle under load, whatever --warmup and --steps are
@@ -332,7 +344,9 @@ def main() -> int:
                    "batch": w.batch, "seq_dense": w.seq_len, "seq_compact": w.seq_compact, "visual_tokens": w.n_visual,
                    "kept_visual": w.kept, "hidden": w.dim, "heads": f"{w.n_q_heads}q/{w.n_kv_heads}kv x {w.head_dim}",
                    "causal": w.causal, "layers_timed": 1, "buffer_sets": len(sets),
-                   "calls": "+".join(STAGES).replace("score", "score_visual"), "stage_launches": n_alone},
+                   "calls": ("+".join(STAGES).replace("score", "score_visual") if args.separate_calls
+                             else "compact_prefill(score_visual,select,compact)+" + "+".join(STAGES[3:])),
+                   "stage_launches": n_alone},
         "dense_equivalent_tokens_per_s": round(w.batch * w.seq_len / (ms_per_step * 1e-3), 1),
         "stages": stages,
         "roofline": roofline,

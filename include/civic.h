@@ -166,6 +166,19 @@ int civic_compact(const void* hidden, int dtype, int32_t dim, const int32_t* pos
                   void* hidden_c, int32_t* pos_c, int32_t* src_idx,
                   void* workspace, size_t workspace_bytes, void* stream);
 
+/* The front of the path in one call: civic_score_visual (Eq. 8), civic_select (budget and
+ * floors) and civic_compact (Eq. 13) enqueued back to back on `stream`, with n_kept =
+ * civic_kept_count(grid).  The results are those of the three calls, bit for bit; what the
+ * call saves is host time (one crossing from the caller's language instead of three).
+ * Arguments as in the three calls; scores [batch, N_v] and kept_idx [batch, K] are outputs
+ * here (intermediate results the caller may want).  Every check of every stage runs before
+ * the first launch. */
+int civic_compact_prefill(const void* hidden, int dtype, int32_t batch, int64_t seq_len, int32_t dim,
+                          const int32_t* pos_ids, const civic_grid* grid /* host */,
+                          const int64_t* frame_start /* host */, const float* anchor_q, float inv_tau,
+                          float* scores, int32_t* kept_idx, void* hidden_c, int32_t* pos_c,
+                          int32_t* src_idx, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Prefill attention over the compact sequence: out[b,i,h,:] = sum_j softmax_j(scale *
  * <q[b,i,h,:], k[b,j,g,:]>) v[b,j,g,:] with g = h / (n_q_heads / n_kv_heads); j <= i when
  * causal (order of the compact sequence, not the position ids), every j otherwise.

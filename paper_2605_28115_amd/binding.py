@@ -22,7 +22,7 @@ MAX_VISUAL_TOKENS, MAX_FRAMES, MAX_SCORE_DIM, MAX_HEAD_DIM = 32768, 128, 8192, 2
 
 EXPORTS = ("civic_last_hip_error", "civic_kept_count", "civic_select_workspace_bytes",
            "civic_compact_workspace_bytes", "civic_anchor_normalize", "civic_score", "civic_score_visual", "civic_select",
-           "civic_compact", "civic_prefill_attn", "civic_kv_write", "civic_prefill_attn_kv",
+           "civic_compact", "civic_compact_prefill", "civic_prefill_attn", "civic_kv_write", "civic_prefill_attn_kv",
            "civic_decode_attn_workspace_bytes", "civic_decode_attn", "civic_decode_attn_noalloc",
            "civic_mrope_table", "civic_mrope_apply", "civic_kv_write_rope", "civic_prefill_attn_rope",
            "civic_anchor_aggregate_workspace_bytes", "civic_anchor_aggregate", "civic_kv_compress_workspace_bytes",
@@ -70,6 +70,9 @@ lib.civic_select.argtypes = [_P, C.c_int32, C.POINTER(Grid), _P, _P, _P, C.c_siz
 lib.civic_compact.restype = C.c_int
 lib.civic_compact.argtypes = [_P, C.c_int, C.c_int32, _P, C.c_int32, C.c_int64, C.POINTER(Grid), _P, _P, C.c_int64,
                               _P, _P, _P, _P, C.c_size_t, _P]
+lib.civic_compact_prefill.restype = C.c_int
+lib.civic_compact_prefill.argtypes = [_P, C.c_int, C.c_int32, C.c_int64, C.c_int32, _P, C.POINTER(Grid), _P, _P, C.c_float,
+                                      _P, _P, _P, _P, _P, _P, C.c_size_t, _P]
 lib.civic_prefill_attn.restype = C.c_int
 lib.civic_prefill_attn.argtypes = [_P, _P, _P, _P, C.c_int, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                    _P, _P, _P, C.c_int32, C.c_float, _P]
@@ -252,6 +255,40 @@ def civic_compact(hidden: torch.Tensor, pos_ids: torch.Tensor, grid, frame_start
                                               _dev(hidden_c), _dev(pos_c), _dev(src_idx), _dev(workspace), ws_bytes,
                                               _stream(stream)))
     return hidden_c, pos_c, src_idx
+
+
+def civic_compact_prefill(hidden: torch.Tensor, pos_ids: torch.Tensor, grid, frame_start: Sequence[int],
+                          anchor_q: torch.Tensor, inv_tau: float = 1.0, scores: Optional[torch.Tensor] = None,
+                          kept_idx: Optional[torch.Tensor] = None, hidden_c: Optional[torch.Tensor] = None,
+                          pos_c: Optional[torch.Tensor] = None, src_idx: Optional[torch.Tensor] = None, stream=None):
+    """Scores, selection and compact merge in one library call -> (scores, kept_idx, hidden_c, pos_c, src_idx)."""
+    g = make_grid(grid)
+    if hidden.dim() != 3 or not hidden.is_contiguous() or not pos_ids.is_contiguous():
+        raise ValueError("hidden [batch, S, dim] and pos_ids [3, batch, S] must be contiguous")
+    batch, seq_len, dim = hidden.shape
+    if tuple(pos_ids.shape) != (3, batch, seq_len) or pos_ids.dtype != torch.int32:
+        raise ValueError("pos_ids must be int32 [3, batch, S]")
+    n_kept = civic_kept_count(grid)
+    seq_c = seq_len - g.n_visual + n_kept
+    fs = np.ascontiguousarray(np.asarray(frame_start, dtype=np.int64))
+    if fs.shape != (g.frames,):
+        raise ValueError("frame_start must have one entry per frame")
+    dev = hidden.device
+    if scores is None:
+        scores = torch.empty((batch, g.n_visual), dtype=torch.float32, device=dev)
+    if kept_idx is None:
+        kept_idx = torch.empty((batch, n_kept), dtype=torch.int32, device=dev)
+    if hidden_c is None:
+        hidden_c = torch.empty((batch, seq_c, dim), dtype=hidden.dtype, device=dev)
+    if pos_c is None:
+        pos_c = torch.empty((3, batch, seq_c), dtype=torch.int32, device=dev)
+    if src_idx is None:
+        src_idx = torch.empty((batch, seq_c), dtype=torch.int32, device=dev)
+    _check("civic_compact_prefill", lib.civic_compact_prefill(
+        _dev(hidden), _dtype_code(hidden), batch, seq_len, dim, _dev(pos_ids), C.byref(g), C.c_void_p(fs.ctypes.data),
+        _dev(anchor_q), float(inv_tau), _dev(scores), _dev(kept_idx), _dev(hidden_c), _dev(pos_c), _dev(src_idx),
+        None, 0, _stream(stream)))
+    return scores, kept_idx, hidden_c, pos_c, src_idx
 
 
 def civic_prefill_attn(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, causal: bool = True,

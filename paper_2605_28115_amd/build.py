@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcivic.so")
-SOURCES = ["api.hip", "score.hip", "select.hip", "compact.hip", "attn.hip", "kv_write.hip", "decode.hip", "rope.hip", "encoder.hip"]
+SOURCES = ["api.hip", "score.hip", "select.hip", "compact.hip", "front.hip", "attn.hip", "kv_write.hip", "decode.hip", "rope.hip", "encoder.hip"]
 
 # Packed-fp32 VALU forms are switched off for all device code (compiler flag, not a host flag).
 HIPCC_FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",

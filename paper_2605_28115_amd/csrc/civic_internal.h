@@ -42,6 +42,15 @@ struct GridInfo {
 // CIVIC_OK and a filled GridInfo, or CIVIC_ERR_INVALID_ARG.
 int grid_info(const civic_grid* g, GridInfo* out);
 
+// Argument checks of the three front stages, each a host function that launches nothing (the stage's entry
+// point runs it first; civic_compact_prefill runs all three before the first launch).
+int score_visual_check(const void* hidden, int dtype, int32_t batch, int64_t seq_len, int32_t dim, const civic_grid* grid,
+                       const int64_t* frame_start, const float* anchor_q, float inv_tau, const float* scores);
+int select_check(const float* scores, int32_t batch, const civic_grid* grid, const int32_t* kept_idx);
+int compact_check(const void* hidden, int dtype, int32_t dim, const int32_t* pos_ids, int32_t batch, int64_t seq_len,
+                  const civic_grid* grid, const int64_t* frame_start, const int32_t* kept_idx, int64_t n_kept,
+                  const void* hidden_c, const int32_t* pos_c, const int32_t* src_idx);
+
 constexpr int kWave = 64;
 
 // Native vector types (the nontemporal load builtin does not take HIP's struct vectors).

@@ -257,13 +257,13 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
 
 }  // namespace civic
 
-extern "C" int civic_compact(const void* hidden, int dtype, int32_t dim, const int32_t* pos_ids, int32_t batch,
-                             int64_t seq_len, const civic_grid* grid, const int64_t* frame_start,
-                             const int32_t* kept_idx, int64_t n_kept, void* hidden_c, int32_t* pos_c,
-                             int32_t* src_idx, void* workspace, size_t workspace_bytes, void* stream)
+namespace civic {
+
+// The argument checks of civic_compact (host only, nothing is launched).
+int compact_check(const void* hidden, int dtype, int32_t dim, const int32_t* pos_ids, int32_t batch, int64_t seq_len,
+                  const civic_grid* grid, const int64_t* frame_start, const int32_t* kept_idx, int64_t n_kept,
+                  const void* hidden_c, const int32_t* pos_c, const int32_t* src_idx)
 {
-    using namespace civic;
-    (void)workspace; (void)workspace_bytes;
     const int esz = dtype_size(dtype);
     GridInfo gi;
     if (grid_info(grid, &gi) != CIVIC_OK) return CIVIC_ERR_INVALID_ARG;
@@ -287,6 +287,27 @@ extern "C" int civic_compact(const void* hidden, int dtype, int32_t dim, const i
          reinterpret_cast<uintptr_t>(src_idx) | reinterpret_cast<uintptr_t>(kept_idx)) & 3u)
         return CIVIC_ERR_INVALID_ARG;
     if (gi.frames > CIVIC_MAX_FRAMES || seq_len > INT32_MAX || batch > 65535) return CIVIC_ERR_UNSUPPORTED;
+    return CIVIC_OK;
+}
+
+}  // namespace civic
+
+extern "C" int civic_compact(const void* hidden, int dtype, int32_t dim, const int32_t* pos_ids, int32_t batch,
+                             int64_t seq_len, const civic_grid* grid, const int64_t* frame_start,
+                             const int32_t* kept_idx, int64_t n_kept, void* hidden_c, int32_t* pos_c,
+                             int32_t* src_idx, void* workspace, size_t workspace_bytes, void* stream)
+{
+    using namespace civic;
+    (void)workspace; (void)workspace_bytes;
+    const int rc_check = compact_check(hidden, dtype, dim, pos_ids, batch, seq_len, grid, frame_start, kept_idx, n_kept,
+                                       hidden_c, pos_c, src_idx);
+    if (rc_check != CIVIC_OK) return rc_check;
+    const int esz = dtype_size(dtype);
+    GridInfo gi;
+    grid_info(grid, &gi);
+    const int64_t row_bytes = static_cast<int64_t>(dim) * esz;
+    int vec = 16;
+    while (row_bytes % vec) vec >>= 1;
     const int64_t seq_c = seq_len - gi.nv + n_kept;
     if (batch == 0 || seq_c == 0) return CIVIC_OK;
 

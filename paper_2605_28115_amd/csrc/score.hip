@@ -339,11 +339,12 @@ extern "C" int civic_score(const void* hidden, int dtype, int64_t n_rows, int64_
     return score_rows(hidden, dtype, n_rows, 1, row_stride, dim, anchor_q, inv_tau, scores, PlainRows{}, stream);
 }
 
-extern "C" int civic_score_visual(const void* hidden, int dtype, int32_t batch, int64_t seq_len, int32_t dim,
-                                  const civic_grid* grid, const int64_t* frame_start, const float* anchor_q,
-                                  float inv_tau, float* scores, void* stream)
+namespace civic {
+
+// The argument checks of civic_score_visual (host only, nothing is launched).
+int score_visual_check(const void* hidden, int dtype, int32_t batch, int64_t seq_len, int32_t dim, const civic_grid* grid,
+                       const int64_t* frame_start, const float* anchor_q, float inv_tau, const float* scores)
 {
-    using namespace civic;
     const int esz = dtype_size(dtype);
     GridInfo gi;
     if (grid_info(grid, &gi) != CIVIC_OK) return CIVIC_ERR_INVALID_ARG;
@@ -362,7 +363,22 @@ extern "C" int civic_score_visual(const void* hidden, int dtype, int32_t batch, 
     if (static_cast<int64_t>(dim) * esz > static_cast<int64_t>(CIVIC_MAX_SCORE_DIM) * 2) return CIVIC_ERR_UNSUPPORTED;
     const int64_t slices = static_cast<int64_t>(batch) * gi.frames;
     if (gi.frames > CIVIC_MAX_FRAMES || seq_len > INT32_MAX || slices > 65535) return CIVIC_ERR_UNSUPPORTED;
+    return CIVIC_OK;
+}
+
+}  // namespace civic
+
+extern "C" int civic_score_visual(const void* hidden, int dtype, int32_t batch, int64_t seq_len, int32_t dim,
+                                  const civic_grid* grid, const int64_t* frame_start, const float* anchor_q,
+                                  float inv_tau, float* scores, void* stream)
+{
+    using namespace civic;
+    const int rc = score_visual_check(hidden, dtype, batch, seq_len, dim, grid, frame_start, anchor_q, inv_tau, scores);
+    if (rc != CIVIC_OK) return rc;
     if (batch == 0) return CIVIC_OK;
+    GridInfo gi;
+    grid_info(grid, &gi);
+    const int64_t slices = static_cast<int64_t>(batch) * gi.frames;
     SpanRows map;
     map.frames = gi.frames; map.hw = gi.hw; map.seq_len = seq_len;
     for (int32_t f = 0; f < CIVIC_MAX_FRAMES; ++f) map.start[f] = f < gi.frames ? static_cast<int32_t>(frame_start[f]) : 0;

@@ -711,18 +711,32 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelArgs a)
 
 }  // namespace civic
 
-extern "C" int civic_select(const float* scores, int32_t batch, const civic_grid* grid, int32_t* kept_idx,
-                            uint8_t* keep_flags, void* workspace, size_t workspace_bytes, void* stream)
+namespace civic {
+
+// The argument checks of civic_select (host only, nothing is launched).
+int select_check(const float* scores, int32_t batch, const civic_grid* grid, const int32_t* kept_idx)
 {
-    using namespace civic;
-    (void)workspace; (void)workspace_bytes;
     GridInfo gi;
     if (grid_info(grid, &gi) != CIVIC_OK) return CIVIC_ERR_INVALID_ARG;
     if (batch < 0) return CIVIC_ERR_INVALID_ARG;
     if (batch > 0 && (!scores || (gi.kept > 0 && !kept_idx))) return CIVIC_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(scores) | reinterpret_cast<uintptr_t>(kept_idx)) & 3u) return CIVIC_ERR_INVALID_ARG;
     if (gi.nv > CIVIC_MAX_VISUAL_TOKENS) return CIVIC_ERR_UNSUPPORTED;
+    return CIVIC_OK;
+}
+
+}  // namespace civic
+
+extern "C" int civic_select(const float* scores, int32_t batch, const civic_grid* grid, int32_t* kept_idx,
+                            uint8_t* keep_flags, void* workspace, size_t workspace_bytes, void* stream)
+{
+    using namespace civic;
+    (void)workspace; (void)workspace_bytes;
+    const int rc_check = select_check(scores, batch, grid, kept_idx);
+    if (rc_check != CIVIC_OK) return rc_check;
     if (batch == 0) return CIVIC_OK;
+    GridInfo gi;
+    grid_info(grid, &gi);
 
     SelArgs a;
     a.scores = scores; a.kept_idx = kept_idx; a.keep_flags = keep_flags;

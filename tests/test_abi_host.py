@@ -125,6 +125,17 @@ def test_argument_errors_precede_any_hip_call(bd):
     assert compact([0, 8], grid=g2) == I and compact([20, 0], grid=g2) == I
     many = bd.make_grid((200, 1, 1, 1, 1, 0, 0, 5))
     assert compact(list(range(200)), seq_len=400, grid=many) == bd.ERR_UNSUPPORTED
+    # civic_compact_prefill: the checks of all three stages, before anything is launched
+    def front(fs=(0,), seq_len=40, grid=g, hidden=F, dim=64, batch=1, pos=F, anchor=F, scores=F, kept=F, hc=F, pc=F, si=F):
+        arr = np.asarray(fs, dtype=np.int64)
+        return L.civic_compact_prefill(hidden, 1, batch, seq_len, dim, pos, C.byref(grid), C.c_void_p(arr.ctypes.data), anchor,
+                                       C.c_float(1.0), scores, kept, hc, pc, si, None, 0, None)
+    assert front(fs=[30]) == I and front(seq_len=15) == I and front(hidden=None) == I and front(hidden=odd) == I
+    assert front(dim=60) == I and front(anchor=None) == I and front(scores=None) == I and front(kept=None) == I
+    assert front(pos=None) == I and front(hc=None) == I and front(pc=None) == I and front(si=None) == I
+    assert front(kept=C.c_void_p(0x1002)) == I and front(batch=-1) == I
+    assert front(grid=big, seq_len=70000) == bd.ERR_UNSUPPORTED and front(dim=16384) == bd.ERR_UNSUPPORTED
+    assert front(batch=0, hidden=None, pos=None, scores=None, kept=None, hc=None, pc=None, si=None) == bd.CIVIC_OK
     # civic_prefill_attn: head mismatch, head_dim, alignment, scale
     def attn(**kw):
         a = dict(q=F, k=F, v=F, o=F, dt=1, b=1, s=8, hq=4, hkv=2, d=64, qs=st, ks=st, os=st, causal=1, scale=0.0)

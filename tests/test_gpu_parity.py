@@ -540,6 +540,34 @@ def test_fused_attention_kv_write_equals_the_two_calls(bd, shape, causal, dtype)
     assert np.array_equal(to_host(kc2), ref_k) and np.array_equal(to_host(vc2), ref_v)
 
 
+@pytest.mark.parametrize("name", ["tiny", "2b", "8b", "vit", "video"])
+def test_front_call_equals_the_three_calls_and_the_oracle(bd, name):
+    """civic_compact_prefill: one call for score -> select -> compact.  Same kernels, so every output equals the
+    three calls' bit for bit; the chain is also checked against the oracle (selection on the GPU's scores)."""
+    w = wl.WORKLOADS[name]
+    log("front call", name)
+    hid, hid32 = wl.hidden(w, 2)
+    pos, fs, grid = wl.position_ids(w), wl.frame_starts(w), w.grid_tuple()
+    hw = w.height * w.width
+    d_hid, d_pos = to_dev(hid), torch.from_numpy(pos.copy()).cuda()
+    q_anchor = bd.civic_anchor_normalize(wl.anchor(w, 2))
+    d_anchor = torch.from_numpy(q_anchor).cuda()
+    scores, kept, hc, pc, si = bd.civic_compact_prefill(d_hid, d_pos, grid, fs, d_anchor, 1.5)
+    scores3 = bd.civic_score_visual(d_hid, grid, fs, d_anchor, 1.5)
+    kept3, _ = bd.civic_select(scores3, grid)
+    hc3, pc3, si3 = bd.civic_compact(d_hid, d_pos, grid, fs, kept3)
+    torch.cuda.synchronize()
+    assert torch.equal(scores, scores3) and torch.equal(kept, kept3)
+    assert torch.equal(si, si3) and torch.equal(pc, pc3) and np.array_equal(to_host(hc), to_host(hc3))
+    h_scores = to_host(scores)
+    vis32 = np.concatenate([hid32[:, s:s + hw] for s in fs], axis=1).reshape(-1, w.dim)
+    assert np.abs(h_scores.reshape(-1) - oracle.score(vis32, q_anchor, 1.5)).max() <= 2e-5 * 1.5
+    ref_kept, _ = oracle.select(h_scores, grid)
+    assert np.array_equal(to_host(kept), ref_kept)
+    rhc, rpc, rsi = oracle.compact(hid, pos, grid, fs, ref_kept)
+    assert np.array_equal(to_host(si), rsi) and np.array_equal(to_host(pc), rpc) and np.array_equal(to_host(hc), rhc)
+
+
 # -------------------------------------------------------------------------------------- the path
 @pytest.mark.parametrize("name", ["tiny", "2b", "8b", "vit", "video"])
 def test_whole_path_chained(bd, name):
