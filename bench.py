@@ -191,6 +191,8 @@ def main() -> int:
                     help="transformer layers N_l of the amortised figure: score, select and compact once, attention and "
                          "KV write per layer (28 = the layer count the paper's Table 1 KV sizes imply for its 2B model)")
     ap.add_argument("--unfused", action="store_true", help="attention and KV write as two calls")
+    ap.add_argument("--path-only", action="store_true",
+                    help="skip the decode, rotary and encoder figures (counter runs: every launch then belongs to the path)")
     ap.add_argument("--separate-calls", action="store_true",
                     help="the timed step calls score_visual, select and compact one by one instead of civic_compact_prefill")
     ap.add_argument("--prewarm-ms", type=float, default=150.0,
@@ -384,7 +386,7 @@ def main() -> int:
                 "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4), "workspace_bytes": need, "cache_sets": reps}
 
     decode = None
-    if w.n_kv_heads != w.n_q_heads or w.causal:              # the encoder-side workload keeps no cache
+    if not args.path_only and (w.n_kv_heads != w.n_q_heads or w.causal):   # the encoder-side workload keeps no cache
         decode = {"kernel": "decode_partial_kernel + decode_merge_kernel (civic_decode_attn)", "bound": "hbm",
                   "unit": "GB/s", "peak": HBM_PEAK_GBS, "workload": decode_figures(w.batch), "batch_64": decode_figures(64)}
 
@@ -392,7 +394,7 @@ def main() -> int:
     # cache (civic_kv_write_rope) and Q rotated inside the attention launch (civic_prefill_attn_rope reading K and
     # V from the cache).  civic_mrope_apply on Q is what the fused attention saves.
     rope = None
-    if w.head_dim % 32 == 0 and w.dtype == "bf16":
+    if not args.path_only and w.head_dim % 32 == 0 and w.dtype == "bf16":
         n_pairs = w.head_dim // 2
         inv_freq = (1.0e6 ** (-np.arange(n_pairs, dtype=np.float64) / n_pairs)).astype(np.float32)
         axis = (np.arange(n_pairs) % 3).astype(np.int32)
@@ -429,7 +431,7 @@ def main() -> int:
     # Encoder-side compaction (the paper's own soft route), timed on the encoder-shaped workload: Eq. 8 from the
     # dense patch grid to K anchors, and Eq. 9 (KV compression to S memory anchors + attention over them).
     encoder = None
-    if w.name == "vit":
+    if not args.path_only and w.name == "vit":
         t_e, m_e, d_v, s_mem = w.n_visual, w.kept, w.dim, 256
         x0 = sets[0].hidden[:, :t_e].contiguous()
         anchors = torch.randn((m_e, d_v), device="cuda").to(x0.dtype)
