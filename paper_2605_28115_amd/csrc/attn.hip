@@ -37,6 +37,12 @@
 
 #include "civic_internal.h"
 
+// LDS fragments (K rows, transposed V) are read this many MFMAs ahead of the MFMA that consumes them (build-time
+// knob for A/B runs; 2-4 measure within 1 % of each other, 2 needs the fewest registers).
+#ifndef CIVIC_ATTN_DIST
+#define CIVIC_ATTN_DIST 2
+#endif
+
 namespace civic {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -484,6 +490,7 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
             asm volatile("" : "+v"(vaddr[hi][dt]));
         }
 
+    constexpr int kDist = CIVIC_ATTN_DIST;                  // LDS fragments are read this many MFMAs ahead of their use
     f32x16 acc_o[DT];
     float m_run;                           // offset subtracted from the raw logits (a recent row maximum)
     float l_run[2];                        // running row sum, two partial accumulators
@@ -502,22 +509,23 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
         for (int t = 0; t < NT; ++t)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc_s[t][r] = 0.f;
+        // (fragments are read two MFMAs ahead of their use, in the order written: a scheduling barrier per MFMA
+        // keeps that order whatever the register pressure around it)
+        {
+            auto read_k = [&](int i) __attribute__((always_inline)) {     // MFMA i = (k-step i / NT, sub-tile i % NT)
+                return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
+                    kaddr[i / NT] + ST * TILEB + 32 * (i % NT) * PITCHB);
+            };
+            bf16x8 kf[kDist + 1];
 #pragma unroll
-        for (int s = 0; s < KSTEPS; ++s)
+            for (int i = 0; i < kDist; ++i) kf[i] = read_k(i);
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const bf16x8 ka = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(
-                    kaddr[s] + ST * TILEB + 32 * t * PITCHB);
-                acc_s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[s], acc_s[t], 0, 0, 0);
+            for (int i = 0; i < NT * KSTEPS; ++i) {
+                if (i + kDist < NT * KSTEPS) kf[(i + kDist) % (kDist + 1)] = read_k(i + kDist);
+                acc_s[i % NT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i % (kDist + 1)], qreg[i / NT], acc_s[i % NT], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
-        // keep 4 K fragments in flight ahead of the MFMA that consumes them
-        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-#pragma unroll
-        for (int i = 0; i < NT * KSTEPS - 4; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
 
         // mask only where the tile crosses the diagonal or the end of the sequence (wave-uniform)
         if ((a.causal && key0 + kBN - 1 > row0) || key0 + kBN > a.kv_seq) {
@@ -588,45 +596,163 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
         }
         l_run[0] += lt[0]; l_run[1] += lt[1];
         // O^T += V^T P^T.  The k-slot (half, e) of step (t, u) is key 32t + 16u + 8(e/4) + 4 half + e%4.
+        {
+            auto read_v = [&](int i) __attribute__((always_inline)) {     // MFMA i = (key step i / DT, output tile i % DT)
+                const int dt = i % DT, row = 16 * (i / DT);
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) s16x4*)(vaddr[0][dt] + ST * TILEB + row * PITCHB));
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) s16x4*)(vaddr[1][dt] + ST * TILEB + row * PITCHB));
+                const s16x8 v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                return __builtin_bit_cast(bf16x8, v8);
+            };
+            bf16x8 vf[kDist + 1];
 #pragma unroll
-        for (int t = 0; t < NT; ++t)
+            for (int i = 0; i < kDist; ++i) vf[i] = read_v(i);
 #pragma unroll
-            for (int u = 0; u < 2; ++u)
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt) {
-                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (__attribute__((address_space(3))) s16x4*)(vaddr[0][dt] + ST * TILEB + (32 * t + 16 * u) * PITCHB));
-                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (__attribute__((address_space(3))) s16x4*)(vaddr[1][dt] + ST * TILEB + (32 * t + 16 * u) * PITCHB));
-                    const s16x8 v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, v8), pb[t][u], acc_o[dt], 0, 0, 0);
-                }
-        // keep the V fragments of 4 MFMAs (two transposing reads each) in flight ahead of their consumer
-        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
-#pragma unroll
-        for (int i = 0; i < NT * 2 * DT - 4; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            for (int i = 0; i < NT * 2 * DT; ++i) {
+                if (i + kDist < NT * 2 * DT) vf[(i + kDist) % (kDist + 1)] = read_v(i + kDist);
+                acc_o[i % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % (kDist + 1)], pb[i / (2 * DT)][(i / DT) % 2], acc_o[i % DT], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+    };
+
+    // The same arithmetic for an inner tile (not the first, nothing masked), written out so that one wavefront's
+    // matrix and vector instructions alternate: the logits of the tile's second 32 keys are multiplied while the
+    // probabilities of its first 32 keys are exponentiated, a pair of scores behind every MFMA, and those enter the
+    // PV product while the second half is exponentiated.  The order below is the order wanted: a scheduling barrier
+    // after every unit keeps the compiler from regrouping it, and bounds the registers it needs.  (Measured against
+    // the plain order with the same explicit fragment prefetch: 1-2 % on the 8B-shaped launch, 2-3 % on long
+    // sequences - the vector work mostly does not hide behind the MFMAs, whatever the order.)  The offset check runs
+    // per half, before that half's probabilities are used; a half whose row sums come out large raises the offset,
+    // rescales what has been accumulated (the first half's PV product included, which carried the old offset like
+    // everything else) and redoes that half's exponentials.
+    auto tile_fast = [&](auto stage_c) {
+        constexpr int ST = decltype(stage_c)::value;
+        auto read_k = [&](int s, int t) __attribute__((always_inline)) {
+            return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(kaddr[s] + ST * TILEB + 32 * t * PITCHB);
+        };
+        auto read_v = [&](int i, int t) __attribute__((always_inline)) {      // fragment i = (u, dt) of key half t
+            const int u = i / DT, dt = i % DT;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) s16x4*)(vaddr[0][dt] + ST * TILEB + (32 * t + 16 * u) * PITCHB));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) s16x4*)(vaddr[1][dt] + ST * TILEB + (32 * t + 16 * u) * PITCHB));
+            const s16x8 v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            return __builtin_bit_cast(bf16x8, v8);
+        };
+        // scores 2i, 2i + 1 of a half -> word i of its packed probabilities, and the lane's partial row sums
+        auto soft_pair = [&](const f32x16& x, int i, float off, uint32_t (&packed)[8], float (&lt)[2]) __attribute__((always_inline)) {
+            const float p0 = __builtin_amdgcn_exp2f(fmaf(x[2 * i], sl2, off));
+            const float p1 = __builtin_amdgcn_exp2f(fmaf(x[2 * i + 1], sl2, off));
+            const bf16x2 pp = {static_cast<__bf16>(p0), static_cast<__bf16>(p1)};
+            packed[i] = __builtin_bit_cast(uint32_t, pp);
+            lt[i & 1] = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, lt[i & 1], false);
+        };
+        auto operand = [&](const uint32_t (&packed)[8], int u) __attribute__((always_inline)) {
+            const u32x4 w = {packed[4 * u], packed[4 * u + 1], packed[4 * u + 2], packed[4 * u + 3]};
+            return __builtin_bit_cast(bf16x8, w);
+        };
+        auto raise_offset = [&](const f32x16& x, uint32_t (&packed)[8], float (&lt)[2]) __attribute__((always_inline)) {
+            float mx = fmaxf(fmaxf(max3(x[0], x[1], x[2]), max3(x[3], x[4], x[5])),
+                             fmaxf(max3(x[6], x[7], x[8]), max3(x[9], x[10], x[11])));
+            mx = fmaxf(fmaxf(mx, max3(x[12], x[13], x[14])), x[15]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+            const float m_new = fmaxf(mx, m_run);
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sl2);
+            l_run[0] *= alpha; l_run[1] *= alpha;
+            // (in place, tied operands: the accumulators stay in the registers they have on the common path)
+#pragma unroll
+            for (int t = 0; t < DT; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float y = acc_o[t][r];
+                    asm volatile("v_mul_f32 %0, %0, %1" : "+v"(y) : "v"(alpha));
+                    acc_o[t][r] = y;
+                }
+            m_run = m_new;
+            const float off = -m_run * sl2;
+            lt[0] = 0.f; lt[1] = 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) soft_pair(x, i, off, packed, lt);
+        };
+        constexpr int NF = 2 * DT;                            // V fragments per key half
+        f32x16 s0, s1;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }
+        uint32_t pk0[8], pk1[8];
+        float lt0[2] = {0.f, 0.f}, lt1[2] = {0.f, 0.f};
+        // K fragments as one sequence of 2 KSTEPS reads (first half, then second), kDist MFMAs ahead of their use
+        auto read_kseq = [&](int i) __attribute__((always_inline)) { return read_k(i % KSTEPS, i / KSTEPS); };
+        bf16x8 kf[kDist + 1];
+#pragma unroll
+        for (int i = 0; i < kDist; ++i) kf[i] = read_kseq(i);
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s) {                    // logits of the first half
+            kf[(s + kDist) % (kDist + 1)] = read_kseq(s + kDist);
+            s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s % (kDist + 1)], qreg[s], s0, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        const float off0 = -m_run * sl2;
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s) {                    // logits of the second half | exponentials of the first
+            if (KSTEPS + s + kDist < 2 * KSTEPS) kf[(KSTEPS + s + kDist) % (kDist + 1)] = read_kseq(KSTEPS + s + kDist);
+            s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[(KSTEPS + s) % (kDist + 1)], qreg[s], s1, 0, 0, 0);
+#pragma unroll
+            for (int i = s * 8 / KSTEPS; i < (s + 1) * 8 / KSTEPS; ++i) soft_pair(s0, i, off0, pk0, lt0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (__builtin_expect(__any(lt0[0] + lt0[1] > 1048576.f), 0)) raise_offset(s0, pk0, lt0);
+        l_run[0] += lt0[0]; l_run[1] += lt0[1];
+        const float off1 = -m_run * sl2;
+        auto read_vseq = [&](int i) __attribute__((always_inline)) { return read_v(i % NF, i / NF); };
+        bf16x8 vf[kDist + 1];
+#pragma unroll
+        for (int i = 0; i < kDist; ++i) vf[i] = read_vseq(i);
+#pragma unroll
+        for (int i = 0; i < NF; ++i) {                        // PV of the first half | exponentials of the second
+            vf[(i + kDist) % (kDist + 1)] = read_vseq(i + kDist);
+            acc_o[i % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % (kDist + 1)], operand(pk0, i / DT), acc_o[i % DT], 0, 0, 0);
+#pragma unroll
+            for (int j = i * 8 / NF; j < (i + 1) * 8 / NF; ++j) soft_pair(s1, j, off1, pk1, lt1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (__builtin_expect(__any(lt1[0] + lt1[1] > 1048576.f), 0)) raise_offset(s1, pk1, lt1);
+        l_run[0] += lt1[0]; l_run[1] += lt1[1];
+#pragma unroll
+        for (int i = 0; i < NF; ++i) {                        // PV of the second half
+            if (NF + i + kDist < 2 * NF) vf[(NF + i + kDist) % (kDist + 1)] = read_vseq(NF + i + kDist);
+            acc_o[i % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[(NF + i) % (kDist + 1)], operand(pk1, i / DT), acc_o[i % DT], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
 
     // One step of the pipeline: wait until the tile has landed, release the previous one, refill the freed
     // stage, compute.  At step q_issue the Q rows of the workgroup's next row tile are requested as well (their
     // area has been free since Q moved into registers); they land with a later tile.
     int q_issue = -1, next_row0 = 0;
-    auto step = [&](int kt, auto stage_c) __attribute__((always_inline)) {
+    auto advance = [&](int kt, auto stage_c) __attribute__((always_inline)) {
         constexpr int ST = decltype(stage_c)::value;
         wait_vmcnt<0>();
         block_barrier();                                      // landed for every wavefront; tile kt-1 is released
         if (kt + 1 < n_tiles) issue_tile(kt + 1, std::integral_constant<int, (ST + 1) % kStages>{});
         if (kt == q_issue) issue_q_next(next_row0);
+    };
+    // a tile that may be the first, cross the diagonal or hold the end of the sequence
+    auto step = [&](int kt, auto stage_c) __attribute__((always_inline)) {
+        advance(kt, stage_c);
         // On the diagonal a wavefront whose rows all precede the tile's second half computes the first half
         // only: half the MFMAs and exponentials of that tile for half of the wavefronts, which the other
         // wavefront of the SIMD turns into time.  The same holds for a last tile whose second half lies past
         // the end of the sequence.
         if ((a.causal && kt * kBN + 32 > row0 + 31) || kt * kBN + 32 >= a.kv_seq) tile(kt, stage_c, std::integral_constant<int, 1>{});
         else tile(kt, stage_c, std::integral_constant<int, 2>{});
+    };
+    // an inner tile: whole, visible to every row of the workgroup, not the first
+    auto step_inner = [&](int kt, auto stage_c) __attribute__((always_inline)) {
+        advance(kt, stage_c);
+        tile_fast(stage_c);
     };
 
     constexpr int OROW = T::OROW;
@@ -645,9 +771,18 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
         q_issue = has_next ? max(n_tiles - 3, 0) : -1;
         next_row0 = rt_next * RB * 32 + wrow;
 
-        for (int kt = 0; kt < n_tiles; kt += kStages) {
-            step(kt, std::integral_constant<int, 0>{});
-            if (kt + 1 < n_tiles) step(kt + 1, std::integral_constant<int, 1>{});
+        // Tile 0, then the inner tiles in a loop of their own (one code path, so the accumulators keep their
+        // registers across it), then whatever is left: the diagonal, the end of the sequence.
+        const int inner_end = min(a.causal ? (block_row0 + 1) / kBN : a.kv_seq / kBN, n_tiles);
+        step(0, std::integral_constant<int, 0>{});
+        int kt = 1;
+        for (; kt + 1 < inner_end; kt += kStages) {
+            step_inner(kt, std::integral_constant<int, 1>{});
+            step_inner(kt + 1, std::integral_constant<int, 0>{});
+        }
+        for (; kt < n_tiles; kt += kStages) {
+            step(kt, std::integral_constant<int, 1>{});
+            if (kt + 1 < n_tiles) step(kt + 1, std::integral_constant<int, 0>{});
         }
         if (has_next) wait_vmcnt<0>();                        // the next Q rows (a one-tile pass waits nowhere else)
         __syncthreads();                                      // every tile consumed: the rings are free
