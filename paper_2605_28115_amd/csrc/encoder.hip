@@ -4,19 +4,22 @@
 //   civic_kv_compress       Eq. 9: K_c = Rbar^T K, V_c = Rbar^T V with the column-normalised assignment matrix
 // (the attention over the compressed keys, softmax(Q K_c^T / sqrt(d)) V_c, is civic_cross_attn in attn.hip).
 //
-// Both are dense contractions and run on the bf16 MFMA pipe through one kernel, C = alpha * A B^T with both
-// operands stored with the contraction index contiguous ("NT").  Operands whose contraction index is the slow
-// one in the caller's layout (X_0 in Z_0 = W_A X_0; K, V and R in Eq. 9) are first transposed into scratch with
-// the contraction length zero-padded to a multiple of 64, so the GEMM has no tail in that direction; row and
-// column tails are clamped loads and masked stores.
+// Both are dense contractions and run on the bf16 MFMA pipe through one kernel, C = alpha * A B^T, whose B operand
+// may be stored either way round: like A, with the contraction index contiguous (the logits Q_A K_0^T), or with the
+// contraction index as the row index, which is how X_0 lies in Z_0 = W_A X_0 and how K and V lie in Eq. 9; those are
+// read where they are (transposing LDS reads), no transposed copy is made.  A is always contraction-contiguous and
+// zero-padded to a multiple of 64 in that direction (W_A and Rbar^T are written that way), so the GEMM has no tail
+// there; row and column tails are clamped loads and masked stores.
 //   - 128 x 128 output tile per 256-thread workgroup, 64 x 64 per wavefront (2 x 2 blocks of
 //     v_mfma_f32_32x32x16_bf16, fp32 accumulators), 64 contraction elements per LDS tile.
-//   - A and B tiles go from global memory straight into a two-stage LDS ring (global_load_lds_dwordx4), rows at a
-//     128-byte pitch with the 16-byte chunks XOR-swizzled by the row, so that the 128-bit operand reads of 32
-//     adjacent rows fall on distinct banks; one tile ahead, explicit vmcnt waits, fence-free barriers.  Two
-//     workgroups share a compute unit.  (A four-stage ring, 128 KB and one workgroup per unit, was slower, 46.6
-//     against 35.3 us on the 1365 x 4096 x 1152 logits: the kernel is bound by the L2 -> LDS traffic of its 128 x 128
-//     tiles, 64 FLOP per byte, not by the latency of a tile.)
+//   - A and B tiles go from global memory straight into an LDS ring (global_load_lds_dwordx4), 16-byte chunks
+//     XOR-swizzled by the row so that operand reads fall on distinct banks; explicit vmcnt waits, fence-free barriers;
+//     the fragments of the next k-step are read while the MFMAs of the current one run, in a hand-written order.
+//   - Two ring depths: two stages and two workgroups per compute unit for grids that fill the chip (the kernel is then
+//     bound by the L2 -> LDS traffic of its tiles, 64 FLOP per byte; a deeper ring at one workgroup per unit was
+//     slower, 46.6 against 35.3 us on the 1365 x 4096 x 1152 logits), four stages for grids that leave units without a
+//     second workgroup anyway, where the latency of a tile is what a workgroup waits for.
+//   - K_c and V_c of Eq. 9 come from one launch (grid z = batch item x tensor).
 // The softmax of Eq. 8 runs over rows of 4096 logits and more, too long for a fused epilogue: the logits go to
 // scratch in fp32, a row kernel turns them into bf16 weights, the second GEMM consumes those.
 #include <cmath>
@@ -32,15 +35,18 @@ typedef __attribute__((address_space(3))) char enc_lds_char;
 constexpr int kGemmBM = 128, kGemmBN = 128, kGemmBK = 64;
 constexpr int kGemmThreads = 256;
 constexpr int kGemmTileBytes = kGemmBM * kGemmBK * 2;         // one operand tile: 16 KB
-constexpr int kGemmStages = 2;                                 // tiles in the LDS ring (2 or 4): all but one in flight ahead of the one consumed
-constexpr int kGemmLds = 2 * kGemmStages * kGemmTileBytes;     // A ring, then B ring
 
 struct GemmArgs {
     const __bf16* a; const __bf16* b; void* c;
-    int64_t lda, ldb, ldc;             // elements between rows
+    // a second (B, C) pair served by the same launch (grid z = 2 * batch item + pair), or null
+    const __bf16* b_alt; void* c_alt;
+    int64_t lda, ldb, ldc;             // elements between rows of A [m x k], of B as stored, of C [m x n]
     int64_t sa, sb, sc;                // elements between batch items (0 = shared)
-    int32_t m, n, k;                   // k a multiple of 64
+    int32_t m, n, k;                   // k a multiple of 64 (A is zero-padded up to it)
+    int32_t kb_rows;                   // B stored [k x n]: the rows that exist (<= k); rows beyond re-read the last one
     float alpha;
+    // output tiles: counts per matrix, tiles of all matrices of the launch, n-tiles per panel (filled in by launch_gemm)
+    int32_t tiles_m, tiles_n, total_tiles, panel;
 };
 
 template <int LDS_IMM>
@@ -61,53 +67,105 @@ __device__ __forceinline__ const char* enc_uniform(const void* p)
 
 // physical chunk = logical chunk ^ swz(row): rows 0..31 of a 128-byte-pitch tile, same logical chunk -> 32 banks groups
 __device__ __forceinline__ int enc_swz(int row) { return (((row >> 1) & 1) << 2) | ((row >> 2) & 3); }
+// the same for a 256-byte pitch (16 chunks per row): a tile stored with the contraction index as its rows
+__device__ __forceinline__ int enc_swz16(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
 
-template <bool C_BF16>
-__global__ __launch_bounds__(kGemmThreads, 2) void gemm_nt_kernel(GemmArgs g)
+typedef short enc_s16x4 __attribute__((ext_vector_type(4)));
+typedef short enc_s16x8 __attribute__((ext_vector_type(8)));
+
+// C = alpha * A B^T.  A is stored [m x k] (contraction index contiguous).  B_KROWS = false: B stored [n x k], the same
+// way.  B_KROWS = true: B stored [k x n], contraction index as the row index - the layout of X_0 in Z_0 = W_A X_0 and of
+// K, V in Eq. 9; its tiles (64 contraction rows x 128 columns, 256-byte pitch) are read with the transposing LDS read,
+// which hands a lane one column and 4 consecutive contraction rows, so no transposed copy is ever made.
+// STAGES: tiles in the LDS ring, all but one in flight ahead of the one consumed: 2 (two workgroups per compute unit)
+// when the grid fills the chip, 4 (one workgroup per unit) when it does not and a tile's latency is what is waited for.
+template <bool C_BF16, bool B_KROWS, int STAGES>
+__global__ __launch_bounds__(kGemmThreads, STAGES == 2 ? 2 : 1) void gemm_kernel(GemmArgs g)
 {
     extern __shared__ __attribute__((aligned(16))) char gemm_lds[];
     enc_lds_char* const lds = (enc_lds_char*)gemm_lds;       // the A stages, then the B stages
     const int tid = threadIdx.x, lane = tid & (kWave - 1), w = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
     const int wm = w >> 1, wn = w & 1;                        // the wavefront's 64 x 64 quadrant
-    const int m0 = blockIdx.y * kGemmBM, n0 = blockIdx.x * kGemmBN;
-    const int64_t bz = blockIdx.z;
+    // Workgroup -> output tile.  The hardware hands consecutive workgroups to the eight XCDs in turn, each with an L2
+    // of its own, so workgroup p takes tile (p mod 8) * (workgroups / 8) + p / 8: every XCD owns a contiguous run of
+    // tiles, and the tiles of a matrix are numbered panel by panel (a panel = `panel` tile columns, all tile rows), so
+    // that run is a compact block whose A row slabs and B column slabs are shared inside one L2 as the workgroups
+    // advance along the contraction together.  With the plain (x, y) numbering every XCD touches every slab and the
+    // kernel runs at the speed of the memory behind the L2s.
+    const uint32_t per_xcd = gridDim.x >> 3;
+    const uint32_t tile = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+    if (tile >= static_cast<uint32_t>(g.total_tiles)) return;            // (the grid is padded to a multiple of 8)
+    const uint32_t per_mat = static_cast<uint32_t>(g.tiles_m) * g.tiles_n;
+    const uint32_t zi = tile / per_mat, rr = tile - zi * per_mat;
+    const uint32_t pn = rr / (static_cast<uint32_t>(g.panel) * g.tiles_m);
+    const uint32_t base_n = pn * g.panel;
+    const uint32_t pw = min(static_cast<uint32_t>(g.panel), static_cast<uint32_t>(g.tiles_n) - base_n);
+    const uint32_t within = rr - pn * g.panel * g.tiles_m;
+    const int m0 = static_cast<int>(within / pw) * kGemmBM, n0 = static_cast<int>(base_n + within % pw) * kGemmBN;
+    const bool alt = g.b_alt != nullptr && (zi & 1u);
+    const int64_t bz = g.b_alt != nullptr ? (zi >> 1) : zi;
+    const __bf16* const b_mat = alt ? g.b_alt : g.b;
 
     // global -> LDS: instruction j of wavefront w fills slots [(4 w + j) * 64, +64) of a tile; slot -> (row, physical chunk)
     const char* a_base = reinterpret_cast<const char*>(g.a + bz * g.sa + static_cast<int64_t>(m0) * g.lda);
-    const char* b_base = reinterpret_cast<const char*>(g.b + bz * g.sb + static_cast<int64_t>(n0) * g.ldb);
-    uint32_t a_off[4], b_off[4];
+    const char* b_base = B_KROWS ? reinterpret_cast<const char*>(b_mat + bz * g.sb + n0)
+                                 : reinterpret_cast<const char*>(b_mat + bz * g.sb + static_cast<int64_t>(n0) * g.ldb);
+    const int last_tile = g.k / kGemmBK - 1;
+    uint32_t a_off[4], b_off[4], b_off_tail[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int slot = (w * 4 + j) * kWave + lane;
         const int row = slot >> 3;
         const int c = (slot & 7) ^ enc_swz(row);
         a_off[j] = static_cast<uint32_t>(min(row, g.m - 1 - m0)) * static_cast<uint32_t>(g.lda * 2) + c * 16;
-        b_off[j] = static_cast<uint32_t>(min(row, g.n - 1 - n0)) * static_cast<uint32_t>(g.ldb * 2) + c * 16;
+        if constexpr (B_KROWS) {
+            const int krow = slot >> 4;                       // contraction row inside the tile
+            const int lc = (slot & 15) ^ enc_swz16(krow);     // logical chunk: columns n0 + 8 lc .. + 7
+            const int cc = min(lc, (g.n - n0) / 8 - 1);       // (n is a multiple of 8; chunks past it re-read a valid one)
+            b_off[j] = static_cast<uint32_t>(krow) * static_cast<uint32_t>(g.ldb * 2) + cc * 16;
+            b_off_tail[j] = static_cast<uint32_t>(min(last_tile * kGemmBK + krow, g.kb_rows - 1) - last_tile * kGemmBK) *
+                                static_cast<uint32_t>(g.ldb * 2) + cc * 16;
+        } else {
+            b_off[j] = static_cast<uint32_t>(min(row, g.n - 1 - n0)) * static_cast<uint32_t>(g.ldb * 2) + c * 16;
+            b_off_tail[j] = b_off[j];
+        }
     }
     const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds)) + w * 4 * kWave * 16);
     auto issue = [&](int kt, auto stage_c) {
         constexpr int st = decltype(stage_c)::value;
         const char* ab = enc_uniform(a_base + static_cast<int64_t>(kt) * kGemmBK * 2);
-        const char* bb = enc_uniform(b_base + static_cast<int64_t>(kt) * kGemmBK * 2);
+        const char* bb = B_KROWS ? enc_uniform(b_base + static_cast<int64_t>(kt) * kGemmBK * g.ldb * 2)
+                                 : enc_uniform(b_base + static_cast<int64_t>(kt) * kGemmBK * 2);
+        const bool tail = B_KROWS && kt == last_tile;
         enc_dma16<st * kGemmTileBytes + 0 * 1024>(ab, a_off[0], lds_wave);
         enc_dma16<st * kGemmTileBytes + 1 * 1024>(ab, a_off[1], lds_wave);
         enc_dma16<st * kGemmTileBytes + 2 * 1024>(ab, a_off[2], lds_wave);
         enc_dma16<st * kGemmTileBytes + 3 * 1024>(ab, a_off[3], lds_wave);
-        enc_dma16<(kGemmStages + st) * kGemmTileBytes + 0 * 1024>(bb, b_off[0], lds_wave);
-        enc_dma16<(kGemmStages + st) * kGemmTileBytes + 1 * 1024>(bb, b_off[1], lds_wave);
-        enc_dma16<(kGemmStages + st) * kGemmTileBytes + 2 * 1024>(bb, b_off[2], lds_wave);
-        enc_dma16<(kGemmStages + st) * kGemmTileBytes + 3 * 1024>(bb, b_off[3], lds_wave);
+        enc_dma16<(STAGES + st) * kGemmTileBytes + 0 * 1024>(bb, tail ? b_off_tail[0] : b_off[0], lds_wave);
+        enc_dma16<(STAGES + st) * kGemmTileBytes + 1 * 1024>(bb, tail ? b_off_tail[1] : b_off[1], lds_wave);
+        enc_dma16<(STAGES + st) * kGemmTileBytes + 2 * 1024>(bb, tail ? b_off_tail[2] : b_off[2], lds_wave);
+        enc_dma16<(STAGES + st) * kGemmTileBytes + 3 * 1024>(bb, tail ? b_off_tail[3] : b_off[3], lds_wave);
     };
 
-    // operand reads: row (quadrant row 32 i + col), logical chunk 2 s + half; the swizzle depends on row bits 1..3 only,
-    // so the second row block is the first plus a constant
+    // A reads: row (quadrant row 32 i + col), logical chunk 2 s + half; the swizzle depends on row bits 1..3 only, so the
+    // second row block is the first plus a constant.  B the same when it is stored like A; when it is stored with the
+    // contraction index as rows, two transposing reads per fragment: a block of 16 lanes fetches a patch of 4
+    // contraction rows (8 half + 4 hi + 0..3 of the 16-row step) x 16 columns and every lane receives one column of it.
     enc_lds_char* a_addr[4];
     enc_lds_char* b_addr[4];
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
         a_addr[s] = lds + (wm * 64 + col) * 128 + (((2 * s + half) ^ enc_swz(col)) << 4);
-        b_addr[s] = lds + kGemmStages * kGemmTileBytes + (wn * 64 + col) * 128 + (((2 * s + half) ^ enc_swz(col)) << 4);
+        if constexpr (B_KROWS) {
+            const int hi = s & 1, j = s >> 1;                 // (the four registers are the (hi, j) combinations)
+            const int l16 = lane & 15, g16 = (lane >> 4) & 1;
+            const int krow = 8 * half + 4 * hi + (l16 >> 2);
+            const int el = wn * 64 + 32 * j + 16 * g16 + 4 * (l16 & 3);
+            b_addr[s] = lds + STAGES * kGemmTileBytes + krow * 256 + (((el >> 3) ^ enc_swz16(krow)) << 4) + (el & 7) * 2;
+        } else {
+            b_addr[s] = lds + STAGES * kGemmTileBytes + (wn * 64 + col) * 128 + (((2 * s + half) ^ enc_swz(col)) << 4);
+        }
         asm volatile("" : "+v"(a_addr[s]), "+v"(b_addr[s]));
     }
 
@@ -120,11 +178,11 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_nt_kernel(GemmArgs g)
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     const int n_tiles = g.k / kGemmBK;
-    issue(0, std::integral_constant<int, 0>{});
-    if constexpr (kGemmStages == 4) {
-        if (n_tiles > 1) issue(1, std::integral_constant<int, 1>{});
-        if (n_tiles > 2) issue(2, std::integral_constant<int, 2>{});
-    }
+#pragma unroll
+    for (int t = 0; t < STAGES - 1; ++t)
+        if (t == 0) issue(0, std::integral_constant<int, 0>{});
+        else if (t == 1) { if (n_tiles > 1) issue(1, std::integral_constant<int, 1>{}); }
+        else { if (n_tiles > 2) issue(2, std::integral_constant<int, 2>{}); }
     // Loads retire in order, 8 per tile and wavefront: tile kt has landed once at most 8 * (tiles issued after it)
     // loads are outstanding.
     auto wait_landed = [&](int younger) {
@@ -134,45 +192,52 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_nt_kernel(GemmArgs g)
     };
     auto step = [&](int kt, auto stage_c) __attribute__((always_inline)) {
         constexpr int st = decltype(stage_c)::value;
-        wait_landed(min(n_tiles - 1 - kt, kGemmStages - 2));
+        wait_landed(min(n_tiles - 1 - kt, STAGES - 2));
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();                         // landed for every wavefront; the stage of tile kt - 1 is free
         asm volatile("" ::: "memory");
-        if (kt + kGemmStages - 1 < n_tiles) issue(kt + kGemmStages - 1, std::integral_constant<int, (st + kGemmStages - 1) % kGemmStages>{});
+        if (kt + STAGES - 1 < n_tiles) issue(kt + STAGES - 1, std::integral_constant<int, (st + STAGES - 1) % STAGES>{});
+        // operand fragments of k-step s + 1 are read while the MFMAs of step s run (in the order written)
+        auto read_a = [&](int s, int i) __attribute__((always_inline)) {
+            return *reinterpret_cast<const __attribute__((address_space(3))) enc_bf16x8*>(a_addr[s] + st * kGemmTileBytes + i * 32 * 128);
+        };
+        auto read_b = [&](int s, int j) __attribute__((always_inline)) {
+            if constexpr (B_KROWS) {
+                const enc_s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) enc_s16x4*)(b_addr[2 * j] + st * kGemmTileBytes + s * 16 * 256));
+                const enc_s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) enc_s16x4*)(b_addr[2 * j + 1] + st * kGemmTileBytes + s * 16 * 256));
+                const enc_s16x8 v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                return __builtin_bit_cast(enc_bf16x8, v8);
+            } else {
+                return *reinterpret_cast<const __attribute__((address_space(3))) enc_bf16x8*>(b_addr[s] + st * kGemmTileBytes + j * 32 * 128);
+            }
+        };
+        enc_bf16x8 af[2][2], bf[2][2];
+        af[0][0] = read_a(0, 0); af[0][1] = read_a(0, 1); bf[0][0] = read_b(0, 0); bf[0][1] = read_b(0, 1);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            enc_bf16x8 af[2], bf[2];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                af[i] = *reinterpret_cast<const __attribute__((address_space(3))) enc_bf16x8*>(a_addr[s] + st * kGemmTileBytes + i * 32 * 128);
-                bf[i] = *reinterpret_cast<const __attribute__((address_space(3))) enc_bf16x8*>(b_addr[s] + st * kGemmTileBytes + i * 32 * 128);
-            }
+            const int cur = s & 1, nxt = cur ^ 1;
+            if (s + 1 < 4) { af[nxt][0] = read_a(s + 1, 0); af[nxt][1] = read_a(s + 1, 1); bf[nxt][0] = read_b(s + 1, 0); bf[nxt][1] = read_b(s + 1, 1); }
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bf[cur][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        // the operands of one k-step (four reads) stay in flight ahead of the MFMAs that consume them
-        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-#pragma unroll
-        for (int i = 0; i < 12; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
     };
-    for (int kt = 0; kt < n_tiles; kt += kGemmStages) {
+    for (int kt = 0; kt < n_tiles; kt += STAGES) {
         step(kt, std::integral_constant<int, 0>{});
         if (kt + 1 < n_tiles) step(kt + 1, std::integral_constant<int, 1>{});
-        if constexpr (kGemmStages == 4) {
+        if constexpr (STAGES == 4) {
             if (kt + 2 < n_tiles) step(kt + 2, std::integral_constant<int, 2>{});
             if (kt + 3 < n_tiles) step(kt + 3, std::integral_constant<int, 3>{});
         }
     }
 
     // register r of block (i, j): row 32 i + 8 (r / 4) + r % 4 + 4 half, column 32 j + col
-    char* c_base = static_cast<char*>(g.c) + (bz * g.sc) * (C_BF16 ? 2 : 4);
+    char* c_base = static_cast<char*>(alt ? g.c_alt : g.c) + (bz * g.sc) * (C_BF16 ? 2 : 4);
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -190,17 +255,41 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_nt_kernel(GemmArgs g)
             }
 }
 
-static int launch_gemm_nt(const GemmArgs& g, int batch, bool c_bf16, hipStream_t s)
+template <bool C_BF16, bool B_KROWS, int STAGES>
+static int launch_gemm_variant(const GemmArgs& g, unsigned blocks, hipStream_t s)
 {
-    const dim3 grid(static_cast<unsigned>((g.n + kGemmBN - 1) / kGemmBN), static_cast<unsigned>((g.m + kGemmBM - 1) / kGemmBM),
-                    static_cast<unsigned>(batch));
-    static std::atomic<uint64_t> allowed_bf16{0}, allowed_f32{0};
-    const int rc = c_bf16 ? allow_dynamic_lds(reinterpret_cast<const void*>(gemm_nt_kernel<true>), kGemmLds, &allowed_bf16)
-                          : allow_dynamic_lds(reinterpret_cast<const void*>(gemm_nt_kernel<false>), kGemmLds, &allowed_f32);
+    const dim3 grid(blocks);
+    constexpr size_t lds = 2 * STAGES * kGemmTileBytes;
+    static std::atomic<uint64_t> allowed{0};
+    const int rc = allow_dynamic_lds(reinterpret_cast<const void*>(gemm_kernel<C_BF16, B_KROWS, STAGES>), lds, &allowed);
     if (rc != CIVIC_OK) return rc;
-    if (c_bf16) hipLaunchKernelGGL((gemm_nt_kernel<true>), grid, dim3(kGemmThreads), kGemmLds, s, g);
-    else hipLaunchKernelGGL((gemm_nt_kernel<false>), grid, dim3(kGemmThreads), kGemmLds, s, g);
+    hipLaunchKernelGGL((gemm_kernel<C_BF16, B_KROWS, STAGES>), grid, dim3(kGemmThreads), lds, s, g);
     return check_launch();
+}
+
+// `batch` batch items; with g.b_alt set every item runs twice, once per (B, C) pair.  b_krows: B is stored [k x n].
+static int launch_gemm(const GemmArgs& g_in, int batch, bool c_bf16, bool b_krows, hipStream_t s)
+{
+    GemmArgs g = g_in;
+    const int64_t z = static_cast<int64_t>(batch) * (g.b_alt ? 2 : 1);
+    g.tiles_n = (g.n + kGemmBN - 1) / kGemmBN;
+    g.tiles_m = (g.m + kGemmBM - 1) / kGemmBM;
+    const int64_t total = z * g.tiles_m * g.tiles_n;
+    if (total > (int64_t{1} << 30)) return CIVIC_ERR_UNSUPPORTED;
+    g.total_tiles = static_cast<int32_t>(total);
+    const unsigned grid = static_cast<unsigned>((total + 7) / 8 * 8);
+    // panel width: about the square root of an XCD's share of the tiles, so that its block is as tall as it is wide
+    int panel = 1;
+    while (static_cast<int64_t>(panel + 1) * (panel + 1) <= (total + 7) / 8) ++panel;
+    g.panel = panel < g.tiles_n ? panel : g.tiles_n;
+    // a grid that leaves compute units without a second workgroup takes the deeper ring
+    const bool deep = total < 2 * 256;
+    if (c_bf16) {
+        if (b_krows) return deep ? launch_gemm_variant<true, true, 4>(g, grid, s) : launch_gemm_variant<true, true, 2>(g, grid, s);
+        return deep ? launch_gemm_variant<true, false, 4>(g, grid, s) : launch_gemm_variant<true, false, 2>(g, grid, s);
+    }
+    if (b_krows) return deep ? launch_gemm_variant<false, true, 4>(g, grid, s) : launch_gemm_variant<false, true, 2>(g, grid, s);
+    return deep ? launch_gemm_variant<false, false, 4>(g, grid, s) : launch_gemm_variant<false, false, 2>(g, grid, s);
 }
 
 // ------------------------------------------------------------------------------------------ row kernels
@@ -212,23 +301,72 @@ __device__ __forceinline__ float enc_load(const void* p, int64_t i)
 }
 
 // out[row, :] = Norm(LN(x[row, :])) = (x - mean) / ||x - mean|| as bf16 (a row without variance gives zeros); one
-// wavefront per row, three passes over a row that stays in L1/L2 after the first.
-template <bool BF16>
-__global__ __launch_bounds__(256) void ln_norm_rows_kernel(const void* __restrict__ x, int64_t rows, int32_t dim, int64_t ld_in,
-                                                           __bf16* __restrict__ out, int64_t ld_out)
+// wavefront per row.  Rows come from two matrices in one launch (the anchors, then the dense tokens): rows [0, rows_a)
+// from xa into outa, the rest from xb into outb.  CH > 0: bf16 rows of up to 64 * 8 * CH elements, dim a multiple of 8
+// and 16-byte aligned rows: the row is read once with 16-byte loads and stays in registers for the centred second pass
+// and the store.  CH == 0: any row, three passes over a row that stays in L1/L2 after the first.
+template <bool BF16, int CH>
+__global__ __launch_bounds__(256) void ln_norm_rows_kernel(const void* __restrict__ xa, int64_t rows_a, const void* __restrict__ xb,
+                                                           int64_t rows_b, int32_t dim, __bf16* __restrict__ outa,
+                                                           __bf16* __restrict__ outb)
 {
     const int lane = threadIdx.x & (kWave - 1);
-    const int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
-    if (row >= rows) return;
-    const int64_t base = row * ld_in;
-    float sum = 0.f;
-    for (int j = lane; j < dim; j += kWave) sum += enc_load<BF16>(x, base + j);
-    const float mean = wave_sum(sum) / static_cast<float>(dim);
-    float n2 = 0.f;
-    for (int j = lane; j < dim; j += kWave) { const float c = enc_load<BF16>(x, base + j) - mean; n2 = fmaf(c, c, n2); }
-    n2 = wave_sum(n2);
-    const float inv = n2 > 0.f ? 1.0f / sqrtf(n2) : 0.f;
-    for (int j = lane; j < dim; j += kWave) out[row * ld_out + j] = static_cast<__bf16>((enc_load<BF16>(x, base + j) - mean) * inv);
+    int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (row >= rows_a + rows_b) return;
+    const void* x = xa;
+    __bf16* out = outa;
+    if (row >= rows_a) { row -= rows_a; x = xb; out = outb; }
+    const int64_t base = row * dim;
+    if constexpr (CH > 0) {
+        static_assert(BF16, "the register-resident path reads packed bf16");
+        const u32x4* src = reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(x) + base);
+        const int n_chunks = dim >> 3;
+        u32x4 v[CH];
+        float sum = 0.f;
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            const int k = c * kWave + lane;
+            v[c] = u32x4{0u, 0u, 0u, 0u};
+            if (k < n_chunks) v[c] = src[k];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) sum += __uint_as_float(v[c][e] << 16) + __uint_as_float(v[c][e] & 0xFFFF0000u);
+        }
+        const float mean = wave_sum(sum) / static_cast<float>(dim);
+        float n2 = 0.f;
+#pragma unroll
+        for (int c = 0; c < CH; ++c)
+            if (c * kWave + lane < n_chunks) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float lo = __uint_as_float(v[c][e] << 16) - mean, hi = __uint_as_float(v[c][e] & 0xFFFF0000u) - mean;
+                    n2 = fmaf(lo, lo, n2); n2 = fmaf(hi, hi, n2);
+                }
+            }
+        n2 = wave_sum(n2);
+        const float inv = n2 > 0.f ? 1.0f / sqrtf(n2) : 0.f;
+        u32x4* dst = reinterpret_cast<u32x4*>(out + base);
+#pragma unroll
+        for (int c = 0; c < CH; ++c)
+            if (c * kWave + lane < n_chunks) {
+                u32x4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const __bf16 lo = static_cast<__bf16>((__uint_as_float(v[c][e] << 16) - mean) * inv);
+                    const __bf16 hi = static_cast<__bf16>((__uint_as_float(v[c][e] & 0xFFFF0000u) - mean) * inv);
+                    o[e] = static_cast<uint32_t>(__builtin_bit_cast(uint16_t, lo)) | (static_cast<uint32_t>(__builtin_bit_cast(uint16_t, hi)) << 16);
+                }
+                dst[c * kWave + lane] = o;
+            }
+    } else {
+        float sum = 0.f;
+        for (int j = lane; j < dim; j += kWave) sum += enc_load<BF16>(x, base + j);
+        const float mean = wave_sum(sum) / static_cast<float>(dim);
+        float n2 = 0.f;
+        for (int j = lane; j < dim; j += kWave) { const float c = enc_load<BF16>(x, base + j) - mean; n2 = fmaf(c, c, n2); }
+        n2 = wave_sum(n2);
+        const float inv = n2 > 0.f ? 1.0f / sqrtf(n2) : 0.f;
+        for (int j = lane; j < dim; j += kWave) out[base + j] = static_cast<__bf16>((enc_load<BF16>(x, base + j) - mean) * inv);
+    }
 }
 
 // p[row, 0..cols) = softmax(s[row, 0..cols)) as bf16, p[row, cols..ld_p) = 0; one wavefront per row.  Rows of up to
@@ -364,7 +502,7 @@ static size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
 struct AggPlan {                         // byte offsets into the workspace of civic_anchor_aggregate
     int64_t t_pad;
-    size_t qa, k0, s, p, xt, total;
+    size_t qa, k0, s, p, total;
 };
 
 static void agg_plan(int32_t batch, int32_t n_tokens, int32_t n_anchors, int32_t dim, AggPlan* p)
@@ -375,7 +513,6 @@ static void agg_plan(int32_t batch, int32_t n_tokens, int32_t n_anchors, int32_t
     p->k0 = off; off += align256(static_cast<size_t>(batch) * n_tokens * dim * 2);
     p->s = off;  off += align256(static_cast<size_t>(batch) * n_anchors * p->t_pad * 4);
     p->p = off;  off += align256(static_cast<size_t>(batch) * n_anchors * p->t_pad * 2);
-    p->xt = off; off += align256(static_cast<size_t>(batch) * dim * p->t_pad * 2);
     p->total = off;
 }
 
@@ -391,7 +528,8 @@ static void compress_plan(int32_t batch, int32_t n_rows, int32_t n_mem, int32_t 
     p->inv = off; off += align256(static_cast<size_t>(n_mem) * 4);
     p->part = off; off += align256(static_cast<size_t>(n_mem) * 4 * kColParts);
     p->rt = off;  off += align256(static_cast<size_t>(n_mem) * p->m_pad * 2);
-    p->xt = off;  off += align256(static_cast<size_t>(batch) * width * p->m_pad * 2);
+    // (a transposed copy of K, then V, only for widths whose rows are not whole 16-byte chunks)
+    p->xt = off;  off += width % 8 ? align256(static_cast<size_t>(batch) * width * p->m_pad * 2) : 0;
     p->total = off;
 }
 
@@ -435,28 +573,31 @@ extern "C" int civic_anchor_aggregate(const void* x0, const void* anchors, int d
     __bf16* k0 = reinterpret_cast<__bf16*>(ws + p.k0);
     float* sl = reinterpret_cast<float*>(ws + p.s);
     __bf16* pw = reinterpret_cast<__bf16*>(ws + p.p);
-    __bf16* xt = reinterpret_cast<__bf16*>(ws + p.xt);
     const int64_t rows_x = static_cast<int64_t>(batch) * n_tokens;
 
-    // Q_A = Norm(LN(A)), K_0 = Norm(LN(X_0))
-    hipLaunchKernelGGL((ln_norm_rows_kernel<true>), dim3(static_cast<unsigned>((n_anchors + 3) / 4)), dim3(256), 0, s, anchors,
-                       static_cast<int64_t>(n_anchors), dim, static_cast<int64_t>(dim), qa, static_cast<int64_t>(dim));
-    hipLaunchKernelGGL((ln_norm_rows_kernel<true>), dim3(static_cast<unsigned>((rows_x + 3) / 4)), dim3(256), 0, s, x0, rows_x, dim,
-                       static_cast<int64_t>(dim), k0, static_cast<int64_t>(dim));
-    // X_0^T with the token axis zero-padded to a multiple of 64
-    hipLaunchKernelGGL((transpose_pad_kernel<__bf16>), dim3(static_cast<unsigned>(p.t_pad / 32), static_cast<unsigned>((dim + 31) / 32),
-                                                            static_cast<unsigned>(batch)),
-                       dim3(256), 0, s, static_cast<const __bf16*>(x0), n_tokens, dim, static_cast<int64_t>(dim),
-                       static_cast<int64_t>(n_tokens) * dim, static_cast<const float*>(nullptr), xt, p.t_pad, static_cast<int64_t>(dim) * p.t_pad);
+    // Q_A = Norm(LN(A)), K_0 = Norm(LN(X_0)): one launch over the rows of both
+    {
+        const dim3 grid(static_cast<unsigned>((n_anchors + rows_x + 3) / 4));
+        const int chunks = (dim / 8 + kWave - 1) / kWave;                              // 16-byte pieces per lane
+#define CIVIC_LN_CASE(N) hipLaunchKernelGGL((ln_norm_rows_kernel<true, N>), grid, dim3(256), 0, s, anchors, static_cast<int64_t>(n_anchors), \
+                                            x0, rows_x, dim, qa, k0)
+        if (chunks <= 1) CIVIC_LN_CASE(1);
+        else if (chunks <= 2) CIVIC_LN_CASE(2);
+        else if (chunks <= 4) CIVIC_LN_CASE(4);
+        else if (chunks <= 8) CIVIC_LN_CASE(8);
+        else CIVIC_LN_CASE(0);
+#undef CIVIC_LN_CASE
+    }
     int rc = check_launch();
     if (rc != CIVIC_OK) return rc;
     // logits = Q_A K_0^T / tau  [n_anchors x n_tokens] per batch item, fp32
     GemmArgs g1;
+    g1.b_alt = nullptr; g1.c_alt = nullptr; g1.kb_rows = 0;
     g1.a = qa; g1.b = k0; g1.c = sl;
     g1.lda = dim; g1.ldb = dim; g1.ldc = p.t_pad;
     g1.sa = 0; g1.sb = static_cast<int64_t>(n_tokens) * dim; g1.sc = static_cast<int64_t>(n_anchors) * p.t_pad;
     g1.m = n_anchors; g1.n = n_tokens; g1.k = dim; g1.alpha = inv_tau;
-    rc = launch_gemm_nt(g1, batch, false, s);
+    rc = launch_gemm(g1, batch, false, false, s);
     if (rc != CIVIC_OK) return rc;
     // W_A = softmax over the dense tokens, bf16, zero in the padding
     const int64_t rows_w = static_cast<int64_t>(batch) * n_anchors;
@@ -476,13 +617,14 @@ extern "C" int civic_anchor_aggregate(const void* x0, const void* anchors, int d
                            pw, n_anchors, n_tokens, p.t_pad, static_cast<int64_t>(n_anchors) * p.t_pad, token_weight);
     rc = check_launch();
     if (rc != CIVIC_OK) return rc;
-    // Z_0 = W_A X_0 = W_A (X_0^T)^T
+    // Z_0 = W_A X_0, X_0 read where it lies (tokens are its rows: the contraction index is the row index)
     GemmArgs g2;
-    g2.a = pw; g2.b = xt; g2.c = z0;
-    g2.lda = p.t_pad; g2.ldb = p.t_pad; g2.ldc = dim;
-    g2.sa = static_cast<int64_t>(n_anchors) * p.t_pad; g2.sb = static_cast<int64_t>(dim) * p.t_pad; g2.sc = static_cast<int64_t>(n_anchors) * dim;
-    g2.m = n_anchors; g2.n = dim; g2.k = static_cast<int32_t>(p.t_pad); g2.alpha = 1.0f;
-    return launch_gemm_nt(g2, batch, true, s);
+    g2.b_alt = nullptr; g2.c_alt = nullptr;
+    g2.a = pw; g2.b = static_cast<const __bf16*>(x0); g2.c = z0;
+    g2.lda = p.t_pad; g2.ldb = dim; g2.ldc = dim;
+    g2.sa = static_cast<int64_t>(n_anchors) * p.t_pad; g2.sb = static_cast<int64_t>(n_tokens) * dim; g2.sc = static_cast<int64_t>(n_anchors) * dim;
+    g2.m = n_anchors; g2.n = dim; g2.k = static_cast<int32_t>(p.t_pad); g2.kb_rows = n_tokens; g2.alpha = 1.0f;
+    return launch_gemm(g2, batch, true, true, s);
 }
 
 extern "C" size_t civic_kv_compress_workspace_bytes(int32_t batch, int32_t n_rows, int32_t n_mem, int32_t width)
@@ -524,10 +666,20 @@ extern "C" int civic_kv_compress(const void* k, const void* v, int dtype, const 
                        dim3(256), 0, s, r, n_rows, n_mem, static_cast<int64_t>(n_mem), int64_t{0}, inv, rt, p.m_pad, int64_t{0});
     int rc = check_launch();
     if (rc != CIVIC_OK) return rc;
+    GemmArgs g;
+    g.a = rt; g.lda = p.m_pad; g.ldc = width;
+    g.sa = 0; g.sc = static_cast<int64_t>(n_mem) * width;
+    g.m = n_mem; g.n = width; g.k = static_cast<int32_t>(p.m_pad); g.alpha = 1.0f;
+    if (width % 8 == 0) {
+        // X_c = Rbar^T X with X read where it lies (its rows are the contraction index); K and V in one launch
+        g.b = static_cast<const __bf16*>(k); g.c = k_c; g.b_alt = static_cast<const __bf16*>(v); g.c_alt = v_c;
+        g.ldb = width; g.sb = static_cast<int64_t>(n_rows) * width; g.kb_rows = n_rows;
+        return launch_gemm(g, batch, true, true, s);
+    }
     const void* src[2] = {k, v};
     void* dst[2] = {k_c, v_c};
     for (int t = 0; t < 2; ++t) {
-        // X^T [width x m_pad] per batch item, then X_c = Rbar^T X = Rbar^T (X^T)^T
+        // X^T [width x m_pad] per batch item, then X_c = Rbar^T (X^T)^T
         hipLaunchKernelGGL((transpose_pad_kernel<__bf16>), dim3(static_cast<unsigned>(p.m_pad / 32), static_cast<unsigned>((width + 31) / 32),
                                                                 static_cast<unsigned>(batch)),
                            dim3(256), 0, s, static_cast<const __bf16*>(src[t]), n_rows, width, static_cast<int64_t>(width),
@@ -535,12 +687,9 @@ extern "C" int civic_kv_compress(const void* k, const void* v, int dtype, const 
                            static_cast<int64_t>(width) * p.m_pad);
         rc = check_launch();
         if (rc != CIVIC_OK) return rc;
-        GemmArgs g;
-        g.a = rt; g.b = xt; g.c = dst[t];
-        g.lda = p.m_pad; g.ldb = p.m_pad; g.ldc = width;
-        g.sa = 0; g.sb = static_cast<int64_t>(width) * p.m_pad; g.sc = static_cast<int64_t>(n_mem) * width;
-        g.m = n_mem; g.n = width; g.k = static_cast<int32_t>(p.m_pad); g.alpha = 1.0f;
-        rc = launch_gemm_nt(g, batch, true, s);
+        g.b = xt; g.c = dst[t]; g.b_alt = nullptr; g.c_alt = nullptr; g.kb_rows = 0;
+        g.ldb = p.m_pad; g.sb = static_cast<int64_t>(width) * p.m_pad;
+        rc = launch_gemm(g, batch, true, false, s);
         if (rc != CIVIC_OK) return rc;
     }
     return CIVIC_OK;
