@@ -214,10 +214,10 @@ int civic_kv_write(const void* k, const void* v, const int64_t* kv_strides /* ho
                    void* stream);
 
 /* civic_prefill_attn followed by civic_kv_write on the same K and V, as one call: the attention
- * term and the KV-write term of Eq. 7 belong to the same layer and read the same rows, so where the
- * MFMA attention kernel runs (bf16, head_dim <= 128) the workgroup that has just streamed a block
- * of K/V rows also copies them into the caches and no second pass over K and V is made; otherwise
- * the two steps run back to back.  Results are those of the two separate calls, bit for bit.
+ * term and the KV-write term of Eq. 7 belong to the same layer and read the same rows, so the
+ * workgroup that owns a block of query rows also copies the K/V rows of those positions into the
+ * caches: one launch, and where the MFMA attention kernel runs (bf16, head_dim <= 128) no second
+ * pass over K and V from memory.  Results are those of the two separate calls, bit for bit.
  * Arguments, layouts and error behaviour are theirs; k_cache and v_cache must not be null. */
 int civic_prefill_attn_kv(const void* q, const void* k, const void* v, void* out,
                           void* k_cache, void* v_cache, int dtype,

@@ -96,6 +96,22 @@ __global__ __launch_bounds__(256) void attn_plain_kernel(AttnArgs a)
     const int g = h / (a.n_q_heads / a.n_kv_heads), d = a.head_dim;
     const int64_t q_off = b * a.qs[0] + i * a.qs[1] + h * a.qs[2];
     const int64_t kv_off = b * a.ks[0] + g * a.ks[2];
+    // KV-cache write of this query row's K and V row (the first head of every KV group does it; 16-byte pieces, loads
+    // and stores fly under everything below), so that this path needs no second launch either
+    if (a.k_cache != nullptr && h == g * (a.n_q_heads / a.n_kv_heads)) {
+        constexpr int EPP = BF16 ? 8 : 4;                     // elements per piece
+        const int64_t src = kv_off + static_cast<int64_t>(i) * a.ks[1];
+        const int64_t dst = ((static_cast<int64_t>(b) * a.n_kv_heads + g) * a.s_max + a.pos0 + i) * d;
+        for (int c = lane * EPP; c < d; c += kWave * EPP) {
+            if constexpr (BF16) {
+                *reinterpret_cast<uint4*>(static_cast<uint16_t*>(a.k_cache) + dst + c) = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(a.k) + src + c);
+                *reinterpret_cast<uint4*>(static_cast<uint16_t*>(a.v_cache) + dst + c) = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(a.v) + src + c);
+            } else {
+                *reinterpret_cast<float4*>(static_cast<float*>(a.k_cache) + dst + c) = *reinterpret_cast<const float4*>(static_cast<const float*>(a.k) + src + c);
+                *reinterpret_cast<float4*>(static_cast<float*>(a.v_cache) + dst + c) = *reinterpret_cast<const float4*>(static_cast<const float*>(a.v) + src + c);
+            }
+        }
+    }
     for (int c = lane; c < d; c += kWave) q_s[w][c] = load_elem<BF16>(a.q, q_off + c) * a.scale;
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -1062,15 +1078,11 @@ static int prefill_attn(const void* q, const void* k, const void* v, void* out, 
         if (2 * per_rt * a.row_tiles > kComputeUnits || !mfma_geometry<4>(a, &per_rt)) return launch_mfma_for<8>(a, s);
         return launch_mfma_for<4>(a, s);
     }
-    // (the limit of the separate KV-write launch that follows, checked before anything is launched)
-    if (k_cache && static_cast<int64_t>(seq) * n_kv_heads * (static_cast<int64_t>(head_dim) * esz / 16) > INT32_MAX)
-        return CIVIC_ERR_UNSUPPORTED;
+    // everything else: the fp32 kernel (which also writes the caches when asked to)
     const dim3 grid(static_cast<unsigned>((seq + 3) / 4), static_cast<unsigned>(n_q_heads), static_cast<unsigned>(batch));
     if (dtype == CIVIC_BF16) hipLaunchKernelGGL((attn_plain_kernel<true>), grid, dim3(256), 0, s, a);
     else hipLaunchKernelGGL((attn_plain_kernel<false>), grid, dim3(256), 0, s, a);
-    const int rc = check_launch();
-    if (rc != CIVIC_OK || !k_cache) return rc;
-    return civic_kv_write(k, v, kv_strides, dtype, k_cache, v_cache, batch, seq, n_kv_heads, head_dim, s_max, pos0, stream);
+    return check_launch();
 }
 
 }  // namespace civic
