@@ -274,3 +274,27 @@ def cross_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: Optional
     sc = (1.0 / np.sqrt(d)) if scale is None else float(scale)
     lib().oracle_cross_attention(_ptr(q), _ptr(k), _ptr(v), _ptr(out), batch, n_q, n_kv, hq, hkv, d, sc)
     return out
+
+
+def _check_offsets(row_offsets, total: int) -> np.ndarray:
+    off = np.asarray(row_offsets, dtype=np.int64)
+    assert off.ndim == 1 and off.size >= 1 and off[0] == 0 and off[-1] == total and np.all(np.diff(off) >= 1)
+    return off
+
+
+def kv_compress_ragged(x: np.ndarray, r: np.ndarray, row_offsets) -> np.ndarray:
+    """Eq. 9 for items of different sizes (images of different grids) packed back to back: item b owns rows
+    [row_offsets[b], row_offsets[b+1]) of x fp32 [total, width] and of its own assignment rows r fp32 [total, S];
+    every item is compressed by itself -> float64 [batch, S, width]."""
+    off = _check_offsets(row_offsets, x.shape[0])
+    assert r.shape[0] == x.shape[0]
+    return np.stack([kv_compress(x[None, a:b], r[a:b])[0] for a, b in zip(off[:-1], off[1:])])
+
+
+def cross_attention_ragged(q: np.ndarray, k: np.ndarray, v: np.ndarray, row_offsets, scale: Optional[float] = None) -> np.ndarray:
+    """q fp32 [total, H_q, d] packed as above; k, v fp32 [batch, n_kv, H_kv, d]: the queries of item b attend to the
+    keys of item b only, no mask -> float64 [total, H_q, d]."""
+    off = _check_offsets(row_offsets, q.shape[0])
+    assert k.shape[0] == off.size - 1
+    return np.concatenate([cross_attention(q[None, a:b], k[i:i + 1], v[i:i + 1], scale)[0]
+                           for i, (a, b) in enumerate(zip(off[:-1], off[1:]))])

@@ -110,3 +110,42 @@ def test_kv_compress_and_cross_attention():
     og = oracle.cross_attention(q, k2, v2)
     rep = lambda a: np.repeat(a, 2, axis=2)
     assert np.abs(og - oracle.cross_attention(q, rep(k2), rep(v2))).max() < 1e-14
+
+
+def test_ragged_items_are_compressed_and_attended_one_by_one():
+    """Items of different sizes packed back to back (images of different grids in one batch, Eq. 9)."""
+    rng = np.random.default_rng(5)
+    sizes, h, d, s = [9, 30, 1, 17], 2, 8, 5
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    total = int(off[-1])
+    q = rng.standard_normal((total, h, d)).astype(np.float32)
+    k = rng.standard_normal((total, h * d)).astype(np.float32)
+    v = rng.standard_normal((total, h * d)).astype(np.float32)
+    r = rng.random((total, s)).astype(np.float32)
+    kc, vc = oracle.kv_compress_ragged(k, r, off), oracle.kv_compress_ragged(v, r, off)
+    assert kc.shape == (4, s, h * d)
+    # every item against the definition written out with numpy, on its own rows only
+    for i, (a, b) in enumerate(zip(off[:-1], off[1:])):
+        rb = r[a:b].astype(np.float64)
+        rb = rb / rb.sum(axis=0, keepdims=True)
+        assert np.abs(kc[i] - rb.T @ k[a:b].astype(np.float64)).max() < 1e-13
+    # an item does not see the others: changing item 1 leaves items 0, 2, 3 as they were
+    k2 = k.copy()
+    k2[off[1]:off[2]] += 3.0
+    kc2 = oracle.kv_compress_ragged(k2, r, off)
+    assert np.array_equal(kc2[[0, 2, 3]], kc[[0, 2, 3]]) and not np.array_equal(kc2[1], kc[1])
+    # attention of the packed queries over their own item's compressed keys: library attention item by item
+    k4, v4 = kc.reshape(4, s, h, d).astype(np.float32), vc.reshape(4, s, h, d).astype(np.float32)
+    o = oracle.cross_attention_ragged(q, k4, v4, off)
+    for i, (a, b) in enumerate(zip(off[:-1], off[1:])):
+        t = lambda x: torch.from_numpy(x).double().permute(1, 0, 2)[None]
+        ref = torch.nn.functional.scaled_dot_product_attention(t(q[a:b]), t(k4[i]), t(v4[i]))[0].permute(1, 0, 2).numpy()
+        assert np.abs(o[a:b] - ref).max() < 1e-12
+    # equal sizes: the packed form is the rectangular one
+    m = 6
+    off_eq = np.arange(0, 4 * m + 1, m)
+    xe = rng.standard_normal((4, m, h * d)).astype(np.float32)
+    re = rng.random((m, s)).astype(np.float32)
+    assert np.array_equal(oracle.kv_compress_ragged(xe.reshape(4 * m, -1), np.tile(re, (4, 1)), off_eq), oracle.kv_compress(xe, re))
+    qe = rng.standard_normal((4, m, h, d)).astype(np.float32)
+    assert np.array_equal(oracle.cross_attention_ragged(qe.reshape(4 * m, h, d), k4, v4, off_eq), oracle.cross_attention(qe, k4, v4).reshape(4 * m, h, d))
