@@ -315,6 +315,30 @@ int civic_cross_attn(const void* q, const void* k, const void* v, void* out, int
                      const int64_t* q_strides /* host [3] */, const int64_t* kv_strides /* host [3] */,
                      const int64_t* o_strides /* host [3] */, float softmax_scale, void* stream);
 
+/* Eq. 9 for a batch whose items differ in size (images of different grids in one batch): the rows of all items are
+ * packed back to back, item b owning rows [row_offsets[b], row_offsets[b+1]) of k, v and of its own assignment rows in
+ * r; every item is compressed and attended by itself, with the kernels of the rectangular calls (one pass per item
+ * on the stream; results equal civic_kv_compress / civic_cross_attn on that item alone, bit for bit).
+ *   k, v         device [total_rows, width] bf16;  r  device [total_rows, n_mem] fp32
+ *   row_offsets  host [batch + 1] int64, row_offsets[0] = 0, strictly increasing (no empty item)
+ *   k_c, v_c     device [batch, n_mem, width] bf16
+ *   workspace    civic_kv_compress_ragged_workspace_bytes(same sizes): the largest item's need, shared in turn
+ * width must be a multiple of 8 and n_mem of 4 (every item's first row 16-byte aligned), else CIVIC_ERR_UNSUPPORTED. */
+size_t civic_kv_compress_ragged_workspace_bytes(int32_t batch, const int64_t* row_offsets /* host */, int32_t n_mem,
+                                                int32_t width);
+int civic_kv_compress_ragged(const void* k, const void* v, int dtype, const float* r, int32_t batch,
+                             const int64_t* row_offsets /* host */, int32_t n_mem, int32_t width, void* k_c, void* v_c,
+                             void* workspace, size_t workspace_bytes, void* stream);
+/*   q, out       device [total_rows, n_q_heads, head_dim], element strides (unused, token, head) in q_strides / o_strides
+ *   k, v         device [batch, n_kv, n_kv_heads, head_dim] (civic_kv_compress_ragged's outputs), strides in kv_strides
+ *   q_offsets    as row_offsets above
+ * Everything else as civic_cross_attn. */
+int civic_cross_attn_ragged(const void* q, const void* k, const void* v, void* out, int dtype, int32_t batch,
+                            const int64_t* q_offsets /* host */, int32_t n_kv, int32_t n_q_heads, int32_t n_kv_heads,
+                            int32_t head_dim, const int64_t* q_strides /* host [3] */,
+                            const int64_t* kv_strides /* host [3] */, const int64_t* o_strides /* host [3] */,
+                            float softmax_scale, void* stream);
+
 /* Decode-step attention over the compact cache: the work one generated token adds to the autoregressive
  * decoding cost C_dec of Eq. 2 / Eq. 7, in which "every generated text token must attend to the entire visual
  * prompt" (latency decomposition, decode column of the latency table) - here to the compact one that

@@ -26,7 +26,8 @@ EXPORTS = ("civic_last_hip_error", "civic_kept_count", "civic_select_workspace_b
            "civic_decode_attn_workspace_bytes", "civic_decode_attn", "civic_decode_attn_noalloc",
            "civic_mrope_table", "civic_mrope_apply", "civic_kv_write_rope", "civic_prefill_attn_rope",
            "civic_anchor_aggregate_workspace_bytes", "civic_anchor_aggregate", "civic_kv_compress_workspace_bytes",
-           "civic_kv_compress", "civic_cross_attn")
+           "civic_kv_compress", "civic_cross_attn", "civic_kv_compress_ragged_workspace_bytes",
+           "civic_kv_compress_ragged", "civic_cross_attn_ragged")
 
 
 class CivicError(RuntimeError):
@@ -105,6 +106,13 @@ lib.civic_kv_compress.argtypes = [_P, _P, C.c_int, _P, C.c_int32, C.c_int32, C.c
 lib.civic_cross_attn.restype = C.c_int
 lib.civic_cross_attn.argtypes = [_P, _P, _P, _P, C.c_int, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                  _P, _P, _P, C.c_float, _P]
+lib.civic_kv_compress_ragged_workspace_bytes.restype = C.c_size_t
+lib.civic_kv_compress_ragged_workspace_bytes.argtypes = [C.c_int32, _P, C.c_int32, C.c_int32]
+lib.civic_kv_compress_ragged.restype = C.c_int
+lib.civic_kv_compress_ragged.argtypes = [_P, _P, C.c_int, _P, C.c_int32, _P, C.c_int32, C.c_int32, _P, _P, _P, C.c_size_t, _P]
+lib.civic_cross_attn_ragged.restype = C.c_int
+lib.civic_cross_attn_ragged.argtypes = [_P, _P, _P, _P, C.c_int, C.c_int32, _P, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _P, _P, _P,
+                                        C.c_float, _P]
 lib.civic_mrope_table.restype = C.c_int
 lib.civic_mrope_table.argtypes = [_P, C.c_int32, C.c_int64, C.c_int32, _P, _P, _P, _P]
 lib.civic_mrope_apply.restype = C.c_int
@@ -498,4 +506,48 @@ def civic_cross_attn(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, softmax_
     _check("civic_cross_attn", lib.civic_cross_attn(_dev(q), _dev(k), _dev(v), _dev(out), _dtype_code(q), batch, n_q, k.shape[1], hq,
                                                     k.shape[2], d, _strides3(q), _strides3(k), _strides3(out), float(softmax_scale),
                                                     _stream(stream)))
+    return out
+
+
+def civic_kv_compress_ragged(k: torch.Tensor, v: torch.Tensor, r: torch.Tensor, row_offsets: Sequence[int],
+                             k_c: Optional[torch.Tensor] = None, v_c: Optional[torch.Tensor] = None,
+                             workspace: Optional[torch.Tensor] = None, stream=None):
+    """Eq. 9 for packed items: k, v [total, ...] (trailing axes flattened to the width), r fp32 [total, S], item b owning
+    rows [row_offsets[b], row_offsets[b+1]) -> k_c, v_c [batch, S, ...]."""
+    if k.shape != v.shape or not k.is_contiguous() or not v.is_contiguous() or not r.is_contiguous() or r.dtype != torch.float32:
+        raise ValueError("k and v must be contiguous of one shape, r contiguous fp32 [total, S]")
+    off = np.ascontiguousarray(np.asarray(row_offsets, dtype=np.int64))
+    batch = off.size - 1
+    width = int(np.prod(k.shape[1:]))
+    s_mem = r.shape[1]
+    if r.shape[0] != k.shape[0] or off[-1] != k.shape[0]:
+        raise ValueError("r and the offsets must cover the packed rows")
+    if k_c is None:
+        k_c = torch.empty((batch, s_mem) + tuple(k.shape[1:]), dtype=k.dtype, device=k.device)
+    if v_c is None:
+        v_c = torch.empty_like(k_c)
+    if workspace is None:
+        need = int(lib.civic_kv_compress_ragged_workspace_bytes(batch, C.c_void_p(off.ctypes.data), s_mem, width))
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=k.device)
+    _check("civic_kv_compress_ragged", lib.civic_kv_compress_ragged(
+        _dev(k), _dev(v), _dtype_code(k), _dev(r), batch, C.c_void_p(off.ctypes.data), s_mem, width, _dev(k_c), _dev(v_c),
+        _dev(workspace), workspace.numel(), _stream(stream)))
+    return k_c, v_c
+
+
+def civic_cross_attn_ragged(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, q_offsets: Sequence[int],
+                            softmax_scale: float = 0.0, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """q [total, H_q, d] packed (item b owning rows [q_offsets[b], q_offsets[b+1])) over k, v [batch, n_kv, H_kv, d]."""
+    if k.shape != v.shape or k.stride() != v.stride() or q.dtype != k.dtype or q.dim() != 3 or q.stride(2) != 1:
+        raise ValueError("q [total, H_q, d]; k and v [batch, n_kv, H_kv, d] of one shape, strides and dtype")
+    off = np.ascontiguousarray(np.asarray(q_offsets, dtype=np.int64))
+    batch = off.size - 1
+    total, hq, d = q.shape
+    if out is None:
+        out = torch.empty((total, hq, d), dtype=q.dtype, device=q.device)
+    qs = (C.c_int64 * 3)(0, q.stride(0), q.stride(1))
+    os_ = (C.c_int64 * 3)(0, out.stride(0), out.stride(1))
+    _check("civic_cross_attn_ragged", lib.civic_cross_attn_ragged(
+        _dev(q), _dev(k), _dev(v), _dev(out), _dtype_code(q), batch, C.c_void_p(off.ctypes.data), k.shape[1], hq, k.shape[2], d,
+        qs, _strides3(k), os_, float(softmax_scale), _stream(stream)))
     return out

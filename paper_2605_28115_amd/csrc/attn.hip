@@ -1124,3 +1124,31 @@ extern "C" int civic_cross_attn(const void* q, const void* k, const void* v, voi
     return civic::prefill_attn(q, k, v, out, dtype, batch, n_q, n_kv, n_q_heads, n_kv_heads, head_dim, q_strides, kv_strides,
                                o_strides, 0, softmax_scale, nullptr, nullptr, 0, 0, nullptr, stream);
 }
+
+extern "C" int civic_cross_attn_ragged(const void* q, const void* k, const void* v, void* out, int dtype, int32_t batch,
+                                       const int64_t* q_offsets, int32_t n_kv, int32_t n_q_heads, int32_t n_kv_heads,
+                                       int32_t head_dim, const int64_t* q_strides, const int64_t* kv_strides,
+                                       const int64_t* o_strides, float softmax_scale, void* stream)
+{
+    const int esz = civic::dtype_size(dtype);
+    if (!esz || batch < 0 || !q_strides || !kv_strides || !o_strides) return CIVIC_ERR_INVALID_ARG;
+    if (batch == 0) return CIVIC_OK;
+    if (!q_offsets || q_offsets[0] != 0 || !q || !k || !v || !out) return CIVIC_ERR_INVALID_ARG;
+    for (int32_t b = 0; b < batch; ++b)
+        if (q_offsets[b + 1] <= q_offsets[b] || q_offsets[b + 1] - q_offsets[b] > INT32_MAX) return CIVIC_ERR_INVALID_ARG;
+    // q_strides[0] / o_strides[0] (the batch stride of the rectangular call) are not used: items are packed along the
+    // token axis; the per-item call checks everything else (a token stride that keeps rows 16-byte aligned keeps every
+    // item's first row aligned as well)
+    const char* qb = static_cast<const char*>(q);
+    char* ob = static_cast<char*>(out);
+    for (int32_t b = 0; b < batch; ++b) {
+        const int64_t row0 = q_offsets[b];
+        const int rc = civic_cross_attn(qb + row0 * q_strides[1] * esz, static_cast<const char*>(k) + b * kv_strides[0] * esz,
+                                        static_cast<const char*>(v) + b * kv_strides[0] * esz, ob + row0 * o_strides[1] * esz, dtype, 1,
+                                        static_cast<int32_t>(q_offsets[b + 1] - row0), n_kv, n_q_heads, n_kv_heads, head_dim, q_strides,
+                                        kv_strides, o_strides, softmax_scale, stream);
+        if (rc != CIVIC_OK) return rc;
+    }
+    return CIVIC_OK;
+}
+

@@ -694,3 +694,57 @@ extern "C" int civic_kv_compress(const void* k, const void* v, int dtype, const 
     }
     return CIVIC_OK;
 }
+
+// ---------------------------------------------------------------------------------------------- ragged batches
+namespace civic {
+
+// host [batch + 1], starting at 0, strictly increasing (every item has at least one row)
+static bool offsets_ok(const int64_t* off, int32_t batch)
+{
+    if (!off || off[0] != 0) return false;
+    for (int32_t b = 0; b < batch; ++b)
+        if (off[b + 1] <= off[b] || off[b + 1] - off[b] > INT32_MAX) return false;
+    return true;
+}
+
+}  // namespace civic
+
+extern "C" size_t civic_kv_compress_ragged_workspace_bytes(int32_t batch, const int64_t* row_offsets, int32_t n_mem, int32_t width)
+{
+    if (batch <= 0 || n_mem <= 0 || width <= 0 || !civic::offsets_ok(row_offsets, batch)) return 0;
+    size_t need = 0;                                          // the items run one after the other and share the scratch
+    for (int32_t b = 0; b < batch; ++b) {
+        const size_t one = civic_kv_compress_workspace_bytes(1, static_cast<int32_t>(row_offsets[b + 1] - row_offsets[b]), n_mem, width);
+        need = one > need ? one : need;
+    }
+    return need;
+}
+
+extern "C" int civic_kv_compress_ragged(const void* k, const void* v, int dtype, const float* r, int32_t batch,
+                                        const int64_t* row_offsets, int32_t n_mem, int32_t width, void* k_c, void* v_c,
+                                        void* workspace, size_t workspace_bytes, void* stream)
+{
+    using namespace civic;
+    const int esz = dtype_size(dtype);
+    if (!esz || batch < 0 || n_mem <= 0 || width <= 0) return CIVIC_ERR_INVALID_ARG;
+    if (batch == 0) return CIVIC_OK;
+    if (!offsets_ok(row_offsets, batch)) return CIVIC_ERR_INVALID_ARG;
+    if (!r || !k || !v || !k_c || !v_c) return CIVIC_ERR_INVALID_ARG;
+    if (!aligned16(k) || !aligned16(v) || !aligned16(k_c) || !aligned16(v_c) || !aligned16(r)) return CIVIC_ERR_INVALID_ARG;
+    if (dtype != CIVIC_BF16) return CIVIC_ERR_UNSUPPORTED;
+    // every item's first row must be 16-byte aligned in K, V and R: whole 16-byte pieces per row
+    if (width % 8 || n_mem % 4) return CIVIC_ERR_UNSUPPORTED;
+    const size_t need = civic_kv_compress_ragged_workspace_bytes(batch, row_offsets, n_mem, width);
+    if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return CIVIC_ERR_WORKSPACE;
+    // (civic_kv_compress checks the rest per item; its limits depend on the item's size only)
+    for (int32_t b = 0; b < batch; ++b) {
+        const int64_t row0 = row_offsets[b];
+        const int rc = civic_kv_compress(static_cast<const __bf16*>(k) + row0 * width, static_cast<const __bf16*>(v) + row0 * width, dtype,
+                                         r + row0 * n_mem, 1, static_cast<int32_t>(row_offsets[b + 1] - row0), n_mem, width,
+                                         static_cast<__bf16*>(k_c) + static_cast<int64_t>(b) * n_mem * width,
+                                         static_cast<__bf16*>(v_c) + static_cast<int64_t>(b) * n_mem * width, workspace, workspace_bytes, stream);
+        if (rc != CIVIC_OK) return rc;
+    }
+    return CIVIC_OK;
+}
+

@@ -248,4 +248,22 @@ def test_argument_errors_precede_any_hip_call(bd):
     assert attn_kv(q=None, k=None, v=None, o=None, kc=None, vc=None, s=0) == OK
     wide = (C.c_int64 * 3)(8192, 1024, 512)
     assert attn_kv(d=512, qs=wide, ks=wide, os=wide) == bd.ERR_UNSUPPORTED and attn_kv(s=0) == bd.CIVIC_OK
+    # ragged Eq. 9 calls: offsets (null, not starting at 0, an empty item), row alignment, workspace
+    def offs(*v):
+        return np.asarray(v, dtype=np.int64)
+    def rcomp(off=offs(0, 5, 12), batch=2, k=F, r=F, n_mem=8, width=64, ws=F, wsb=1 << 30, dt=1):
+        return L.civic_kv_compress_ragged(k, F, dt, r, batch, C.c_void_p(off.ctypes.data) if off is not None else None, n_mem, width,
+                                          F, F, ws, wsb, None)
+    assert rcomp(off=None) == I and rcomp(off=offs(1, 5, 12)) == I and rcomp(off=offs(0, 5, 5)) == I and rcomp(off=offs(0, 5, 3)) == I
+    assert rcomp(k=None) == I and rcomp(r=None) == I and rcomp(k=odd) == I and rcomp(batch=-1) == I and rcomp(dt=9) == I
+    assert rcomp(width=60) == bd.ERR_UNSUPPORTED and rcomp(n_mem=6) == bd.ERR_UNSUPPORTED and rcomp(dt=0) == bd.ERR_UNSUPPORTED
+    assert rcomp(ws=None, wsb=0) == bd.ERR_WORKSPACE and rcomp(wsb=16) == bd.ERR_WORKSPACE and rcomp(batch=0, off=None) == OK
+    o3 = offs(0, 5, 12)
+    need = L.civic_kv_compress_ragged_workspace_bytes(2, C.c_void_p(o3.ctypes.data), 8, 64)
+    assert need == max(L.civic_kv_compress_workspace_bytes(1, 5, 8, 64), L.civic_kv_compress_workspace_bytes(1, 7, 8, 64)) > 0
+    def rattn(off=offs(0, 5, 12), batch=2, q=F, k=F, o=F, hq=4, hkv=2, d=64, qs=st, ks=st):
+        return L.civic_cross_attn_ragged(q, k, k, o, 1, batch, C.c_void_p(off.ctypes.data) if off is not None else None, 8, hq, hkv, d,
+                                         qs, ks, st, C.c_float(0.0), None)
+    assert rattn(off=None) == I and rattn(off=offs(2, 5, 12)) == I and rattn(off=offs(0, 5, 5)) == I and rattn(q=None) == I
+    assert rattn(hq=3) == I and rattn(d=60) == I and rattn(qs=None) == I and rattn(k=odd) == I and rattn(batch=0, off=None) == OK
     assert bd.lib.civic_last_hip_error() == 0

@@ -116,3 +116,33 @@ def test_token_weights_feed_the_selection(bd):
     kept, _ = bd.civic_select(tw, w.grid_tuple())
     ref_kept, _ = oracle.select(to_host(tw), w.grid_tuple())
     assert np.array_equal(to_host(kept), ref_kept)
+
+
+@pytest.mark.parametrize("sizes", [[300, 1365, 77, 1024], [64], [1, 2, 3, 500], [1365, 341, 85]])
+def test_ragged_items_match_oracle_and_the_rectangular_calls(bd, sizes):
+    """Eq. 9 on images of different grid sizes in one batch: packed rows, every item by itself."""
+    log("ragged Eq. 9", sizes)
+    h, d, s = 4, 64, 128
+    rng = np.random.default_rng(sum(sizes))
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    total = int(off[-1])
+    mk = lambda: wl.quantize(rng.standard_normal((total, h, d)).astype(np.float32), "bf16")
+    (q, q32), (k, k32), (v, v32) = mk(), mk(), mk()
+    r = (rng.random((total, s)) ** 4).astype(np.float32)
+    dq, dk, dv, dr = to_dev(q), to_dev(k), to_dev(v), torch.from_numpy(r).cuda()
+    kc, vc = bd.civic_kv_compress_ragged(dk, dv, dr, off)
+    out = bd.civic_cross_attn_ragged(dq, kc, vc, off)
+    torch.cuda.synchronize()
+    ref_kc = oracle.kv_compress_ragged(k32.reshape(total, h * d), r, off).reshape(len(sizes), s, h, d)
+    ref_vc = oracle.kv_compress_ragged(v32.reshape(total, h * d), r, off).reshape(len(sizes), s, h, d)
+    for got, ref in ((kc, ref_kc), (vc, ref_vc)):
+        assert np.abs(widen(to_host(got)).astype(np.float64) - ref).max() <= attn_tol(ref, "bf16")
+    ref = oracle.cross_attention_ragged(q32, widen(to_host(kc)), widen(to_host(vc)), off)
+    err = float(np.abs(widen(to_host(out)).astype(np.float64) - ref).max())
+    log("   attention max abs err", err, "tol", attn_tol(ref, "bf16"))
+    assert np.isfinite(widen(to_host(out))).all() and err <= attn_tol(ref, "bf16")
+    # every item equals the rectangular calls on that item alone, bit for bit
+    for i, (a, b) in enumerate(zip(off[:-1], off[1:])):
+        kc1, vc1 = bd.civic_kv_compress(dk[a:b][None], dv[a:b][None], dr[a:b].contiguous())
+        assert torch.equal(kc1[0], kc[i]) and torch.equal(vc1[0], vc[i])
+        assert torch.equal(bd.civic_cross_attn(dq[a:b][None], kc[i:i + 1], vc[i:i + 1])[0], out[a:b])
