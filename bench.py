@@ -191,6 +191,9 @@ def main() -> int:
                     help="transformer layers N_l of the amortised figure: score, select and compact once, attention and "
                          "KV write per layer (28 = the layer count the paper's Table 1 KV sizes imply for its 2B model)")
     ap.add_argument("--unfused", action="store_true", help="attention and KV write as two calls")
+    ap.add_argument("--batch", type=int, default=0,
+                    help="scale-up run: the same shapes at this batch size instead of the workload's own (labelled in the "
+                         "JSON line; shows the stages at steady state, does not replace the workload)")
     ap.add_argument("--path-only", action="store_true",
                     help="skip the decode, rotary and encoder figures (counter runs: every launch then belongs to the path)")
     ap.add_argument("--separate-calls", action="store_true",
@@ -222,6 +225,9 @@ def main() -> int:
         return 0
     from paper_2605_28115_amd import binding as bd     # raises if libcivic.so is not built
     w = wl.WORKLOADS[args.workload]
+    if args.batch > 0 and args.batch != w.batch:
+        import dataclasses
+        w = dataclasses.replace(w, batch=args.batch)
     assert bd.civic_kept_count(w.grid_tuple()) == w.kept
     fs = wl.frame_starts(w)
     sets = [BufferSet(bd, w, trial) for trial in range(max(1, args.sets))]
@@ -330,7 +336,7 @@ def main() -> int:
     if w.dtype == "bf16":
         roofline = {"bound": "mfma", "kernel": f"attn_mfma_kernel (civic_prefill_{attn_name})", "achieved": round(attn_tf, 2),
                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(attn_tf / MFMA_BF16_PEAK_TFLOPS, 4),
-                    "traffic": measured_traffic(w.name, attn_name), "launch_us": round(attn_us, 2), "flops_per_launch": work["attn_flops"]}
+                    "traffic": measured_traffic(w.name, attn_name) if w.batch == wl.WORKLOADS[w.name].batch else None, "launch_us": round(attn_us, 2), "flops_per_launch": work["attn_flops"]}
     else:
         roofline = {"bound": "alu", "kernel": f"attn_plain_kernel (civic_prefill_{attn_name})", "achieved": round(attn_tf, 3),
                     "peak": 157.3, "unit": "TFLOP/s", "frac": round(attn_tf / 157.3, 5), "traffic": None,
@@ -342,7 +348,8 @@ def main() -> int:
         "prewarm_steps": prewarm_steps, "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": f"Qwen3-VL-{w.name}-shaped" if w.name in ("2b", "8b") else w.name,
+        "config": {"workload": (f"Qwen3-VL-{w.name}-shaped" if w.name in ("2b", "8b") else w.name) +
+                               (f", scale-up to batch {w.batch}" if w.batch != wl.WORKLOADS[w.name].batch else ""),
                    "batch": w.batch, "seq_dense": w.seq_len, "seq_compact": w.seq_compact, "visual_tokens": w.n_visual,
                    "kept_visual": w.kept, "hidden": w.dim, "heads": f"{w.n_q_heads}q/{w.n_kv_heads}kv x {w.head_dim}",
                    "causal": w.causal, "layers_timed": 1, "buffer_sets": len(sets),
