@@ -18,12 +18,15 @@ untimed warm-up steps, then exactly K timed steps between device synchronisation
 compact-prefill tokens/s = batch * S_c * K / time.
 
 A second pass of the same K steps brackets every stage with HIP events (recorded on the stream the
-kernels run on); `roofline` describes the dominant kernel (the attention) against the MI355X bf16
-MFMA peak from those in-step durations.  A third pass times every stage alone as a GPU number: a
+kernels run on: `us_in_step`, which carries the 2-3 us an event between two short dependent launches
+costs).  Another pass of the same K steps arms the library's one-shot kernel timer before every
+stage, so that the stage's kernel carries its own pair of HIP events and their difference is the
+kernel's duration inside the step (`us_kernel_in_step`, the figure a kernel trace reports);
+`roofline` describes the dominant kernel (the attention) against the MI355X bf16 MFMA peak from that
+duration.  A third pass times every stage alone as a GPU number: a
 spin kernel holds the stream while --stage-launches launches of the stage are queued behind it, and
 two events bracket them, so the figure under `stages` (`us`) is the kernels' own back-to-back time
-and carries no host launch cost (`us_in_step` is the event-bracketed one, which carries the 2-3 us
-an event between two short dependent launches costs).  `decode` reports the decode-step attention
+and carries no host launch cost.  `decode` reports the decode-step attention
 over the cache the step has just written (one query per sequence, HBM-bound).  `cpu_baseline` times
 the CPU oracle, as it stands, on a bounded sample of the same workload on this machine's host cores.
 Prints one JSON line.
@@ -277,6 +280,24 @@ def main() -> int:
         d = np.asarray([ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(args.steps)]) * 1e3
         stage_us[name] = {"mean": float(d.mean()), "median": float(np.median(d)), "min": float(d.min())}
 
+    # the same steps once more, every stage's kernel carrying its own pair of events (the library's one-shot kernel
+    # timer): the kernel's duration inside the step, without the gap to the launch before it
+    kev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in STAGES]
+           for _ in range(args.steps)]
+    for per_step in kev:
+        for a, b in per_step:
+            a.record(); b.record()                  # torch creates an event's handle at its first record
+    torch.cuda.synchronize()
+    for i in range(args.steps):
+        s = sets[i % len(sets)]
+        for j, c in enumerate(order):
+            bd.civic_time_next_kernel(*kev[i][j])
+            c(s)
+    torch.cuda.synchronize()
+    for j, name in enumerate(STAGES):
+        d = np.asarray([kev[i][j][0].elapsed_time(kev[i][j][1]) for i in range(args.steps)]) * 1e3
+        stage_us[name]["kernel"] = float(d.mean())
+
     # third pass: every stage alone as a GPU number.  A spin kernel occupies the stream while the host queues
     # the launches behind it, so that the two events bracket kernels that start back to back, without the
     # ~8 us of host time a launch from Python costs; the average is the kernel's duration plus the gap the
@@ -302,8 +323,8 @@ def main() -> int:
     for name in STAGES:
         if name in ("attn", "attn_kv"):
             # attention launches back to back run slower than in a step (the chip holds a lower clock under
-            # sustained MFMA load), and 40 us of MFMA work hides the event's cost: the in-step time is the kernel time
-            stage_us[name]["alone"] = stage_us[name]["mean"]
+            # sustained MFMA load): the kernel's own duration inside the step is its figure
+            stage_us[name]["alone"] = stage_us[name]["kernel"]
             stage_us[name]["back_to_back"] = alone(calls[name])
             continue
         stage_us[name]["alone"] = alone(calls[name])
@@ -314,7 +335,8 @@ def main() -> int:
     for name in STAGES:
         us = stage_us[name]["alone"]
         entry = {"us": round(us, 2), "us_in_step": round(stage_us[name]["mean"], 2),
-                 "us_in_step_median": round(stage_us[name]["median"], 2)}
+                 "us_in_step_median": round(stage_us[name]["median"], 2),
+                 "us_kernel_in_step": round(stage_us[name]["kernel"], 2)}
         if "back_to_back" in stage_us[name]:
             entry["us_back_to_back"] = round(stage_us[name]["back_to_back"], 2)
         if name in ("attn", "attn_kv"):
@@ -331,12 +353,13 @@ def main() -> int:
     stages["select+compact"] = {"gbs": round(sg, 1), "frac_hbm_peak": round(sg / HBM_PEAK_GBS, 4)}
 
     attn_name = "attn" if args.unfused else "attn_kv"
-    attn_us = stage_us[attn_name]["mean"]
+    attn_us = stage_us[attn_name]["kernel"]          # the events ride on the kernel's own dispatch, inside the step
     attn_tf = work["attn_flops"] / (attn_us * 1e-6) / 1e12
     if w.dtype == "bf16":
         roofline = {"bound": "mfma", "kernel": f"attn_mfma_kernel (civic_prefill_{attn_name})", "achieved": round(attn_tf, 2),
                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(attn_tf / MFMA_BF16_PEAK_TFLOPS, 4),
-                    "traffic": measured_traffic(w.name, attn_name) if w.batch == wl.WORKLOADS[w.name].batch else None, "launch_us": round(attn_us, 2), "flops_per_launch": work["attn_flops"]}
+                    "traffic": measured_traffic(w.name, attn_name) if w.batch == wl.WORKLOADS[w.name].batch else None, "launch_us": round(attn_us, 2),
+                    "launch_us_between_events": round(stage_us[attn_name]["mean"], 2), "flops_per_launch": work["attn_flops"]}
     else:
         roofline = {"bound": "alu", "kernel": f"attn_plain_kernel (civic_prefill_{attn_name})", "achieved": round(attn_tf, 3),
                     "peak": 157.3, "unit": "TFLOP/s", "frac": round(attn_tf / 157.3, 5), "traffic": None,

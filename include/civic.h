@@ -82,6 +82,17 @@ typedef struct {
  * process; 0 if none. */
 int civic_last_hip_error(void);
 
+/* Measurement hook (no passage of the paper: it serves whoever reports a kernel's own duration).
+ * Arms a one-shot timer on the calling thread: the next kernel that thread launches through this
+ * library - the first kernel of the next entry-point call, for calls that launch several - carries
+ * the two events on its stream, `start_event` taking the time the kernel begins to run and
+ * `stop_event` the time it ends, so hipEventElapsedTime(start, stop) after a synchronisation is the
+ * kernel's duration without launch latency or the gap to the kernel before it.  Both are hipEvent_t
+ * handles (host values) created with timing enabled, owned by the caller, distinct.  Two null
+ * pointers disarm.  The timed launch uses the extended launch call and must not be captured into a
+ * HIP graph.  CIVIC_ERR_INVALID_ARG if exactly one is null or both are the same event. */
+int civic_time_next_kernel(void* start_event, void* stop_event);
+
 /* Number of visual tokens civic_select keeps per sample: K = max(budget, sum of floors),
  * where a cell contributes min(cell_floor, its size) and a frame min(frame_floor, what its
  * cell floors leave).  A pure host function of the grid; negative CIVIC_ERR_* on a bad grid.

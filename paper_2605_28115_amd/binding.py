@@ -20,7 +20,7 @@ CIVIC_OK, ERR_INVALID_ARG, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_HIP = 0, -1, -2, 
 CIVIC_F32, CIVIC_BF16 = 0, 1
 MAX_VISUAL_TOKENS, MAX_FRAMES, MAX_SCORE_DIM, MAX_HEAD_DIM = 32768, 128, 8192, 256
 
-EXPORTS = ("civic_last_hip_error", "civic_kept_count", "civic_select_workspace_bytes",
+EXPORTS = ("civic_last_hip_error", "civic_time_next_kernel", "civic_kept_count", "civic_select_workspace_bytes",
            "civic_compact_workspace_bytes", "civic_anchor_normalize", "civic_score", "civic_score_visual", "civic_select",
            "civic_compact", "civic_compact_prefill", "civic_prefill_attn", "civic_kv_write", "civic_prefill_attn_kv",
            "civic_decode_attn_workspace_bytes", "civic_decode_attn", "civic_decode_attn_noalloc",
@@ -54,6 +54,8 @@ if not os.path.exists(LIB_PATH):
 lib = C.CDLL(LIB_PATH)
 _P = C.c_void_p
 lib.civic_last_hip_error.restype = C.c_int
+lib.civic_time_next_kernel.restype = C.c_int
+lib.civic_time_next_kernel.argtypes = [_P, _P]
 lib.civic_kept_count.restype = C.c_int64
 lib.civic_kept_count.argtypes = [C.POINTER(Grid)]
 lib.civic_select_workspace_bytes.restype = C.c_size_t
@@ -163,6 +165,13 @@ def _strides3(t: torch.Tensor):
 
 
 # ------------------------------------------------------------------------------ host functions
+def civic_time_next_kernel(start: Optional[torch.cuda.Event], stop: Optional[torch.cuda.Event]) -> None:
+    """Arms the one-shot kernel timer with two timing events that have been recorded at least once (torch creates an
+    event's handle at its first record), or disarms it with (None, None)."""
+    handle = lambda ev: None if ev is None else C.c_void_p(ev.cuda_event)
+    _check("civic_time_next_kernel", lib.civic_time_next_kernel(handle(start), handle(stop)))
+
+
 def civic_kept_count(grid) -> int:
     k = int(lib.civic_kept_count(C.byref(make_grid(grid))))
     if k < 0:

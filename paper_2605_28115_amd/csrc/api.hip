@@ -28,6 +28,12 @@ int allow_dynamic_lds(const void* kernel, size_t bytes, std::atomic<uint64_t>* d
     return CIVIC_OK;
 }
 
+KernelTimer& kernel_timer()
+{
+    static thread_local KernelTimer t;
+    return t;
+}
+
 int grid_info(const civic_grid* g, GridInfo* out)
 {
     if (!g || !out) return CIVIC_ERR_INVALID_ARG;
@@ -67,6 +73,17 @@ int grid_info(const civic_grid* g, GridInfo* out)
 extern "C" {
 
 int civic_last_hip_error(void) { return civic::g_last_hip_error.load(); }
+
+int civic_time_next_kernel(void* start_event, void* stop_event)
+{
+    civic::KernelTimer& t = civic::kernel_timer();
+    if (!start_event && !stop_event) { t = civic::KernelTimer{}; return CIVIC_OK; }
+    if (!start_event || !stop_event || start_event == stop_event) return CIVIC_ERR_INVALID_ARG;
+    t.start = static_cast<hipEvent_t>(start_event);
+    t.stop = static_cast<hipEvent_t>(stop_event);
+    t.armed = true;
+    return CIVIC_OK;
+}
 
 int64_t civic_kept_count(const civic_grid* grid)
 {

@@ -1002,7 +1002,7 @@ static int launch_mfma(AttnArgs& a, hipStream_t s)
         const int rc = allow_dynamic_lds(reinterpret_cast<const void*>(attn_mfma_kernel<DP, WAVES, STAGES>), lds, &allowed);
         if (rc != CIVIC_OK) return rc;
     }
-    hipLaunchKernelGGL((attn_mfma_kernel<DP, WAVES, STAGES>), dim3(static_cast<unsigned>(per_rt), grid_y),
+    civic::launch((attn_mfma_kernel<DP, WAVES, STAGES>), dim3(static_cast<unsigned>(per_rt), grid_y),
                        dim3(T::THREADS), lds, s, a);
     return check_launch();
 }
@@ -1080,8 +1080,8 @@ static int prefill_attn(const void* q, const void* k, const void* v, void* out, 
     }
     // everything else: the fp32 kernel (which also writes the caches when asked to)
     const dim3 grid(static_cast<unsigned>((seq + 3) / 4), static_cast<unsigned>(n_q_heads), static_cast<unsigned>(batch));
-    if (dtype == CIVIC_BF16) hipLaunchKernelGGL((attn_plain_kernel<true>), grid, dim3(256), 0, s, a);
-    else hipLaunchKernelGGL((attn_plain_kernel<false>), grid, dim3(256), 0, s, a);
+    if (dtype == CIVIC_BF16) civic::launch((attn_plain_kernel<true>), grid, dim3(256), 0, s, a);
+    else civic::launch((attn_plain_kernel<false>), grid, dim3(256), 0, s, a);
     return check_launch();
 }
 

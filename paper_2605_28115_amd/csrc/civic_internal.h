@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include <atomic>
@@ -17,6 +18,30 @@ int record_hip_error(hipError_t e);
 // Raises a kernel's dynamic LDS limit to `bytes` on the current device; the attribute belongs to the device's
 // copy of the kernel, so it is set once per device (bit d of *done: device d has it).  CIVIC_OK or an error code.
 int allow_dynamic_lds(const void* kernel, size_t bytes, std::atomic<uint64_t>* done);
+
+// One-shot kernel timer of the calling thread (civic_time_next_kernel arms it).
+struct KernelTimer {
+    hipEvent_t start = nullptr, stop = nullptr;
+    bool armed = false;
+};
+KernelTimer& kernel_timer();
+
+// Every kernel of the library is launched through here.  The arguments are converted to the kernel's own
+// parameter types first, so both launch forms pack the same bytes.  When the thread's timer is armed, this launch
+// carries its two events (recorded by the command processor at the kernel's start and end) and disarms it.
+template <typename... Params, typename... Args>
+static inline void launch(void (*kernel)(Params...), dim3 grid, dim3 block, size_t lds, hipStream_t s, Args&&... args)
+{
+    static_assert(sizeof...(Params) == sizeof...(Args), "kernel argument count");
+    KernelTimer& t = kernel_timer();
+    if (__builtin_expect(t.armed, 0)) {
+        t.armed = false;
+        hipExtLaunchKernelGGL(kernel, grid, block, static_cast<uint32_t>(lds), s, t.start, t.stop, 0u,
+                              static_cast<Params>(args)...);
+    } else {
+        hipLaunchKernelGGL(kernel, grid, block, lds, s, static_cast<Params>(args)...);
+    }
+}
 
 static inline int check_launch()
 {

@@ -354,7 +354,7 @@ extern "C" int civic_compact(const void* hidden, int dtype, int32_t dim, const i
     const dim3 g(static_cast<unsigned>(blocks), static_cast<unsigned>(batch)), blk(kCompactThreads);
     hipStream_t s = static_cast<hipStream_t>(stream);
 #define CIVIC_COMPACT_LAUNCH(V, U, LONG)                                                                      \
-    hipLaunchKernelGGL((compact_kernel<V, U, LONG>), g, blk, 0, s, h, row_bytes, pos_ids, batch,                \
+    civic::launch((compact_kernel<V, U, LONG>), g, blk, 0, s, h, row_bytes, pos_ids, batch,                \
                        static_cast<int32_t>(seq_len), ft, kept_idx, static_cast<int32_t>(n_kept),               \
                        static_cast<int32_t>(seq_c), static_cast<int32_t>(rpb), tpr, hc, pos_c, src_idx)
     switch (vec) {

@@ -324,7 +324,7 @@ static int launch_decode_lpr(const DecodeArgs& a, const DecodePlan& p, hipStream
             const int rc = allow_dynamic_lds(reinterpret_cast<const void*>(decode_partial_kernel<BF16, HG, L>), p.lds_bytes, &allowed); \
             if (rc != CIVIC_OK) return rc;                                                                             \
         }                                                                                                              \
-        hipLaunchKernelGGL((decode_partial_kernel<BF16, HG, L>), grid, dim3(kDecThreads), p.lds_bytes, s, a);          \
+        civic::launch((decode_partial_kernel<BF16, HG, L>), grid, dim3(kDecThreads), p.lds_bytes, s, a);          \
         break;                                                                                                         \
     }
     switch (p.lpr) {
@@ -364,8 +364,8 @@ static int decode_attn(const void* q, const void* k_cache, const void* v_cache, 
     int rc = dtype == CIVIC_BF16 ? launch_decode<true>(a, p, s) : launch_decode<false>(a, p, s);
     if (rc != CIVIC_OK || p.splits == 1) return rc;
     const unsigned rows = static_cast<unsigned>(batch) * static_cast<unsigned>(n_q_heads);
-    if (dtype == CIVIC_BF16) hipLaunchKernelGGL((decode_merge_kernel<true>), dim3(rows), dim3(128), 0, s, ws, out, p.splits, head_dim);
-    else hipLaunchKernelGGL((decode_merge_kernel<false>), dim3(rows), dim3(128), 0, s, ws, out, p.splits, head_dim);
+    if (dtype == CIVIC_BF16) civic::launch((decode_merge_kernel<true>), dim3(rows), dim3(128), 0, s, ws, out, p.splits, head_dim);
+    else civic::launch((decode_merge_kernel<false>), dim3(rows), dim3(128), 0, s, ws, out, p.splits, head_dim);
     return check_launch();
 }
 

@@ -263,7 +263,7 @@ static int launch_gemm_variant(const GemmArgs& g, unsigned blocks, hipStream_t s
     static std::atomic<uint64_t> allowed{0};
     const int rc = allow_dynamic_lds(reinterpret_cast<const void*>(gemm_kernel<C_BF16, B_KROWS, STAGES>), lds, &allowed);
     if (rc != CIVIC_OK) return rc;
-    hipLaunchKernelGGL((gemm_kernel<C_BF16, B_KROWS, STAGES>), grid, dim3(kGemmThreads), lds, s, g);
+    civic::launch((gemm_kernel<C_BF16, B_KROWS, STAGES>), grid, dim3(kGemmThreads), lds, s, g);
     return check_launch();
 }
 
@@ -579,7 +579,7 @@ extern "C" int civic_anchor_aggregate(const void* x0, const void* anchors, int d
     {
         const dim3 grid(static_cast<unsigned>((n_anchors + rows_x + 3) / 4));
         const int chunks = (dim / 8 + kWave - 1) / kWave;                              // 16-byte pieces per lane
-#define CIVIC_LN_CASE(N) hipLaunchKernelGGL((ln_norm_rows_kernel<true, N>), grid, dim3(256), 0, s, anchors, static_cast<int64_t>(n_anchors), \
+#define CIVIC_LN_CASE(N) civic::launch((ln_norm_rows_kernel<true, N>), grid, dim3(256), 0, s, anchors, static_cast<int64_t>(n_anchors), \
                                             x0, rows_x, dim, qa, k0)
         if (chunks <= 1) CIVIC_LN_CASE(1);
         else if (chunks <= 2) CIVIC_LN_CASE(2);
@@ -604,7 +604,7 @@ extern "C" int civic_anchor_aggregate(const void* x0, const void* anchors, int d
     {
         const dim3 grid(static_cast<unsigned>((rows_w + 3) / 4));
         const int chunks = static_cast<int>((p.t_pad / 4 + kWave - 1) / kWave);       // float4 per lane
-#define CIVIC_SOFTMAX_CASE(N) hipLaunchKernelGGL((row_softmax_kernel<N>), grid, dim3(256), 0, s, sl, rows_w, n_tokens, p.t_pad, pw, p.t_pad)
+#define CIVIC_SOFTMAX_CASE(N) civic::launch((row_softmax_kernel<N>), grid, dim3(256), 0, s, sl, rows_w, n_tokens, p.t_pad, pw, p.t_pad)
         if (chunks <= 4) CIVIC_SOFTMAX_CASE(4);
         else if (chunks <= 8) CIVIC_SOFTMAX_CASE(8);
         else if (chunks <= 16) CIVIC_SOFTMAX_CASE(16);
@@ -613,7 +613,7 @@ extern "C" int civic_anchor_aggregate(const void* x0, const void* anchors, int d
 #undef CIVIC_SOFTMAX_CASE
     }
     if (token_weight)
-        hipLaunchKernelGGL(col_sum_kernel, dim3(static_cast<unsigned>((n_tokens + 255) / 256), static_cast<unsigned>(batch)), dim3(256), 0, s,
+        civic::launch(col_sum_kernel, dim3(static_cast<unsigned>((n_tokens + 255) / 256), static_cast<unsigned>(batch)), dim3(256), 0, s,
                            pw, n_anchors, n_tokens, p.t_pad, static_cast<int64_t>(n_anchors) * p.t_pad, token_weight);
     rc = check_launch();
     if (rc != CIVIC_OK) return rc;
@@ -659,10 +659,10 @@ extern "C" int civic_kv_compress(const void* k, const void* v, int dtype, const 
     __bf16* xt = reinterpret_cast<__bf16*>(ws + p.xt);
     // Rbar^T [n_mem x m_pad]: every column of R over its sum, transposed, zero beyond n_rows
     float* part = reinterpret_cast<float*>(ws + p.part);
-    hipLaunchKernelGGL(col_part_sum_kernel, dim3(static_cast<unsigned>((n_mem + kWave - 1) / kWave), kColParts), dim3(256), 0, s, r, n_rows,
+    civic::launch(col_part_sum_kernel, dim3(static_cast<unsigned>((n_mem + kWave - 1) / kWave), kColParts), dim3(256), 0, s, r, n_rows,
                        n_mem, part);
-    hipLaunchKernelGGL(col_inv_kernel, dim3(static_cast<unsigned>((n_mem + 255) / 256)), dim3(256), 0, s, part, n_mem, inv);
-    hipLaunchKernelGGL((transpose_pad_kernel<float>), dim3(static_cast<unsigned>(p.m_pad / 32), static_cast<unsigned>((n_mem + 31) / 32), 1u),
+    civic::launch(col_inv_kernel, dim3(static_cast<unsigned>((n_mem + 255) / 256)), dim3(256), 0, s, part, n_mem, inv);
+    civic::launch((transpose_pad_kernel<float>), dim3(static_cast<unsigned>(p.m_pad / 32), static_cast<unsigned>((n_mem + 31) / 32), 1u),
                        dim3(256), 0, s, r, n_rows, n_mem, static_cast<int64_t>(n_mem), int64_t{0}, inv, rt, p.m_pad, int64_t{0});
     int rc = check_launch();
     if (rc != CIVIC_OK) return rc;
@@ -680,7 +680,7 @@ extern "C" int civic_kv_compress(const void* k, const void* v, int dtype, const 
     void* dst[2] = {k_c, v_c};
     for (int t = 0; t < 2; ++t) {
         // X^T [width x m_pad] per batch item, then X_c = Rbar^T (X^T)^T
-        hipLaunchKernelGGL((transpose_pad_kernel<__bf16>), dim3(static_cast<unsigned>(p.m_pad / 32), static_cast<unsigned>((width + 31) / 32),
+        civic::launch((transpose_pad_kernel<__bf16>), dim3(static_cast<unsigned>(p.m_pad / 32), static_cast<unsigned>((width + 31) / 32),
                                                                 static_cast<unsigned>(batch)),
                            dim3(256), 0, s, static_cast<const __bf16*>(src[t]), n_rows, width, static_cast<int64_t>(width),
                            static_cast<int64_t>(n_rows) * width, static_cast<const float*>(nullptr), xt, p.m_pad,

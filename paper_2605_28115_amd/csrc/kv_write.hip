@@ -81,7 +81,7 @@ extern "C" int civic_kv_write(const void* k, const void* v, const int64_t* kv_st
     const int64_t per_block = kKvThreads * kKvUnroll;
     const int64_t blocks = (total + per_block - 1) / per_block;
     if (blocks > INT32_MAX) return CIVIC_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(kv_write_kernel, dim3(static_cast<unsigned>(blocks), static_cast<unsigned>(batch), 2),
+    civic::launch(kv_write_kernel, dim3(static_cast<unsigned>(blocks), static_cast<unsigned>(batch), 2),
                        dim3(kKvThreads), 0, static_cast<hipStream_t>(stream), a);
     return check_launch();
 }

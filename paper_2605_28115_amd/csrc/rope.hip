@@ -199,7 +199,7 @@ extern "C" int civic_mrope_table(const int32_t* pos_ids, int32_t batch, int64_t 
     if (total > 0 && (!pos_ids || !cos_sin)) return CIVIC_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(pos_ids) & 3u) || !aligned16(cos_sin)) return CIVIC_ERR_INVALID_ARG;
     if (total == 0) return CIVIC_OK;
-    hipLaunchKernelGGL(mrope_table_kernel, dim3(rope_blocks(total)), dim3(256), 0, static_cast<hipStream_t>(stream), pos_ids, batch,
+    civic::launch(mrope_table_kernel, dim3(rope_blocks(total)), dim3(256), 0, static_cast<hipStream_t>(stream), pos_ids, batch,
                        seq, n_pairs, tab, reinterpret_cast<float2*>(cos_sin));
     return check_launch();
 }
@@ -226,8 +226,8 @@ extern "C" int civic_mrope_apply(const void* x, void* out, int dtype, int32_t ba
     a.seq = seq; a.batch = batch; a.heads = heads; a.n_pairs = head_dim / 2;
     a.half_chunks = (head_dim / 2) * esz / 16;
     const dim3 grid(rope_blocks(seq * heads * a.half_chunks), static_cast<unsigned>(batch));
-    if (dtype == CIVIC_BF16) hipLaunchKernelGGL((mrope_apply_kernel<true>), grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
-    else hipLaunchKernelGGL((mrope_apply_kernel<false>), grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
+    if (dtype == CIVIC_BF16) civic::launch((mrope_apply_kernel<true>), grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
+    else civic::launch((mrope_apply_kernel<false>), grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
     return check_launch();
 }
 
@@ -254,7 +254,7 @@ extern "C" int civic_kv_write_rope(const void* k, const void* v, const int64_t* 
     a.s_max = s_max; a.pos0 = pos0; a.seq = seq; a.n_kv_heads = n_kv_heads; a.head_dim = head_dim;
     a.n_pairs = head_dim / 2; a.half_chunks = (head_dim / 2) * esz / 16;
     const dim3 grid(rope_blocks(static_cast<int64_t>(seq) * n_kv_heads * a.half_chunks), static_cast<unsigned>(batch));
-    if (dtype == CIVIC_BF16) hipLaunchKernelGGL((kv_write_rope_kernel<true>), grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
-    else hipLaunchKernelGGL((kv_write_rope_kernel<false>), grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
+    if (dtype == CIVIC_BF16) civic::launch((kv_write_rope_kernel<true>), grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
+    else civic::launch((kv_write_rope_kernel<false>), grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
     return check_launch();
 }

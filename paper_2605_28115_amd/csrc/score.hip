@@ -291,11 +291,11 @@ static int launch_score(bool bf16, const void* hidden, int64_t n_rows, int64_t s
     const size_t lds = sizeof(float) * static_cast<size_t>(dim);
     const dim3 grid(static_cast<unsigned>(blocks), static_cast<unsigned>(slices));
     if (bf16)
-        hipLaunchKernelGGL((score_bf16_kernel<CHUNKS, MAP>), grid, dim3(kScoreThreads),
+        civic::launch((score_bf16_kernel<CHUNKS, MAP>), grid, dim3(kScoreThreads),
                            lds + sizeof(float) * rows_per_block, stream, h, n_rows, row_stride_bytes, dim, anchor_q,
                            inv_tau, scores, map);
     else
-        hipLaunchKernelGGL((score_f32_kernel<CHUNKS, MAP>), grid, dim3(kScoreThreads), lds,
+        civic::launch((score_f32_kernel<CHUNKS, MAP>), grid, dim3(kScoreThreads), lds,
                            stream, h, n_rows, row_stride_bytes, dim, anchor_q, inv_tau, scores, map);
     return check_launch();
 }

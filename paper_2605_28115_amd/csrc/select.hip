@@ -776,6 +776,6 @@ extern "C" int civic_select(const float* scores, int32_t batch, const civic_grid
         const int rc = allow_dynamic_lds(reinterpret_cast<const void*>(select_kernel), max_lds, &allowed);
         if (rc != CIVIC_OK) return rc;
     }
-    hipLaunchKernelGGL(select_kernel, dim3(static_cast<unsigned>(batch)), dim3(kSelThreads), lds, s, a);
+    civic::launch(select_kernel, dim3(static_cast<unsigned>(batch)), dim3(kSelThreads), lds, s, a);
     return check_launch();
 }

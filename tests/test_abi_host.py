@@ -267,3 +267,14 @@ def test_argument_errors_precede_any_hip_call(bd):
     assert rattn(off=None) == I and rattn(off=offs(2, 5, 12)) == I and rattn(off=offs(0, 5, 5)) == I and rattn(q=None) == I
     assert rattn(hq=3) == I and rattn(d=60) == I and rattn(qs=None) == I and rattn(k=odd) == I and rattn(batch=0, off=None) == OK
     assert bd.lib.civic_last_hip_error() == 0
+
+
+def test_kernel_timer_argument_checks(bd):
+    # only the handles' values are looked at here: nothing is launched, so nothing touches them
+    one, two = C.c_void_p(0x1000), C.c_void_p(0x2000)
+    f = bd.lib.civic_time_next_kernel
+    assert f(one, None) == bd.ERR_INVALID_ARG
+    assert f(None, two) == bd.ERR_INVALID_ARG
+    assert f(one, one) == bd.ERR_INVALID_ARG
+    assert f(one, two) == bd.CIVIC_OK
+    assert f(None, None) == bd.CIVIC_OK             # disarmed again: no later launch of this thread sees the handles

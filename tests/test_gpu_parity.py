@@ -614,3 +614,31 @@ def test_whole_path_chained(bd, name):
     rkv_bits = rhc[:, :, :w.n_kv_heads * w.head_dim].reshape(w.batch, s_c, w.n_kv_heads, w.head_dim)
     oracle.kv_write(rkv_bits, rkv_bits, rkc, rvc, 0)
     assert np.array_equal(to_host(kc), rkc) and np.array_equal(to_host(vc), rvc)
+
+
+# ---------------------------------------------------------------------------------- kernel timer
+def test_kernel_timer_brackets_one_launch_and_leaves_results_alone(bd):
+    w = wl.WORKLOADS["8b"]
+    log("kernel timer", w.name)
+    hid, _ = wl.hidden(w, 0)
+    h = to_dev(hid.reshape(-1, w.dim))
+    q = torch.from_numpy(bd.civic_anchor_normalize(wl.anchor(w, 0))).cuda()
+    plain = bd.civic_score(h, q, 1.0)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    outer0, outer1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(); b.record()
+    torch.cuda.synchronize()
+    bd.civic_time_next_kernel(a, b)
+    outer0.record()
+    timed = bd.civic_score(h, q, 1.0)
+    outer1.record()
+    torch.cuda.synchronize()
+    kernel_ms, outer_ms = a.elapsed_time(b), outer0.elapsed_time(outer1)
+    log("  kernel", kernel_ms * 1e3, "us inside", outer_ms * 1e3, "us")
+    assert torch.equal(plain, timed)
+    assert 1e-3 < kernel_ms <= outer_ms             # 8b scoring reads 32 MB: several microseconds at any clock
+    # one-shot: the next launch does not touch the two events
+    again = bd.civic_score(h, q, 1.0)
+    torch.cuda.synchronize()
+    assert a.elapsed_time(b) == kernel_ms and torch.equal(again, plain)
