@@ -266,8 +266,15 @@ def main() -> int:
     ms_per_step = 1e3 * elapsed / args.steps
     tokens = w.batch * w.seq_compact
 
+    def rewarm():
+        # ~30 ms of untimed steps queued right ahead of a measuring pass (no synchronisation in between), so that a
+        # short pass does not start on a chip that idled while the host prepared it
+        for i in range(max(20, int(30.0 / ms_per_step)) if args.prewarm_ms > 0 else 0):
+            step(i)
+
     # second pass: the same steps with an event between stages (torch's current stream is the launch stream)
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(STAGES) + 1)] for _ in range(args.steps)]
+    rewarm()
     for i in range(args.steps):
         s = sets[i % len(sets)]
         ev[i][0].record()
@@ -288,6 +295,7 @@ def main() -> int:
         for a, b in per_step:
             a.record(); b.record()                  # torch creates an event's handle at its first record
     torch.cuda.synchronize()
+    rewarm()
     for i in range(args.steps):
         s = sets[i % len(sets)]
         for j, c in enumerate(order):
