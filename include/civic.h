@@ -32,7 +32,8 @@
  *     empty batch, nothing kept and no text); otherwise NULL is CIVIC_ERR_INVALID_ARG.
  *   - dtype: CIVIC_F32 (4-byte IEEE) or CIVIC_BF16 (2-byte bfloat16).
  *   - Re-entrant.  Global mutable state: the last HIP error code, and per kernel and device one flag
- *     that its dynamic LDS limit has been raised (set once, never cleared).
+ *     that its dynamic LDS limit has been raised (set once, never cleared); per thread, the two
+ *     event handles of civic_time_next_kernel between arming and the next launch.
  */
 #ifndef CIVIC_H
 #define CIVIC_H
