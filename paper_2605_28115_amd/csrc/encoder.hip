@@ -186,7 +186,7 @@ __global__ __launch_bounds__(kGemmThreads, STAGES == 2 ? 2 : 1) void gemm_kernel
     // Loads retire in order, 8 per tile and wavefront: tile kt has landed once at most 8 * (tiles issued after it)
     // loads are outstanding.
     auto wait_landed = [&](int younger) {
-        if (younger >= 2) __builtin_amdgcn_s_waitcnt(0x0F70 | 16);       // vmcnt(16)
+        if (younger >= 2) __builtin_amdgcn_s_waitcnt(0x4F70);            // vmcnt(16): the count's bits 5:4 sit in bits 15:14
         else if (younger == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | 8);   // vmcnt(8)
         else __builtin_amdgcn_s_waitcnt(0x0F70);                         // vmcnt(0)
     };
