@@ -177,7 +177,8 @@ def cpu_baseline(w: wl.Workload, target_seconds: float = 20.0) -> dict:
     model = next((l.split(":", 1)[1].strip() for l in open("/proc/cpuinfo") if l.startswith("model name")), "unknown")
     return {"value": w.batch * w.seq_compact / total, "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
             "cpu_model": model,
-            "sample": (f"workload {w.name}: score, select, compact and kv_write in full; attention on every "
+            "sample": (f"workload {w.name}: every stage in full, one pass" if row_step == 1 else
+                       f"workload {w.name}: score, select, compact and kv_write in full; attention on every "
                        f"{row_step}-th query row, its time scaled by {row_step}"),
             "stage_ms": {s: round(1e3 * x, 3) for s, x in t.items()}}
 
