@@ -318,10 +318,10 @@ def main() -> int:
     n_alone = max(1, args.stage_launches)
     hold_cycles = int(spin_cycles * (n_alone * 0.012 + 1.0) / spin_ms)     # 12 us of host time per launch, and 1 ms
 
-    def alone(call):
+    def alone(call, cost=1):
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
-        torch.cuda._sleep(hold_cycles)
+        torch.cuda._sleep(hold_cycles * cost)            # (cost: library calls per invocation, so the hold covers the queueing)
         a.record()
         for i in range(n_alone):
             call(sets[i % len(sets)])
@@ -485,6 +485,18 @@ def main() -> int:
         t_cmp = alone(lambda s_: bd.civic_kv_compress(kq, vq, r, k_c=kc, v_c=vc, workspace=ws_c))
         t_x = alone(lambda s_: bd.civic_cross_attn(qq, kc, vc, out=oc))
         t_full = alone(lambda s_: bd.civic_prefill_attn(qq, kq, vq, False, out=oc))
+        # images of different grid sizes in one batch (packed rows): the Eq. 9 attention as one launch over all items,
+        # against one rectangular call per item; the compression runs item by item either way
+        sizes = [1365, 341, 85, 1024, 600, 341, 1365, 85]
+        off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+        qr = torch.randn((int(off[-1]), w.n_q_heads, w.head_dim), device="cuda").to(x0.dtype)
+        kr = torch.randn((len(sizes), s_mem, w.n_kv_heads, w.head_dim), device="cuda").to(x0.dtype); vr = torch.randn_like(kr)
+        outr = torch.empty_like(qr)
+        t_rag = alone(lambda s_: bd.civic_cross_attn_ragged(qr, kr, vr, off, out=outr))
+        def per_item(s_):
+            for i in range(len(sizes)):
+                bd.civic_cross_attn(qr[off[i]:off[i + 1]][None], kr[i:i + 1], vr[i:i + 1], out=outr[off[i]:off[i + 1]][None])
+        t_items = alone(per_item, cost=len(sizes))
         f_agg = 4.0 * m_e * t_e * d_v * w.batch
         f_cmp = 4.0 * s_mem * m_e * w.n_kv_heads * w.head_dim * w.batch
         f_x = 4.0 * w.n_q_heads * w.head_dim * m_e * s_mem * w.batch
@@ -494,7 +506,9 @@ def main() -> int:
                                         "workspace_bytes": ws_a.numel(), "launches": 6},
                    "kv_compress": {"us": round(t_cmp, 2), "flops": f_cmp, "tflops": round(f_cmp / t_cmp / 1e6, 1)},
                    "cross_attn": {"us": round(t_x, 2), "flops": f_x, "tflops": round(f_x / t_x / 1e6, 1)},
-                   "uncompressed_attn_us": round(t_full, 2)}
+                   "uncompressed_attn_us": round(t_full, 2),
+                   "cross_attn_ragged": {"items": sizes, "us": round(t_rag, 2), "us_one_call_per_item": round(t_items, 2),
+                                         "flops": 4.0 * w.n_q_heads * w.head_dim * float(off[-1]) * s_mem}}
 
     # the selection runs once per prompt, the attention and the KV write once per layer: one measured step plus
     # layers - 1 further attention launches (in-step duration)

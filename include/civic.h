@@ -329,8 +329,10 @@ int civic_cross_attn(const void* q, const void* k, const void* v, void* out, int
 
 /* Eq. 9 for a batch whose items differ in size (images of different grids in one batch): the rows of all items are
  * packed back to back, item b owning rows [row_offsets[b], row_offsets[b+1]) of k, v and of its own assignment rows in
- * r; every item is compressed and attended by itself, with the kernels of the rectangular calls (one pass per item
- * on the stream; results equal civic_kv_compress / civic_cross_attn on that item alone, bit for bit).
+ * r; every item is compressed and attended by itself, and the results equal civic_kv_compress / civic_cross_attn on
+ * that item alone, bit for bit.  The compression runs the rectangular kernels once per item on the stream; the
+ * attention is ONE launch for up to 64 items (a workgroup finds its item's rows in a table passed with the launch;
+ * longer lists go out in groups of 64; fp32 or head_dim > 128 fall back to one launch per item).
  *   k, v         device [total_rows, width] bf16;  r  device [total_rows, n_mem] fp32
  *   row_offsets  host [batch + 1] int64, row_offsets[0] = 0, strictly increasing (no empty item)
  *   k_c, v_c     device [batch, n_mem, width] bf16
@@ -343,8 +345,8 @@ int civic_kv_compress_ragged(const void* k, const void* v, int dtype, const floa
                              void* workspace, size_t workspace_bytes, void* stream);
 /*   q, out       device [total_rows, n_q_heads, head_dim], element strides (unused, token, head) in q_strides / o_strides
  *   k, v         device [batch, n_kv, n_kv_heads, head_dim] (civic_kv_compress_ragged's outputs), strides in kv_strides
- *   q_offsets    as row_offsets above
- * Everything else as civic_cross_attn. */
+ *   q_offsets    as row_offsets above; q_offsets[batch] <= INT32_MAX, else CIVIC_ERR_UNSUPPORTED
+ * Everything else as civic_cross_attn; every group of items is checked before the first launch. */
 int civic_cross_attn_ragged(const void* q, const void* k, const void* v, void* out, int dtype, int32_t batch,
                             const int64_t* q_offsets /* host */, int32_t n_kv, int32_t n_q_heads, int32_t n_kv_heads,
                             int32_t head_dim, const int64_t* q_strides /* host [3] */,

@@ -51,6 +51,8 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
+constexpr int kRaggedItems = 64;          // items of one ragged launch (longer lists go out in several)
+
 struct AttnArgs {
     const void* q; const void* k; const void* v; void* out;
     int64_t qs[3], ks[3], os[3];          // element strides: batch, token, head
@@ -68,6 +70,9 @@ struct AttnArgs {
     int64_t s_max, pos0;
     // rotary embedding of Q from a (cos, sin) table [batch, seq, head_dim / 2] (null = none): civic_prefill_attn_rope
     const float2* q_cs;
+    // ragged queries (civic_cross_attn_ragged; read by the RAGGED instantiations only): `batch` items packed along the
+    // token axis, item b owning query and output rows [item_row[b], item_row[b + 1]); `seq` is the longest item
+    int32_t item_row[kRaggedItems + 1];
 };
 
 // ------------------------------------------------------------------------------------ fp32 ALU path
@@ -309,7 +314,7 @@ __device__ __forceinline__ void wait_tiles(int younger)
     }
 }
 
-template <int DP, int WAVES, int STAGES>
+template <int DP, int WAVES, int STAGES, bool RAGGED = false>
 __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
 {
     using T = AttnTile<DP, WAVES, STAGES>;
@@ -342,6 +347,19 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
 
     const int h = g * group + hb * HB + (w & (HB - 1));
     const int wrow = (w >> a.hb_shift) * 32;                  // this wavefront's first query row inside a row tile
+    // Query rows of this sample and where they start.  Ragged launches (no mask, one row tile per workgroup): item b's
+    // rows come from the table in the arguments, and a workgroup whose row tile lies past its item's end has nothing
+    // to do (the grid covers the longest item); it leaves before any load or barrier.
+    int seq_item = a.seq;
+    int64_t q_first = b * a.qs[0], o_first = b * a.os[0];
+    if constexpr (RAGGED) {
+        const int32_t first = a.item_row[b];
+        seq_item = a.item_row[b + 1] - first;
+        q_first = static_cast<int64_t>(first) * a.qs[1];
+        o_first = static_cast<int64_t>(first) * a.os[1];
+        if (rt * RB * 32 >= seq_item) return;
+    }
+    const int seq = seq_item;
     const float sl2 = a.scale * 1.4426950408889634f;          // scale * log2(e)
 
     // geometry of the row tile being computed
@@ -349,7 +367,7 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
     auto set_rows = [&](int t) {
         block_row0 = t * RB * 32;
         row0 = block_row0 + wrow;                             // this wavefront's first query row
-        block_rows_end = min(block_row0 + RB * 32, a.seq);
+        block_rows_end = min(block_row0 + RB * 32, seq);
         qi = row0 + col;                                      // this lane's query row
         const int kv_end = a.causal ? block_rows_end : a.kv_seq; // keys [0, kv_end) are visible to the block
         n_tiles = (kv_end + kBN - 1) / kBN;
@@ -364,7 +382,7 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
     // own area behind the rings), so that the main loop holds no register-destination global load: the
     // compiler then never emits a vmcnt wait of its own there.
     const uint32_t q_lds = 2 * VBASE + w * T::WAREA;
-    const char* qb = reinterpret_cast<const char*>(static_cast<const __bf16*>(a.q) + b * a.qs[0] + h * a.qs[2]);
+    const char* qb = reinterpret_cast<const char*>(static_cast<const __bf16*>(a.q) + q_first + h * a.qs[2]);
     const uint64_t qb_bits = reinterpret_cast<uint64_t>(qb);
     // (the builtin returns a signed int: widen each half as unsigned)
     const uint32_t qb_hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(qb_bits >> 32)));
@@ -380,7 +398,7 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
         const int row = slot / PITCH;
         const int c = (slot % PITCH) ^ swz<PITCH>(row);
         const uint32_t cb = (c * 8 < a.head_dim) ? c * 16 : 0;
-        const int r = clamp ? min(first_row + row, a.seq - 1) : first_row + row;
+        const int r = clamp ? min(first_row + row, seq - 1) : first_row + row;
         return static_cast<uint32_t>(r) * q_row_bytes + cb;
     };
     auto issue_q = [&](int first_row) {                       // any row tile: rows past the sequence re-read its last row
@@ -459,7 +477,7 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
             // head_dim a multiple of 32 the partner of an element, head_dim / 2 further on, sits KSTEPS / 2
             // k-steps later in the same lane.  (cos, sin) of the row's 8 consecutive pairs come as four 16-byte loads.
             constexpr int HS = KSTEPS / 2;
-            const float2* cs_row = a.q_cs + (static_cast<int64_t>(b) * a.seq + min(qi, a.seq - 1)) * (DP / 2) + 8 * half;
+            const float2* cs_row = a.q_cs + (static_cast<int64_t>(b) * seq + min(qi, seq - 1)) * (DP / 2) + 8 * half;
 #pragma unroll
             for (int s = 0; s < HS; ++s) {
                 float2 cs[8];
@@ -861,8 +879,8 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
                 }
             }
         }
-        __bf16* ob = static_cast<__bf16*>(a.out) + b * a.os[0] + h * a.os[2];
-        if (kWave % CPR == 0 && e_row0 + 32 <= a.seq && a.head_dim == DP) {
+        __bf16* ob = static_cast<__bf16*>(a.out) + o_first + h * a.os[2];
+        if (kWave % CPR == 0 && e_row0 + 32 <= seq && a.head_dim == DP) {
             // whole tile, unpadded head: the lane keeps its column, rows advance by 64 / CPR per store
             constexpr int RPI = kWave / CPR > 0 ? kWave / CPR : 1;
             const int r0 = lane_late / CPR, dc = lane_late - r0 * CPR;
@@ -877,7 +895,7 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
             for (int it = 0; it < 32 * CPR / kWave; ++it) {
                 const int id = it * kWave + lane_late;
                 const int r = id / CPR, dc = id - r * CPR;
-                if (e_row0 + r < a.seq && dc * 8 < a.head_dim)
+                if (e_row0 + r < seq && dc * 8 < a.head_dim)
                     *reinterpret_cast<bf16x8*>(ob + static_cast<int64_t>(e_row0 + r) * a.os[1] + dc * 8) =
                         *reinterpret_cast<const bf16x8*>(&o_s[r * OROW + dc * 8]);
             }
@@ -985,7 +1003,7 @@ static bool choose_paired(const AttnArgs& a, int64_t per_rt, int rows_per_block)
     return paired;
 }
 
-template <int DP, int WAVES, int STAGES>
+template <int DP, int WAVES, int STAGES, bool RAGGED>
 static int launch_mfma(AttnArgs& a, hipStream_t s)
 {
     using T = AttnTile<DP, WAVES, STAGES>;
@@ -999,10 +1017,10 @@ static int launch_mfma(AttnArgs& a, hipStream_t s)
     constexpr size_t lds = T::LDS_BYTES;
     if (lds > 64 * 1024) {
         static std::atomic<uint64_t> allowed{0};
-        const int rc = allow_dynamic_lds(reinterpret_cast<const void*>(attn_mfma_kernel<DP, WAVES, STAGES>), lds, &allowed);
+        const int rc = allow_dynamic_lds(reinterpret_cast<const void*>(attn_mfma_kernel<DP, WAVES, STAGES, RAGGED>), lds, &allowed);
         if (rc != CIVIC_OK) return rc;
     }
-    civic::launch((attn_mfma_kernel<DP, WAVES, STAGES>), dim3(static_cast<unsigned>(per_rt), grid_y),
+    civic::launch((attn_mfma_kernel<DP, WAVES, STAGES, RAGGED>), dim3(static_cast<unsigned>(per_rt), grid_y),
                        dim3(T::THREADS), lds, s, a);
     return check_launch();
 }
@@ -1010,12 +1028,12 @@ static int launch_mfma(AttnArgs& a, hipStream_t s)
 #ifndef CIVIC_ATTN_STAGES
 #define CIVIC_ATTN_STAGES 2
 #endif
-template <int WAVES>
+template <int WAVES, bool RAGGED>
 static int launch_mfma_for(AttnArgs& a, hipStream_t s)
 {
-    if (a.head_dim <= 64) return launch_mfma<64, WAVES, CIVIC_ATTN_STAGES>(a, s);
-    if (a.head_dim <= 96) return launch_mfma<96, WAVES, CIVIC_ATTN_STAGES>(a, s);
-    return launch_mfma<128, WAVES, CIVIC_ATTN_STAGES>(a, s);
+    if (a.head_dim <= 64) return launch_mfma<64, WAVES, CIVIC_ATTN_STAGES, RAGGED>(a, s);
+    if (a.head_dim <= 96) return launch_mfma<96, WAVES, CIVIC_ATTN_STAGES, RAGGED>(a, s);
+    return launch_mfma<128, WAVES, CIVIC_ATTN_STAGES, RAGGED>(a, s);
 }
 
 }  // namespace civic
@@ -1024,10 +1042,14 @@ namespace civic {
 
 // Attention, and the KV-cache write when k_cache is not null (inside the attention kernel where the
 // MFMA path runs, as a second launch otherwise).
+// item_row (host, batch + 1 ascending row numbers, or null): the queries and outputs of the `batch` items are packed
+// along the token axis, item b owning rows [item_row[b], item_row[b + 1]) of q and out, and `seq` is the longest item;
+// at most kRaggedItems items, no mask, no caches, no rotary table.  dry_run: every check and nothing launched.
 static int prefill_attn(const void* q, const void* k, const void* v, void* out, int dtype, int32_t batch, int32_t seq,
                         int32_t kv_seq, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, const int64_t* q_strides,
                         const int64_t* kv_strides, const int64_t* o_strides, int32_t causal, float softmax_scale,
-                        void* k_cache, void* v_cache, int64_t s_max, int64_t pos0, const float* q_cos_sin, void* stream)
+                        void* k_cache, void* v_cache, int64_t s_max, int64_t pos0, const float* q_cos_sin, void* stream,
+                        const int32_t* item_row = nullptr, bool dry_run = false)
 {
     const int esz = dtype_size(dtype);
     if (!esz || !q_strides || !kv_strides || !o_strides) return CIVIC_ERR_INVALID_ARG;
@@ -1050,6 +1072,7 @@ static int prefill_attn(const void* q, const void* k, const void* v, void* out, 
     }
     if (q_cos_sin && (!aligned16(q_cos_sin) || head_dim % 4)) return CIVIC_ERR_INVALID_ARG;
     if (head_dim > CIVIC_MAX_HEAD_DIM || batch > 65535 || n_q_heads > 65535) return CIVIC_ERR_UNSUPPORTED;
+    if (item_row && (batch > kRaggedItems || causal || k_cache || q_cos_sin)) return CIVIC_ERR_INVALID_ARG;
     if (batch == 0 || seq == 0) return CIVIC_OK;
 
     AttnArgs a;
@@ -1062,6 +1085,7 @@ static int prefill_attn(const void* q, const void* k, const void* v, void* out, 
     a.group = n_q_heads / n_kv_heads; a.head_blocks = 0; a.hb_shift = 0; a.magic_head_blocks = 0; a.magic_kv_heads = 0;
     a.k_cache = k_cache; a.v_cache = v_cache; a.s_max = s_max; a.pos0 = pos0;
     a.q_cs = reinterpret_cast<const float2*>(q_cos_sin);
+    for (int i = 0; i <= kRaggedItems; ++i) a.item_row[i] = item_row && i <= batch ? item_row[i] : 0;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
     // the MFMA path addresses a K/V tile, and a head's Q rows, with 32-bit per-lane byte offsets, and its grid
@@ -1075,14 +1099,29 @@ static int prefill_attn(const void* q, const void* k, const void* v, void* out, 
     const bool rope_fits = !q_cos_sin || head_dim == 64 || head_dim == 96 || head_dim == 128;
     if (dtype == CIVIC_BF16 && head_dim <= 128 && rope_fits && kv_strides[1] * 2 < (1 << 25) &&
         static_cast<int64_t>(seq) * q_strides[1] * 2 < (int64_t{1} << 32) && mfma_geometry<8>(a, &per_rt)) {
-        if (2 * per_rt * a.row_tiles > kComputeUnits || !mfma_geometry<4>(a, &per_rt)) return launch_mfma_for<8>(a, s);
-        return launch_mfma_for<4>(a, s);
+        if (dry_run) return CIVIC_OK;
+        const bool eight = 2 * per_rt * a.row_tiles > kComputeUnits || !mfma_geometry<4>(a, &per_rt);
+        if (item_row) return eight ? launch_mfma_for<8, true>(a, s) : launch_mfma_for<4, true>(a, s);
+        return eight ? launch_mfma_for<8, false>(a, s) : launch_mfma_for<4, false>(a, s);
     }
-    // everything else: the fp32 kernel (which also writes the caches when asked to)
-    const dim3 grid(static_cast<unsigned>((seq + 3) / 4), static_cast<unsigned>(n_q_heads), static_cast<unsigned>(batch));
-    if (dtype == CIVIC_BF16) civic::launch((attn_plain_kernel<true>), grid, dim3(256), 0, s, a);
-    else civic::launch((attn_plain_kernel<false>), grid, dim3(256), 0, s, a);
-    return check_launch();
+    if (dry_run) return CIVIC_OK;
+    // everything else: the fp32 kernel (which also writes the caches when asked to); ragged items one launch each
+    for (int32_t it = 0; it < (item_row ? batch : 1); ++it) {
+        AttnArgs ai = a;
+        if (item_row) {
+            ai.batch = 1; ai.seq = item_row[it + 1] - item_row[it];
+            ai.q = static_cast<const char*>(q) + static_cast<int64_t>(item_row[it]) * q_strides[1] * esz;
+            ai.out = static_cast<char*>(out) + static_cast<int64_t>(item_row[it]) * o_strides[1] * esz;
+            ai.k = static_cast<const char*>(k) + static_cast<int64_t>(it) * kv_strides[0] * esz;
+            ai.v = static_cast<const char*>(v) + static_cast<int64_t>(it) * kv_strides[0] * esz;
+        }
+        const dim3 grid(static_cast<unsigned>((ai.seq + 3) / 4), static_cast<unsigned>(n_q_heads), static_cast<unsigned>(ai.batch));
+        if (dtype == CIVIC_BF16) civic::launch((attn_plain_kernel<true>), grid, dim3(256), 0, s, ai);
+        else civic::launch((attn_plain_kernel<false>), grid, dim3(256), 0, s, ai);
+        const int rc = check_launch();
+        if (rc != CIVIC_OK) return rc;
+    }
+    return CIVIC_OK;
 }
 
 }  // namespace civic
@@ -1137,18 +1176,22 @@ extern "C" int civic_cross_attn_ragged(const void* q, const void* k, const void*
     for (int32_t b = 0; b < batch; ++b)
         if (q_offsets[b + 1] <= q_offsets[b] || q_offsets[b + 1] - q_offsets[b] > INT32_MAX) return CIVIC_ERR_INVALID_ARG;
     // q_strides[0] / o_strides[0] (the batch stride of the rectangular call) are not used: items are packed along the
-    // token axis; the per-item call checks everything else (a token stride that keeps rows 16-byte aligned keeps every
-    // item's first row aligned as well)
-    const char* qb = static_cast<const char*>(q);
-    char* ob = static_cast<char*>(out);
-    for (int32_t b = 0; b < batch; ++b) {
-        const int64_t row0 = q_offsets[b];
-        const int rc = civic_cross_attn(qb + row0 * q_strides[1] * esz, static_cast<const char*>(k) + b * kv_strides[0] * esz,
-                                        static_cast<const char*>(v) + b * kv_strides[0] * esz, ob + row0 * o_strides[1] * esz, dtype, 1,
-                                        static_cast<int32_t>(q_offsets[b + 1] - row0), n_kv, n_q_heads, n_kv_heads, head_dim, q_strides,
-                                        kv_strides, o_strides, softmax_scale, stream);
-        if (rc != CIVIC_OK) return rc;
-    }
+    // token axis (a token stride that keeps rows 16-byte aligned keeps every item's first row aligned as well).  Up to
+    // kRaggedItems items go out as ONE launch whose workgroups look their item's rows up in a table in the kernel
+    // arguments; longer lists in several.  Every group is checked before the first one is launched.
+    if (q_offsets[batch] > INT32_MAX) return CIVIC_ERR_UNSUPPORTED;
+    for (int pass = 0; pass < 2; ++pass)
+        for (int32_t b0 = 0; b0 < batch; b0 += civic::kRaggedItems) {
+            const int32_t nb = batch - b0 < civic::kRaggedItems ? batch - b0 : civic::kRaggedItems;
+            int32_t rows[civic::kRaggedItems + 1], longest = 0;
+            for (int32_t i = 0; i <= nb; ++i) rows[i] = static_cast<int32_t>(q_offsets[b0 + i]);
+            for (int32_t i = 0; i < nb; ++i) longest = rows[i + 1] - rows[i] > longest ? rows[i + 1] - rows[i] : longest;
+            const int rc = civic::prefill_attn(q, static_cast<const char*>(k) + static_cast<int64_t>(b0) * kv_strides[0] * esz,
+                                               static_cast<const char*>(v) + static_cast<int64_t>(b0) * kv_strides[0] * esz, out, dtype, nb,
+                                               longest, n_kv, n_q_heads, n_kv_heads, head_dim, q_strides, kv_strides, o_strides, 0,
+                                               softmax_scale, nullptr, nullptr, 0, 0, nullptr, stream, rows, pass == 0);
+            if (rc != CIVIC_OK) return rc;
+        }
     return CIVIC_OK;
 }
 

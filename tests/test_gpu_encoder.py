@@ -146,3 +146,32 @@ def test_ragged_items_match_oracle_and_the_rectangular_calls(bd, sizes):
         kc1, vc1 = bd.civic_kv_compress(dk[a:b][None], dv[a:b][None], dr[a:b].contiguous())
         assert torch.equal(kc1[0], kc[i]) and torch.equal(vc1[0], vc[i])
         assert torch.equal(bd.civic_cross_attn(dq[a:b][None], kc[i:i + 1], vc[i:i + 1])[0], out[a:b])
+
+
+@pytest.mark.parametrize("dtype,hq,hkv,d,n_items,n_kv", [
+    ("bf16", 8, 2, 128, 150, 96),      # more items than one launch's table holds, 4 query heads per KV head
+    ("bf16", 4, 4, 72, 70, 33),        # padded head, a key count that ends inside a tile
+    ("bf16", 2, 1, 64, 3, 700),        # few long items
+    ("fp32", 4, 2, 64, 9, 40),         # the fp32 kernel: one launch per item
+])
+def test_ragged_cross_attention_in_one_launch(bd, dtype, hq, hkv, d, n_items, n_kv):
+    """Packed queries of many items against each item's own keys: the workgroups find their item in the launch's table."""
+    log("ragged cross attention", dtype, hq, hkv, d, n_items, n_kv)
+    rng = np.random.default_rng(n_items * 1000 + n_kv)
+    sizes = rng.integers(1, 90, n_items)
+    sizes[::7] = rng.integers(150, 400, sizes[::7].size)          # some items several row tiles long
+    sizes[-1] = 1
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    total = int(off[-1])
+    q, q32 = wl.quantize(rng.standard_normal((total, hq, d)).astype(np.float32), dtype)
+    k, k32 = wl.quantize(rng.standard_normal((n_items, n_kv, hkv, d)).astype(np.float32), dtype)
+    v, v32 = wl.quantize(rng.standard_normal((n_items, n_kv, hkv, d)).astype(np.float32), dtype)
+    out = torch.full((total + 2, hq, d), 7.0, dtype=to_dev(q).dtype, device="cuda")     # two sentinel rows behind the last item
+    bd.civic_cross_attn_ragged(to_dev(q), to_dev(k), to_dev(v), off, out=out[:total])
+    torch.cuda.synchronize()
+    ref = oracle.cross_attention_ragged(q32, k32, v32, off)
+    got = widen(to_host(out))
+    err = float(np.abs(got[:total].astype(np.float64) - ref).max())
+    log("   rows", total, "max abs err", err, "tol", attn_tol(ref, dtype))
+    assert np.isfinite(got).all() and err <= attn_tol(ref, dtype)
+    assert np.all(got[total:] == 7.0)
