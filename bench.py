@@ -497,6 +497,13 @@ def main() -> int:
             for i in range(len(sizes)):
                 bd.civic_cross_attn(qr[off[i]:off[i + 1]][None], kr[i:i + 1], vr[i:i + 1], out=outr[off[i]:off[i + 1]][None])
         t_items = alone(per_item, cost=len(sizes))
+        width = w.n_kv_heads * w.head_dim
+        kp = torch.randn((int(off[-1]), width), device="cuda").to(x0.dtype); vp = torch.randn_like(kp)
+        rp = torch.rand((int(off[-1]), s_mem), device="cuda") ** 4
+        kcr = torch.empty((len(sizes), s_mem, width), dtype=x0.dtype, device="cuda"); vcr = torch.empty_like(kcr)
+        ws_r = torch.empty(int(bd.lib.civic_kv_compress_ragged_workspace_bytes(len(sizes), off.ctypes.data, s_mem, width)),
+                           dtype=torch.uint8, device="cuda")
+        t_cmp_rag = alone(lambda s_: bd.civic_kv_compress_ragged(kp, vp, rp, off, k_c=kcr, v_c=vcr, workspace=ws_r), cost=len(sizes))
         f_agg = 4.0 * m_e * t_e * d_v * w.batch
         f_cmp = 4.0 * s_mem * m_e * w.n_kv_heads * w.head_dim * w.batch
         f_x = 4.0 * w.n_q_heads * w.head_dim * m_e * s_mem * w.batch
@@ -508,7 +515,8 @@ def main() -> int:
                    "cross_attn": {"us": round(t_x, 2), "flops": f_x, "tflops": round(f_x / t_x / 1e6, 1)},
                    "uncompressed_attn_us": round(t_full, 2),
                    "cross_attn_ragged": {"items": sizes, "us": round(t_rag, 2), "us_one_call_per_item": round(t_items, 2),
-                                         "flops": 4.0 * w.n_q_heads * w.head_dim * float(off[-1]) * s_mem}}
+                                         "flops": 4.0 * w.n_q_heads * w.head_dim * float(off[-1]) * s_mem},
+                   "kv_compress_ragged": {"items": sizes, "us": round(t_cmp_rag, 2), "flops": 4.0 * s_mem * float(off[-1]) * width}}
 
     # the selection runs once per prompt, the attention and the KV write once per layer: one measured step plus
     # layers - 1 further attention launches (in-step duration)

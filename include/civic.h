@@ -330,13 +330,14 @@ int civic_cross_attn(const void* q, const void* k, const void* v, void* out, int
 /* Eq. 9 for a batch whose items differ in size (images of different grids in one batch): the rows of all items are
  * packed back to back, item b owning rows [row_offsets[b], row_offsets[b+1]) of k, v and of its own assignment rows in
  * r; every item is compressed and attended by itself, and the results equal civic_kv_compress / civic_cross_attn on
- * that item alone, bit for bit.  The compression runs the rectangular kernels once per item on the stream; the
- * attention is ONE launch for up to 64 items (a workgroup finds its item's rows in a table passed with the launch;
- * longer lists go out in groups of 64; fp32 or head_dim > 128 fall back to one launch per item).
+ * that item alone, bit for bit.  Items travel in groups of up to 64 whose row numbers are passed with the launch: the
+ * compression is four launches per group (column sums, their inverses, Rbar^T of every item, one grouped GEMM for
+ * K_c and V_c of all items), the attention ONE launch per group (fp32 or head_dim > 128: one launch per item).
  *   k, v         device [total_rows, width] bf16;  r  device [total_rows, n_mem] fp32
  *   row_offsets  host [batch + 1] int64, row_offsets[0] = 0, strictly increasing (no empty item)
  *   k_c, v_c     device [batch, n_mem, width] bf16
- *   workspace    civic_kv_compress_ragged_workspace_bytes(same sizes): the largest item's need, shared in turn
+ *   workspace    civic_kv_compress_ragged_workspace_bytes(same sizes): every item's column sums and padded Rbar^T
+ *   row_offsets[batch] <= INT32_MAX, else CIVIC_ERR_UNSUPPORTED
  * width must be a multiple of 8 and n_mem of 4 (every item's first row 16-byte aligned), else CIVIC_ERR_UNSUPPORTED. */
 size_t civic_kv_compress_ragged_workspace_bytes(int32_t batch, const int64_t* row_offsets /* host */, int32_t n_mem,
                                                 int32_t width);

@@ -36,6 +36,16 @@ constexpr int kGemmBM = 128, kGemmBN = 128, kGemmBK = 64;
 constexpr int kGemmThreads = 256;
 constexpr int kGemmTileBytes = kGemmBM * kGemmBK * 2;         // one operand tile: 16 KB
 
+constexpr int kGroupItems = 64;    // items of one grouped launch (longer lists go out in several)
+
+// Items of different row counts packed along the row axis (the ragged Eq. 9 calls): item i owns rows
+// [row[i], row[i + 1]) of the packed tensors; pad_row counts the same rows with every item's length rounded up to 64,
+// which is how the items' zero-padded Rbar^T blocks follow one another in scratch memory.
+struct Group {
+    int32_t row[kGroupItems + 1];
+    int32_t pad_row[kGroupItems + 1];
+};
+
 struct GemmArgs {
     const __bf16* a; const __bf16* b; void* c;
     // a second (B, C) pair served by the same launch (grid z = 2 * batch item + pair), or null
@@ -47,6 +57,9 @@ struct GemmArgs {
     float alpha;
     // output tiles: counts per matrix, tiles of all matrices of the launch, n-tiles per panel (filled in by launch_gemm)
     int32_t tiles_m, tiles_n, total_tiles, panel;
+    // GROUPED launches only: batch item i multiplies A_i = a + m * pad_row[i] (its own contraction length
+    // pad_row[i + 1] - pad_row[i], which is also its row pitch) with the rows [row[i], row[i + 1]) of b
+    Group grp;
 };
 
 template <int LDS_IMM>
@@ -79,7 +92,7 @@ typedef short enc_s16x8 __attribute__((ext_vector_type(8)));
 // which hands a lane one column and 4 consecutive contraction rows, so no transposed copy is ever made.
 // STAGES: tiles in the LDS ring, all but one in flight ahead of the one consumed: 2 (two workgroups per compute unit)
 // when the grid fills the chip, 4 (one workgroup per unit) when it does not and a tile's latency is what is waited for.
-template <bool C_BF16, bool B_KROWS, int STAGES>
+template <bool C_BF16, bool B_KROWS, int STAGES, bool GROUPED = false>
 __global__ __launch_bounds__(kGemmThreads, STAGES == 2 ? 2 : 1) void gemm_kernel(GemmArgs g)
 {
     extern __shared__ __attribute__((aligned(16))) char gemm_lds[];
@@ -106,25 +119,37 @@ __global__ __launch_bounds__(kGemmThreads, STAGES == 2 ? 2 : 1) void gemm_kernel
     const bool alt = g.b_alt != nullptr && (zi & 1u);
     const int64_t bz = g.b_alt != nullptr ? (zi >> 1) : zi;
     const __bf16* const b_mat = alt ? g.b_alt : g.b;
+    // contraction length, A's row pitch and the operands' first elements for this batch item
+    int32_t k_len = g.k, kb_rows = g.kb_rows;
+    int64_t lda = g.lda, a_first = bz * g.sa, b_first = bz * g.sb;
+    if constexpr (GROUPED) {
+        static_assert(B_KROWS, "grouped items differ in their contraction rows");
+        const int32_t r0 = g.grp.row[bz], p0 = g.grp.pad_row[bz];
+        k_len = g.grp.pad_row[bz + 1] - p0;
+        kb_rows = g.grp.row[bz + 1] - r0;
+        lda = k_len;
+        a_first = static_cast<int64_t>(g.m) * p0;
+        b_first = static_cast<int64_t>(r0) * g.ldb;
+    }
 
     // global -> LDS: instruction j of wavefront w fills slots [(4 w + j) * 64, +64) of a tile; slot -> (row, physical chunk)
-    const char* a_base = reinterpret_cast<const char*>(g.a + bz * g.sa + static_cast<int64_t>(m0) * g.lda);
-    const char* b_base = B_KROWS ? reinterpret_cast<const char*>(b_mat + bz * g.sb + n0)
-                                 : reinterpret_cast<const char*>(b_mat + bz * g.sb + static_cast<int64_t>(n0) * g.ldb);
-    const int last_tile = g.k / kGemmBK - 1;
+    const char* a_base = reinterpret_cast<const char*>(g.a + a_first + static_cast<int64_t>(m0) * lda);
+    const char* b_base = B_KROWS ? reinterpret_cast<const char*>(b_mat + b_first + n0)
+                                 : reinterpret_cast<const char*>(b_mat + b_first + static_cast<int64_t>(n0) * g.ldb);
+    const int last_tile = k_len / kGemmBK - 1;
     uint32_t a_off[4], b_off[4], b_off_tail[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int slot = (w * 4 + j) * kWave + lane;
         const int row = slot >> 3;
         const int c = (slot & 7) ^ enc_swz(row);
-        a_off[j] = static_cast<uint32_t>(min(row, g.m - 1 - m0)) * static_cast<uint32_t>(g.lda * 2) + c * 16;
+        a_off[j] = static_cast<uint32_t>(min(row, g.m - 1 - m0)) * static_cast<uint32_t>(lda * 2) + c * 16;
         if constexpr (B_KROWS) {
             const int krow = slot >> 4;                       // contraction row inside the tile
             const int lc = (slot & 15) ^ enc_swz16(krow);     // logical chunk: columns n0 + 8 lc .. + 7
             const int cc = min(lc, (g.n - n0) / 8 - 1);       // (n is a multiple of 8; chunks past it re-read a valid one)
             b_off[j] = static_cast<uint32_t>(krow) * static_cast<uint32_t>(g.ldb * 2) + cc * 16;
-            b_off_tail[j] = static_cast<uint32_t>(min(last_tile * kGemmBK + krow, g.kb_rows - 1) - last_tile * kGemmBK) *
+            b_off_tail[j] = static_cast<uint32_t>(min(last_tile * kGemmBK + krow, kb_rows - 1) - last_tile * kGemmBK) *
                                 static_cast<uint32_t>(g.ldb * 2) + cc * 16;
         } else {
             b_off[j] = static_cast<uint32_t>(min(row, g.n - 1 - n0)) * static_cast<uint32_t>(g.ldb * 2) + c * 16;
@@ -177,7 +202,7 @@ __global__ __launch_bounds__(kGemmThreads, STAGES == 2 ? 2 : 1) void gemm_kernel
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    const int n_tiles = g.k / kGemmBK;
+    const int n_tiles = k_len / kGemmBK;
 #pragma unroll
     for (int t = 0; t < STAGES - 1; ++t)
         if (t == 0) issue(0, std::integral_constant<int, 0>{});
@@ -255,20 +280,21 @@ __global__ __launch_bounds__(kGemmThreads, STAGES == 2 ? 2 : 1) void gemm_kernel
             }
 }
 
-template <bool C_BF16, bool B_KROWS, int STAGES>
+template <bool C_BF16, bool B_KROWS, int STAGES, bool GROUPED = false>
 static int launch_gemm_variant(const GemmArgs& g, unsigned blocks, hipStream_t s)
 {
     const dim3 grid(blocks);
     constexpr size_t lds = 2 * STAGES * kGemmTileBytes;
     static std::atomic<uint64_t> allowed{0};
-    const int rc = allow_dynamic_lds(reinterpret_cast<const void*>(gemm_kernel<C_BF16, B_KROWS, STAGES>), lds, &allowed);
+    const int rc = allow_dynamic_lds(reinterpret_cast<const void*>(gemm_kernel<C_BF16, B_KROWS, STAGES, GROUPED>), lds, &allowed);
     if (rc != CIVIC_OK) return rc;
-    civic::launch((gemm_kernel<C_BF16, B_KROWS, STAGES>), grid, dim3(kGemmThreads), lds, s, g);
+    civic::launch((gemm_kernel<C_BF16, B_KROWS, STAGES, GROUPED>), grid, dim3(kGemmThreads), lds, s, g);
     return check_launch();
 }
 
 // `batch` batch items; with g.b_alt set every item runs twice, once per (B, C) pair.  b_krows: B is stored [k x n].
-static int launch_gemm(const GemmArgs& g_in, int batch, bool c_bf16, bool b_krows, hipStream_t s)
+// grouped: g.grp describes the `batch` items (bf16 result, B stored [k x n] only).
+static int launch_gemm(const GemmArgs& g_in, int batch, bool c_bf16, bool b_krows, hipStream_t s, bool grouped = false)
 {
     GemmArgs g = g_in;
     const int64_t z = static_cast<int64_t>(batch) * (g.b_alt ? 2 : 1);
@@ -284,6 +310,7 @@ static int launch_gemm(const GemmArgs& g_in, int batch, bool c_bf16, bool b_krow
     g.panel = panel < g.tiles_n ? panel : g.tiles_n;
     // a grid that leaves compute units without a second workgroup takes the deeper ring
     const bool deep = total < 2 * 256;
+    if (grouped) return deep ? launch_gemm_variant<true, true, 4, true>(g, grid, s) : launch_gemm_variant<true, true, 2, true>(g, grid, s);
     if (c_bf16) {
         if (b_krows) return deep ? launch_gemm_variant<true, true, 4>(g, grid, s) : launch_gemm_variant<true, true, 2>(g, grid, s);
         return deep ? launch_gemm_variant<true, false, 4>(g, grid, s) : launch_gemm_variant<true, false, 2>(g, grid, s);
@@ -442,14 +469,13 @@ __global__ __launch_bounds__(256) void col_sum_kernel(const __bf16* __restrict__
 
 // out[b, c, r] = in[b, r, c] * scale[c] (scale may be null) for r < rows, 0 for rows <= r < ld_out; 32 x 32 tiles through LDS.
 template <typename TIN>
-__global__ __launch_bounds__(256) void transpose_pad_kernel(const TIN* __restrict__ in, int32_t rows, int32_t cols, int64_t ld_in,
-                                                            int64_t in_batch, const float* __restrict__ scale,
-                                                            __bf16* __restrict__ out, int64_t ld_out, int64_t out_batch)
+__device__ __forceinline__ void transpose_pad_block(const TIN* __restrict__ in, int32_t rows, int32_t cols, int64_t ld_in,
+                                                    int64_t in_batch, const float* __restrict__ scale,
+                                                    __bf16* __restrict__ out, int64_t ld_out, int64_t out_batch, int64_t b)
 {
     __shared__ float tile[32][33];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
     const int r0 = blockIdx.x * 32, c0 = blockIdx.y * 32;
-    const int64_t b = blockIdx.z;
     for (int k = ty; k < 32; k += 8) {
         const int r = r0 + k, c = c0 + tx;
         float v = 0.f;
@@ -469,11 +495,30 @@ __global__ __launch_bounds__(256) void transpose_pad_kernel(const TIN* __restric
     }
 }
 
+template <typename TIN>
+__global__ __launch_bounds__(256) void transpose_pad_kernel(const TIN* __restrict__ in, int32_t rows, int32_t cols, int64_t ld_in,
+                                                            int64_t in_batch, const float* __restrict__ scale,
+                                                            __bf16* __restrict__ out, int64_t ld_out, int64_t out_batch)
+{
+    transpose_pad_block<TIN>(in, rows, cols, ld_in, in_batch, scale, out, ld_out, out_batch, blockIdx.z);
+}
+
+// The same for the items of a group (grid z): item i's rows of r [.., cols], scaled by its own inv row, to its own
+// block of the padded Rbar^T scratch (cols x its padded length); blocks past an item's padded length write nothing.
+__global__ __launch_bounds__(256) void transpose_pad_grouped_kernel(const float* __restrict__ r, int32_t cols,
+                                                                    const float* __restrict__ inv, __bf16* __restrict__ out, Group grp)
+{
+    const int i = blockIdx.z;
+    const int32_t r0 = grp.row[i], p0 = grp.pad_row[i];
+    transpose_pad_block<float>(r + static_cast<int64_t>(r0) * cols, grp.row[i + 1] - r0, cols, cols, 0, inv + static_cast<int64_t>(i) * cols,
+                               out + static_cast<int64_t>(cols) * p0, grp.pad_row[i + 1] - p0, 0, 0);
+}
+
 // Column sums of r [rows, cols] in two steps: block (x, y) adds the rows y, y + gridDim.y, ... of 64 columns (its four
 // wavefronts four rows apart, coalesced 256-byte reads, meeting in LDS) into part[y, c]; the second kernel turns the
 // partial sums of a column into inv[c] = 1 / sum (0 for a column that sums to zero).
 constexpr int kColParts = 32;
-__global__ __launch_bounds__(256) void col_part_sum_kernel(const float* __restrict__ r, int32_t rows, int32_t cols, float* __restrict__ part)
+__device__ __forceinline__ void col_part_sum_block(const float* __restrict__ r, int32_t rows, int32_t cols, float* __restrict__ part)
 {
     __shared__ float lds_part[4][kWave];
     const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
@@ -487,14 +532,28 @@ __global__ __launch_bounds__(256) void col_part_sum_kernel(const float* __restri
         part[static_cast<int64_t>(blockIdx.y) * cols + c] = (lds_part[0][lane] + lds_part[1][lane]) + (lds_part[2][lane] + lds_part[3][lane]);
 }
 
+__global__ __launch_bounds__(256) void col_part_sum_kernel(const float* __restrict__ r, int32_t rows, int32_t cols, float* __restrict__ part)
+{
+    col_part_sum_block(r, rows, cols, part);
+}
+
+__global__ __launch_bounds__(256) void col_part_sum_grouped_kernel(const float* __restrict__ r, int32_t cols, float* __restrict__ part, Group grp)
+{
+    const int i = blockIdx.z;                                 // the item: its own rows, its own kColParts x cols partial sums
+    const int32_t r0 = grp.row[i];
+    col_part_sum_block(r + static_cast<int64_t>(r0) * cols, grp.row[i + 1] - r0, cols, part + static_cast<int64_t>(i) * kColParts * cols);
+}
+
+// grid y = item (1 for the rectangular call): part [items, kColParts, cols] -> inv [items, cols]
 __global__ __launch_bounds__(256) void col_inv_kernel(const float* __restrict__ part, int32_t cols, float* __restrict__ inv)
 {
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= cols) return;
+    part += static_cast<int64_t>(blockIdx.y) * kColParts * cols;
     float t = 0.f;
 #pragma unroll
     for (int p = 0; p < kColParts; ++p) t += part[static_cast<int64_t>(p) * cols + c];
-    inv[c] = t != 0.f ? 1.0f / t : 0.f;
+    inv[static_cast<int64_t>(blockIdx.y) * cols + c] = t != 0.f ? 1.0f / t : 0.f;
 }
 
 static int64_t pad64(int64_t x) { return (x + 63) / 64 * 64; }
@@ -709,15 +768,32 @@ static bool offsets_ok(const int64_t* off, int32_t batch)
 
 }  // namespace civic
 
+namespace civic {
+
+struct RaggedPlan {                      // byte offsets into the workspace of civic_kv_compress_ragged
+    int64_t pad_total;                   // sum of the items' row counts, each rounded up to 64
+    size_t inv, part, rt, total;
+};
+
+static void ragged_plan(int32_t batch, const int64_t* off, int32_t n_mem, RaggedPlan* p)
+{
+    p->pad_total = 0;
+    for (int32_t b = 0; b < batch; ++b) p->pad_total += pad64(off[b + 1] - off[b]);
+    size_t at = 0;
+    p->inv = at;  at += align256(static_cast<size_t>(batch) * n_mem * 4);
+    p->part = at; at += align256(static_cast<size_t>(batch) * n_mem * 4 * kColParts);
+    p->rt = at;   at += align256(static_cast<size_t>(n_mem) * p->pad_total * 2);
+    p->total = at;
+}
+
+}  // namespace civic
+
 extern "C" size_t civic_kv_compress_ragged_workspace_bytes(int32_t batch, const int64_t* row_offsets, int32_t n_mem, int32_t width)
 {
     if (batch <= 0 || n_mem <= 0 || width <= 0 || !civic::offsets_ok(row_offsets, batch)) return 0;
-    size_t need = 0;                                          // the items run one after the other and share the scratch
-    for (int32_t b = 0; b < batch; ++b) {
-        const size_t one = civic_kv_compress_workspace_bytes(1, static_cast<int32_t>(row_offsets[b + 1] - row_offsets[b]), n_mem, width);
-        need = one > need ? one : need;
-    }
-    return need;
+    civic::RaggedPlan p;                                      // every item keeps its own column sums and its own Rbar^T
+    civic::ragged_plan(batch, row_offsets, n_mem, &p);
+    return p.total;
 }
 
 extern "C" int civic_kv_compress_ragged(const void* k, const void* v, int dtype, const float* r, int32_t batch,
@@ -734,17 +810,54 @@ extern "C" int civic_kv_compress_ragged(const void* k, const void* v, int dtype,
     if (dtype != CIVIC_BF16) return CIVIC_ERR_UNSUPPORTED;
     // every item's first row must be 16-byte aligned in K, V and R: whole 16-byte pieces per row
     if (width % 8 || n_mem % 4) return CIVIC_ERR_UNSUPPORTED;
-    const size_t need = civic_kv_compress_ragged_workspace_bytes(batch, row_offsets, n_mem, width);
-    if (need > 0 && (!workspace || workspace_bytes < need || !aligned16(workspace))) return CIVIC_ERR_WORKSPACE;
-    // (civic_kv_compress checks the rest per item; its limits depend on the item's size only)
-    for (int32_t b = 0; b < batch; ++b) {
-        const int64_t row0 = row_offsets[b];
-        const int rc = civic_kv_compress(static_cast<const __bf16*>(k) + row0 * width, static_cast<const __bf16*>(v) + row0 * width, dtype,
-                                         r + row0 * n_mem, 1, static_cast<int32_t>(row_offsets[b + 1] - row0), n_mem, width,
-                                         static_cast<__bf16*>(k_c) + static_cast<int64_t>(b) * n_mem * width,
-                                         static_cast<__bf16*>(v_c) + static_cast<int64_t>(b) * n_mem * width, workspace, workspace_bytes, stream);
+    if (row_offsets[batch] > INT32_MAX) return CIVIC_ERR_UNSUPPORTED;       // (row numbers travel as 32-bit kernel arguments)
+    for (int32_t b = 0; b < batch; ++b) {                                     // 32-bit row offsets inside one item, as in civic_kv_compress
+        const int64_t padded = pad64(row_offsets[b + 1] - row_offsets[b]);
+        if (padded * width * 2 >= (int64_t{1} << 32) || padded * n_mem * 2 >= (int64_t{1} << 32)) return CIVIC_ERR_UNSUPPORTED;
+    }
+    RaggedPlan p;
+    ragged_plan(batch, row_offsets, n_mem, &p);
+    if (!workspace || workspace_bytes < p.total || !aligned16(workspace)) return CIVIC_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* ws = static_cast<char*>(workspace);
+    // Groups of up to kGroupItems items, four launches each: the column sums of every item's R rows, their inverses,
+    // Rbar^T of every item (transposed, scaled, zero-padded to a multiple of 64 contraction rows) and ONE grouped GEMM
+    // for K_c and V_c of all items (grid z = item x tensor; an item's contraction length comes from the group's table).
+    int64_t pad_done = 0;
+    for (int32_t b0 = 0; b0 < batch; b0 += kGroupItems) {
+        const int32_t nb = batch - b0 < kGroupItems ? batch - b0 : kGroupItems;
+        GemmArgs g;
+        int32_t longest_pad = 0;
+        g.grp.pad_row[0] = 0;
+        for (int32_t i = 0; i <= kGroupItems; ++i) {
+            const int32_t at = i <= nb ? i : nb;                              // (entries past the group repeat its end)
+            g.grp.row[i] = static_cast<int32_t>(row_offsets[b0 + at]);
+            if (i > 0) {
+                const int32_t padded = i <= nb ? static_cast<int32_t>(pad64(row_offsets[b0 + i] - row_offsets[b0 + i - 1])) : 0;
+                g.grp.pad_row[i] = g.grp.pad_row[i - 1] + padded;
+                longest_pad = padded > longest_pad ? padded : longest_pad;
+            }
+        }
+        float* inv = reinterpret_cast<float*>(ws + p.inv) + static_cast<int64_t>(b0) * n_mem;
+        float* part = reinterpret_cast<float*>(ws + p.part) + static_cast<int64_t>(b0) * n_mem * kColParts;
+        __bf16* rt = reinterpret_cast<__bf16*>(ws + p.rt) + static_cast<int64_t>(n_mem) * pad_done;
+        civic::launch(col_part_sum_grouped_kernel, dim3(static_cast<unsigned>((n_mem + kWave - 1) / kWave), kColParts, static_cast<unsigned>(nb)),
+                      dim3(256), 0, s, r, n_mem, part, g.grp);
+        civic::launch(col_inv_kernel, dim3(static_cast<unsigned>((n_mem + 255) / 256), static_cast<unsigned>(nb)), dim3(256), 0, s, part, n_mem, inv);
+        civic::launch(transpose_pad_grouped_kernel, dim3(static_cast<unsigned>(longest_pad / 32), static_cast<unsigned>((n_mem + 31) / 32),
+                                                        static_cast<unsigned>(nb)),
+                      dim3(256), 0, s, r, n_mem, inv, rt, g.grp);
+        int rc = check_launch();
         if (rc != CIVIC_OK) return rc;
+        g.a = rt; g.lda = 0; g.sa = 0; g.k = 0; g.kb_rows = 0;                // (per item, from the table)
+        g.b = static_cast<const __bf16*>(k); g.b_alt = static_cast<const __bf16*>(v); g.ldb = width; g.sb = 0;
+        g.c = static_cast<__bf16*>(k_c) + static_cast<int64_t>(b0) * n_mem * width;
+        g.c_alt = static_cast<__bf16*>(v_c) + static_cast<int64_t>(b0) * n_mem * width;
+        g.ldc = width; g.sc = static_cast<int64_t>(n_mem) * width;
+        g.m = n_mem; g.n = width; g.alpha = 1.0f;
+        rc = launch_gemm(g, nb, true, true, s, true);
+        if (rc != CIVIC_OK) return rc;
+        pad_done += g.grp.pad_row[nb];
     }
     return CIVIC_OK;
 }
-

@@ -175,3 +175,28 @@ def test_ragged_cross_attention_in_one_launch(bd, dtype, hq, hkv, d, n_items, n_
     log("   rows", total, "max abs err", err, "tol", attn_tol(ref, dtype))
     assert np.isfinite(got).all() and err <= attn_tol(ref, dtype)
     assert np.all(got[total:] == 7.0)
+
+
+def test_ragged_compression_of_more_items_than_one_group(bd):
+    """70 items of 1 to 200 rows: two groups of launches, every item with its own column sums and contraction length."""
+    rng = np.random.default_rng(70)
+    sizes = rng.integers(1, 200, 70)
+    sizes[[0, 63, 64, 69]] = [1, 64, 65, 128]
+    log("ragged compression", len(sizes), "items")
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    total, width, s = int(off[-1]), 136, 20
+    k, k32 = wl.quantize(rng.standard_normal((total, width)).astype(np.float32), "bf16")
+    v, v32 = wl.quantize(rng.standard_normal((total, width)).astype(np.float32), "bf16")
+    r = (rng.random((total, s)) ** 4).astype(np.float32)
+    dk, dv, dr = to_dev(k), to_dev(v), torch.from_numpy(r).cuda()
+    kc, vc = bd.civic_kv_compress_ragged(dk, dv, dr, off)
+    torch.cuda.synchronize()
+    for got, x32 in ((kc, k32), (vc, v32)):
+        ref = oracle.kv_compress_ragged(x32, r, off)
+        err = float(np.abs(widen(to_host(got)).astype(np.float64) - ref).max())
+        log("   max abs err", err, "tol", attn_tol(ref, "bf16"))
+        assert np.isfinite(widen(to_host(got))).all() and err <= attn_tol(ref, "bf16")
+    for i in (0, 1, 63, 64, 69):
+        a, b = off[i], off[i + 1]
+        kc1, vc1 = bd.civic_kv_compress(dk[a:b][None], dv[a:b][None], dr[a:b].contiguous())
+        assert torch.equal(kc1[0], kc[i]) and torch.equal(vc1[0], vc[i])
