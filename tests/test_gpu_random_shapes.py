@@ -198,3 +198,39 @@ def test_score_random_rows(bd):
             assert s[1] == 0.0 and s[2] == 0.0
         done += 1
     log("   worst error / tolerance", worst)
+
+
+def test_ragged_random_batches(bd):
+    """Eq. 9 on packed items of random sizes: the grouped compression and the one-launch attention against the oracle
+    item by item; item counts around the 64 of one group, lengths around the 64-row contraction tile, head sizes that
+    are padded or not, grouped heads."""
+    rng = np.random.default_rng(99)
+    worst_c, worst_a = 0.0, 0.0
+    for case in range(40):
+        n_items = int(rng.choice([1, 2, 5, 63, 64, 65, 90])) if case % 4 == 0 else int(rng.integers(1, 12))
+        sizes = rng.choice([1, 2, 63, 64, 65, 127, 128, 129, 300], n_items) if case % 3 == 0 else rng.integers(1, 200, n_items)
+        off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+        total = int(off[-1])
+        hkv = int(rng.choice([1, 2, 4]))
+        hq = hkv * int(rng.choice([1, 2, 4]))
+        d = int(rng.choice([32, 64, 72, 96, 128]))
+        s = 4 * int(rng.integers(1, 40))
+        k, k32 = wl.quantize(rng.standard_normal((total, hkv, d)).astype(np.float32), "bf16")
+        v, v32 = wl.quantize(rng.standard_normal((total, hkv, d)).astype(np.float32), "bf16")
+        q, q32 = wl.quantize((rng.standard_normal((total, hq, d)) * rng.choice([0.5, 1.0, 2.0])).astype(np.float32), "bf16")
+        r = (rng.random((total, s)) ** 4).astype(np.float32)
+        log("ragged case", case, "items", n_items, "rows", total, "heads", hq, hkv, "d", d, "S", s)
+        kc, vc = bd.civic_kv_compress_ragged(to_dev(k), to_dev(v), torch.from_numpy(r).cuda(), off)
+        out = bd.civic_cross_attn_ragged(to_dev(q), kc, vc, off)
+        torch.cuda.synchronize()
+        for got, x32 in ((kc, k32), (vc, v32)):
+            ref = oracle.kv_compress_ragged(x32.reshape(total, hkv * d), r, off).reshape(n_items, s, hkv, d)
+            err = float(np.abs(widen(to_host(got)).astype(np.float64) - ref).max())
+            worst_c = max(worst_c, err / attn_tol(ref, "bf16"))
+            assert err <= attn_tol(ref, "bf16")
+        ref = oracle.cross_attention_ragged(q32, widen(to_host(kc)), widen(to_host(vc)), off)
+        got = widen(to_host(out)).astype(np.float64)
+        err = float(np.abs(got - ref).max())
+        worst_a = max(worst_a, err / attn_tol(ref, "bf16"))
+        assert np.isfinite(got).all() and err <= attn_tol(ref, "bf16")
+    log("ragged: worst error / tolerance, compression", worst_c, "attention", worst_a)
