@@ -817,6 +817,7 @@ extern "C" int civic_kv_compress_ragged(const void* k, const void* v, int dtype,
     }
     RaggedPlan p;
     ragged_plan(batch, row_offsets, n_mem, &p);
+    if (p.pad_total > INT32_MAX) return CIVIC_ERR_UNSUPPORTED;                // (padded row numbers are 32-bit as well)
     if (!workspace || workspace_bytes < p.total || !aligned16(workspace)) return CIVIC_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
