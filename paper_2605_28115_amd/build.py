@@ -17,10 +17,7 @@ HIPCC_FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
                "-Wall", "-Wno-unused-command-line-argument", "-Wno-unknown-attributes"]
 
 
-def build(verbose: bool = False) -> str:
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           "-o", LIB, *[os.path.join(CSRC, s) for s in SOURCES]]
+def _run(cmd, verbose: bool) -> None:
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -31,6 +28,20 @@ def build(verbose: bool = False) -> str:
         print(out, file=sys.stderr)
     if proc.returncode != 0:
         raise RuntimeError("hipcc failed building libcivic.so")
+
+
+def build(verbose: bool = False) -> str:
+    """One object per source, compiled side by side (the translation units share no device code), then one link."""
+    import tempfile
+    from concurrent.futures import ThreadPoolExecutor
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    common = [f for f in HIPCC_FLAGS if f != "-shared"] + ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    with tempfile.TemporaryDirectory(prefix="civic_build_") as tmp:
+        objs = [os.path.join(tmp, s.replace(".hip", ".o")) for s in SOURCES]
+        jobs = [[hipcc, *common, "-c", "-o", o, os.path.join(CSRC, s)] for s, o in zip(SOURCES, objs)]
+        with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as pool:
+            list(pool.map(lambda c: _run(c, verbose), jobs))
+        _run([hipcc, "--offload-arch=gfx950", "-fPIC", "-shared", "-Wno-unused-command-line-argument", "-o", LIB, *objs], verbose)
     return LIB
 
 
