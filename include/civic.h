@@ -331,8 +331,8 @@ int civic_cross_attn(const void* q, const void* k, const void* v, void* out, int
  * packed back to back, item b owning rows [row_offsets[b], row_offsets[b+1]) of k, v and of its own assignment rows in
  * r; every item is compressed and attended by itself, and the results equal civic_kv_compress / civic_cross_attn on
  * that item alone, bit for bit.  Items travel in groups of up to 64 whose row numbers are passed with the launch: the
- * compression is four launches per group (column sums, their inverses, Rbar^T of every item, one grouped GEMM for
- * K_c and V_c of all items), the attention ONE launch per group (fp32 or head_dim > 128: one launch per item).
+ * compression is three launches per group (partial column sums, Rbar^T of every item, one grouped GEMM for K_c and
+ * V_c of all items), the attention ONE launch per group (fp32 or head_dim > 128: one launch per item).
  *   k, v         device [total_rows, width] bf16;  r  device [total_rows, n_mem] fp32
  *   row_offsets  host [batch + 1] int64, row_offsets[0] = 0, strictly increasing (no empty item)
  *   k_c, v_c     device [batch, n_mem, width] bf16

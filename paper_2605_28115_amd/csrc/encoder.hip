@@ -467,15 +467,29 @@ __global__ __launch_bounds__(256) void col_sum_kernel(const __bf16* __restrict__
     out[b * cols + j] = acc;
 }
 
-// out[b, c, r] = in[b, r, c] * scale[c] (scale may be null) for r < rows, 0 for rows <= r < ld_out; 32 x 32 tiles through LDS.
+constexpr int kColParts = 32;             // partial column sums per column (col_part_sum_kernel below)
+
+// out[b, c, r] = in[b, r, c] * inv[c] for r < rows, 0 for rows <= r < ld_out; 32 x 32 tiles through LDS.  inv[c] is one
+// over column c's sum, taken here from its kColParts partial sums part[p, c] (0 for a column that sums to zero); with
+// part null the values are copied unscaled.
 template <typename TIN>
 __device__ __forceinline__ void transpose_pad_block(const TIN* __restrict__ in, int32_t rows, int32_t cols, int64_t ld_in,
-                                                    int64_t in_batch, const float* __restrict__ scale,
+                                                    int64_t in_batch, const float* __restrict__ part,
                                                     __bf16* __restrict__ out, int64_t ld_out, int64_t out_batch, int64_t b)
 {
     __shared__ float tile[32][33];
+    __shared__ float inv_s[32];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
     const int r0 = blockIdx.x * 32, c0 = blockIdx.y * 32;
+    if (part != nullptr && threadIdx.x < 32) {
+        const int c = c0 + threadIdx.x;
+        float t = 0.f;
+        if (c < cols) {
+#pragma unroll
+            for (int p = 0; p < kColParts; ++p) t += part[static_cast<int64_t>(p) * cols + c];
+        }
+        inv_s[threadIdx.x] = t != 0.f ? 1.0f / t : 0.f;      // (read after the barrier below)
+    }
     for (int k = ty; k < 32; k += 8) {
         const int r = r0 + k, c = c0 + tx;
         float v = 0.f;
@@ -489,7 +503,7 @@ __device__ __forceinline__ void transpose_pad_block(const TIN* __restrict__ in, 
     for (int k = ty; k < 32; k += 8) {
         const int c = c0 + k, r = r0 + tx;
         if (c < cols && r < ld_out) {
-            const float sc = scale ? scale[c] : 1.0f;
+            const float sc = part ? inv_s[k] : 1.0f;
             out[b * out_batch + static_cast<int64_t>(c) * ld_out + r] = static_cast<__bf16>(tile[tx][k] * sc);
         }
     }
@@ -497,27 +511,28 @@ __device__ __forceinline__ void transpose_pad_block(const TIN* __restrict__ in, 
 
 template <typename TIN>
 __global__ __launch_bounds__(256) void transpose_pad_kernel(const TIN* __restrict__ in, int32_t rows, int32_t cols, int64_t ld_in,
-                                                            int64_t in_batch, const float* __restrict__ scale,
+                                                            int64_t in_batch, const float* __restrict__ part,
                                                             __bf16* __restrict__ out, int64_t ld_out, int64_t out_batch)
 {
-    transpose_pad_block<TIN>(in, rows, cols, ld_in, in_batch, scale, out, ld_out, out_batch, blockIdx.z);
+    transpose_pad_block<TIN>(in, rows, cols, ld_in, in_batch, part, out, ld_out, out_batch, blockIdx.z);
 }
 
-// The same for the items of a group (grid z): item i's rows of r [.., cols], scaled by its own inv row, to its own
-// block of the padded Rbar^T scratch (cols x its padded length); blocks past an item's padded length write nothing.
+// The same for the items of a group (grid z): item i's rows of r [.., cols], every column over its own sum (the item's
+// kColParts x cols partial sums), to the item's block of the padded Rbar^T scratch (cols x its padded length); blocks
+// past an item's padded length write nothing.
 __global__ __launch_bounds__(256) void transpose_pad_grouped_kernel(const float* __restrict__ r, int32_t cols,
-                                                                    const float* __restrict__ inv, __bf16* __restrict__ out, Group grp)
+                                                                    const float* __restrict__ part, __bf16* __restrict__ out, Group grp)
 {
     const int i = blockIdx.z;
     const int32_t r0 = grp.row[i], p0 = grp.pad_row[i];
-    transpose_pad_block<float>(r + static_cast<int64_t>(r0) * cols, grp.row[i + 1] - r0, cols, cols, 0, inv + static_cast<int64_t>(i) * cols,
-                               out + static_cast<int64_t>(cols) * p0, grp.pad_row[i + 1] - p0, 0, 0);
+    transpose_pad_block<float>(r + static_cast<int64_t>(r0) * cols, grp.row[i + 1] - r0, cols, cols, 0,
+                               part + static_cast<int64_t>(i) * kColParts * cols, out + static_cast<int64_t>(cols) * p0,
+                               grp.pad_row[i + 1] - p0, 0, 0);
 }
 
-// Column sums of r [rows, cols] in two steps: block (x, y) adds the rows y, y + gridDim.y, ... of 64 columns (its four
-// wavefronts four rows apart, coalesced 256-byte reads, meeting in LDS) into part[y, c]; the second kernel turns the
-// partial sums of a column into inv[c] = 1 / sum (0 for a column that sums to zero).
-constexpr int kColParts = 32;
+// Column sums of r [rows, cols], first step: block (x, y) adds the rows y, y + gridDim.y, ... of 64 columns (its four
+// wavefronts four rows apart, coalesced 256-byte reads, meeting in LDS) into part[y, c]; the transposing kernel above
+// adds a column's kColParts partial sums and inverts the total.
 __device__ __forceinline__ void col_part_sum_block(const float* __restrict__ r, int32_t rows, int32_t cols, float* __restrict__ part)
 {
     __shared__ float lds_part[4][kWave];
@@ -544,18 +559,6 @@ __global__ __launch_bounds__(256) void col_part_sum_grouped_kernel(const float* 
     col_part_sum_block(r + static_cast<int64_t>(r0) * cols, grp.row[i + 1] - r0, cols, part + static_cast<int64_t>(i) * kColParts * cols);
 }
 
-// grid y = item (1 for the rectangular call): part [items, kColParts, cols] -> inv [items, cols]
-__global__ __launch_bounds__(256) void col_inv_kernel(const float* __restrict__ part, int32_t cols, float* __restrict__ inv)
-{
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= cols) return;
-    part += static_cast<int64_t>(blockIdx.y) * kColParts * cols;
-    float t = 0.f;
-#pragma unroll
-    for (int p = 0; p < kColParts; ++p) t += part[static_cast<int64_t>(p) * cols + c];
-    inv[static_cast<int64_t>(blockIdx.y) * cols + c] = t != 0.f ? 1.0f / t : 0.f;
-}
-
 static int64_t pad64(int64_t x) { return (x + 63) / 64 * 64; }
 static size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
@@ -577,14 +580,13 @@ static void agg_plan(int32_t batch, int32_t n_tokens, int32_t n_anchors, int32_t
 
 struct CompressPlan {                    // byte offsets into the workspace of civic_kv_compress
     int64_t m_pad;
-    size_t inv, part, rt, xt, total;
+    size_t part, rt, xt, total;
 };
 
 static void compress_plan(int32_t batch, int32_t n_rows, int32_t n_mem, int32_t width, CompressPlan* p)
 {
     p->m_pad = pad64(n_rows);
     size_t off = 0;
-    p->inv = off; off += align256(static_cast<size_t>(n_mem) * 4);
     p->part = off; off += align256(static_cast<size_t>(n_mem) * 4 * kColParts);
     p->rt = off;  off += align256(static_cast<size_t>(n_mem) * p->m_pad * 2);
     // (a transposed copy of K, then V, only for widths whose rows are not whole 16-byte chunks)
@@ -713,16 +715,14 @@ extern "C" int civic_kv_compress(const void* k, const void* v, int dtype, const 
     if (batch == 0) return CIVIC_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
-    float* inv = reinterpret_cast<float*>(ws + p.inv);
     __bf16* rt = reinterpret_cast<__bf16*>(ws + p.rt);
     __bf16* xt = reinterpret_cast<__bf16*>(ws + p.xt);
     // Rbar^T [n_mem x m_pad]: every column of R over its sum, transposed, zero beyond n_rows
     float* part = reinterpret_cast<float*>(ws + p.part);
     civic::launch(col_part_sum_kernel, dim3(static_cast<unsigned>((n_mem + kWave - 1) / kWave), kColParts), dim3(256), 0, s, r, n_rows,
                        n_mem, part);
-    civic::launch(col_inv_kernel, dim3(static_cast<unsigned>((n_mem + 255) / 256)), dim3(256), 0, s, part, n_mem, inv);
     civic::launch((transpose_pad_kernel<float>), dim3(static_cast<unsigned>(p.m_pad / 32), static_cast<unsigned>((n_mem + 31) / 32), 1u),
-                       dim3(256), 0, s, r, n_rows, n_mem, static_cast<int64_t>(n_mem), int64_t{0}, inv, rt, p.m_pad, int64_t{0});
+                       dim3(256), 0, s, r, n_rows, n_mem, static_cast<int64_t>(n_mem), int64_t{0}, part, rt, p.m_pad, int64_t{0});
     int rc = check_launch();
     if (rc != CIVIC_OK) return rc;
     GemmArgs g;
@@ -772,7 +772,7 @@ namespace civic {
 
 struct RaggedPlan {                      // byte offsets into the workspace of civic_kv_compress_ragged
     int64_t pad_total;                   // sum of the items' row counts, each rounded up to 64
-    size_t inv, part, rt, total;
+    size_t part, rt, total;
 };
 
 static void ragged_plan(int32_t batch, const int64_t* off, int32_t n_mem, RaggedPlan* p)
@@ -780,7 +780,6 @@ static void ragged_plan(int32_t batch, const int64_t* off, int32_t n_mem, Ragged
     p->pad_total = 0;
     for (int32_t b = 0; b < batch; ++b) p->pad_total += pad64(off[b + 1] - off[b]);
     size_t at = 0;
-    p->inv = at;  at += align256(static_cast<size_t>(batch) * n_mem * 4);
     p->part = at; at += align256(static_cast<size_t>(batch) * n_mem * 4 * kColParts);
     p->rt = at;   at += align256(static_cast<size_t>(n_mem) * p->pad_total * 2);
     p->total = at;
@@ -821,7 +820,7 @@ extern "C" int civic_kv_compress_ragged(const void* k, const void* v, int dtype,
     if (!workspace || workspace_bytes < p.total || !aligned16(workspace)) return CIVIC_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     char* ws = static_cast<char*>(workspace);
-    // Groups of up to kGroupItems items, four launches each: the column sums of every item's R rows, their inverses,
+    // Groups of up to kGroupItems items, three launches each: the partial column sums of every item's R rows,
     // Rbar^T of every item (transposed, scaled, zero-padded to a multiple of 64 contraction rows) and ONE grouped GEMM
     // for K_c and V_c of all items (grid z = item x tensor; an item's contraction length comes from the group's table).
     int64_t pad_done = 0;
@@ -839,15 +838,13 @@ extern "C" int civic_kv_compress_ragged(const void* k, const void* v, int dtype,
                 longest_pad = padded > longest_pad ? padded : longest_pad;
             }
         }
-        float* inv = reinterpret_cast<float*>(ws + p.inv) + static_cast<int64_t>(b0) * n_mem;
         float* part = reinterpret_cast<float*>(ws + p.part) + static_cast<int64_t>(b0) * n_mem * kColParts;
         __bf16* rt = reinterpret_cast<__bf16*>(ws + p.rt) + static_cast<int64_t>(n_mem) * pad_done;
         civic::launch(col_part_sum_grouped_kernel, dim3(static_cast<unsigned>((n_mem + kWave - 1) / kWave), kColParts, static_cast<unsigned>(nb)),
                       dim3(256), 0, s, r, n_mem, part, g.grp);
-        civic::launch(col_inv_kernel, dim3(static_cast<unsigned>((n_mem + 255) / 256), static_cast<unsigned>(nb)), dim3(256), 0, s, part, n_mem, inv);
         civic::launch(transpose_pad_grouped_kernel, dim3(static_cast<unsigned>(longest_pad / 32), static_cast<unsigned>((n_mem + 31) / 32),
                                                         static_cast<unsigned>(nb)),
-                      dim3(256), 0, s, r, n_mem, inv, rt, g.grp);
+                      dim3(256), 0, s, r, n_mem, part, rt, g.grp);
         int rc = check_launch();
         if (rc != CIVIC_OK) return rc;
         g.a = rt; g.lda = 0; g.sa = 0; g.k = 0; g.kb_rows = 0;                // (per item, from the table)

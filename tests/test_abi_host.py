@@ -260,9 +260,9 @@ def test_argument_errors_precede_any_hip_call(bd):
     assert rcomp(ws=None, wsb=0) == bd.ERR_WORKSPACE and rcomp(wsb=16) == bd.ERR_WORKSPACE and rcomp(batch=0, off=None) == OK
     o3 = offs(0, 5, 12)
     need = L.civic_kv_compress_ragged_workspace_bytes(2, C.c_void_p(o3.ctypes.data), 8, 64)
-    # per item its column inverses (S floats), 32 rows of partial column sums and Rbar^T (S x its rows rounded up to 64, bf16)
+    # per item 32 rows of partial column sums and Rbar^T (S x its rows rounded up to 64, bf16)
     a256 = lambda x: (x + 255) // 256 * 256
-    assert need == a256(2 * 8 * 4) + a256(2 * 8 * 4 * 32) + a256(8 * (64 + 64) * 2)
+    assert need == a256(2 * 8 * 4 * 32) + a256(8 * (64 + 64) * 2)
     def rattn(off=offs(0, 5, 12), batch=2, q=F, k=F, o=F, hq=4, hkv=2, d=64, qs=st, ks=st):
         return L.civic_cross_attn_ragged(q, k, k, o, 1, batch, C.c_void_p(off.ctypes.data) if off is not None else None, 8, hq, hkv, d,
                                          qs, ks, st, C.c_float(0.0), None)
