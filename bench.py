@@ -510,7 +510,7 @@ def main() -> int:
         encoder = {"tokens": t_e, "anchors": m_e, "dim": d_v, "memory_anchors": s_mem,
                    "anchor_aggregate": {"us": round(t_agg, 2), "flops": f_agg, "tflops": round(f_agg / t_agg / 1e6, 1),
                                         "frac_mfma_peak": round(f_agg / t_agg / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4),
-                                        "workspace_bytes": ws_a.numel(), "launches": 6},
+                                        "workspace_bytes": ws_a.numel(), "launches": 4},
                    "kv_compress": {"us": round(t_cmp, 2), "flops": f_cmp, "tflops": round(f_cmp / t_cmp / 1e6, 1)},
                    "cross_attn": {"us": round(t_x, 2), "flops": f_x, "tflops": round(f_x / t_x / 1e6, 1)},
                    "uncompressed_attn_us": round(t_full, 2),
