@@ -298,3 +298,67 @@ def cross_attention_ragged(q: np.ndarray, k: np.ndarray, v: np.ndarray, row_offs
     assert k.shape[0] == off.size - 1
     return np.concatenate([cross_attention(q[None, a:b], k[i:i + 1], v[i:i + 1], scale)[0]
                            for i, (a, b) in enumerate(zip(off[:-1], off[1:]))])
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# The path for a batch whose samples differ in size and grid (images of different grid sizes in one batch): every
+# sample's rows are packed back to back along the token axis, and every sample is scored, selected, merged, attended
+# and cached by itself with the functions above (plain loops over the samples; the definitions are per sample).
+def ragged_offsets(seq_lens: Sequence[int], grids: Sequence[Sequence[int]]):
+    """Row offsets [batch + 1] of the packed tensors: (dense rows, visual tokens, kept tokens, compact rows) per sample,
+    where a sample's compact length is its length minus its visual tokens plus K of its grid (Eq. 13)."""
+    seq, vis, kept, comp = [0], [0], [0], [0]
+    for s, g in zip(seq_lens, grids):
+        nv = int(g[0]) * int(g[1]) * int(g[2])
+        k = kept_count(g)
+        assert s >= nv
+        seq.append(seq[-1] + int(s)); vis.append(vis[-1] + nv); kept.append(kept[-1] + k); comp.append(comp[-1] + int(s) - nv + k)
+    return tuple(np.asarray(x, dtype=np.int64) for x in (seq, vis, kept, comp))
+
+
+def select_ragged(scores: np.ndarray, grids: Sequence[Sequence[int]]) -> np.ndarray:
+    """scores fp32 [sum of N_v] packed sample by sample -> kept indices int32 [sum of K], each sample's own ascending
+    visual-local indices."""
+    out, at = [], 0
+    for g in grids:
+        nv = int(g[0]) * int(g[1]) * int(g[2])
+        out.append(select(scores[None, at:at + nv], g)[0][0])
+        at += nv
+    assert at == scores.shape[0]
+    return np.concatenate(out) if out else np.zeros(0, dtype=np.int32)
+
+
+def compact_ragged(hidden: np.ndarray, pos_ids: np.ndarray, seq_lens: Sequence[int], grids: Sequence[Sequence[int]],
+                   frame_starts: Sequence[np.ndarray], kept_idx: np.ndarray) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """hidden [total, dim], pos_ids int32 [3, total], kept_idx int32 [sum of K] (sample-local), frame_starts one array
+    of sample-local sequence indices per sample -> (hidden_c [sum of S_c, dim], pos_c [3, sum of S_c], src_idx
+    [sum of S_c], sample-local dense indices)."""
+    seq, _, kept, _ = ragged_offsets(seq_lens, grids)
+    assert seq[-1] == hidden.shape[0] == pos_ids.shape[1] and kept[-1] == kept_idx.shape[0]
+    hc, pc, si = [], [], []
+    for b, g in enumerate(grids):
+        a, e = seq[b], seq[b + 1]
+        h1, p1, s1 = compact(hidden[None, a:e], pos_ids[:, None, a:e], g, frame_starts[b], kept_idx[None, kept[b]:kept[b + 1]])
+        hc.append(h1[0]); pc.append(p1[:, 0]); si.append(s1[0])
+    return np.concatenate(hc), np.concatenate(pc, axis=1), np.concatenate(si)
+
+
+def attention_ragged(q: np.ndarray, k: np.ndarray, v: np.ndarray, row_offsets, causal: bool,
+                     scale: Optional[float] = None) -> np.ndarray:
+    """q fp32 [total, H_q, d], k, v fp32 [total, H_kv, d], sample b owning rows [row_offsets[b], row_offsets[b+1]):
+    every sample attends to its own keys only, the causal mask counts from the sample's first row -> float64
+    [total, H_q, d]."""
+    off = _check_offsets(row_offsets, q.shape[0])
+    assert k.shape[0] == q.shape[0] == v.shape[0]
+    return np.concatenate([attention(np.ascontiguousarray(q[None, a:b]), np.ascontiguousarray(k[None, a:b]),
+                                     np.ascontiguousarray(v[None, a:b]), causal, scale)[0]
+                           for a, b in zip(off[:-1], off[1:])])
+
+
+def kv_write_ragged(k: np.ndarray, v: np.ndarray, row_offsets, k_cache: np.ndarray, v_cache: np.ndarray, pos0: int = 0) -> int:
+    """k, v [total, H_kv, d] packed as above: sample b's rows go to rows [pos0, pos0 + its length) of
+    k_cache[b], v_cache[b] ([batch, H_kv, s_max, d], modified in place).  Returns the bytes written."""
+    off = _check_offsets(row_offsets, k.shape[0])
+    assert k_cache.shape[0] == off.size - 1
+    return sum(kv_write(np.ascontiguousarray(k[None, a:b]), np.ascontiguousarray(v[None, a:b]), k_cache[i:i + 1], v_cache[i:i + 1], pos0)
+               for i, (a, b) in enumerate(zip(off[:-1], off[1:])))
