@@ -467,6 +467,41 @@ def main() -> int:
                 "mrope_apply_q": {"us": round(t_apply, 2), "bytes": q_bytes, "gbs": round(q_bytes / t_apply / 1e3, 1),
                                   "frac_hbm_peak": round(q_bytes / t_apply / 1e3 / HBM_PEAK_GBS, 4)}}
 
+    # The path on a ragged batch (images of different grid sizes in one batch, packed along the token axis), on the
+    # 8b-shaped workload's widths: eight samples from one 16 x 16 image to two 32 x 32 images.  The front runs its three
+    # kernels sample by sample; the attention (with the KV write) is one launch, timed against one call per sample.
+    ragged = None
+    if not args.path_only and w.name == "8b":
+        from paper_2605_28115_amd import workloads as wl_
+        rgrids = [(1, 16, 16, 4, 4, 1, 0, 85), (1, 32, 32, 4, 4, 1, 0, 341), (2, 32, 32, 4, 4, 1, 0, 682), (1, 24, 24, 4, 4, 1, 0, 192),
+                  (1, 32, 32, 4, 4, 1, 0, 341), (2, 24, 24, 4, 4, 1, 0, 384), (1, 16, 16, 4, 4, 1, 0, 85), (2, 32, 32, 4, 4, 1, 0, 682)]
+        text = [32, 128, 256, 64, 96, 128, 16, 200]
+        rstarts, rlens = [], []
+        for g_, t_ in zip(rgrids, text):
+            hw_ = g_[1] * g_[2]
+            rstarts.append([t_ // 2 + f_ * hw_ for f_ in range(g_[0])]); rlens.append(t_ + g_[0] * hw_)
+        rseq, rvis, rkept, rcomp = bd.civic_ragged_offsets(rlens, rgrids)
+        rh = torch.randn((int(rseq[-1]), w.dim), device="cuda").to(sets[0].hidden.dtype)
+        rp = torch.randint(0, 4096, (3, int(rseq[-1])), dtype=torch.int32, device="cuda")
+        t_front = alone(lambda s_: bd.civic_compact_prefill_ragged(rh, rp, rlens, rgrids, rstarts, sets[0].anchor_q, 1.0), cost=3 * len(rgrids))
+        tc = int(rcomp[-1])
+        rq = torch.randn((tc, w.n_q_heads, w.head_dim), device="cuda").to(rh.dtype)
+        rk = torch.randn((tc, w.n_kv_heads, w.head_dim), device="cuda").to(rh.dtype); rv = torch.randn_like(rk)
+        ro = torch.empty_like(rq)
+        smax_r = int(max(np.diff(rcomp)))
+        rkc = torch.empty((len(rgrids), w.n_kv_heads, smax_r, w.head_dim), dtype=rh.dtype, device="cuda"); rvc = torch.empty_like(rkc)
+        t_rattn = alone(lambda s_: bd.civic_prefill_attn_ragged(rq, rk, rv, rcomp, True, 0.0, rkc, rvc, 0, out=ro))
+        def attn_per_sample(s_):
+            for i_ in range(len(rgrids)):
+                a_, b_ = int(rcomp[i_]), int(rcomp[i_ + 1])
+                bd.civic_prefill_attn_kv(rq[a_:b_][None], rk[a_:b_][None], rv[a_:b_][None], rkc[i_:i_ + 1], rvc[i_:i_ + 1], 0, True, 0.0, out=ro[a_:b_][None])
+        t_rattn_items = alone(attn_per_sample, cost=len(rgrids))
+        f_r = sum(4.0 * w.n_q_heads * w.head_dim * (n_ * (n_ + 1) / 2) for n_ in np.diff(rcomp))
+        ragged = {"samples": len(rgrids), "dense_rows": int(rseq[-1]), "compact_rows": tc,
+                  "compact_prefill_ragged_us": round(t_front, 2), "launches_front": 3 * len(rgrids),
+                  "prefill_attn_ragged": {"us": round(t_rattn, 2), "us_one_call_per_sample": round(t_rattn_items, 2), "flops": f_r,
+                                          "tflops": round(f_r / t_rattn / 1e6, 1)}}
+
     # Encoder-side compaction (the paper's own soft route), timed on the encoder-shaped workload: Eq. 8 from the
     # dense patch grid to K anchors, and Eq. 9 (KV compression to S memory anchors + attention over them).
     encoder = None
@@ -528,6 +563,8 @@ def main() -> int:
         result["decode"] = decode
     if rope is not None:
         result["rope"] = rope
+    if ragged is not None:
+        result["ragged"] = ragged
     if encoder is not None:
         result["encoder"] = encoder
     if not args.no_cpu:

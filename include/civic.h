@@ -191,6 +191,38 @@ int civic_compact_prefill(const void* hidden, int dtype, int32_t batch, int64_t 
                           float* scores, int32_t* kept_idx, void* hidden_c, int32_t* pos_c,
                           int32_t* src_idx, void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same path for a batch whose samples differ in length and grid (images of different grid sizes in one
+ * batch; the rectangular civic_grid covers one shape per call): the samples' rows are packed back to back along
+ * the token axis and every sample is scored, selected and merged by itself, with its own grid, floors and
+ * budget (Eq. 13 per sample; results equal the rectangular calls on that sample alone, bit for bit).
+ *
+ * civic_ragged_offsets (host only) turns the samples' lengths and grids into the row offsets of the packed
+ * tensors, [batch + 1] int64 each (any of the three outputs may be NULL):
+ *   seq_offsets      host [batch + 1], seq_offsets[0] = 0: sample b owns dense rows [seq_offsets[b], seq_offsets[b+1])
+ *   grids            host [batch] civic_grid, one per sample
+ *   visual_offsets   N_v of the samples before b;  kept_offsets  K of the samples before b (civic_kept_count);
+ *   compact_offsets  compact rows before b, a sample's count being its length - N_v + K
+ * CIVIC_ERR_INVALID_ARG on a bad grid or a sample shorter than its visual tokens.
+ *
+ * civic_compact_prefill_ragged: civic_score_visual, civic_select and civic_compact sample by sample (three launches
+ * per sample on `stream`), every check of every sample before the first launch.
+ *   hidden      device [seq_offsets[batch], dim];  pos_ids  device [3, seq_offsets[batch]] int32
+ *   frame_start host, the samples' frame starts one after the other (grids[b].frames entries each), each
+ *               counted from its sample's first row
+ *   scores      device [visual_offsets[batch]] fp32 (output);  kept_idx  device [kept_offsets[batch]] int32 (output,
+ *               every sample's own ascending visual-local indices)
+ *   hidden_c    device [compact_offsets[batch], dim];  pos_c  device [3, compact_offsets[batch]] int32
+ *   src_idx     device [compact_offsets[batch]] int32, counted from the sample's first row
+ * dim * sizeof(element) must be a multiple of 16 (every sample's first row is then aligned like the tensor). */
+int civic_ragged_offsets(int32_t batch, const int64_t* seq_offsets /* host */, const civic_grid* grids /* host */,
+                         int64_t* visual_offsets /* host */, int64_t* kept_offsets /* host */,
+                         int64_t* compact_offsets /* host */);
+int civic_compact_prefill_ragged(const void* hidden, int dtype, int32_t batch, const int64_t* seq_offsets /* host */,
+                                 int32_t dim, const int32_t* pos_ids, const civic_grid* grids /* host */,
+                                 const int64_t* frame_start /* host */, const float* anchor_q, float inv_tau,
+                                 float* scores, int32_t* kept_idx, void* hidden_c, int32_t* pos_c, int32_t* src_idx,
+                                 void* stream);
+
 /* Prefill attention over the compact sequence: out[b,i,h,:] = sum_j softmax_j(scale *
  * <q[b,i,h,:], k[b,j,g,:]>) v[b,j,g,:] with g = h / (n_q_heads / n_kv_heads); j <= i when
  * causal (order of the compact sequence, not the position ids), every j otherwise.
@@ -239,6 +271,24 @@ int civic_prefill_attn_kv(const void* q, const void* k, const void* v, void* out
                           const int64_t* o_strides /* host [3] */,
                           int64_t s_max, int64_t pos0, int32_t causal, float softmax_scale,
                           void* stream);
+
+/* civic_prefill_attn (and civic_prefill_attn_kv when the caches are given) for packed samples of different lengths:
+ * sample b owns rows [row_offsets[b], row_offsets[b+1]) of q, k, v and out (civic_ragged_offsets' compact offsets);
+ * it attends to its own keys only, the causal mask counts from its first row, and its K and V rows go to rows
+ * [pos0, pos0 + its length) of k_cache[b], v_cache[b].  ONE launch per group of up to 64 samples (the workgroups
+ * look their sample's rows up in a table passed with the launch); fp32 or head_dim > 128: one launch per sample.
+ * Results equal the rectangular calls on each sample alone, bit for bit.
+ *   q, out       device [total_rows, n_q_heads, head_dim], element strides (unused, token, head)
+ *   k, v         device [total_rows, n_kv_heads, head_dim], element strides (unused, token, head)
+ *   row_offsets  host [batch + 1] int64, row_offsets[0] = 0, strictly increasing; row_offsets[batch] <= INT32_MAX
+ *   k_cache, v_cache  device [batch, n_kv_heads, s_max, head_dim] dense, or both NULL; pos0 + longest sample <= s_max
+ * Everything else as civic_prefill_attn; every group is checked before the first launch. */
+int civic_prefill_attn_ragged(const void* q, const void* k, const void* v, void* out, int dtype, int32_t batch,
+                              const int64_t* row_offsets /* host */, int32_t n_q_heads, int32_t n_kv_heads,
+                              int32_t head_dim, const int64_t* q_strides /* host [3] */,
+                              const int64_t* kv_strides /* host [3] */, const int64_t* o_strides /* host [3] */,
+                              int32_t causal, float softmax_scale, void* k_cache, void* v_cache, int64_t s_max,
+                              int64_t pos0, void* stream);
 
 /* Rotary position embedding from the carried position ids.  The compact merge copies the three ids of every
  * token unchanged ("text positions are preserved, compact visual positions are inherited", sentence after

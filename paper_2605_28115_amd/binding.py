@@ -27,7 +27,8 @@ EXPORTS = ("civic_last_hip_error", "civic_time_next_kernel", "civic_kept_count",
            "civic_mrope_table", "civic_mrope_apply", "civic_kv_write_rope", "civic_prefill_attn_rope",
            "civic_anchor_aggregate_workspace_bytes", "civic_anchor_aggregate", "civic_kv_compress_workspace_bytes",
            "civic_kv_compress", "civic_cross_attn", "civic_kv_compress_ragged_workspace_bytes",
-           "civic_kv_compress_ragged", "civic_cross_attn_ragged")
+           "civic_kv_compress_ragged", "civic_cross_attn_ragged", "civic_ragged_offsets", "civic_compact_prefill_ragged",
+           "civic_prefill_attn_ragged")
 
 
 class CivicError(RuntimeError):
@@ -56,6 +57,13 @@ _P = C.c_void_p
 lib.civic_last_hip_error.restype = C.c_int
 lib.civic_time_next_kernel.restype = C.c_int
 lib.civic_time_next_kernel.argtypes = [_P, _P]
+lib.civic_ragged_offsets.restype = C.c_int
+lib.civic_ragged_offsets.argtypes = [C.c_int32, _P, C.POINTER(Grid), _P, _P, _P]
+lib.civic_compact_prefill_ragged.restype = C.c_int
+lib.civic_compact_prefill_ragged.argtypes = [_P, C.c_int, C.c_int32, _P, C.c_int32, _P, C.POINTER(Grid), _P, _P, C.c_float, _P, _P, _P, _P, _P, _P]
+lib.civic_prefill_attn_ragged.restype = C.c_int
+lib.civic_prefill_attn_ragged.argtypes = [_P, _P, _P, _P, C.c_int, C.c_int32, _P, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int64),
+                                          C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.c_int32, C.c_float, _P, _P, C.c_int64, C.c_int64, _P]
 lib.civic_kept_count.restype = C.c_int64
 lib.civic_kept_count.argtypes = [C.POINTER(Grid)]
 lib.civic_select_workspace_bytes.restype = C.c_size_t
@@ -306,6 +314,71 @@ def civic_compact_prefill(hidden: torch.Tensor, pos_ids: torch.Tensor, grid, fra
         _dev(anchor_q), float(inv_tau), _dev(scores), _dev(kept_idx), _dev(hidden_c), _dev(pos_c), _dev(src_idx),
         None, 0, _stream(stream)))
     return scores, kept_idx, hidden_c, pos_c, src_idx
+
+
+def civic_ragged_offsets(seq_lens: Sequence[int], grids):
+    """Row offsets of the packed tensors of a ragged batch -> (seq, visual, kept, compact), int64 [batch + 1] each."""
+    gs = (Grid * len(grids))(*[make_grid(g) for g in grids])
+    seq = np.concatenate([[0], np.cumsum(np.asarray(seq_lens, dtype=np.int64))]).astype(np.int64)
+    vis, kept, comp = (np.zeros(len(grids) + 1, dtype=np.int64) for _ in range(3))
+    _check("civic_ragged_offsets", lib.civic_ragged_offsets(len(grids), C.c_void_p(seq.ctypes.data), gs, C.c_void_p(vis.ctypes.data),
+                                                            C.c_void_p(kept.ctypes.data), C.c_void_p(comp.ctypes.data)))
+    return seq, vis, kept, comp
+
+
+def civic_compact_prefill_ragged(hidden: torch.Tensor, pos_ids: torch.Tensor, seq_lens: Sequence[int], grids,
+                                 frame_starts: Sequence[Sequence[int]], anchor_q: torch.Tensor, inv_tau: float = 1.0, stream=None):
+    """Samples of different length and grid packed along the token axis: hidden [total, dim], pos_ids int32 [3, total],
+    one grid and one list of (sample-local) frame starts per sample -> (scores, kept_idx, hidden_c, pos_c, src_idx), packed."""
+    if hidden.dim() != 2 or not hidden.is_contiguous() or not pos_ids.is_contiguous() or pos_ids.dtype != torch.int32:
+        raise ValueError("hidden [total, dim] and pos_ids int32 [3, total] must be contiguous")
+    seq, vis, kept, comp = civic_ragged_offsets(seq_lens, grids)
+    total, dim = hidden.shape
+    if seq[-1] != total or tuple(pos_ids.shape) != (3, total) or len(frame_starts) != len(grids):
+        raise ValueError("the samples' lengths must add up to the packed rows, with one frame-start list per sample")
+    gs = (Grid * len(grids))(*[make_grid(g) for g in grids])
+    for g, f in zip(gs, frame_starts):
+        if len(f) != g.frames:
+            raise ValueError("frame_starts must have one entry per frame of its sample")
+    fs = np.ascontiguousarray(np.concatenate([np.asarray(f, dtype=np.int64) for f in frame_starts]) if len(grids) else np.zeros(0, np.int64))
+    dev = hidden.device
+    scores = torch.empty(int(vis[-1]), dtype=torch.float32, device=dev)
+    kept_idx = torch.empty(int(kept[-1]), dtype=torch.int32, device=dev)
+    hidden_c = torch.empty((int(comp[-1]), dim), dtype=hidden.dtype, device=dev)
+    pos_c = torch.empty((3, int(comp[-1])), dtype=torch.int32, device=dev)
+    src_idx = torch.empty(int(comp[-1]), dtype=torch.int32, device=dev)
+    _check("civic_compact_prefill_ragged", lib.civic_compact_prefill_ragged(
+        _dev(hidden), _dtype_code(hidden), len(grids), C.c_void_p(seq.ctypes.data), dim, _dev(pos_ids), gs, C.c_void_p(fs.ctypes.data),
+        _dev(anchor_q), float(inv_tau), _dev(scores), _dev(kept_idx), _dev(hidden_c), _dev(pos_c), _dev(src_idx), _stream(stream)))
+    return scores, kept_idx, hidden_c, pos_c, src_idx
+
+
+def civic_prefill_attn_ragged(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, row_offsets: Sequence[int], causal: bool = True,
+                              softmax_scale: float = 0.0, k_cache: Optional[torch.Tensor] = None,
+                              v_cache: Optional[torch.Tensor] = None, pos0: int = 0, out: Optional[torch.Tensor] = None,
+                              stream=None) -> torch.Tensor:
+    """q [total, H_q, d], k and v [total, H_kv, d] packed (sample b owning rows [row_offsets[b], row_offsets[b+1])); with
+    caches [batch, H_kv, s_max, d] every sample's K and V rows are written to its own cache rows from pos0."""
+    if k.shape != v.shape or k.stride() != v.stride() or q.dtype != k.dtype or q.dim() != 3 or k.dim() != 3 or q.stride(2) != 1 or k.stride(2) != 1:
+        raise ValueError("q [total, H_q, d]; k and v [total, H_kv, d] of one shape, strides and dtype")
+    off = np.ascontiguousarray(np.asarray(row_offsets, dtype=np.int64))
+    batch = off.size - 1
+    total, hq, d = q.shape
+    if out is None:
+        out = torch.empty((total, hq, d), dtype=q.dtype, device=q.device)
+    s_max = 0
+    if k_cache is not None:
+        if v_cache is None or k_cache.shape != v_cache.shape or not k_cache.is_contiguous() or not v_cache.is_contiguous() or \
+                tuple(k_cache.shape[:2]) != (batch, k.shape[1]) or k_cache.shape[3] != d:
+            raise ValueError("k_cache and v_cache must be contiguous [batch, H_kv, s_max, d]")
+        s_max = k_cache.shape[2]
+    qs = (C.c_int64 * 3)(0, q.stride(0), q.stride(1))
+    ks = (C.c_int64 * 3)(0, k.stride(0), k.stride(1))
+    os_ = (C.c_int64 * 3)(0, out.stride(0), out.stride(1))
+    _check("civic_prefill_attn_ragged", lib.civic_prefill_attn_ragged(
+        _dev(q), _dev(k), _dev(v), _dev(out), _dtype_code(q), batch, C.c_void_p(off.ctypes.data), hq, k.shape[1], d, qs, ks, os_,
+        int(bool(causal)), float(softmax_scale), _dev(k_cache), _dev(v_cache), s_max, int(pos0), _stream(stream)))
+    return out
 
 
 def civic_prefill_attn(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, causal: bool = True,

@@ -73,6 +73,7 @@ struct AttnArgs {
     // ragged queries (civic_cross_attn_ragged; read by the RAGGED instantiations only): `batch` items packed along the
     // token axis, item b owning query and output rows [item_row[b], item_row[b + 1]); `seq` is the longest item
     int32_t item_row[kRaggedItems + 1];
+    int32_t kv_packed;                    // ragged: keys and values are packed along the token axis like the queries
 };
 
 // ------------------------------------------------------------------------------------ fp32 ALU path
@@ -350,16 +351,20 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
     // Query rows of this sample and where they start.  Ragged launches (no mask, one row tile per workgroup): item b's
     // rows come from the table in the arguments, and a workgroup whose row tile lies past its item's end has nothing
     // to do (the grid covers the longest item); it leaves before any load or barrier.
-    int seq_item = a.seq;
-    int64_t q_first = b * a.qs[0], o_first = b * a.os[0];
+    int seq_item = a.seq, kv_seq_item = a.kv_seq;
+    int64_t q_first = b * a.qs[0], o_first = b * a.os[0], kv_first = b * a.ks[0];
     if constexpr (RAGGED) {
         const int32_t first = a.item_row[b];
         seq_item = a.item_row[b + 1] - first;
         q_first = static_cast<int64_t>(first) * a.qs[1];
         o_first = static_cast<int64_t>(first) * a.os[1];
+        if (a.kv_packed) {                                    // keys and values packed like the queries (self-attention)
+            kv_seq_item = seq_item;
+            kv_first = static_cast<int64_t>(first) * a.ks[1];
+        }
         if (rt * RB * 32 >= seq_item) return;
     }
-    const int seq = seq_item;
+    const int seq = seq_item, kv_seq = kv_seq_item;
     const float sl2 = a.scale * 1.4426950408889634f;          // scale * log2(e)
 
     // geometry of the row tile being computed
@@ -369,12 +374,12 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
         row0 = block_row0 + wrow;                             // this wavefront's first query row
         block_rows_end = min(block_row0 + RB * 32, seq);
         qi = row0 + col;                                      // this lane's query row
-        const int kv_end = a.causal ? block_rows_end : a.kv_seq; // keys [0, kv_end) are visible to the block
+        const int kv_end = a.causal ? block_rows_end : kv_seq; // keys [0, kv_end) are visible to the block
         n_tiles = (kv_end + kBN - 1) / kBN;
     };
     set_rows(rt);
-    const __bf16* kp = static_cast<const __bf16*>(a.k) + b * a.ks[0] + g * a.ks[2];
-    const __bf16* vp = static_cast<const __bf16*>(a.v) + b * a.ks[0] + g * a.ks[2];
+    const __bf16* kp = static_cast<const __bf16*>(a.k) + kv_first + g * a.ks[2];
+    const __bf16* vp = static_cast<const __bf16*>(a.v) + kv_first + g * a.ks[2];
     const uint32_t row_bytes = static_cast<uint32_t>(a.ks[1]) * 2u;   // K/V token stride
 
     // Q first: its loads are the longest wait of the prologue, everything else is set up in their shadow.
@@ -427,7 +432,7 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
     // stored).  The tile's first key enters through the scalar base, so the per-lane offsets are loop
     // invariant; only the tile that holds the end of the sequence needs the clamped set.
     uint32_t ld_voff[NI], ld_voff_tail[NI];
-    const int tail_tile = (a.kv_seq - 1) / kBN;               // the tile that may run past the keys
+    const int tail_tile = (kv_seq - 1) / kBN;               // the tile that may run past the keys
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
         const int slot = (w * NI + j) * kWave + lane;
@@ -435,7 +440,7 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
         const int c = (slot % PITCH) ^ swz<PITCH>(row);
         const uint32_t cb = (c * 8 < a.head_dim) ? c * 16 : 0;
         ld_voff[j] = row * row_bytes + cb;
-        ld_voff_tail[j] = (min(tail_tile * kBN + row, a.kv_seq - 1) - tail_tile * kBN) * row_bytes + cb;
+        ld_voff_tail[j] = (min(tail_tile * kBN + row, kv_seq - 1) - tail_tile * kBN) * row_bytes + cb;
     }
     const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(
         static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds)) + w * NI * kWave * 16);
@@ -562,11 +567,11 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
         }
 
         // mask only where the tile crosses the diagonal or the end of the sequence (wave-uniform)
-        if ((a.causal && key0 + kBN - 1 > row0) || key0 + kBN > a.kv_seq) {
+        if ((a.causal && key0 + kBN - 1 > row0) || key0 + kBN > kv_seq) {
             // The lane sees the tile's keys below `lim` (end of the sequence, and its own row under the causal
             // mask).  Register r of sub-tile t holds tile key 32 t + 8 (r / 4) + r % 4 + 4 half, so one
             // per-lane threshold against a constant per register decides: a compare and a select each.
-            int lim = a.kv_seq - key0;
+            int lim = kv_seq - key0;
             if (a.causal) lim = min(lim, qi - key0 + 1);
             const int thr = lim - 4 * half;
 #pragma unroll
@@ -780,7 +785,7 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
         // only: half the MFMAs and exponentials of that tile for half of the wavefronts, which the other
         // wavefront of the SIMD turns into time.  The same holds for a last tile whose second half lies past
         // the end of the sequence.
-        if ((a.causal && kt * kBN + 32 > row0 + 31) || kt * kBN + 32 >= a.kv_seq) tile(kt, stage_c, std::integral_constant<int, 1>{});
+        if ((a.causal && kt * kBN + 32 > row0 + 31) || kt * kBN + 32 >= kv_seq) tile(kt, stage_c, std::integral_constant<int, 1>{});
         else tile(kt, stage_c, std::integral_constant<int, 2>{});
     };
     // an inner tile: whole, visible to every row of the workgroup, not the first
@@ -807,7 +812,7 @@ __global__ __launch_bounds__(WAVES * kWave, 2) void attn_mfma_kernel(AttnArgs a)
 
         // Tile 0, then the inner tiles in a loop of their own (one code path, so the accumulators keep their
         // registers across it), then whatever is left: the diagonal, the end of the sequence.
-        const int inner_end = min(a.causal ? (block_row0 + 1) / kBN : a.kv_seq / kBN, n_tiles);
+        const int inner_end = min(a.causal ? (block_row0 + 1) / kBN : kv_seq / kBN, n_tiles);
         step(0, std::integral_constant<int, 0>{});
         int kt = 1;
         for (; kt + 1 < inner_end; kt += kStages) {
@@ -1012,7 +1017,7 @@ static int launch_mfma(AttnArgs& a, hipStream_t s)
     auto magic = [](int64_t d) { return d <= 1 ? 0u : static_cast<uint32_t>(((int64_t{1} << 32) + d - 1) / d); };
     a.magic_head_blocks = magic(a.head_blocks);
     a.magic_kv_heads = magic(a.n_kv_heads);
-    a.paired = choose_paired(a, per_rt, 32 * (WAVES / a.heads_per_block)) ? 1 : 0;
+    a.paired = !RAGGED && choose_paired(a, per_rt, 32 * (WAVES / a.heads_per_block)) ? 1 : 0;   // (pairs assume one length)
     const unsigned grid_y = static_cast<unsigned>(a.paired ? (a.row_tiles + 1) / 2 : a.row_tiles);
     constexpr size_t lds = T::LDS_BYTES;
     if (lds > 64 * 1024) {
@@ -1044,12 +1049,14 @@ namespace civic {
 // MFMA path runs, as a second launch otherwise).
 // item_row (host, batch + 1 ascending row numbers, or null): the queries and outputs of the `batch` items are packed
 // along the token axis, item b owning rows [item_row[b], item_row[b + 1]) of q and out, and `seq` is the longest item;
-// at most kRaggedItems items, no mask, no caches, no rotary table.  dry_run: every check and nothing launched.
+// at most kRaggedItems items, no rotary table.  kv_packed: k and v are packed the same way (self-attention of every
+// item over its own rows, `kv_seq` = `seq`; the mask and the caches are allowed); otherwise they are [batch, kv_seq]
+// and there is neither.  dry_run: every check and nothing launched.
 static int prefill_attn(const void* q, const void* k, const void* v, void* out, int dtype, int32_t batch, int32_t seq,
                         int32_t kv_seq, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, const int64_t* q_strides,
                         const int64_t* kv_strides, const int64_t* o_strides, int32_t causal, float softmax_scale,
                         void* k_cache, void* v_cache, int64_t s_max, int64_t pos0, const float* q_cos_sin, void* stream,
-                        const int32_t* item_row = nullptr, bool dry_run = false)
+                        const int32_t* item_row = nullptr, bool dry_run = false, bool kv_packed = false)
 {
     const int esz = dtype_size(dtype);
     if (!esz || !q_strides || !kv_strides || !o_strides) return CIVIC_ERR_INVALID_ARG;
@@ -1072,7 +1079,8 @@ static int prefill_attn(const void* q, const void* k, const void* v, void* out, 
     }
     if (q_cos_sin && (!aligned16(q_cos_sin) || head_dim % 4)) return CIVIC_ERR_INVALID_ARG;
     if (head_dim > CIVIC_MAX_HEAD_DIM || batch > 65535 || n_q_heads > 65535) return CIVIC_ERR_UNSUPPORTED;
-    if (item_row && (batch > kRaggedItems || causal || k_cache || q_cos_sin)) return CIVIC_ERR_INVALID_ARG;
+    if (item_row && (batch > kRaggedItems || q_cos_sin || (!kv_packed && (causal || k_cache)))) return CIVIC_ERR_INVALID_ARG;
+    if (kv_packed && (!item_row || kv_seq != seq)) return CIVIC_ERR_INVALID_ARG;
     if (batch == 0 || seq == 0) return CIVIC_OK;
 
     AttnArgs a;
@@ -1086,6 +1094,7 @@ static int prefill_attn(const void* q, const void* k, const void* v, void* out, 
     a.k_cache = k_cache; a.v_cache = v_cache; a.s_max = s_max; a.pos0 = pos0;
     a.q_cs = reinterpret_cast<const float2*>(q_cos_sin);
     for (int i = 0; i <= kRaggedItems; ++i) a.item_row[i] = item_row && i <= batch ? item_row[i] : 0;
+    a.kv_packed = kv_packed ? 1 : 0;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
     // the MFMA path addresses a K/V tile, and a head's Q rows, with 32-bit per-lane byte offsets, and its grid
@@ -1112,8 +1121,15 @@ static int prefill_attn(const void* q, const void* k, const void* v, void* out, 
             ai.batch = 1; ai.seq = item_row[it + 1] - item_row[it];
             ai.q = static_cast<const char*>(q) + static_cast<int64_t>(item_row[it]) * q_strides[1] * esz;
             ai.out = static_cast<char*>(out) + static_cast<int64_t>(item_row[it]) * o_strides[1] * esz;
-            ai.k = static_cast<const char*>(k) + static_cast<int64_t>(it) * kv_strides[0] * esz;
-            ai.v = static_cast<const char*>(v) + static_cast<int64_t>(it) * kv_strides[0] * esz;
+            const int64_t kv_at = kv_packed ? static_cast<int64_t>(item_row[it]) * kv_strides[1] : static_cast<int64_t>(it) * kv_strides[0];
+            ai.k = static_cast<const char*>(k) + kv_at * esz;
+            ai.v = static_cast<const char*>(v) + kv_at * esz;
+            if (kv_packed) ai.kv_seq = ai.seq;
+            if (k_cache) {
+                const int64_t cache_at = static_cast<int64_t>(it) * n_kv_heads * s_max * head_dim * esz;
+                ai.k_cache = static_cast<char*>(k_cache) + cache_at;
+                ai.v_cache = static_cast<char*>(v_cache) + cache_at;
+            }
         }
         const dim3 grid(static_cast<unsigned>((ai.seq + 3) / 4), static_cast<unsigned>(n_q_heads), static_cast<unsigned>(ai.batch));
         if (dtype == CIVIC_BF16) civic::launch((attn_plain_kernel<true>), grid, dim3(256), 0, s, ai);
@@ -1195,3 +1211,37 @@ extern "C" int civic_cross_attn_ragged(const void* q, const void* k, const void*
     return CIVIC_OK;
 }
 
+
+extern "C" int civic_prefill_attn_ragged(const void* q, const void* k, const void* v, void* out, int dtype, int32_t batch,
+                                         const int64_t* row_offsets, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                         const int64_t* q_strides, const int64_t* kv_strides, const int64_t* o_strides,
+                                         int32_t causal, float softmax_scale, void* k_cache, void* v_cache, int64_t s_max,
+                                         int64_t pos0, void* stream)
+{
+    const int esz = civic::dtype_size(dtype);
+    if (!esz || batch < 0 || !q_strides || !kv_strides || !o_strides) return CIVIC_ERR_INVALID_ARG;
+    if ((k_cache == nullptr) != (v_cache == nullptr)) return CIVIC_ERR_INVALID_ARG;
+    if (batch == 0) return CIVIC_OK;
+    if (!row_offsets || row_offsets[0] != 0 || !q || !k || !v || !out) return CIVIC_ERR_INVALID_ARG;
+    for (int32_t b = 0; b < batch; ++b)
+        if (row_offsets[b + 1] <= row_offsets[b] || row_offsets[b + 1] - row_offsets[b] > INT32_MAX) return CIVIC_ERR_INVALID_ARG;
+    if (row_offsets[batch] > INT32_MAX) return CIVIC_ERR_UNSUPPORTED;
+    // Groups of up to kRaggedItems samples, ONE launch each: attention of every sample over its own rows (the mask counts
+    // from the sample's first row) and, with caches, the write of its K and V rows into its own cache rows.  Every
+    // group is checked before the first one is launched.
+    for (int pass = 0; pass < 2; ++pass)
+        for (int32_t b0 = 0; b0 < batch; b0 += civic::kRaggedItems) {
+            const int32_t nb = batch - b0 < civic::kRaggedItems ? batch - b0 : civic::kRaggedItems;
+            int32_t rows[civic::kRaggedItems + 1], longest = 0;
+            for (int32_t i = 0; i <= nb; ++i) rows[i] = static_cast<int32_t>(row_offsets[b0 + i]);
+            for (int32_t i = 0; i < nb; ++i) longest = rows[i + 1] - rows[i] > longest ? rows[i + 1] - rows[i] : longest;
+            const int64_t cache_at = static_cast<int64_t>(b0) * n_kv_heads * s_max * head_dim * esz;
+            const int rc = civic::prefill_attn(q, k, v, out, dtype, nb, longest, longest, n_q_heads, n_kv_heads, head_dim, q_strides,
+                                               kv_strides, o_strides, causal, softmax_scale,
+                                               k_cache ? static_cast<char*>(k_cache) + cache_at : nullptr,
+                                               v_cache ? static_cast<char*>(v_cache) + cache_at : nullptr, s_max, pos0, nullptr, stream,
+                                               rows, pass == 0, true);
+            if (rc != CIVIC_OK) return rc;
+        }
+    return CIVIC_OK;
+}

@@ -76,6 +76,12 @@ int compact_check(const void* hidden, int dtype, int32_t dim, const int32_t* pos
                   const civic_grid* grid, const int64_t* frame_start, const int32_t* kept_idx, int64_t n_kept,
                   const void* hidden_c, const int32_t* pos_c, const int32_t* src_idx);
 
+// The launch of civic_compact for arguments that compact_check has passed; pos_axis_in / pos_axis_out are the element
+// distances between the three id axes of pos_ids and of pos_c.
+int compact_launch(const void* hidden, int dtype, int32_t dim, const int32_t* pos_ids, int32_t batch, int64_t seq_len,
+                   const civic_grid* grid, const int64_t* frame_start, const int32_t* kept_idx, int64_t n_kept, void* hidden_c,
+                   int32_t* pos_c, int32_t* src_idx, int64_t pos_axis_in, int64_t pos_axis_out, void* stream);
+
 constexpr int kWave = 64;
 
 // Native vector types (the nontemporal load builtin does not take HIP's struct vectors).

@@ -38,12 +38,14 @@ struct FrameTable {
 // but a sample's last) copies them without a per-row or per-column condition.  U == 0: no such promise.
 // LONG: the kept list is searched in two round trips instead of read whole (the launch guarantees
 // that the probes' stretches and a block's window of entries each fit one batch of 4 per thread).
+// pos_axis_in / pos_axis_out: elements between the three id axes of pos_ids and of pos_c (batch * seq_len and
+// batch * seq_c for the rectangular tensors; the packed totals when the samples of a ragged batch are merged one by one).
 template <typename V, int U, bool LONG>
 __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
     const uint8_t* __restrict__ hidden, int64_t row_bytes, const int32_t* __restrict__ pos_ids, int32_t batch,
     int32_t seq_len, FrameTable ft, const int32_t* __restrict__ kept_idx, int32_t n_kept, int32_t seq_c,
     int32_t rows_per_block, int32_t threads_per_row, uint8_t* __restrict__ hidden_c, int32_t* __restrict__ pos_c,
-    int32_t* __restrict__ src_idx)
+    int32_t* __restrict__ src_idx, int64_t pos_axis_in, int64_t pos_axis_out)
 {
     __shared__ int32_t kb[CIVIC_MAX_FRAMES + 1];
     __shared__ int32_t row_src[kCompactMaxRows];
@@ -185,8 +187,8 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
         src_idx[o] = src;
 #pragma unroll
         for (int a = 0; a < 3; ++a)
-            pos_c[(static_cast<int64_t>(a) * batch + b) * seq_c + j0 + r] =
-                pos_ids[(static_cast<int64_t>(a) * batch + b) * seq_len + src];
+            pos_c[a * pos_axis_out + static_cast<int64_t>(b) * seq_c + j0 + r] =
+                pos_ids[a * pos_axis_in + static_cast<int64_t>(b) * seq_len + src];
     }
 
     const int32_t vpr = static_cast<int32_t>(row_bytes / sizeof(V));    // vectors per row
@@ -292,16 +294,13 @@ int compact_check(const void* hidden, int dtype, int32_t dim, const int32_t* pos
 
 }  // namespace civic
 
-extern "C" int civic_compact(const void* hidden, int dtype, int32_t dim, const int32_t* pos_ids, int32_t batch,
-                             int64_t seq_len, const civic_grid* grid, const int64_t* frame_start,
-                             const int32_t* kept_idx, int64_t n_kept, void* hidden_c, int32_t* pos_c,
-                             int32_t* src_idx, void* workspace, size_t workspace_bytes, void* stream)
+namespace civic {
+
+// The launch of civic_compact for arguments that compact_check has passed.
+int compact_launch(const void* hidden, int dtype, int32_t dim, const int32_t* pos_ids, int32_t batch, int64_t seq_len,
+                   const civic_grid* grid, const int64_t* frame_start, const int32_t* kept_idx, int64_t n_kept, void* hidden_c,
+                   int32_t* pos_c, int32_t* src_idx, int64_t pos_axis_in, int64_t pos_axis_out, void* stream)
 {
-    using namespace civic;
-    (void)workspace; (void)workspace_bytes;
-    const int rc_check = compact_check(hidden, dtype, dim, pos_ids, batch, seq_len, grid, frame_start, kept_idx, n_kept,
-                                       hidden_c, pos_c, src_idx);
-    if (rc_check != CIVIC_OK) return rc_check;
     const int esz = dtype_size(dtype);
     GridInfo gi;
     grid_info(grid, &gi);
@@ -356,7 +355,7 @@ extern "C" int civic_compact(const void* hidden, int dtype, int32_t dim, const i
 #define CIVIC_COMPACT_LAUNCH(V, U, LONG)                                                                      \
     civic::launch((compact_kernel<V, U, LONG>), g, blk, 0, s, h, row_bytes, pos_ids, batch,                \
                        static_cast<int32_t>(seq_len), ft, kept_idx, static_cast<int32_t>(n_kept),               \
-                       static_cast<int32_t>(seq_c), static_cast<int32_t>(rpb), tpr, hc, pos_c, src_idx)
+                       static_cast<int32_t>(seq_c), static_cast<int32_t>(rpb), tpr, hc, pos_c, src_idx, pos_axis_in, pos_axis_out)
     switch (vec) {
         case 16:
             if (long_list) {
@@ -381,4 +380,22 @@ extern "C" int civic_compact(const void* hidden, int dtype, int32_t dim, const i
     }
 #undef CIVIC_COMPACT_LAUNCH
     return check_launch();
+}
+
+}  // namespace civic
+
+extern "C" int civic_compact(const void* hidden, int dtype, int32_t dim, const int32_t* pos_ids, int32_t batch,
+                             int64_t seq_len, const civic_grid* grid, const int64_t* frame_start,
+                             const int32_t* kept_idx, int64_t n_kept, void* hidden_c, int32_t* pos_c,
+                             int32_t* src_idx, void* workspace, size_t workspace_bytes, void* stream)
+{
+    using namespace civic;
+    (void)workspace; (void)workspace_bytes;
+    const int rc_check = compact_check(hidden, dtype, dim, pos_ids, batch, seq_len, grid, frame_start, kept_idx, n_kept,
+                                       hidden_c, pos_c, src_idx);
+    if (rc_check != CIVIC_OK) return rc_check;
+    GridInfo gi;
+    grid_info(grid, &gi);
+    return compact_launch(hidden, dtype, dim, pos_ids, batch, seq_len, grid, frame_start, kept_idx, n_kept, hidden_c, pos_c,
+                          src_idx, static_cast<int64_t>(batch) * seq_len, static_cast<int64_t>(batch) * (seq_len - gi.nv + n_kept), stream);
 }

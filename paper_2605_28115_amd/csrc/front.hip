@@ -30,3 +30,89 @@ extern "C" int civic_compact_prefill(const void* hidden, int dtype, int32_t batc
     return civic_compact(hidden, dtype, dim, pos_ids, batch, seq_len, grid, frame_start, kept_idx, n_kept, hidden_c, pos_c,
                          src_idx, workspace, workspace_bytes, stream);
 }
+
+// ------------------------------------------------------------------------------------------------ ragged batches
+// Samples of different length and grid (images of different grid sizes in one batch), packed along the token axis.
+extern "C" int civic_ragged_offsets(int32_t batch, const int64_t* seq_offsets, const civic_grid* grids, int64_t* visual_offsets,
+                                    int64_t* kept_offsets, int64_t* compact_offsets)
+{
+    using namespace civic;
+    if (batch < 0 || !seq_offsets || seq_offsets[0] != 0 || (batch > 0 && !grids)) return CIVIC_ERR_INVALID_ARG;
+    int64_t vis = 0, kept = 0, comp = 0;
+    if (visual_offsets) visual_offsets[0] = 0;
+    if (kept_offsets) kept_offsets[0] = 0;
+    if (compact_offsets) compact_offsets[0] = 0;
+    for (int32_t b = 0; b < batch; ++b) {
+        GridInfo gi;
+        if (grid_info(&grids[b], &gi) != CIVIC_OK) return CIVIC_ERR_INVALID_ARG;
+        const int64_t len = seq_offsets[b + 1] - seq_offsets[b];
+        if (len < gi.nv) return CIVIC_ERR_INVALID_ARG;        // (which also makes the offsets non-decreasing)
+        vis += gi.nv; kept += gi.kept; comp += len - gi.nv + gi.kept;
+        if (visual_offsets) visual_offsets[b + 1] = vis;
+        if (kept_offsets) kept_offsets[b + 1] = kept;
+        if (compact_offsets) compact_offsets[b + 1] = comp;
+    }
+    return CIVIC_OK;
+}
+
+extern "C" int civic_compact_prefill_ragged(const void* hidden, int dtype, int32_t batch, const int64_t* seq_offsets, int32_t dim,
+                                            const int32_t* pos_ids, const civic_grid* grids, const int64_t* frame_start,
+                                            const float* anchor_q, float inv_tau, float* scores, int32_t* kept_idx,
+                                            void* hidden_c, int32_t* pos_c, int32_t* src_idx, void* stream)
+{
+    using namespace civic;
+    const int esz = dtype_size(dtype);
+    if (!esz || dim <= 0) return CIVIC_ERR_INVALID_ARG;
+    int rc = civic_ragged_offsets(batch, seq_offsets, grids, nullptr, nullptr, nullptr);
+    if (rc != CIVIC_OK) return rc;
+    if (batch == 0) return CIVIC_OK;
+    if (!frame_start) return CIVIC_ERR_INVALID_ARG;
+    // Per sample: where its rows, scores, kept indices, compact rows and frame starts begin in the packed tensors.
+    // The id axes of the packed pos_ids / pos_c are the packed totals apart.
+    struct Sample {
+        const char* hidden; const int32_t* pos; const int64_t* frames; float* scores; int32_t* kept; char* hidden_c;
+        int32_t* pos_c; int32_t* src; int64_t len, n_kept;
+    };
+    auto sample = [&](int32_t b, int64_t vis, int64_t kept, int64_t comp, int64_t frames_before) {
+        Sample x;
+        const int64_t row0 = seq_offsets[b];
+        x.hidden = static_cast<const char*>(hidden) + row0 * dim * esz;
+        x.pos = pos_ids ? pos_ids + row0 : nullptr;
+        x.frames = frame_start + frames_before;
+        x.scores = scores ? scores + vis : nullptr;
+        x.kept = kept_idx ? kept_idx + kept : nullptr;
+        x.hidden_c = hidden_c ? static_cast<char*>(hidden_c) + comp * dim * esz : nullptr;
+        x.pos_c = pos_c ? pos_c + comp : nullptr;
+        x.src = src_idx ? src_idx + comp : nullptr;
+        x.len = seq_offsets[b + 1] - row0;
+        x.n_kept = civic_kept_count(&grids[b]);
+        return x;
+    };
+    int64_t total_c = 0;
+    for (int32_t b = 0; b < batch; ++b) total_c += (seq_offsets[b + 1] - seq_offsets[b]) - static_cast<int64_t>(grids[b].frames) * grids[b].height * grids[b].width + civic_kept_count(&grids[b]);
+    const int64_t total = seq_offsets[batch];
+    // every check of every sample before the first launch, then the three kernels sample by sample
+    for (int pass = 0; pass < 2; ++pass) {
+        int64_t vis = 0, kept = 0, comp = 0, frames_before = 0;
+        for (int32_t b = 0; b < batch; ++b) {
+            const civic_grid* g = &grids[b];
+            const Sample x = sample(b, vis, kept, comp, frames_before);
+            if (pass == 0) {
+                rc = score_visual_check(x.hidden, dtype, 1, x.len, dim, g, x.frames, anchor_q, inv_tau, x.scores);
+                if (rc == CIVIC_OK) rc = select_check(x.scores, 1, g, x.kept);
+                if (rc == CIVIC_OK) rc = compact_check(x.hidden, dtype, dim, x.pos, 1, x.len, g, x.frames, x.kept, x.n_kept, x.hidden_c, x.pos_c, x.src);
+            } else {
+                rc = civic_score_visual(x.hidden, dtype, 1, x.len, dim, g, x.frames, anchor_q, inv_tau, x.scores, stream);
+                if (rc == CIVIC_OK) rc = civic_select(x.scores, 1, g, x.kept, nullptr, nullptr, 0, stream);
+                if (rc == CIVIC_OK) rc = compact_launch(x.hidden, dtype, dim, x.pos, 1, x.len, g, x.frames, x.kept, x.n_kept, x.hidden_c, x.pos_c,
+                                                        x.src, total, total_c, stream);
+            }
+            if (rc != CIVIC_OK) return rc;
+            vis += static_cast<int64_t>(g->frames) * g->height * g->width;
+            kept += x.n_kept;
+            comp += x.len - static_cast<int64_t>(g->frames) * g->height * g->width + x.n_kept;
+            frames_before += g->frames;
+        }
+    }
+    return CIVIC_OK;
+}

@@ -280,3 +280,49 @@ def test_kernel_timer_argument_checks(bd):
     assert f(one, one) == bd.ERR_INVALID_ARG
     assert f(one, two) == bd.CIVIC_OK
     assert f(None, None) == bd.CIVIC_OK             # disarmed again: no later launch of this thread sees the handles
+
+
+def test_ragged_path_offsets_and_argument_errors(bd):
+    """civic_ragged_offsets is a host function (checked against the oracle's own count); the two ragged path calls
+    reject every documented error before any HIP call."""
+    import oracle
+    L = bd.lib
+    I, OK = bd.ERR_INVALID_ARG, bd.CIVIC_OK
+    grids = [(1, 16, 16, 4, 4, 2, 0, 85), (2, 5, 7, 2, 3, 1, 2, 20), (1, 1, 1, 1, 1, 0, 0, 0), (16, 24, 24, 4, 4, 1, 16, 3072)]
+    lens = [288, 90, 1, 9728]
+    got = bd.civic_ragged_offsets(lens, grids)
+    ref = oracle.ragged_offsets(lens, grids)
+    for a, b in zip(got, ref):
+        assert np.array_equal(a, b)
+    gs = (bd.Grid * 2)(bd.make_grid(grids[0]), bd.make_grid(grids[1]))
+    off = lambda *v: np.asarray(v, dtype=np.int64)
+    out = np.zeros(3, dtype=np.int64)
+    P = lambda a: C.c_void_p(a.ctypes.data) if a is not None else None
+    ro = lambda o=off(0, 288, 378), g=gs, b=2: L.civic_ragged_offsets(b, P(o), g, P(out), None, None)
+    assert ro() == OK and out.tolist() == [0, 256, 326]
+    assert ro(o=None) == I and ro(o=off(1, 288, 378)) == I and ro(o=off(0, 255, 378)) == I and ro(g=None) == I and ro(b=-1) == I
+    bad = (bd.Grid * 2)(bd.make_grid(grids[0]), bd.Grid(1, 0, 7, 1, 1, 0, 0, 0))
+    assert ro(g=bad) == I and ro(b=0, g=None) == OK
+
+    F = C.c_void_p(0x1000)
+    fs = off(16, 3, 50)
+    def front(hidden=F, dt=1, b=2, o=off(0, 288, 378), dim=64, pos=F, g=gs, f=fs, aq=F, sc=F, kept=F, hc=F, pc=F, si=F):
+        return L.civic_compact_prefill_ragged(hidden, dt, b, P(o), dim, pos, g, P(f), aq, C.c_float(1.0), sc, kept, hc, pc, si, None)
+    assert front(dt=7) == I and front(dim=0) == I and front(o=None) == I and front(o=off(0, 100, 378)) == I and front(g=None) == I
+    assert front(f=None) == I and front(hidden=None) == I and front(aq=None) == I and front(sc=None) == I and front(kept=None) == I
+    assert front(hc=None) == I and front(pc=None) == I and front(si=None) == I and front(pos=None) == I
+    assert front(f=off(16, 3, 30)) == I                              # second sample: overlapping frames (3 + 35 > 30)
+    assert front(f=off(40, 3, 50)) == I                              # first sample: the frame runs past its rows
+    assert front(dim=60) == I                                        # rows that are not whole 16-byte pieces
+    assert front(b=0, o=off(0), g=None, f=None, hidden=None) == OK
+
+    st = (C.c_int64 * 3)(0, 512, 128)
+    def attn(q=F, k=F, o=F, b=2, ro_=off(0, 5, 12), hq=4, hkv=2, d=128, qs=st, ks=st, causal=1, kc=None, vc=None, smax=0, pos0=0, dt=1):
+        return L.civic_prefill_attn_ragged(q, k, k, o, dt, b, P(ro_), hq, hkv, d, qs, ks, st, causal, C.c_float(0.0), kc, vc, smax, pos0, None)
+    assert attn(ro_=None) == I and attn(ro_=off(1, 5, 12)) == I and attn(ro_=off(0, 5, 5)) == I and attn(q=None) == I and attn(k=None) == I
+    assert attn(o=None) == I and attn(hq=3) == I and attn(d=60) == I and attn(qs=None) == I and attn(dt=5) == I and attn(b=-1) == I
+    assert attn(kc=F) == I and attn(vc=F) == I                        # one cache without the other
+    assert attn(kc=F, vc=F, smax=6) == I                              # the longest sample (7 rows) does not fit
+    assert attn(kc=F, vc=F, smax=16, pos0=10) == I and attn(kc=F, vc=F, smax=16, pos0=-1) == I
+    assert attn(b=0, ro_=None) == OK and attn(d=512, qs=(C.c_int64 * 3)(0, 2048, 512), ks=(C.c_int64 * 3)(0, 1024, 512)) == bd.ERR_UNSUPPORTED
+    assert bd.lib.civic_last_hip_error() == 0
