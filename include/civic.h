@@ -205,7 +205,8 @@ int civic_compact_prefill(const void* hidden, int dtype, int32_t batch, int64_t 
  * CIVIC_ERR_INVALID_ARG on a bad grid or a sample shorter than its visual tokens.
  *
  * civic_compact_prefill_ragged: civic_score_visual, civic_select and civic_compact sample by sample (three launches
- * per sample on `stream`), every check of every sample before the first launch.
+ * per sample on `stream`; a run of consecutive samples of one grid, length and frame layout goes through them as
+ * one batch), every check of every sample before the first launch.
  *   hidden      device [seq_offsets[batch], dim];  pos_ids  device [3, seq_offsets[batch]] int32
  *   frame_start host, the samples' frame starts one after the other (grids[b].frames entries each), each
  *               counted from its sample's first row

@@ -5,6 +5,8 @@
 // microseconds each.
 #include "civic_internal.h"
 
+#include <cstring>
+
 extern "C" int civic_compact_prefill(const void* hidden, int dtype, int32_t batch, int64_t seq_len, int32_t dim,
                                      const int32_t* pos_ids, const civic_grid* grid, const int64_t* frame_start,
                                      const float* anchor_q, float inv_tau, float* scores, int32_t* kept_idx,
@@ -91,27 +93,46 @@ extern "C" int civic_compact_prefill_ragged(const void* hidden, int dtype, int32
     int64_t total_c = 0;
     for (int32_t b = 0; b < batch; ++b) total_c += (seq_offsets[b + 1] - seq_offsets[b]) - static_cast<int64_t>(grids[b].frames) * grids[b].height * grids[b].width + civic_kept_count(&grids[b]);
     const int64_t total = seq_offsets[batch];
-    // every check of every sample before the first launch, then the three kernels sample by sample
+    // A run of consecutive samples of one shape (same grid, length and frame starts) is a rectangular batch where it
+    // lies in the packed tensors, so it goes through the kernels as one: `n` samples per launch.
+    auto run_length = [&](int32_t b, int64_t frames_before) {
+        const civic_grid& g = grids[b];
+        const int64_t len = seq_offsets[b + 1] - seq_offsets[b];
+        int32_t n = 1;
+        while (b + n < batch && n < 65535) {
+            const civic_grid& h = grids[b + n];
+            if (std::memcmp(&g, &h, sizeof(civic_grid)) != 0 || seq_offsets[b + n + 1] - seq_offsets[b + n] != len) break;
+            if (std::memcmp(frame_start + frames_before, frame_start + frames_before + static_cast<int64_t>(n) * g.frames,
+                            sizeof(int64_t) * g.frames) != 0)
+                break;
+            ++n;
+        }
+        return n;
+    };
+    // every check of every run before the first launch, then the three kernels run by run
     for (int pass = 0; pass < 2; ++pass) {
         int64_t vis = 0, kept = 0, comp = 0, frames_before = 0;
-        for (int32_t b = 0; b < batch; ++b) {
+        for (int32_t b = 0; b < batch;) {
             const civic_grid* g = &grids[b];
             const Sample x = sample(b, vis, kept, comp, frames_before);
+            const int32_t n = run_length(b, frames_before);
             if (pass == 0) {
-                rc = score_visual_check(x.hidden, dtype, 1, x.len, dim, g, x.frames, anchor_q, inv_tau, x.scores);
-                if (rc == CIVIC_OK) rc = select_check(x.scores, 1, g, x.kept);
-                if (rc == CIVIC_OK) rc = compact_check(x.hidden, dtype, dim, x.pos, 1, x.len, g, x.frames, x.kept, x.n_kept, x.hidden_c, x.pos_c, x.src);
+                rc = score_visual_check(x.hidden, dtype, n, x.len, dim, g, x.frames, anchor_q, inv_tau, x.scores);
+                if (rc == CIVIC_OK) rc = select_check(x.scores, n, g, x.kept);
+                if (rc == CIVIC_OK) rc = compact_check(x.hidden, dtype, dim, x.pos, n, x.len, g, x.frames, x.kept, x.n_kept, x.hidden_c, x.pos_c, x.src);
             } else {
-                rc = civic_score_visual(x.hidden, dtype, 1, x.len, dim, g, x.frames, anchor_q, inv_tau, x.scores, stream);
-                if (rc == CIVIC_OK) rc = civic_select(x.scores, 1, g, x.kept, nullptr, nullptr, 0, stream);
-                if (rc == CIVIC_OK) rc = compact_launch(x.hidden, dtype, dim, x.pos, 1, x.len, g, x.frames, x.kept, x.n_kept, x.hidden_c, x.pos_c,
+                rc = civic_score_visual(x.hidden, dtype, n, x.len, dim, g, x.frames, anchor_q, inv_tau, x.scores, stream);
+                if (rc == CIVIC_OK) rc = civic_select(x.scores, n, g, x.kept, nullptr, nullptr, 0, stream);
+                if (rc == CIVIC_OK) rc = compact_launch(x.hidden, dtype, dim, x.pos, n, x.len, g, x.frames, x.kept, x.n_kept, x.hidden_c, x.pos_c,
                                                         x.src, total, total_c, stream);
             }
             if (rc != CIVIC_OK) return rc;
-            vis += static_cast<int64_t>(g->frames) * g->height * g->width;
-            kept += x.n_kept;
-            comp += x.len - static_cast<int64_t>(g->frames) * g->height * g->width + x.n_kept;
-            frames_before += g->frames;
+            const int64_t nv = static_cast<int64_t>(g->frames) * g->height * g->width;
+            vis += n * nv;
+            kept += n * x.n_kept;
+            comp += n * (x.len - nv + x.n_kept);
+            frames_before += static_cast<int64_t>(n) * g->frames;
+            b += n;
         }
     }
     return CIVIC_OK;

@@ -25,7 +25,7 @@ def layout(rng, grids, max_gap):
     starts, lens = [], []
     for g in grids:
         frames, hw = g[0], g[1] * g[2]
-        gaps = rng.integers(0, max_gap + 1, frames + 1)
+        gaps = rng.integers(0, max_gap + 1, frames + 1) if max_gap >= 0 else np.full(frames + 1, -max_gap)   # (negative: that gap everywhere)
         s, p = [], int(gaps[0])
         for f in range(frames):
             s.append(p)
@@ -37,6 +37,8 @@ def layout(rng, grids, max_gap):
 MIXES = {
     # grids of the tabulated workloads side by side, and small ragged ones (odd cells, frame floors, nothing kept)
     "workload grids": ([(1, 16, 16, 4, 4, 2, 0, 85), (2, 32, 32, 4, 4, 1, 0, 682), (1, 32, 32, 4, 4, 1, 0, 341), (4, 24, 24, 4, 4, 1, 16, 768)], 96),
+    # runs of samples of one shape (same grid, length and frame starts), which go through the kernels as one batch each
+    "repeated shapes": ([(1, 16, 16, 4, 4, 2, 0, 85)] * 3 + [(2, 8, 8, 4, 4, 1, 0, 40)] + [(1, 32, 32, 4, 4, 1, 0, 341)] * 2 + [(1, 16, 16, 4, 4, 2, 0, 85)], -5),
     "small grids": ([(1, 3, 5, 2, 2, 1, 0, 4), (3, 2, 2, 2, 2, 0, 1, 5), (1, 1, 1, 1, 1, 0, 0, 0), (2, 7, 9, 3, 4, 2, 3, 40), (1, 8, 8, 8, 8, 0, 0, 64)], 7),
 }
 
