@@ -362,3 +362,11 @@ def kv_write_ragged(k: np.ndarray, v: np.ndarray, row_offsets, k_cache: np.ndarr
     assert k_cache.shape[0] == off.size - 1
     return sum(kv_write(np.ascontiguousarray(k[None, a:b]), np.ascontiguousarray(v[None, a:b]), k_cache[i:i + 1], v_cache[i:i + 1], pos0)
                for i, (a, b) in enumerate(zip(off[:-1], off[1:])))
+
+
+def decode_attention_ragged(q: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray, n_ctx: Sequence[int],
+                            scale: Optional[float] = None) -> np.ndarray:
+    """The decode step over caches that hold a different number of rows per sample (what a ragged prefill leaves):
+    q [batch, H_q, d]; sample b attends to rows [0, n_ctx[b]) of its own cache -> float64 [batch, H_q, d]."""
+    assert len(n_ctx) == q.shape[0] == k_cache.shape[0]
+    return np.concatenate([decode_attention(q[b:b + 1], k_cache[b:b + 1], v_cache[b:b + 1], int(n), scale) for b, n in enumerate(n_ctx)])

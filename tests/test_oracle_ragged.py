@@ -141,3 +141,26 @@ def test_every_sample_is_cached_at_its_own_rows():
         assert np.array_equal(vc[i, :, pos0:pos0 + (b - a)], v[a:b].transpose(1, 0, 2))
         assert np.all(kc[i, :, :pos0] == 0xBEEF) and np.all(kc[i, :, pos0 + (b - a):] == 0xBEEF)
         assert np.all(vc[i, :, :pos0] == 0xBEEF) and np.all(vc[i, :, pos0 + (b - a):] == 0xBEEF)
+
+
+def test_decode_step_reads_every_sample_up_to_its_own_length():
+    rng = np.random.default_rng(6)
+    sizes = [1, 9, 4, 17]
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    hq, hkv, d, s_max = 4, 2, 8, 20
+    q = rng.standard_normal((off[-1], hq, d)).astype(np.float32)
+    k = rng.standard_normal((off[-1], hkv, d)).astype(np.float32)
+    v = rng.standard_normal((off[-1], hkv, d)).astype(np.float32)
+    kc = rng.standard_normal((len(sizes), hkv, s_max, d)).astype(np.float32) * 50.0      # rows past a sample's length: loud garbage
+    vc = rng.standard_normal((len(sizes), hkv, s_max, d)).astype(np.float32) * 50.0
+    oracle.kv_write_ragged(k, v, off, kc, vc, 0)
+    last_q = np.stack([q[b - 1] for b in off[1:]])                                           # every sample's last query
+    dec = oracle.decode_attention_ragged(last_q, kc, vc, sizes)
+    full = oracle.attention_ragged(q, k, v, off, True)
+    assert np.abs(dec - np.stack([full[b - 1] for b in off[1:]])).max() < 1e-12
+    # and against library attention over exactly the rows the sample owns
+    for i, n in enumerate(sizes):
+        t = lambda x: torch.from_numpy(x).double()
+        ref = torch.nn.functional.scaled_dot_product_attention(t(last_q[i])[None, :, None, :], t(kc[i, :, :n]).repeat_interleave(hq // hkv, 0)[None],
+                                                               t(vc[i, :, :n]).repeat_interleave(hq // hkv, 0)[None])[0, :, 0].numpy()
+        assert np.abs(dec[i] - ref).max() < 1e-12
