@@ -496,11 +496,19 @@ def main() -> int:
                 a_, b_ = int(rcomp[i_]), int(rcomp[i_ + 1])
                 bd.civic_prefill_attn_kv(rq[a_:b_][None], rk[a_:b_][None], rv[a_:b_][None], rkc[i_:i_ + 1], rvc[i_:i_ + 1], 0, True, 0.0, out=ro[a_:b_][None])
         t_rattn_items = alone(attn_per_sample, cost=len(rgrids))
+        # the decode step over the caches the ragged prefill has left: one context length per sample
+        rctx = [int(n_) for n_ in np.diff(rcomp)]
+        rdq = torch.randn((len(rgrids), w.n_q_heads, w.head_dim), device="cuda").to(rh.dtype)
+        rdo = torch.empty_like(rdq)
+        rws = torch.empty(max(16, int(bd.lib.civic_decode_attn_ragged_workspace_bytes(1, len(rctx), np.asarray(rctx, dtype=np.int32).ctypes.data,
+                                                                                      w.n_q_heads, w.n_kv_heads, w.head_dim))), dtype=torch.uint8, device="cuda")
+        t_rdec = alone(lambda s_: bd.civic_decode_attn_ragged(rdq, rkc, rvc, rctx, out=rdo, workspace=rws), cost=2)
         f_r = sum(4.0 * w.n_q_heads * w.head_dim * (n_ * (n_ + 1) / 2) for n_ in np.diff(rcomp))
         ragged = {"samples": len(rgrids), "dense_rows": int(rseq[-1]), "compact_rows": tc,
                   "compact_prefill_ragged_us": round(t_front, 2), "launches_front": 3 * len(rgrids),
                   "prefill_attn_ragged": {"us": round(t_rattn, 2), "us_one_call_per_sample": round(t_rattn_items, 2), "flops": f_r,
-                                          "tflops": round(f_r / t_rattn / 1e6, 1)}}
+                                          "tflops": round(f_r / t_rattn / 1e6, 1)},
+                  "decode_attn_ragged_us": round(t_rdec, 2)}
 
     # Encoder-side compaction (the paper's own soft route), timed on the encoder-shaped workload: Eq. 8 from the
     # dense patch grid to K anchors, and Eq. 9 (KV compression to S memory anchors + attention over them).

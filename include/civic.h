@@ -442,6 +442,19 @@ int civic_decode_attn_noalloc(const void* q, const void* k_cache, const void* v_
                               int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int64_t s_max,
                               int64_t n_ctx, float softmax_scale, void* stream);
 
+/* civic_decode_attn over caches that hold a different number of rows per sample (what civic_prefill_attn_ragged
+ * leaves): sample b attends to rows [0, n_ctx[b]) of k_cache[b], v_cache[b].  Groups of up to 256 samples, each the two
+ * launches of civic_decode_attn laid out for the group's longest context (a split that starts past a sample's rows
+ * contributes nothing); results equal civic_decode_attn on every sample alone up to the order of the partial sums.
+ *   n_ctx      host [batch] int32, every entry in [1, s_max]
+ *   workspace  civic_decode_attn_ragged_workspace_bytes(same sizes), 16-byte aligned (shared by the groups in turn)
+ * Everything else as civic_decode_attn; every group is checked before the first launch. */
+size_t civic_decode_attn_ragged_workspace_bytes(int dtype, int32_t batch, const int32_t* n_ctx /* host */, int32_t n_q_heads,
+                                                int32_t n_kv_heads, int32_t head_dim);
+int civic_decode_attn_ragged(const void* q, const void* k_cache, const void* v_cache, void* out, int dtype, int32_t batch,
+                             const int32_t* n_ctx /* host */, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                             int64_t s_max, float softmax_scale, void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

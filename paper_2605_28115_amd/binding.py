@@ -28,7 +28,7 @@ EXPORTS = ("civic_last_hip_error", "civic_time_next_kernel", "civic_kept_count",
            "civic_anchor_aggregate_workspace_bytes", "civic_anchor_aggregate", "civic_kv_compress_workspace_bytes",
            "civic_kv_compress", "civic_cross_attn", "civic_kv_compress_ragged_workspace_bytes",
            "civic_kv_compress_ragged", "civic_cross_attn_ragged", "civic_ragged_offsets", "civic_compact_prefill_ragged",
-           "civic_prefill_attn_ragged")
+           "civic_prefill_attn_ragged", "civic_decode_attn_ragged_workspace_bytes", "civic_decode_attn_ragged")
 
 
 class CivicError(RuntimeError):
@@ -64,6 +64,11 @@ lib.civic_compact_prefill_ragged.argtypes = [_P, C.c_int, C.c_int32, _P, C.c_int
 lib.civic_prefill_attn_ragged.restype = C.c_int
 lib.civic_prefill_attn_ragged.argtypes = [_P, _P, _P, _P, C.c_int, C.c_int32, _P, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int64),
                                           C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.c_int32, C.c_float, _P, _P, C.c_int64, C.c_int64, _P]
+lib.civic_decode_attn_ragged_workspace_bytes.restype = C.c_size_t
+lib.civic_decode_attn_ragged_workspace_bytes.argtypes = [C.c_int, C.c_int32, _P, C.c_int32, C.c_int32, C.c_int32]
+lib.civic_decode_attn_ragged.restype = C.c_int
+lib.civic_decode_attn_ragged.argtypes = [_P, _P, _P, _P, C.c_int, C.c_int32, _P, C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_float, _P,
+                                         C.c_size_t, _P]
 lib.civic_kept_count.restype = C.c_int64
 lib.civic_kept_count.argtypes = [C.POINTER(Grid)]
 lib.civic_select_workspace_bytes.restype = C.c_size_t
@@ -460,6 +465,24 @@ def civic_decode_attn(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Ten
     _check("civic_decode_attn", lib.civic_decode_attn(_dev(q), _dev(k_cache), _dev(v_cache), _dev(out), _dtype_code(q), batch,
                                                       hq, hkv, d, s_max, int(n_ctx), float(softmax_scale), _dev(workspace),
                                                       ws_bytes, _stream(stream)))
+    return out
+
+
+def civic_decode_attn_ragged(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, n_ctx: Sequence[int], softmax_scale: float = 0.0,
+                             out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """The decode step with one context length per sample: q [batch, H_q, d] over rows [0, n_ctx[b]) of the caches."""
+    batch, hq, hkv, d, s_max = _decode_shapes(q, k_cache, v_cache)
+    ctx = np.ascontiguousarray(np.asarray(n_ctx, dtype=np.int32))
+    if ctx.shape != (batch,):
+        raise ValueError("one context length per sample")
+    if out is None:
+        out = torch.empty_like(q)
+    if workspace is None:
+        need = int(lib.civic_decode_attn_ragged_workspace_bytes(_dtype_code(q), batch, C.c_void_p(ctx.ctypes.data), hq, hkv, d))
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    _check("civic_decode_attn_ragged", lib.civic_decode_attn_ragged(
+        _dev(q), _dev(k_cache), _dev(v_cache), _dev(out), _dtype_code(q), batch, C.c_void_p(ctx.ctypes.data), hq, hkv, d, s_max,
+        float(softmax_scale), _dev(workspace), workspace.numel(), _stream(stream)))
     return out
 
 

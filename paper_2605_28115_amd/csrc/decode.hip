@@ -26,6 +26,8 @@ constexpr int kDecThreads = 256;
 constexpr int kDecWaves = kDecThreads / kWave;
 constexpr int kDecU = 4;                 // cache rows per lane and round
 
+constexpr int kDecRaggedItems = 256;     // samples of one launch when every sample has its own context length
+
 struct DecodeArgs {
     const void* q; const void* kc; const void* vc; void* out; float* ws;
     int64_t s_max;
@@ -33,6 +35,10 @@ struct DecodeArgs {
     int32_t n_ctx, splits, keys_per_split;
     int32_t cpr;                          // 16-byte chunks per cache row
     float scale_log2;                     // softmax scale * log2(e)
+    // civic_decode_attn_ragged: sample b attends to its cache rows [0, ctx_of[b]) (n_ctx is then the longest, which the
+    // splits are laid out for; a split that starts past a sample's rows contributes an empty partial result)
+    int32_t per_item;
+    int32_t ctx_of[kDecRaggedItems];
 };
 
 typedef __bf16 dec_bf16x2 __attribute__((ext_vector_type(2)));
@@ -87,7 +93,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(DecodeArgs 
     const int b = blockIdx.z;
     const int d = a.head_dim;
     const int k0 = split * a.keys_per_split;
-    const int k1 = min(k0 + a.keys_per_split, a.n_ctx);
+    const int n_ctx = a.per_item ? a.ctx_of[b] : a.n_ctx;
+    const int k1 = min(k0 + a.keys_per_split, n_ctx);
 
     // the lane's chunk of every query head of the pass (heads past the group repeat the last one; never written)
     u32x4 qw[HG];
@@ -349,9 +356,11 @@ static int launch_decode(const DecodeArgs& a, const DecodePlan& p, hipStream_t s
 // Everything but the choice of the workspace: `ws` holds at least plan.ws_bytes when the plan splits.
 static int decode_attn(const void* q, const void* k_cache, const void* v_cache, void* out, int dtype, int32_t batch,
                        int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim, int64_t s_max, int64_t n_ctx,
-                       float softmax_scale, const DecodePlan& p, float* ws, void* stream)
+                       float softmax_scale, const DecodePlan& p, float* ws, void* stream, const int32_t* ctx_of = nullptr)
 {
     DecodeArgs a;
+    a.per_item = ctx_of ? 1 : 0;
+    for (int i = 0; i < kDecRaggedItems; ++i) a.ctx_of[i] = ctx_of && i < batch ? ctx_of[i] : 0;
     a.q = q; a.kc = k_cache; a.vc = v_cache; a.out = out; a.ws = ws;
     a.s_max = s_max;
     a.batch = batch; a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads; a.head_dim = head_dim;
@@ -460,4 +469,72 @@ extern "C" int civic_decode_attn(const void* q, const void* k_cache, const void*
     if (p.ws_bytes > 0 && (!workspace || workspace_bytes < p.ws_bytes || !aligned16(workspace))) return CIVIC_ERR_WORKSPACE;
     return decode_attn(q, k_cache, v_cache, out, dtype, batch, n_q_heads, n_kv_heads, head_dim, s_max, n_ctx, softmax_scale,
                        p, static_cast<float*>(workspace), stream);
+}
+
+// ---------------------------------------------------------------------------------------------- ragged caches
+namespace civic {
+
+// The longest context of samples [b0, b0 + nb); -1 if one of them is shorter than one row or longer than the caches.
+static int64_t longest_ctx(const int32_t* n_ctx, int32_t b0, int32_t nb, int64_t s_max)
+{
+    int64_t longest = 0;
+    for (int32_t i = 0; i < nb; ++i) {
+        const int64_t n = n_ctx[b0 + i];
+        if (n < 1 || n > s_max) return -1;
+        longest = n > longest ? n : longest;
+    }
+    return longest;
+}
+
+}  // namespace civic
+
+extern "C" size_t civic_decode_attn_ragged_workspace_bytes(int dtype, int32_t batch, const int32_t* n_ctx, int32_t n_q_heads,
+                                                           int32_t n_kv_heads, int32_t head_dim)
+{
+    using namespace civic;
+    if (batch <= 0 || !n_ctx) return 0;
+    size_t need = 0;                                          // the groups run one after the other and share the workspace
+    for (int32_t b0 = 0; b0 < batch; b0 += kDecRaggedItems) {
+        const int32_t nb = batch - b0 < kDecRaggedItems ? batch - b0 : kDecRaggedItems;
+        const int64_t longest = longest_ctx(n_ctx, b0, nb, INT32_MAX);
+        DecodePlan p;
+        if (longest < 0 || decode_plan(dtype, nb, n_q_heads, n_kv_heads, head_dim, longest, &p) != CIVIC_OK) return 0;
+        need = p.ws_bytes > need ? p.ws_bytes : need;
+    }
+    return need;
+}
+
+extern "C" int civic_decode_attn_ragged(const void* q, const void* k_cache, const void* v_cache, void* out, int dtype,
+                                        int32_t batch, const int32_t* n_ctx, int32_t n_q_heads, int32_t n_kv_heads,
+                                        int32_t head_dim, int64_t s_max, float softmax_scale, void* workspace,
+                                        size_t workspace_bytes, void* stream)
+{
+    using namespace civic;
+    const int esz = dtype_size(dtype);
+    if (!esz || batch < 0) return CIVIC_ERR_INVALID_ARG;
+    if (batch > 0 && !n_ctx) return CIVIC_ERR_INVALID_ARG;
+    // Groups of up to kDecRaggedItems samples, each the two launches of civic_decode_attn laid out for the group's
+    // longest context; every group is checked before the first launch.
+    for (int pass = 0; pass < 2; ++pass)
+        for (int32_t b0 = 0; b0 < batch; b0 += kDecRaggedItems) {
+            const int32_t nb = batch - b0 < kDecRaggedItems ? batch - b0 : kDecRaggedItems;
+            const int64_t longest = longest_ctx(n_ctx, b0, nb, s_max);
+            if (longest < 0) return CIVIC_ERR_INVALID_ARG;
+            const char* qb = static_cast<const char*>(q) + static_cast<int64_t>(b0) * n_q_heads * head_dim * esz;
+            char* ob = static_cast<char*>(out) + static_cast<int64_t>(b0) * n_q_heads * head_dim * esz;
+            const int64_t cache_at = static_cast<int64_t>(b0) * n_kv_heads * s_max * head_dim * esz;
+            const char* kb = static_cast<const char*>(k_cache) + cache_at;
+            const char* vb = static_cast<const char*>(v_cache) + cache_at;
+            DecodePlan p;
+            bool nothing = false;
+            int rc = decode_check(q ? qb : nullptr, k_cache ? kb : nullptr, v_cache ? vb : nullptr, out ? ob : nullptr, dtype, nb, n_q_heads,
+                                  n_kv_heads, head_dim, s_max, longest, softmax_scale, &p, &nothing);
+            if (rc != CIVIC_OK) return rc;
+            if (p.ws_bytes > 0 && (!workspace || workspace_bytes < p.ws_bytes || !aligned16(workspace))) return CIVIC_ERR_WORKSPACE;
+            if (pass == 0 || nothing) continue;
+            rc = decode_attn(qb, kb, vb, ob, dtype, nb, n_q_heads, n_kv_heads, head_dim, s_max, longest, softmax_scale, p,
+                             static_cast<float*>(workspace), stream, n_ctx + b0);
+            if (rc != CIVIC_OK) return rc;
+        }
+    return CIVIC_OK;
 }

@@ -326,3 +326,21 @@ def test_ragged_path_offsets_and_argument_errors(bd):
     assert attn(kc=F, vc=F, smax=16, pos0=10) == I and attn(kc=F, vc=F, smax=16, pos0=-1) == I
     assert attn(b=0, ro_=None) == OK and attn(d=512, qs=(C.c_int64 * 3)(0, 2048, 512), ks=(C.c_int64 * 3)(0, 1024, 512)) == bd.ERR_UNSUPPORTED
     assert bd.lib.civic_last_hip_error() == 0
+
+
+def test_ragged_decode_argument_errors(bd):
+    L, F = bd.lib, C.c_void_p(0x1000)
+    I, OK = bd.ERR_INVALID_ARG, bd.CIVIC_OK
+    ctx = lambda *v: np.asarray(v, dtype=np.int32)
+    P = lambda a: C.c_void_p(a.ctypes.data) if a is not None else None
+    def dec(q=F, kc=F, vc=F, o=F, dt=1, b=3, n=ctx(5, 938, 17), hq=32, hkv=8, d=128, smax=1000, scale=0.0, ws=F, wsb=1 << 30):
+        return L.civic_decode_attn_ragged(q, kc, vc, o, dt, b, P(n), hq, hkv, d, smax, C.c_float(scale), ws, wsb, None)
+    assert dec(n=None) == I and dec(n=ctx(5, 0, 17)) == I and dec(n=ctx(5, 1001, 17)) == I and dec(n=ctx(-1, 2, 3)) == I
+    assert dec(q=None) == I and dec(kc=None) == I and dec(vc=None) == I and dec(o=None) == I and dec(dt=4) == I and dec(b=-1) == I
+    assert dec(hq=30) == I and dec(d=60) == I and dec(scale=-1.0) == I and dec(q=C.c_void_p(0x1004)) == I
+    assert dec(d=1024) == bd.ERR_UNSUPPORTED and dec(b=0, n=None, q=None) == OK
+    need = L.civic_decode_attn_ragged_workspace_bytes(1, 3, P(ctx(5, 938, 17)), 32, 8, 128)
+    assert need == L.civic_decode_attn_workspace_bytes(1, 3, 32, 8, 128, 938) > 0      # laid out for the longest context
+    assert dec(ws=None, wsb=0) == bd.ERR_WORKSPACE and dec(wsb=need - 1) == bd.ERR_WORKSPACE
+    assert L.civic_decode_attn_ragged_workspace_bytes(1, 3, P(ctx(5, 0, 17)), 32, 8, 128) == 0
+    assert bd.lib.civic_last_hip_error() == 0

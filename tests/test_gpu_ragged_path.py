@@ -148,3 +148,33 @@ def test_ragged_path_chained(bd):
     for i in range(len(grids)):
         a, b = int(comp[i]), int(comp[i + 1])
         assert torch.equal(kc[i, :, :b - a], kv[a:b].permute(1, 0, 2)) and torch.equal(kc[i, :, b - a:], torch.zeros_like(kc[i, :, b - a:]))
+
+
+@pytest.mark.parametrize("case", [
+    # dtype, H_q, H_kv, d, context lengths
+    ("bf16", 32, 8, 128, [117, 938, 469, 64, 65, 1]),
+    ("bf16", 8, 8, 72, [300, 2, 1365]),
+    ("bf16", 4, 2, 64, list(range(1, 301))),                 # 300 samples: two groups of launches
+    ("fp32", 4, 2, 64, [117, 5, 40, 4000]),
+    ("bf16", 16, 2, 128, [3000, 1, 1, 1]),                    # one long context next to empty-handed splits
+])
+def test_ragged_decode_matches_oracle_and_the_rectangular_call(bd, case):
+    dtype, hq, hkv, d, sizes = case
+    log("ragged decode", case[:4], len(sizes), "samples")
+    rng = np.random.default_rng(sum(sizes) + d)
+    n, s_max = len(sizes), max(sizes) + 3
+    q, q32 = wl.quantize(rng.standard_normal((n, hq, d)).astype(np.float32), dtype)
+    kc, kc32 = wl.quantize(rng.standard_normal((n, hkv, s_max, d)).astype(np.float32), dtype)     # rows past a sample's length hold data too
+    vc, vc32 = wl.quantize(rng.standard_normal((n, hkv, s_max, d)).astype(np.float32), dtype)
+    dq, dkc, dvc = to_dev(q), to_dev(kc), to_dev(vc)
+    out = bd.civic_decode_attn_ragged(dq, dkc, dvc, sizes)
+    torch.cuda.synchronize()
+    ref = oracle.decode_attention_ragged(q32, kc32, vc32, sizes)
+    got = widen(to_host(out)).astype(np.float64)
+    err = float(np.abs(got - ref).max())
+    log("   max abs err", err, "tol", attn_tol(ref, dtype))
+    assert np.isfinite(got).all() and err <= attn_tol(ref, dtype)
+    # a sample alone through the rectangular call: the same rows, possibly another split of them
+    for i in sorted({0, n // 2, n - 1}):
+        one = bd.civic_decode_attn(dq[i:i + 1], dkc[i:i + 1], dvc[i:i + 1], int(sizes[i]))
+        assert np.abs(widen(to_host(one)).astype(np.float64) - got[i:i + 1]).max() <= attn_tol(ref, dtype)
