@@ -78,7 +78,7 @@ extern "C" int civic_compact_prefill_ragged(const void* hidden, int dtype, int32
     auto sample = [&](int32_t b, int64_t vis, int64_t kept, int64_t comp, int64_t frames_before) {
         Sample x;
         const int64_t row0 = seq_offsets[b];
-        x.hidden = static_cast<const char*>(hidden) + row0 * dim * esz;
+        x.hidden = hidden ? static_cast<const char*>(hidden) + row0 * dim * esz : nullptr;
         x.pos = pos_ids ? pos_ids + row0 : nullptr;
         x.frames = frame_start + frames_before;
         x.scores = scores ? scores + vis : nullptr;
