@@ -204,9 +204,11 @@ int civic_compact_prefill(const void* hidden, int dtype, int32_t batch, int64_t 
  *   compact_offsets  compact rows before b, a sample's count being its length - N_v + K
  * CIVIC_ERR_INVALID_ARG on a bad grid or a sample shorter than its visual tokens.
  *
- * civic_compact_prefill_ragged: civic_score_visual, civic_select and civic_compact sample by sample (three launches
- * per sample on `stream`; a run of consecutive samples of one grid, length and frame layout goes through them as
- * one batch), every check of every sample before the first launch.
+ * civic_compact_prefill_ragged: the three stages of civic_compact_prefill for all samples - the scores of up to 64
+ * frame spans per launch, the selection of up to 16 samples per launch (a workgroup per sample, each with its own
+ * grid), the merge one launch per run of consecutive samples of one grid, length and frame layout - with every check
+ * of every sample before the first launch.  seq_offsets[batch] and the visual tokens together <= INT32_MAX, else
+ * CIVIC_ERR_UNSUPPORTED.
  *   hidden      device [seq_offsets[batch], dim];  pos_ids  device [3, seq_offsets[batch]] int32
  *   frame_start host, the samples' frame starts one after the other (grids[b].frames entries each), each
  *               counted from its sample's first row

@@ -82,6 +82,13 @@ int compact_launch(const void* hidden, int dtype, int32_t dim, const int32_t* po
                    const civic_grid* grid, const int64_t* frame_start, const int32_t* kept_idx, int64_t n_kept, void* hidden_c,
                    int32_t* pos_c, int32_t* src_idx, int64_t pos_axis_in, int64_t pos_axis_out, void* stream);
 
+// Up to 64 spans of rows of a packed tensor scored in one launch (the ragged front); arguments checked by the caller.
+int score_slices_launch(const void* hidden, int dtype, int32_t dim, const float* anchor_q, float inv_tau, float* scores,
+                        const int32_t* first, const int32_t* count, const int32_t* out, int32_t n_slices, int32_t longest, void* stream);
+
+// Up to 16 samples of different grids selected in one launch (the ragged front); every sample checked by the caller.
+int select_samples_launch(const float* const* scores, int32_t* const* kept_idx, const civic_grid* const* grids, int32_t n, void* stream);
+
 constexpr int kWave = 64;
 
 // Native vector types (the nontemporal load builtin does not take HIP's struct vectors).

@@ -109,29 +109,76 @@ extern "C" int civic_compact_prefill_ragged(const void* hidden, int dtype, int32
         }
         return n;
     };
-    // every check of every run before the first launch, then the three kernels run by run
-    for (int pass = 0; pass < 2; ++pass) {
+    // every check of every run before the first launch
+    {
         int64_t vis = 0, kept = 0, comp = 0, frames_before = 0;
         for (int32_t b = 0; b < batch;) {
             const civic_grid* g = &grids[b];
             const Sample x = sample(b, vis, kept, comp, frames_before);
             const int32_t n = run_length(b, frames_before);
-            if (pass == 0) {
-                rc = score_visual_check(x.hidden, dtype, n, x.len, dim, g, x.frames, anchor_q, inv_tau, x.scores);
-                if (rc == CIVIC_OK) rc = select_check(x.scores, n, g, x.kept);
-                if (rc == CIVIC_OK) rc = compact_check(x.hidden, dtype, dim, x.pos, n, x.len, g, x.frames, x.kept, x.n_kept, x.hidden_c, x.pos_c, x.src);
-            } else {
-                rc = civic_score_visual(x.hidden, dtype, n, x.len, dim, g, x.frames, anchor_q, inv_tau, x.scores, stream);
-                if (rc == CIVIC_OK) rc = civic_select(x.scores, n, g, x.kept, nullptr, nullptr, 0, stream);
-                if (rc == CIVIC_OK) rc = compact_launch(x.hidden, dtype, dim, x.pos, n, x.len, g, x.frames, x.kept, x.n_kept, x.hidden_c, x.pos_c,
-                                                        x.src, total, total_c, stream);
-            }
+            rc = score_visual_check(x.hidden, dtype, n, x.len, dim, g, x.frames, anchor_q, inv_tau, x.scores);
+            if (rc == CIVIC_OK) rc = select_check(x.scores, n, g, x.kept);
+            if (rc == CIVIC_OK) rc = compact_check(x.hidden, dtype, dim, x.pos, n, x.len, g, x.frames, x.kept, x.n_kept, x.hidden_c, x.pos_c, x.src);
             if (rc != CIVIC_OK) return rc;
             const int64_t nv = static_cast<int64_t>(g->frames) * g->height * g->width;
-            vis += n * nv;
-            kept += n * x.n_kept;
-            comp += n * (x.len - nv + x.n_kept);
-            frames_before += static_cast<int64_t>(n) * g->frames;
+            vis += n * nv; kept += n * x.n_kept; comp += n * (x.len - nv + x.n_kept); frames_before += static_cast<int64_t>(n) * g->frames;
+            b += n;
+        }
+        if (total > INT32_MAX || vis > INT32_MAX) return CIVIC_ERR_UNSUPPORTED;     // (row numbers travel as 32-bit kernel arguments)
+    }
+    // Scores: the frames of all samples, 64 spans per launch.  Selection: 16 samples per launch, each workgroup with its
+    // own sample's grid.  Merge: run by run.
+    {
+        constexpr int kSlices = 64, kSamples = 16;
+        int32_t first[kSlices], count[kSlices], out[kSlices], n_sl = 0, longest = 0;
+        auto flush_scores = [&]() {
+            const int r = n_sl ? score_slices_launch(hidden, dtype, dim, anchor_q, inv_tau, scores, first, count, out, n_sl, longest, stream) : CIVIC_OK;
+            n_sl = 0; longest = 0;
+            return r;
+        };
+        int64_t vis = 0, frames_before = 0;
+        for (int32_t b = 0; b < batch; ++b) {
+            const civic_grid& g = grids[b];
+            const int32_t hw = g.height * g.width;
+            for (int32_t f = 0; f < g.frames; ++f) {
+                first[n_sl] = static_cast<int32_t>(seq_offsets[b] + frame_start[frames_before + f]);
+                count[n_sl] = hw;
+                out[n_sl] = static_cast<int32_t>(vis + static_cast<int64_t>(f) * hw);
+                longest = hw > longest ? hw : longest;
+                if (++n_sl == kSlices && (rc = flush_scores()) != CIVIC_OK) return rc;
+            }
+            vis += static_cast<int64_t>(g.frames) * hw;
+            frames_before += g.frames;
+        }
+        if ((rc = flush_scores()) != CIVIC_OK) return rc;
+
+        const float* sc[kSamples];
+        int32_t* kp[kSamples];
+        const civic_grid* gp[kSamples];
+        int32_t n_sm = 0;
+        int64_t kept = 0;
+        vis = 0;
+        for (int32_t b = 0; b < batch; ++b) {
+            sc[n_sm] = scores + vis; kp[n_sm] = kept_idx + kept; gp[n_sm] = &grids[b];
+            vis += static_cast<int64_t>(grids[b].frames) * grids[b].height * grids[b].width;
+            kept += civic_kept_count(&grids[b]);
+            if (++n_sm == kSamples || b + 1 == batch) {
+                if ((rc = select_samples_launch(sc, kp, gp, n_sm, stream)) != CIVIC_OK) return rc;
+                n_sm = 0;
+            }
+        }
+    }
+    {
+        int64_t vis = 0, kept = 0, comp = 0, frames_before = 0;
+        for (int32_t b = 0; b < batch;) {
+            const civic_grid* g = &grids[b];
+            const Sample x = sample(b, vis, kept, comp, frames_before);
+            const int32_t n = run_length(b, frames_before);
+            rc = compact_launch(x.hidden, dtype, dim, x.pos, n, x.len, g, x.frames, x.kept, x.n_kept, x.hidden_c, x.pos_c, x.src, total,
+                                total_c, stream);
+            if (rc != CIVIC_OK) return rc;
+            const int64_t nv = static_cast<int64_t>(g->frames) * g->height * g->width;
+            vis += n * nv; kept += n * x.n_kept; comp += n * (x.len - nv + x.n_kept); frames_before += static_cast<int64_t>(n) * g->frames;
             b += n;
         }
     }

@@ -55,6 +55,7 @@ constexpr int kScoreWavesPerSimd = CIVIC_SCORE_WAVES_PER_SIMD;   // register bud
 // SpanRows (civic_score_visual): grid y runs over (batch item, frame); a block scores rows of ONE frame span
 // of the dense sequence, so all it needs is that span's first row, found once per block, and the kernels below
 // stay what they are: a uniform-stride walk over n_rows = height * width rows.
+constexpr int kRaggedSlices = 64;       // frame spans of one ragged launch
 struct PlainRows {
     static constexpr bool kSpans = false;
 };
@@ -69,6 +70,17 @@ struct SpanRows {
         const uint32_t b = y / static_cast<uint32_t>(frames), f = y - b * static_cast<uint32_t>(frames);
         return static_cast<int64_t>(b) * seq_len + start[f];
     }
+    __device__ __forceinline__ int64_t out_offset(uint32_t y) const { return static_cast<int64_t>(y) * hw; }
+    __device__ __forceinline__ int64_t rows(uint32_t, int64_t n_rows) const { return n_rows; }
+};
+// RaggedRows (the ragged front): grid y runs over the frames of samples of different grids packed along the token
+// axis; every slice brings its own first row, row count and place in the packed scores.
+struct RaggedRows {
+    static constexpr bool kSpans = true;
+    int32_t first[kRaggedSlices], count[kRaggedSlices], out[kRaggedSlices];
+    __device__ __forceinline__ int64_t first_row(uint32_t y) const { return first[y]; }
+    __device__ __forceinline__ int64_t out_offset(uint32_t y) const { return out[y]; }
+    __device__ __forceinline__ int64_t rows(uint32_t y, int64_t) const { return count[y]; }
 };
 
 // fp32 rows: two passes over a row held in registers.
@@ -79,7 +91,8 @@ __global__ __launch_bounds__(kScoreThreads, kScoreBlocksPerCu) void score_f32_ke
 {
     if constexpr (MAP::kSpans) {
         hidden += map.first_row(blockIdx.y) * row_stride_bytes;
-        scores += static_cast<int64_t>(blockIdx.y) * map.hw;
+        scores += map.out_offset(blockIdx.y);
+        n_rows = map.rows(blockIdx.y, n_rows);
     }
     constexpr int E = 4;
     extern __shared__ __attribute__((aligned(16))) float q_s[];      // [dim]
@@ -154,7 +167,8 @@ __global__ __launch_bounds__(kScoreThreads, kScoreWavesPerSimd) void score_bf16_
 {
     if constexpr (MAP::kSpans) {
         hidden += map.first_row(blockIdx.y) * row_stride_bytes;
-        scores += static_cast<int64_t>(blockIdx.y) * map.hw;
+        scores += map.out_offset(blockIdx.y);
+        n_rows = map.rows(blockIdx.y, n_rows);
     }
     constexpr int kWaves = kScoreThreads / kWave;
     extern __shared__ __attribute__((aligned(16))) uint32_t q_w[];
@@ -364,6 +378,20 @@ int score_visual_check(const void* hidden, int dtype, int32_t batch, int64_t seq
     const int64_t slices = static_cast<int64_t>(batch) * gi.frames;
     if (gi.frames > CIVIC_MAX_FRAMES || seq_len > INT32_MAX || slices > 65535) return CIVIC_ERR_UNSUPPORTED;
     return CIVIC_OK;
+}
+
+// The frames of `n_slices` (<= kRaggedSlices) spans of a packed tensor in one launch: slice i is `count[i]` rows from
+// row `first[i]`, scored into scores[out[i] ..]; `longest` is the largest count.  Arguments checked by the caller.
+int score_slices_launch(const void* hidden, int dtype, int32_t dim, const float* anchor_q, float inv_tau, float* scores,
+                        const int32_t* first, const int32_t* count, const int32_t* out, int32_t n_slices, int32_t longest, void* stream)
+{
+    RaggedRows map;
+    for (int i = 0; i < kRaggedSlices; ++i) {
+        map.first[i] = i < n_slices ? first[i] : 0;
+        map.count[i] = i < n_slices ? count[i] : 0;
+        map.out[i] = i < n_slices ? out[i] : 0;
+    }
+    return score_rows(hidden, dtype, longest, n_slices, dim, dim, anchor_q, inv_tau, scores, map, stream);
 }
 
 }  // namespace civic

@@ -424,7 +424,9 @@ __device__ void select_first(const uint32_t* keys, uint32_t* marks, uint32_t* hi
     team_sync<false>();
 }
 
-__global__ __launch_bounds__(kSelThreads) void select_kernel(SelArgs a)
+// One workgroup selects one sample: `a` describes it, `b` is its place in the tensors a.scores, a.kept_idx and
+// a.keep_flags point at.
+__device__ __forceinline__ void select_sample(const SelArgs& a, const int b)
 {
     extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
     uint32_t* keys = smem;                                   // [nv_pad]; this and the next start on 16-byte boundaries
@@ -435,7 +437,6 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelArgs a)
     float* extremes = reinterpret_cast<float*>(smem + a.lds_words - 2 * kSelWaves);   // [2][kSelWaves], 16-byte aligned
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
-    const int b = blockIdx.x;
     const float* s = a.scores + static_cast<int64_t>(b) * a.nv;
 
     // Keys into LDS; on the way the sample's smallest and largest score (NaN ignored), which steer the
@@ -709,6 +710,23 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelArgs a)
     }
 }
 
+__global__ __launch_bounds__(kSelThreads) void select_kernel(SelArgs a)
+{
+    select_sample(a, blockIdx.x);
+}
+
+// Samples of different grids in one launch (the ragged front): workgroup i takes the i-th description of a table in
+// the kernel arguments, each with its own pointers, so its place in them is 0.
+constexpr int kSelRaggedItems = 16;
+struct SelTable {
+    SelArgs item[kSelRaggedItems];
+};
+__global__ __launch_bounds__(kSelThreads) void select_ragged_kernel(SelTable t)
+{
+    select_sample(t.item[blockIdx.x], 0);
+}
+
+
 }  // namespace civic
 
 namespace civic {
@@ -727,17 +745,11 @@ int select_check(const float* scores, int32_t batch, const civic_grid* grid, con
 
 }  // namespace civic
 
-extern "C" int civic_select(const float* scores, int32_t batch, const civic_grid* grid, int32_t* kept_idx,
-                            uint8_t* keep_flags, void* workspace, size_t workspace_bytes, void* stream)
-{
-    using namespace civic;
-    (void)workspace; (void)workspace_bytes;
-    const int rc_check = select_check(scores, batch, grid, kept_idx);
-    if (rc_check != CIVIC_OK) return rc_check;
-    if (batch == 0) return CIVIC_OK;
-    GridInfo gi;
-    grid_info(grid, &gi);
+namespace civic {
 
+// What the kernel needs to know about a sample of grid `gi` (checked), and the dynamic LDS it takes in bytes.
+static SelArgs make_sel_args(const float* scores, int32_t* kept_idx, uint8_t* keep_flags, const GridInfo& gi, size_t* lds_bytes)
+{
     SelArgs a;
     a.scores = scores; a.kept_idx = kept_idx; a.keep_flags = keep_flags;
     a.frames = gi.frames; a.height = gi.height; a.width = gi.width; a.hw = gi.hw; a.nv = gi.nv;
@@ -761,19 +773,64 @@ extern "C" int civic_select(const float* scores, int32_t batch, const civic_grid
     if (a.cell_w % 4 == 0 && a.cells_x * a.cell_w == a.width && !a.big_cells && a.cell_h * (a.cell_w / 4) >= 16) {
         a.cell_team = 16; a.cell_team_shift = 4;
     }
-
     // keys | histograms | per-team words | mark bits | word prefixes, rounded up to 16 bytes | per-wavefront extremes
     const size_t lds_words = (static_cast<size_t>(a.nv_pad) + kSelWaves * 256 + kSelWaves * 8 + a.nv_pad / 32 + a.nv_pad / 64 + 3) / 4 * 4 +
                              2 * kSelWaves;
     a.lds_words = static_cast<int32_t>(lds_words);
-    const size_t lds = sizeof(uint32_t) * lds_words;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    if (lds > 64 * 1024) {                                   // allowed once per device, for the largest sample there is
-        constexpr size_t max_pad = (CIVIC_MAX_VISUAL_TOKENS + 63) / 64 * 64;
-        constexpr size_t max_lds = sizeof(uint32_t) * ((max_pad + kSelWaves * 256 + kSelWaves * 8 + max_pad / 32 + max_pad / 64 + 3) / 4 * 4 +
-                                                       2 * kSelWaves);
+    *lds_bytes = sizeof(uint32_t) * lds_words;
+    return a;
+}
+
+// The limit of dynamic LDS is raised once per device and kernel, for the largest sample there is.
+static int allow_select_lds(const void* kernel, std::atomic<uint64_t>* done)
+{
+    constexpr size_t max_pad = (CIVIC_MAX_VISUAL_TOKENS + 63) / 64 * 64;
+    constexpr size_t max_lds = sizeof(uint32_t) * ((max_pad + kSelWaves * 256 + kSelWaves * 8 + max_pad / 32 + max_pad / 64 + 3) / 4 * 4 +
+                                                   2 * kSelWaves);
+    return allow_dynamic_lds(kernel, max_lds, done);
+}
+
+// `n` (<= 16) samples of different grids in one launch: sample i reads scores[i], writes kept_idx[i] (arguments checked
+// by the caller with select_check, one sample each).
+int select_samples_launch(const float* const* scores, int32_t* const* kept_idx, const civic_grid* const* grids, int32_t n, void* stream)
+{
+    SelTable t;
+    size_t lds = 0;
+    for (int i = 0; i < kSelRaggedItems; ++i) {
+        const int at = i < n ? i : 0;                             // (entries past the launch repeat the first; never read)
+        GridInfo gi;
+        grid_info(grids[at], &gi);
+        size_t one = 0;
+        t.item[i] = make_sel_args(scores[at], kept_idx[at], nullptr, gi, &one);
+        if (i < n && one > lds) lds = one;
+    }
+    if (lds > 64 * 1024) {
         static std::atomic<uint64_t> allowed{0};
-        const int rc = allow_dynamic_lds(reinterpret_cast<const void*>(select_kernel), max_lds, &allowed);
+        const int rc = allow_select_lds(reinterpret_cast<const void*>(select_ragged_kernel), &allowed);
+        if (rc != CIVIC_OK) return rc;
+    }
+    civic::launch(select_ragged_kernel, dim3(static_cast<unsigned>(n)), dim3(kSelThreads), lds, static_cast<hipStream_t>(stream), t);
+    return check_launch();
+}
+
+}  // namespace civic
+
+extern "C" int civic_select(const float* scores, int32_t batch, const civic_grid* grid, int32_t* kept_idx,
+                            uint8_t* keep_flags, void* workspace, size_t workspace_bytes, void* stream)
+{
+    using namespace civic;
+    (void)workspace; (void)workspace_bytes;
+    const int rc_check = select_check(scores, batch, grid, kept_idx);
+    if (rc_check != CIVIC_OK) return rc_check;
+    if (batch == 0) return CIVIC_OK;
+    GridInfo gi;
+    grid_info(grid, &gi);
+    size_t lds = 0;
+    const SelArgs a = make_sel_args(scores, kept_idx, keep_flags, gi, &lds);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (lds > 64 * 1024) {
+        static std::atomic<uint64_t> allowed{0};
+        const int rc = allow_select_lds(reinterpret_cast<const void*>(select_kernel), &allowed);
         if (rc != CIVIC_OK) return rc;
     }
     civic::launch(select_kernel, dim3(static_cast<unsigned>(batch)), dim3(kSelThreads), lds, s, a);
