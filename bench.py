@@ -506,9 +506,8 @@ def main() -> int:
         f_r = sum(4.0 * w.n_q_heads * w.head_dim * (n_ * (n_ + 1) / 2) for n_ in np.diff(rcomp))
         ragged = {"samples": len(rgrids), "dense_rows": int(rseq[-1]), "compact_rows": tc,
                   "compact_prefill_ragged_us": round(t_front, 2),
-                  # scores 64 frame spans per launch, selection 16 samples per launch, merge one launch per run of one shape
-                  "launches_front": -(-sum(g_[0] for g_ in rgrids) // 64) + -(-len(rgrids) // 16) +
-                                    sum(1 for i_ in range(len(rgrids)) if i_ == 0 or (rgrids[i_], rlens[i_]) != (rgrids[i_ - 1], rlens[i_ - 1])),
+                  # scores 64 frame spans per launch, selection 16 samples per launch, merge 24 samples per launch (all have few frames)
+                  "launches_front": -(-sum(g_[0] for g_ in rgrids) // 64) + -(-len(rgrids) // 16) + -(-len(rgrids) // 24),
                   "prefill_attn_ragged": {"us": round(t_rattn, 2), "us_one_call_per_sample": round(t_rattn_items, 2), "flops": f_r,
                                           "tflops": round(f_r / t_rattn / 1e6, 1)},
                   "decode_attn_ragged_us": round(t_rdec, 2)}

@@ -206,8 +206,8 @@ int civic_compact_prefill(const void* hidden, int dtype, int32_t batch, int64_t 
  *
  * civic_compact_prefill_ragged: the three stages of civic_compact_prefill for all samples - the scores of up to 64
  * frame spans per launch, the selection of up to 16 samples per launch (a workgroup per sample, each with its own
- * grid), the merge one launch per run of consecutive samples of one grid, length and frame layout - with every check
- * of every sample before the first launch.  seq_offsets[batch] and the visual tokens together <= INT32_MAX, else
+ * grid), the merge of up to 24 samples per launch (a sample of more than 8 frames by a launch of its own, together
+ * with the samples of the same shape that follow it) - with every check of every sample before the first launch.  seq_offsets[batch] and the visual tokens together <= INT32_MAX, else
  * CIVIC_ERR_UNSUPPORTED.
  *   hidden      device [seq_offsets[batch], dim];  pos_ids  device [3, seq_offsets[batch]] int32
  *   frame_start host, the samples' frame starts one after the other (grids[b].frames entries each), each

@@ -89,6 +89,19 @@ int score_slices_launch(const void* hidden, int dtype, int32_t dim, const float*
 // Up to 16 samples of different grids selected in one launch (the ragged front); every sample checked by the caller.
 int select_samples_launch(const float* const* scores, int32_t* const* kept_idx, const civic_grid* const* grids, int32_t n, void* stream);
 
+// One sample of a ragged batch for compact_samples_launch: where its rows, kept indices and compact rows begin in the
+// packed tensors, its kept count, length, grid and (sample-local) frame starts.
+struct RaggedSample {
+    int64_t row0, comp0, kept0, n_kept, seq_len;
+    const civic_grid* grid;
+    const int64_t* frame_start;
+};
+constexpr int kCompactRaggedItems = 24, kCompactRaggedFrames = 8;
+// Up to kCompactRaggedItems samples (each checked by the caller, at most kCompactRaggedFrames frames) merged by one launch.
+int compact_samples_launch(const void* hidden, int dtype, int32_t dim, const int32_t* pos_ids, const int32_t* kept_idx, void* hidden_c,
+                           int32_t* pos_c, int32_t* src_idx, const RaggedSample* samples, int32_t n, int64_t pos_axis_in,
+                           int64_t pos_axis_out, void* stream);
+
 constexpr int kWave = 64;
 
 // Native vector types (the nontemporal load builtin does not take HIP's struct vectors).

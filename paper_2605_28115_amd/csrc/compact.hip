@@ -40,12 +40,13 @@ struct FrameTable {
 // that the probes' stretches and a block's window of entries each fit one batch of 4 per thread).
 // pos_axis_in / pos_axis_out: elements between the three id axes of pos_ids and of pos_c (batch * seq_len and
 // batch * seq_c for the rectangular tensors; the packed totals when the samples of a ragged batch are merged one by one).
-template <typename V, int U, bool LONG>
-__global__ __launch_bounds__(kCompactThreads) void compact_kernel(
-    const uint8_t* __restrict__ hidden, int64_t row_bytes, const int32_t* __restrict__ pos_ids, int32_t batch,
-    int32_t seq_len, FrameTable ft, const int32_t* __restrict__ kept_idx, int32_t n_kept, int32_t seq_c,
+// The block's work for batch item `b` of the tensors the pointers name; FT is a frame table (n, hw, start[]).
+template <typename V, int U, bool LONG, typename FT>
+__device__ __forceinline__ void compact_rows(
+    const uint8_t* __restrict__ hidden, int64_t row_bytes, const int32_t* __restrict__ pos_ids,
+    int32_t seq_len, const FT& ft, const int32_t* __restrict__ kept_idx, int32_t n_kept, int32_t seq_c,
     int32_t rows_per_block, int32_t threads_per_row, uint8_t* __restrict__ hidden_c, int32_t* __restrict__ pos_c,
-    int32_t* __restrict__ src_idx, int64_t pos_axis_in, int64_t pos_axis_out)
+    int32_t* __restrict__ src_idx, int64_t pos_axis_in, int64_t pos_axis_out, const int b)
 {
     __shared__ int32_t kb[CIVIC_MAX_FRAMES + 1];
     __shared__ int32_t row_src[kCompactMaxRows];
@@ -53,7 +54,6 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
     __shared__ int32_t stretch[CIVIC_MAX_FRAMES];  // long lists: the probe at whose entry, or in the P - 1 before it, frame f's boundary lies
 
     const int tid = threadIdx.x;
-    const int b = blockIdx.y;
     const int32_t j0 = blockIdx.x * rows_per_block;
     const int32_t nrows = min(rows_per_block, seq_c - j0);
     const int32_t* kept = kept_idx + static_cast<int64_t>(b) * n_kept;
@@ -257,6 +257,43 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
 
 }
 
+template <typename V, int U, bool LONG>
+__global__ __launch_bounds__(kCompactThreads) void compact_kernel(
+    const uint8_t* __restrict__ hidden, int64_t row_bytes, const int32_t* __restrict__ pos_ids, int32_t batch,
+    int32_t seq_len, FrameTable ft, const int32_t* __restrict__ kept_idx, int32_t n_kept, int32_t seq_c,
+    int32_t rows_per_block, int32_t threads_per_row, uint8_t* __restrict__ hidden_c, int32_t* __restrict__ pos_c,
+    int32_t* __restrict__ src_idx, int64_t pos_axis_in, int64_t pos_axis_out)
+{
+    (void)batch;
+    compact_rows<V, U, LONG>(hidden, row_bytes, pos_ids, seq_len, ft, kept_idx, n_kept, seq_c, rows_per_block, threads_per_row,
+                             hidden_c, pos_c, src_idx, pos_axis_in, pos_axis_out, blockIdx.y);
+}
+
+// Samples of different length and grid in one launch (the ragged front): grid y = sample, described by an entry of a
+// table in the kernel arguments - where its rows, kept indices and compact rows begin in the packed tensors, and its
+// frame table (up to kCompactRaggedFrames frames; samples with more are merged by a launch of their own).  Grid x
+// covers the longest sample; a block past its sample's compact rows has nothing to do.
+struct CompactItem {
+    int32_t row0, comp0, kept0, n_kept, seq_len, seq_c;
+    int32_t n, hw, start[kCompactRaggedFrames];              // the sample's frame table
+};
+struct CompactTable {
+    CompactItem item[kCompactRaggedItems];
+};
+template <typename V, int U>
+__global__ __launch_bounds__(kCompactThreads) void compact_ragged_kernel(
+    const uint8_t* __restrict__ hidden, int64_t row_bytes, const int32_t* __restrict__ pos_ids, CompactTable t,
+    const int32_t* __restrict__ kept_idx, int32_t rows_per_block, int32_t threads_per_row, uint8_t* __restrict__ hidden_c,
+    int32_t* __restrict__ pos_c, int32_t* __restrict__ src_idx, int64_t pos_axis_in, int64_t pos_axis_out)
+{
+    const CompactItem& it = t.item[blockIdx.y];
+    if (static_cast<int64_t>(blockIdx.x) * rows_per_block >= it.seq_c) return;
+    compact_rows<V, U, false>(hidden + static_cast<int64_t>(it.row0) * row_bytes, row_bytes, pos_ids + it.row0, it.seq_len, it,
+                              kept_idx + it.kept0, it.n_kept, it.seq_c, rows_per_block, threads_per_row,
+                              hidden_c + static_cast<int64_t>(it.comp0) * row_bytes, pos_c + it.comp0, src_idx + it.comp0,
+                              pos_axis_in, pos_axis_out, 0);
+}
+
 }  // namespace civic
 
 namespace civic {
@@ -296,6 +333,44 @@ int compact_check(const void* hidden, int dtype, int32_t dim, const int32_t* pos
 
 namespace civic {
 
+// How a launch copies rows of `row_bytes` bytes when it has `total_rows` of them to move.
+struct CompactGeom {
+    int vec;        // bytes per vector
+    int tpr;        // threads per row
+    int unroll;     // passes of the condition-free copy (0: the general loop)
+    int64_t rpb;    // rows per block
+};
+static CompactGeom compact_geom(int64_t row_bytes, int64_t total_rows)
+{
+    int vec = 16;
+    while (row_bytes % vec) vec >>= 1;
+    // Threads per row: the power of two in [16, 256] that wastes the fewest lanes on this row length; among
+    // equals the largest whose double divides the row, which is what the condition-free copy needs.
+    const int64_t vpr = row_bytes / vec;
+    int tpr = 256;
+    int64_t best = -1;
+    bool best_even = false;
+    for (int t = 256; t >= 16; t >>= 1) {
+        const int64_t slots = (vpr + t - 1) / t * t;
+        const bool even = vpr % (2 * t) == 0;
+        if (best < 0 || slots < best || (slots == best && even && !best_even)) { best = slots; tpr = t; best_even = even; }
+    }
+    // Rows per block: small blocks win (about 8 per CU on 256 CUs keep more loads in flight, and the
+    // per-block pass over kept_idx is a few KB of L2 hits), as long as every thread has a vector to move.
+    int64_t rpb = total_rows / (256 * CIVIC_COMPACT_BLOCKS_PER_CU);
+    const int64_t min_rows = 256 / tpr > 2 ? 256 / tpr : 2;
+    if (rpb < min_rows) rpb = min_rows;
+    if (rpb > kCompactMaxRows) rpb = kCompactMaxRows;
+    // Condition-free copy: 1, 2 or 4 passes of 256 / tpr rows per block (more rows per block go the general way).
+    const int64_t rpp = 256 / tpr;
+    int unroll = 0;
+    if (best_even && rpb <= 4 * rpp) {
+        unroll = rpb <= rpp ? 1 : rpb <= 2 * rpp ? 2 : 4;
+        rpb = unroll * rpp;
+    }
+    return CompactGeom{vec, tpr, unroll, rpb};
+}
+
 // The launch of civic_compact for arguments that compact_check has passed.
 int compact_launch(const void* hidden, int dtype, int32_t dim, const int32_t* pos_ids, int32_t batch, int64_t seq_len,
                    const civic_grid* grid, const int64_t* frame_start, const int32_t* kept_idx, int64_t n_kept, void* hidden_c,
@@ -314,31 +389,9 @@ int compact_launch(const void* hidden, int dtype, int32_t dim, const int32_t* po
     ft.n = gi.frames; ft.hw = gi.hw;
     for (int32_t f = 0; f < CIVIC_MAX_FRAMES; ++f) ft.start[f] = f < gi.frames ? static_cast<int32_t>(frame_start[f]) : 0;
 
-    // Threads per row: the power of two in [16, 256] that wastes the fewest lanes on this row length; among
-    // equals the largest whose double divides the row, which is what the condition-free copy needs.
-    const int64_t vpr = row_bytes / vec;
-    int tpr = 256;
-    int64_t best = -1;
-    bool best_even = false;
-    for (int t = 256; t >= 16; t >>= 1) {
-        const int64_t slots = (vpr + t - 1) / t * t;
-        const bool even = vpr % (2 * t) == 0;
-        if (best < 0 || slots < best || (slots == best && even && !best_even)) { best = slots; tpr = t; best_even = even; }
-    }
-    // Rows per block: small blocks win (about 8 per CU on 256 CUs keep more loads in flight, and the
-    // per-block pass over kept_idx is a few KB of L2 hits), as long as every thread has a vector to move.
-    const int64_t total_rows = seq_c * batch;
-    int64_t rpb = total_rows / (256 * CIVIC_COMPACT_BLOCKS_PER_CU);
-    const int64_t min_rows = 256 / tpr > 2 ? 256 / tpr : 2;
-    if (rpb < min_rows) rpb = min_rows;
-    if (rpb > kCompactMaxRows) rpb = kCompactMaxRows;
-    // Condition-free copy: 1, 2 or 4 passes of 256 / tpr rows per block (more rows per block go the general way).
-    const int64_t rpp = 256 / tpr;
-    int unroll = 0;
-    if (best_even && rpb <= 4 * rpp) {
-        unroll = rpb <= rpp ? 1 : rpb <= 2 * rpp ? 2 : 4;
-        rpb = unroll * rpp;
-    }
+    const CompactGeom geom = compact_geom(row_bytes, seq_c * batch);
+    const int tpr = geom.tpr, unroll = geom.unroll;
+    const int64_t rpb = geom.rpb;
     const int64_t blocks = (seq_c + rpb - 1) / rpb;
     // Long kept lists (more than one batch of 4 entries per thread) are searched instead of read whole when
     // the stretches between the probes, (frames - 1) * ceil(n_kept / 256) entries, and the entries that can land
@@ -379,6 +432,56 @@ int compact_launch(const void* hidden, int dtype, int32_t dim, const int32_t* po
         default: CIVIC_COMPACT_LAUNCH(uint16_t, 0, false); break;
     }
 #undef CIVIC_COMPACT_LAUNCH
+    return check_launch();
+}
+
+// Up to kCompactRaggedItems samples of different length and grid merged by ONE launch (the ragged front).  Every sample
+// has passed compact_check on its own and has at most kCompactRaggedFrames frames; row numbers fit 32 bits.
+int compact_samples_launch(const void* hidden, int dtype, int32_t dim, const int32_t* pos_ids, const int32_t* kept_idx, void* hidden_c,
+                           int32_t* pos_c, int32_t* src_idx, const RaggedSample* samples, int32_t n, int64_t pos_axis_in,
+                           int64_t pos_axis_out, void* stream)
+{
+    const int64_t row_bytes = static_cast<int64_t>(dim) * dtype_size(dtype);
+    CompactTable t;
+    int64_t total_rows = 0, longest = 0;
+    for (int i = 0; i < kCompactRaggedItems; ++i) {
+        CompactItem& it = t.item[i];
+        if (i >= n) { it = t.item[0]; it.seq_c = 0; continue; }   // (never read: the grid has n samples)
+        const RaggedSample& x = samples[i];
+        GridInfo gi;
+        grid_info(x.grid, &gi);
+        it.row0 = static_cast<int32_t>(x.row0); it.comp0 = static_cast<int32_t>(x.comp0); it.kept0 = static_cast<int32_t>(x.kept0);
+        it.n_kept = static_cast<int32_t>(x.n_kept); it.seq_len = static_cast<int32_t>(x.seq_len);
+        it.seq_c = static_cast<int32_t>(x.seq_len - gi.nv + x.n_kept);
+        it.n = gi.frames; it.hw = gi.hw;
+        for (int f = 0; f < kCompactRaggedFrames; ++f) it.start[f] = f < gi.frames ? static_cast<int32_t>(x.frame_start[f]) : 0;
+        total_rows += it.seq_c;
+        longest = it.seq_c > longest ? it.seq_c : longest;
+    }
+    if (longest == 0) return CIVIC_OK;
+    const CompactGeom geom = compact_geom(row_bytes, total_rows);
+    const int64_t blocks = (longest + geom.rpb - 1) / geom.rpb;
+    const uint8_t* h = static_cast<const uint8_t*>(hidden);
+    uint8_t* hc = static_cast<uint8_t*>(hidden_c);
+    const dim3 g(static_cast<unsigned>(blocks), static_cast<unsigned>(n)), blk(kCompactThreads);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+#define CIVIC_COMPACT_RAGGED(V, U)                                                                                  \
+    civic::launch((compact_ragged_kernel<V, U>), g, blk, 0, s, h, row_bytes, pos_ids, t, kept_idx,                    \
+                  static_cast<int32_t>(geom.rpb), geom.tpr, hc, pos_c, src_idx, pos_axis_in, pos_axis_out)
+    switch (geom.vec) {
+        case 16:
+            switch (geom.unroll) {
+                case 1: CIVIC_COMPACT_RAGGED(u32x4, 1); break;
+                case 2: CIVIC_COMPACT_RAGGED(u32x4, 2); break;
+                case 4: CIVIC_COMPACT_RAGGED(u32x4, 4); break;
+                default: CIVIC_COMPACT_RAGGED(u32x4, 0); break;
+            }
+            break;
+        case 8: CIVIC_COMPACT_RAGGED(u32x2, 0); break;
+        case 4: CIVIC_COMPACT_RAGGED(uint32_t, 0); break;
+        default: CIVIC_COMPACT_RAGGED(uint16_t, 0); break;
+    }
+#undef CIVIC_COMPACT_RAGGED
     return check_launch();
 }
 

@@ -168,19 +168,37 @@ extern "C" int civic_compact_prefill_ragged(const void* hidden, int dtype, int32
             }
         }
     }
+    // Merge: samples with few frames 24 per launch (a table of sample descriptions in the kernel arguments); a sample
+    // with more frames than the table holds per sample goes out by itself, together with its run of equal samples.
     {
+        RaggedSample rs[kCompactRaggedItems];
+        int32_t n_rs = 0;
+        auto flush_merge = [&]() {
+            const int r = n_rs ? compact_samples_launch(hidden, dtype, dim, pos_ids, kept_idx, hidden_c, pos_c, src_idx, rs, n_rs, total,
+                                                        total_c, stream)
+                               : CIVIC_OK;
+            n_rs = 0;
+            return r;
+        };
         int64_t vis = 0, kept = 0, comp = 0, frames_before = 0;
         for (int32_t b = 0; b < batch;) {
             const civic_grid* g = &grids[b];
             const Sample x = sample(b, vis, kept, comp, frames_before);
-            const int32_t n = run_length(b, frames_before);
-            rc = compact_launch(x.hidden, dtype, dim, x.pos, n, x.len, g, x.frames, x.kept, x.n_kept, x.hidden_c, x.pos_c, x.src, total,
-                                total_c, stream);
-            if (rc != CIVIC_OK) return rc;
             const int64_t nv = static_cast<int64_t>(g->frames) * g->height * g->width;
+            int32_t n = 1;
+            if (g->frames > kCompactRaggedFrames) {
+                n = run_length(b, frames_before);
+                rc = compact_launch(x.hidden, dtype, dim, x.pos, n, x.len, g, x.frames, x.kept, x.n_kept, x.hidden_c, x.pos_c, x.src, total,
+                                    total_c, stream);
+                if (rc != CIVIC_OK) return rc;
+            } else {
+                rs[n_rs++] = RaggedSample{seq_offsets[b], comp, kept, x.n_kept, x.len, g, x.frames};
+                if (n_rs == kCompactRaggedItems && (rc = flush_merge()) != CIVIC_OK) return rc;
+            }
             vis += n * nv; kept += n * x.n_kept; comp += n * (x.len - nv + x.n_kept); frames_before += static_cast<int64_t>(n) * g->frames;
             b += n;
         }
+        if ((rc = flush_merge()) != CIVIC_OK) return rc;
     }
     return CIVIC_OK;
 }

@@ -40,6 +40,9 @@ MIXES = {
     # runs of samples of one shape (same grid, length and frame starts), which go through the kernels as one batch each
     "repeated shapes": ([(1, 16, 16, 4, 4, 2, 0, 85)] * 3 + [(2, 8, 8, 4, 4, 1, 0, 40)] + [(1, 32, 32, 4, 4, 1, 0, 341)] * 2 + [(1, 16, 16, 4, 4, 2, 0, 85)], -5),
     "small grids": ([(1, 3, 5, 2, 2, 1, 0, 4), (3, 2, 2, 2, 2, 0, 1, 5), (1, 1, 1, 1, 1, 0, 0, 0), (2, 7, 9, 3, 4, 2, 3, 40), (1, 8, 8, 8, 8, 0, 0, 64)], 7),
+    # more frames than the merge's table holds per sample (those go out by themselves), and more samples than one launch takes
+    "many frames, many samples": ([(9, 2, 3, 1, 1, 0, 1, 20), (1, 4, 4, 2, 2, 1, 0, 5), (16, 4, 4, 4, 4, 1, 2, 90), (16, 4, 4, 4, 4, 1, 2, 90)] +
+                                  [(1 + i % 3, 3 + i % 4, 2 + i % 5, 2, 2, i % 2, i % 3, (1 + i % 3) * (3 + i % 4) * (2 + i % 5) // 3) for i in range(40)], 4),
 }
 
 
