@@ -344,3 +344,14 @@ def test_ragged_decode_argument_errors(bd):
     assert dec(ws=None, wsb=0) == bd.ERR_WORKSPACE and dec(wsb=need - 1) == bd.ERR_WORKSPACE
     assert L.civic_decode_attn_ragged_workspace_bytes(1, 3, P(ctx(5, 0, 17)), 32, 8, 128) == 0
     assert bd.lib.civic_last_hip_error() == 0
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/civic.h is a C ABI: it compiles as C99 and as C++ with nothing but the standard headers."""
+    import subprocess
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "civic.h"\nint main(void) { return civic_kept_count == 0; }\n')
+    inc = os.path.join(ROOT, "include")
+    for cmd in (["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror"], ["g++", "-std=c++17", "-x", "c++", "-Wall", "-Wextra", "-pedantic"]):
+        r = subprocess.run(cmd + ["-I", inc, "-fsyntax-only", str(src)], capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
