@@ -350,7 +350,7 @@ def test_header_is_plain_c(tmp_path):
     """include/civic.h is a C ABI: it compiles as C99 and as C++ with nothing but the standard headers."""
     import subprocess
     src = tmp_path / "use_header.c"
-    src.write_text('#include "civic.h"\nint main(void) { return civic_kept_count == 0; }\n')
+    src.write_text('#include "civic.h"\nint main(void) { return CIVIC_OK; }\n')
     inc = os.path.join(ROOT, "include")
     for cmd in (["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror"], ["g++", "-std=c++17", "-x", "c++", "-Wall", "-Wextra", "-pedantic"]):
         r = subprocess.run(cmd + ["-I", inc, "-fsyntax-only", str(src)], capture_output=True, text=True)
